@@ -1,0 +1,150 @@
+/*
+ * flashformer.h -- C ABI of the MI355X whole-model decode library.
+ *
+ * One call to ff_decode_step runs one forward step of a Llama-style decoder (paper Section 2.1:
+ * pre-RMSNorm, grouped-query attention with RoPE, SwiGLU FFN) for a batch of independent sequences
+ * in ONE persistent kernel launch covering all layers (paper abstract and Section 3: a single
+ * kernel invocation per generated token), followed inside the same launch by the final norm and the
+ * LM head.  ff_decode_step_perop runs the same step as one launch per operation on the same
+ * buffers (the paper's "Baseline": separate kernel launches, Section 3 / latency tables).
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory on the current HIP device; it is allocated and
+ *     owned by the caller (the library never allocates or frees device memory).  Sizes come from
+ *     the *_bytes queries.  All device buffers must be 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls that take a
+ *     stream are asynchronous on it.
+ *   - Every function returns FF_OK (0) or a negative FF_ERR_* code; ff_last_error() returns a
+ *     thread-local description of the last failure.  No exception crosses this boundary.
+ *   - Canonical (caller-side) layouts: every projection matrix is row-major [out, in].
+ *       FF_W_BF16      : bf16 [N][K]
+ *       FF_W_INT8_PC   : int8 [N][K] codes, fp16 scale s[N];            w = q * s[n]
+ *       FF_W_INT4_G128 : uint8 [N][K/2], two codes per byte, low nibble = even k,
+ *                        fp16 s[N][K/128], fp16 z[N][K/128] (integer valued, 0..15);
+ *                        w = (code - z[n][k/128]) * s[n][k/128]
+ *     Norm gains and the embedding table are bf16.  The library repacks these into a private
+ *     tile order inside `packed_dev`; the caller may free the canonical tensors after loading.
+ */
+#ifndef FLASHFORMER_H
+#define FLASHFORMER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ff_model ff_model;
+typedef struct ff_kv ff_kv;
+
+enum {
+    FF_OK = 0,
+    FF_ERR_ARG = -1,         /* null pointer, batch outside [1, max_batch], bad index */
+    FF_ERR_UNSUPPORTED = -2, /* configuration has no compiled kernel instance */
+    FF_ERR_RANGE = -3,       /* a position is >= max_ctx, or a token id >= vocab (seen on device) */
+    FF_ERR_NOMEM = -4,       /* a caller-provided buffer is too small or misaligned */
+    FF_ERR_TIMEOUT = -5,     /* the in-kernel grid barrier gave up waiting (CTAs not co-resident) */
+    FF_ERR_HIP = -6          /* a HIP runtime call failed; text in ff_last_error() */
+};
+
+enum { FF_W_BF16 = 0, FF_W_INT8_PC = 1, FF_W_INT4_G128 = 2 };
+
+/* Which matrix ff_debug_dequant exports. */
+enum { FF_MAT_WQ = 0, FF_MAT_WK, FF_MAT_WV, FF_MAT_WO, FF_MAT_WGATE, FF_MAT_WUP, FF_MAT_WDOWN, FF_MAT_LMHEAD };
+
+/* Model dimensions (paper Section 2.1, model-configuration table) and weight format. */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rms_eps, rope_theta;
+    int32_t wdtype;        /* FF_W_* for the seven per-layer projections */
+    int32_t max_batch;     /* largest batch any step will use (1..4) */
+    int32_t quant_lm_head; /* nonzero: LM head uses wdtype too; zero: LM head is bf16 */
+} ff_config;
+
+/* One projection matrix in canonical layout (device pointers; s/z NULL when unused). */
+typedef struct {
+    const void *w, *s, *z;
+} ff_matrix;
+
+typedef struct {
+    const void *attn_norm, *ffn_norm; /* bf16 [d_model] */
+    ff_matrix wq, wk, wv, wo, w_gate, w_up, w_down;
+} ff_layer_weights;
+
+typedef struct {
+    const void *embed;      /* bf16 [vocab][d_model] */
+    const void *final_norm; /* bf16 [d_model] */
+    ff_matrix lm_head;      /* [vocab][d_model] */
+} ff_head_weights;
+
+const char *ff_last_error(void);
+
+/* Bytes the caller must provide for the repacked parameters and for the activation-exchange /
+ * synchronisation scratch of a model with this configuration. */
+int ff_model_bytes(const ff_config *cfg, size_t *packed_bytes, size_t *scratch_bytes);
+
+/* Creates a model over caller-owned device buffers (contents of packed_dev undefined until the
+ * load calls below have run; scratch_dev is cleared here on `stream`).  FF_ERR_NOMEM if a buffer
+ * is smaller than ff_model_bytes reports, FF_ERR_UNSUPPORTED for dimensions without a kernel
+ * instance (head_dim must be 64 or 128, n_q_heads/n_kv_heads in {1,2,4,8}, d_model % 8 == 0 ...). */
+int ff_model_create(const ff_config *cfg, void *packed_dev, size_t packed_bytes, void *scratch_dev,
+                    size_t scratch_bytes, void *stream, ff_model **out);
+
+/* Repack one layer / the head from canonical layout into the model (device-to-device on `stream`).
+ * Layers may be loaded in any order, one at a time, so a caller can generate, load and free a
+ * layer at a time for models whose canonical copy would not fit beside the packed one. */
+int ff_model_load_layer(ff_model *m, int32_t layer, const ff_layer_weights *w, void *stream);
+int ff_model_load_head(ff_model *m, const ff_head_weights *w, void *stream);
+
+/* Convenience: create + load every layer (layers = host array [n_layers]) + head. */
+int ff_model_load(const ff_config *cfg, const ff_layer_weights *layers, const ff_head_weights *head,
+                  void *packed_dev, size_t packed_bytes, void *scratch_dev, size_t scratch_bytes,
+                  void *stream, ff_model **out);
+int ff_model_free(ff_model *m);
+
+/* KV cache for `batch` independent sequences of at most max_ctx positions (paper Section 4.2:
+ * caches are distinct per sequence).  bf16; keys are stored rotated.  Also holds the RoPE
+ * cos/sin table for positions [0, max_ctx), built here on `stream`. */
+int ff_kv_bytes(const ff_model *m, int32_t batch, int32_t max_ctx, size_t *bytes);
+int ff_kv_alloc(ff_model *m, int32_t batch, int32_t max_ctx, void *kv_dev, size_t bytes, void *stream,
+                ff_kv **out);
+/* Copy n cache rows [pos0, pos0+n) of (layer, seq) from / to canonical bf16 [n][n_kv_heads][head_dim]. */
+int ff_kv_fill(ff_kv *kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, const void *k_dev,
+               const void *v_dev, void *stream);
+int ff_kv_read(ff_kv *kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, void *k_dev, void *v_dev,
+               void *stream);
+int ff_kv_free(ff_kv *kv);
+
+/* One decode step (paper Section 3.2, attention and GLU schedules; final norm and LM head added).
+ *   tokens_dev    int32 [batch]   token ids, each in [0, vocab)
+ *   positions_dev int32 [batch]   number of rows already cached for each sequence (= the position
+ *                                 of this token); this step appends K,V at that row and attends to
+ *                                 rows 0..position inclusive.  The caller advances positions.
+ *   logits_dev    fp32  [batch][vocab]   valid once `stream` has synchronised.
+ * Asynchronous; an out-of-range position or token makes the kernel skip the step and record
+ * FF_ERR_RANGE in the model's status word (see ff_status).  Steps on one model must not overlap. */
+int ff_decode_step(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
+                   float *logits_dev, int32_t batch, void *stream);
+
+/* Same step as separate per-operation launches (baseline of the paper's latency tables). */
+int ff_decode_step_perop(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
+                         float *logits_dev, int32_t batch, void *stream);
+
+/* Synchronises `stream`, returns the device status word (FF_OK, FF_ERR_RANGE or FF_ERR_TIMEOUT)
+ * recorded by the steps so far, and clears it. */
+int ff_status(ff_model *m, void *stream);
+
+/* Writes matrix `which` (FF_MAT_*) of `layer` (ignored for FF_MAT_LMHEAD) as fp32, canonical
+ * [N][K] order, dequantised from the PACKED copy exactly as the decode kernels dequantise it. */
+int ff_debug_dequant(const ff_model *m, int32_t layer, int32_t which, float *out_dev, void *stream);
+
+/* Number of grid barriers one fused step executes (for tests of the schedule), and the number of
+ * workgroups / threads per workgroup the fused kernel launches with. */
+int ff_fused_schedule(const ff_model *m, int32_t *barriers_per_step, int32_t *n_workgroups,
+                      int32_t *threads_per_workgroup);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHFORMER_H */

@@ -1,0 +1,136 @@
+// Device-side structures and primitives shared by the fused whole-model kernel and the
+// per-operation baseline kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ff {
+
+typedef unsigned int u32;
+typedef unsigned long long u64;
+typedef __attribute__((ext_vector_type(4))) u32 u32x4;
+typedef __attribute__((ext_vector_type(2))) u32 u32x2;
+typedef uint16_t bf16_t;   // raw bits
+typedef uint16_t f16_t;    // raw bits
+
+constexpr int kThreads = 256;            // threads per workgroup (4 waves, one per SIMD)
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxBatch = 4;
+constexpr int kMaxSplits = 64;           // max KV splits per (sequence, kv head)
+constexpr int kMinSplitLen = 64;         // do not split the cache finer than this many rows
+constexpr int kLdsActBytes = 128 * 1024; // LDS region holding the staged activation vector(s)
+constexpr int kLdsAuxBytes = 24 * 1024;  // partial sums, reduction scratch
+constexpr int kSpinLimit = 1 << 22;
+
+enum { W_BF16 = 0, W_INT8 = 1, W_INT4 = 2 };
+
+// A projection matrix in packed (device-private) row order.
+struct PMat {
+    const uint8_t* w;   // rows of row_bytes each
+    const f16_t* s;     // int8: [n]; int4: [n][k/128]
+    const f16_t* z;     // int4: [n][k/128]
+    int n, k;           // rows (outputs), columns (inputs)
+    int wd;
+    __host__ __device__ size_t row_bytes() const { return wd == W_BF16 ? (size_t)k * 2 : wd == W_INT8 ? (size_t)k : (size_t)k / 2; }
+};
+
+struct PLayer {
+    const bf16_t* g1;   // attention pre-norm gain
+    const bf16_t* g2;   // FFN pre-norm gain
+    PMat qkv;           // rows: q heads, k heads (RoPE partners adjacent), then v heads
+    PMat o;
+    PMat gu;            // rows 2i = gate_i, 2i+1 = up_i
+    PMat down;
+};
+
+// Everything the kernels need about the model and its exchange buffers.
+struct DevModel {
+    int L, d, Hq, Hkv, hd, F, V;
+    float eps;
+    const PLayer* layers;    // device array [L]
+    const bf16_t* embed;
+    const bf16_t* gf;
+    PMat lm;
+    // exchange buffers (device scratch)
+    float* x;        // residual stream            [B][d]
+    float* xn;       // normed activation (per-op)  [B][d]
+    float* q;        // rotated queries            [B][Hq*hd]
+    float* kvcur;    // this step's k,v (bf16-rounded values as fp32) [B][2][Hkv*hd]
+    float* attn_o;   // merged attention output    [B][Hq*hd]
+    float* h;        // SwiGLU output              [B][F]
+    float* y;        // per-op: raw projection out [B][max rows]
+    float* part_m;   // split partials             [B][Hq][kMaxSplits]
+    float* part_l;
+    float* part_o;   //                            [B][Hq][kMaxSplits][hd]
+    u32* head_ctr;   // arrivals per (b, kv head)  [B][Hkv]
+    u32* bar_flags;  // one arrival flag per workgroup
+    int* status;
+};
+
+struct DevKV {
+    bf16_t* base;        // [L][batch][Hkv][2][max_ctx][hd]
+    const float2* rope;  // [max_ctx][hd/2] (cos, sin)
+    int max_ctx, batch;
+    __device__ bf16_t* plane(const DevModel& M, int l, int b, int j, int kv) const {
+        return base + ((((size_t)l * batch + b) * M.Hkv + j) * 2 + kv) * (size_t)max_ctx * M.hd;
+    }
+};
+
+// ---------------------------------------------------------------- coherent exchange accesses
+// Activations exchanged between workgroups inside one launch are read and written with
+// agent-scope relaxed atomics: these bypass the per-XCD L2's non-coherent lines, so no cache
+// write-back / invalidate is needed at a grid barrier.
+__device__ __forceinline__ float xld(const float* p) {
+    return __uint_as_float(__hip_atomic_load((const u32*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ float2 xld2(const float* p) {
+    u64 v = __hip_atomic_load((const u64*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((u32)v), __uint_as_float((u32)(v >> 32)));
+}
+__device__ __forceinline__ void xst(float* p, float v) {
+    __hip_atomic_store((u32*)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void xst2(float* p, float a, float b) {
+    u64 v = (u64)__float_as_uint(a) | ((u64)__float_as_uint(b) << 32);
+    __hip_atomic_store((u64*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ u32 xld_u32(const u32* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void xst_u32(u32* p, u32 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Plain (launch-boundary ordered) accessors with the same signatures, for the per-op kernels.
+struct PlainIO {
+    static __device__ __forceinline__ float ld(const float* p) { return *p; }
+    static __device__ __forceinline__ float2 ld2(const float* p) { return *(const float2*)p; }
+    static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+    static __device__ __forceinline__ void st2(float* p, float a, float b) { *(float2*)p = make_float2(a, b); }
+};
+struct CoherentIO {
+    static __device__ __forceinline__ float ld(const float* p) { return xld(p); }
+    static __device__ __forceinline__ float2 ld2(const float* p) { return xld2(p); }
+    static __device__ __forceinline__ void st(float* p, float v) { xst(p, v); }
+    static __device__ __forceinline__ void st2(float* p, float a, float b) { xst2(p, a, b); }
+};
+
+// ---------------------------------------------------------------- scalar helpers
+__device__ __forceinline__ float bf_lo(u32 w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(u32 w) { return __uint_as_float(w & 0xFFFF0000u); }
+__device__ __forceinline__ float bf_to_f(bf16_t h) { return __uint_as_float((u32)h << 16); }
+// fp32 -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ bf16_t f_to_bf(float f) {
+    u32 u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float f16_to_f(f16_t h) {
+    _Float16 v;
+    __builtin_memcpy(&v, &h, 2);
+    return (float)v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ u32x4 ldg_stream(const void* p) { return __builtin_nontemporal_load((const u32x4*)p); }
+
+}  // namespace ff

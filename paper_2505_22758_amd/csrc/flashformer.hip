@@ -1,0 +1,523 @@
+// C ABI of the MI355X whole-model decode library (see include/flashformer.h).
+#include "../../include/flashformer.h"
+#include "ff_kernels.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace ff;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+#define HIPCHK(expr)                                                                                   \
+    do {                                                                                               \
+        hipError_t e_ = (expr);                                                                        \
+        if (e_ != hipSuccess) return fail(FF_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));  \
+    } while (0)
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct MatPlan { size_t w, s, z; int n, k, wd; };   // byte offsets into packed_dev
+struct LayerPlan { size_t g1, g2; MatPlan qkv, o, gu, down; };
+struct Plan {
+    size_t layers_tab;
+    std::vector<LayerPlan> layers;
+    size_t embed, gf;
+    MatPlan lm;
+    size_t packed_bytes;
+    // scratch
+    size_t x, xn, q, kvcur, attn_o, h, y, part_m, part_l, part_o, head_ctr, bar_flags, status, scratch_bytes;
+};
+
+size_t mat_w_bytes(int n, int k, int wd) { return wd == W_BF16 ? (size_t)n * k * 2 : wd == W_INT8 ? (size_t)n * k : (size_t)n * k / 2; }
+size_t mat_s_bytes(int n, int k, int wd) { return wd == W_INT8 ? (size_t)n * 2 : wd == W_INT4 ? (size_t)n * (k / 128) * 2 : 0; }
+
+MatPlan plan_mat(size_t& off, int n, int k, int wd) {
+    MatPlan p{0, 0, 0, n, k, wd};
+    p.w = off; off = align256(off + mat_w_bytes(n, k, wd));
+    p.s = off; off = align256(off + mat_s_bytes(n, k, wd));
+    p.z = off; off = align256(off + (wd == W_INT4 ? mat_s_bytes(n, k, wd) : 0));
+    return p;
+}
+
+int check_config(const ff_config* c) {
+    if (!c) return fail(FF_ERR_ARG, "config is null");
+    if (c->n_layers < 1 || c->d_model < 8 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 8 || c->vocab < 2)
+        return fail(FF_ERR_ARG, "non-positive model dimension");
+    if (c->max_batch < 1 || c->max_batch > kMaxBatch) return fail(FF_ERR_ARG, "max_batch %d outside [1,%d]", c->max_batch, kMaxBatch);
+    if (c->wdtype < 0 || c->wdtype > 2) return fail(FF_ERR_ARG, "unknown wdtype %d", c->wdtype);
+    if (c->n_q_heads % c->n_kv_heads) return fail(FF_ERR_UNSUPPORTED, "n_q_heads must be a multiple of n_kv_heads");
+    int G = c->n_q_heads / c->n_kv_heads;
+    bool inst = (c->head_dim == 64 && G == 4) || (c->head_dim == 128 && G == 4) || (c->head_dim == 128 && G == 8);
+    if (!inst) return fail(FF_ERR_UNSUPPORTED, "no attention instance for head_dim %d with %d query heads per kv head", c->head_dim, G);
+    int epu = c->wdtype == W_BF16 ? 8 : c->wdtype == W_INT8 ? 16 : 128;
+    int qd = c->n_q_heads * c->head_dim;
+    if (c->d_model % epu || qd % epu || c->d_ffn % epu)
+        return fail(FF_ERR_UNSUPPORTED, "d_model, n_q_heads*head_dim and d_ffn must be multiples of %d for this weight type", epu);
+    if (c->d_model % 8 || c->d_ffn % 2 || c->vocab < 2) return fail(FF_ERR_UNSUPPORTED, "d_model must be a multiple of 8");
+    return FF_OK;
+}
+
+Plan make_plan(const ff_config& c) {
+    Plan P;
+    size_t off = 0;
+    P.layers_tab = off; off = align256(off + sizeof(PLayer) * c.n_layers);
+    int qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, qd = c.n_q_heads * c.head_dim;
+    for (int l = 0; l < c.n_layers; l++) {
+        LayerPlan L;
+        L.g1 = off; off = align256(off + (size_t)c.d_model * 2);
+        L.g2 = off; off = align256(off + (size_t)c.d_model * 2);
+        L.qkv = plan_mat(off, qkv_rows, c.d_model, c.wdtype);
+        L.o = plan_mat(off, c.d_model, qd, c.wdtype);
+        L.gu = plan_mat(off, 2 * c.d_ffn, c.d_model, c.wdtype);
+        L.down = plan_mat(off, c.d_model, c.d_ffn, c.wdtype);
+        P.layers.push_back(L);
+    }
+    P.embed = off; off = align256(off + (size_t)c.vocab * c.d_model * 2);
+    P.gf = off; off = align256(off + (size_t)c.d_model * 2);
+    P.lm = plan_mat(off, c.vocab, c.d_model, c.quant_lm_head ? c.wdtype : W_BF16);
+    P.packed_bytes = off;
+
+    size_t s = 0;
+    size_t mb = c.max_batch;
+    auto take = [&](size_t bytes) { size_t o = s; s = align256(s + bytes); return o; };
+    P.x = take(mb * c.d_model * 4);
+    P.xn = take(mb * c.d_model * 4);
+    P.q = take(mb * qd * 4);
+    P.kvcur = take(mb * 2 * c.n_kv_heads * c.head_dim * 4);
+    P.attn_o = take(mb * qd * 4);
+    P.h = take(mb * c.d_ffn * 4);
+    size_t ymax = std::max((size_t)qkv_rows, (size_t)2 * c.d_ffn);
+    P.y = take(mb * ymax * 4);
+    P.part_m = take(mb * c.n_q_heads * kMaxSplits * 4);
+    P.part_l = take(mb * c.n_q_heads * kMaxSplits * 4);
+    P.part_o = take(mb * c.n_q_heads * kMaxSplits * c.head_dim * 4);
+    P.head_ctr = take(mb * c.n_kv_heads * 4);
+    P.bar_flags = take(4096 * 4);
+    P.status = take(256);
+    P.scratch_bytes = s;
+    return P;
+}
+
+}  // namespace
+
+struct ff_model {
+    ff_config cfg;
+    Plan plan;
+    uint8_t* packed;
+    uint8_t* scratch;
+    DevModel dev;
+    std::vector<PLayer> host_layers;
+    std::vector<char> layer_loaded;
+    bool head_loaded;
+    uint32_t bar_gen;
+    int n_cta;
+    size_t lds_bytes;
+};
+struct ff_kv {
+    ff_model* model;
+    DevKV dev;
+    int batch, max_ctx;
+};
+
+namespace {
+
+PMat to_pmat(const MatPlan& p, uint8_t* base) {
+    PMat m;
+    m.w = base + p.w;
+    m.s = (const f16_t*)(base + p.s);
+    m.z = (const f16_t*)(base + p.z);
+    m.n = p.n; m.k = p.k; m.wd = p.wd;
+    return m;
+}
+
+// copy canonical rows [n_rows] of `src` into packed rows starting at dst_row, with row mapping
+int repack(const MatPlan& dst, uint8_t* packed, int dst_row, int n_rows, const ff_matrix& a, const ff_matrix* b, int mode, int hd,
+           hipStream_t st) {
+    if (!a.w || (b && !b->w)) return fail(FF_ERR_ARG, "matrix pointer is null");
+    size_t rb = dst.wd == W_BF16 ? (size_t)dst.k * 2 : dst.wd == W_INT8 ? (size_t)dst.k : (size_t)dst.k / 2;
+    int grid = std::min(n_rows, 4096);
+    k_repack_rows<<<grid, kThreads, 0, st>>>(packed + dst.w + (size_t)dst_row * rb, (const uint8_t*)a.w, b ? (const uint8_t*)b->w : nullptr,
+                                             n_rows, rb, mode, hd);
+    if (dst.wd != W_BF16) {
+        if (!a.s || (b && !b->s)) return fail(FF_ERR_ARG, "scale pointer is null for a quantised matrix");
+        size_t sb = dst.wd == W_INT8 ? 2 : (size_t)(dst.k / 128) * 2;
+        k_repack_rows<<<grid, kThreads, 0, st>>>(packed + dst.s + (size_t)dst_row * sb, (const uint8_t*)a.s, b ? (const uint8_t*)b->s : nullptr,
+                                                 n_rows, sb, mode, hd);
+        if (dst.wd == W_INT4) {
+            if (!a.z || (b && !b->z)) return fail(FF_ERR_ARG, "zero-point pointer is null for an int4 matrix");
+            k_repack_rows<<<grid, kThreads, 0, st>>>(packed + dst.z + (size_t)dst_row * sb, (const uint8_t*)a.z,
+                                                     b ? (const uint8_t*)b->z : nullptr, n_rows, sb, mode, hd);
+        }
+    }
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+
+template <typename K>
+int set_lds(K kernel, size_t bytes) {
+    HIPCHK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    return FF_OK;
+}
+
+int check_step_args(ff_model* m, const int32_t* tokens, const int32_t* pos, ff_kv* kv, float* logits, int32_t batch) {
+    if (!m || !tokens || !pos || !kv || !logits) return fail(FF_ERR_ARG, "null argument to decode step");
+    if (kv->model != m) return fail(FF_ERR_ARG, "kv cache belongs to a different model");
+    if (batch < 1 || batch > m->cfg.max_batch || batch > kv->batch)
+        return fail(FF_ERR_ARG, "batch %d outside [1, min(max_batch %d, cache batch %d)]", batch, m->cfg.max_batch, kv->batch);
+    for (int l = 0; l < m->cfg.n_layers; l++)
+        if (!m->layer_loaded[l]) return fail(FF_ERR_ARG, "layer %d has not been loaded", l);
+    if (!m->head_loaded) return fail(FF_ERR_ARG, "embedding / LM head have not been loaded");
+    return FF_OK;
+}
+
+template <int WD, int B>
+int launch_fused(ff_model* m, const int32_t* tokens, const int32_t* pos, ff_kv* kv, float* logits, int batch, hipStream_t st) {
+    auto kern = fused_decode_kernel<WD, B>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        int rc = set_lds(kern, m->lds_bytes);
+        if (rc) return rc;
+        int occ = 0;
+        HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, kThreads, m->lds_bytes));
+        if (occ < 1) return fail(FF_ERR_UNSUPPORTED, "fused kernel does not fit on a compute unit");
+        attr_set = true;
+    }
+    kern<<<m->n_cta, kThreads, m->lds_bytes, st>>>(m->dev, kv->dev, tokens, pos, logits, batch, m->bar_gen);
+    HIPCHK(hipGetLastError());
+    m->bar_gen += (uint32_t)(kBarriersPerLayer * m->cfg.n_layers);
+    return FF_OK;
+}
+
+template <int WD, int B>
+int launch_gemv(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st) {
+    auto kern = op_gemv<WD, B>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        int rc = set_lds(kern, m->lds_bytes);
+        if (rc) return rc;
+        attr_set = true;
+    }
+    kern<<<m->n_cta, kThreads, m->lds_bytes, st>>>(W, in, in_stride, out, batch, epi);
+    return FF_OK;
+}
+template <int B>
+int gemv_any(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st) {
+    switch (W.wd) {
+        case W_BF16: return launch_gemv<W_BF16, B>(m, W, in, in_stride, out, batch, epi, st);
+        case W_INT8: return launch_gemv<W_INT8, B>(m, W, in, in_stride, out, batch, epi, st);
+        default: return launch_gemv<W_INT4, B>(m, W, in, in_stride, out, batch, epi, st);
+    }
+}
+int gemv_op(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st) {
+    if (batch == 1) return gemv_any<1>(m, W, in, in_stride, out, batch, epi, st);
+    if (batch == 2) return gemv_any<2>(m, W, in, in_stride, out, batch, epi, st);
+    return gemv_any<4>(m, W, in, in_stride, out, batch, epi, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ff_last_error(void) { return g_err.c_str(); }
+
+int ff_model_bytes(const ff_config* cfg, size_t* packed_bytes, size_t* scratch_bytes) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!packed_bytes || !scratch_bytes) return fail(FF_ERR_ARG, "null output pointer");
+    Plan P = make_plan(*cfg);
+    *packed_bytes = P.packed_bytes;
+    *scratch_bytes = P.scratch_bytes;
+    return FF_OK;
+}
+
+int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes, void* scratch_dev, size_t scratch_bytes,
+                    void* stream, ff_model** out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!packed_dev || !scratch_dev || !out) return fail(FF_ERR_ARG, "null argument");
+    if (((uintptr_t)packed_dev | (uintptr_t)scratch_dev) & 255) return fail(FF_ERR_NOMEM, "device buffers must be 256-byte aligned");
+    Plan P = make_plan(*cfg);
+    if (packed_bytes < P.packed_bytes) return fail(FF_ERR_NOMEM, "packed buffer too small: %zu < %zu", packed_bytes, P.packed_bytes);
+    if (scratch_bytes < P.scratch_bytes) return fail(FF_ERR_NOMEM, "scratch buffer too small: %zu < %zu", scratch_bytes, P.scratch_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIPCHK(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return fail(FF_ERR_UNSUPPORTED, "device is %s, kernels are built for gfx950", prop.gcnArchName);
+
+    ff_model* m = new (std::nothrow) ff_model();
+    if (!m) return fail(FF_ERR_NOMEM, "host allocation failed");
+    m->cfg = *cfg;
+    m->plan = P;
+    m->packed = (uint8_t*)packed_dev;
+    m->scratch = (uint8_t*)scratch_dev;
+    m->layer_loaded.assign(cfg->n_layers, 0);
+    m->head_loaded = false;
+    m->bar_gen = 0;
+    m->n_cta = prop.multiProcessorCount;
+    m->lds_bytes = kLdsActBytes + kLdsAuxBytes;
+    if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
+    if (m->n_cta > 4096) { delete m; return fail(FF_ERR_UNSUPPORTED, "too many compute units"); }
+
+    DevModel& D = m->dev;
+    D.L = cfg->n_layers; D.d = cfg->d_model; D.Hq = cfg->n_q_heads; D.Hkv = cfg->n_kv_heads; D.hd = cfg->head_dim;
+    D.F = cfg->d_ffn; D.V = cfg->vocab; D.eps = cfg->rms_eps;
+    D.layers = (const PLayer*)(m->packed + P.layers_tab);
+    D.embed = (const bf16_t*)(m->packed + P.embed);
+    D.gf = (const bf16_t*)(m->packed + P.gf);
+    D.lm = to_pmat(P.lm, m->packed);
+    uint8_t* s = m->scratch;
+    D.x = (float*)(s + P.x); D.xn = (float*)(s + P.xn); D.q = (float*)(s + P.q); D.kvcur = (float*)(s + P.kvcur);
+    D.attn_o = (float*)(s + P.attn_o); D.h = (float*)(s + P.h); D.y = (float*)(s + P.y);
+    D.part_m = (float*)(s + P.part_m); D.part_l = (float*)(s + P.part_l); D.part_o = (float*)(s + P.part_o);
+    D.head_ctr = (u32*)(s + P.head_ctr); D.bar_flags = (u32*)(s + P.bar_flags); D.status = (int*)(s + P.status);
+    for (int l = 0; l < cfg->n_layers; l++) {
+        const LayerPlan& L = P.layers[l];
+        PLayer pl;
+        pl.g1 = (const bf16_t*)(m->packed + L.g1);
+        pl.g2 = (const bf16_t*)(m->packed + L.g2);
+        pl.qkv = to_pmat(L.qkv, m->packed); pl.o = to_pmat(L.o, m->packed);
+        pl.gu = to_pmat(L.gu, m->packed); pl.down = to_pmat(L.down, m->packed);
+        m->host_layers.push_back(pl);
+    }
+    hipError_t e = hipMemcpyAsync(m->packed + P.layers_tab, m->host_layers.data(), sizeof(PLayer) * cfg->n_layers, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) {
+        k_fill_u32<<<256, 256, 0, st>>>((u32*)m->scratch, P.scratch_bytes / 4, 0u);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(st);   // host_layers is pageable: finish the copy before returning
+    if (e != hipSuccess) { delete m; return fail(FF_ERR_HIP, "model create: %s", hipGetErrorString(e)); }
+    *out = m;
+    return FF_OK;
+}
+
+int ff_model_load_layer(ff_model* m, int32_t layer, const ff_layer_weights* w, void* stream) {
+    if (!m || !w) return fail(FF_ERR_ARG, "null argument");
+    if (layer < 0 || layer >= m->cfg.n_layers) return fail(FF_ERR_ARG, "layer %d out of range", layer);
+    if (!w->attn_norm || !w->ffn_norm) return fail(FF_ERR_ARG, "norm gain pointer is null");
+    hipStream_t st = (hipStream_t)stream;
+    const ff_config& c = m->cfg;
+    const LayerPlan& L = m->plan.layers[layer];
+    HIPCHK(hipMemcpyAsync(m->packed + L.g1, w->attn_norm, (size_t)c.d_model * 2, hipMemcpyDeviceToDevice, st));
+    HIPCHK(hipMemcpyAsync(m->packed + L.g2, w->ffn_norm, (size_t)c.d_model * 2, hipMemcpyDeviceToDevice, st));
+    int qr = c.n_q_heads * c.head_dim, kr = c.n_kv_heads * c.head_dim, rc;
+    if ((rc = repack(L.qkv, m->packed, 0, qr, w->wq, nullptr, REPACK_ROPE, c.head_dim, st))) return rc;
+    if ((rc = repack(L.qkv, m->packed, qr, kr, w->wk, nullptr, REPACK_ROPE, c.head_dim, st))) return rc;
+    if ((rc = repack(L.qkv, m->packed, qr + kr, kr, w->wv, nullptr, REPACK_COPY, c.head_dim, st))) return rc;
+    if ((rc = repack(L.o, m->packed, 0, c.d_model, w->wo, nullptr, REPACK_COPY, c.head_dim, st))) return rc;
+    if ((rc = repack(L.gu, m->packed, 0, 2 * c.d_ffn, w->w_gate, &w->w_up, REPACK_INTERLEAVE, c.head_dim, st))) return rc;
+    if ((rc = repack(L.down, m->packed, 0, c.d_model, w->w_down, nullptr, REPACK_COPY, c.head_dim, st))) return rc;
+    m->layer_loaded[layer] = 1;
+    return FF_OK;
+}
+
+int ff_model_load_head(ff_model* m, const ff_head_weights* w, void* stream) {
+    if (!m || !w) return fail(FF_ERR_ARG, "null argument");
+    if (!w->embed || !w->final_norm) return fail(FF_ERR_ARG, "embedding / final norm pointer is null");
+    hipStream_t st = (hipStream_t)stream;
+    const ff_config& c = m->cfg;
+    HIPCHK(hipMemcpyAsync(m->packed + m->plan.embed, w->embed, (size_t)c.vocab * c.d_model * 2, hipMemcpyDeviceToDevice, st));
+    HIPCHK(hipMemcpyAsync(m->packed + m->plan.gf, w->final_norm, (size_t)c.d_model * 2, hipMemcpyDeviceToDevice, st));
+    int rc = repack(m->plan.lm, m->packed, 0, c.vocab, w->lm_head, nullptr, REPACK_COPY, c.head_dim, st);
+    if (rc) return rc;
+    m->head_loaded = true;
+    return FF_OK;
+}
+
+int ff_model_load(const ff_config* cfg, const ff_layer_weights* layers, const ff_head_weights* head, void* packed_dev,
+                  size_t packed_bytes, void* scratch_dev, size_t scratch_bytes, void* stream, ff_model** out) {
+    if (!layers || !head) return fail(FF_ERR_ARG, "null argument");
+    ff_model* m = nullptr;
+    int rc = ff_model_create(cfg, packed_dev, packed_bytes, scratch_dev, scratch_bytes, stream, &m);
+    if (rc) return rc;
+    for (int l = 0; l < cfg->n_layers && !rc; l++) rc = ff_model_load_layer(m, l, &layers[l], stream);
+    if (!rc) rc = ff_model_load_head(m, head, stream);
+    if (rc) { delete m; return rc; }
+    *out = m;
+    return FF_OK;
+}
+
+int ff_model_free(ff_model* m) {
+    delete m;
+    return FF_OK;
+}
+
+int ff_kv_bytes(const ff_model* m, int32_t batch, int32_t max_ctx, size_t* bytes) {
+    if (!m || !bytes) return fail(FF_ERR_ARG, "null argument");
+    if (batch < 1 || batch > m->cfg.max_batch) return fail(FF_ERR_ARG, "batch %d outside [1,%d]", batch, m->cfg.max_batch);
+    if (max_ctx < 1) return fail(FF_ERR_ARG, "max_ctx must be positive");
+    const ff_config& c = m->cfg;
+    size_t cache = align256((size_t)c.n_layers * batch * c.n_kv_heads * 2 * (size_t)max_ctx * c.head_dim * 2);
+    size_t rope = align256((size_t)max_ctx * (c.head_dim / 2) * sizeof(float2));
+    *bytes = cache + rope;
+    return FF_OK;
+}
+
+int ff_kv_alloc(ff_model* m, int32_t batch, int32_t max_ctx, void* kv_dev, size_t bytes, void* stream, ff_kv** out) {
+    size_t need = 0;
+    int rc = ff_kv_bytes(m, batch, max_ctx, &need);
+    if (rc) return rc;
+    if (!kv_dev || !out) return fail(FF_ERR_ARG, "null argument");
+    if ((uintptr_t)kv_dev & 255) return fail(FF_ERR_NOMEM, "kv buffer must be 256-byte aligned");
+    if (bytes < need) return fail(FF_ERR_NOMEM, "kv buffer too small: %zu < %zu", bytes, need);
+    const ff_config& c = m->cfg;
+    ff_kv* kv = new (std::nothrow) ff_kv();
+    if (!kv) return fail(FF_ERR_NOMEM, "host allocation failed");
+    kv->model = m; kv->batch = batch; kv->max_ctx = max_ctx;
+    size_t cache = align256((size_t)c.n_layers * batch * c.n_kv_heads * 2 * (size_t)max_ctx * c.head_dim * 2);
+    kv->dev.base = (bf16_t*)kv_dev;
+    kv->dev.rope = (const float2*)((uint8_t*)kv_dev + cache);
+    kv->dev.max_ctx = max_ctx; kv->dev.batch = batch;
+    int n = max_ctx * (c.head_dim / 2);
+    k_rope_table<<<(n + 255) / 256, 256, 0, (hipStream_t)stream>>>((float2*)kv->dev.rope, max_ctx, c.head_dim, (double)c.rope_theta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { delete kv; return fail(FF_ERR_HIP, "rope table: %s", hipGetErrorString(e)); }
+    *out = kv;
+    return FF_OK;
+}
+
+static int kv_copy(ff_kv* kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, void* k, void* v, void* stream, int dir) {
+    if (!kv || !k || !v) return fail(FF_ERR_ARG, "null argument");
+    const ff_config& c = kv->model->cfg;
+    if (layer < 0 || layer >= c.n_layers || seq < 0 || seq >= kv->batch) return fail(FF_ERR_ARG, "layer/sequence index out of range");
+    if (pos0 < 0 || n < 0 || (long)pos0 + n > kv->max_ctx) return fail(FF_ERR_RANGE, "rows [%d,%d) outside the cache (max_ctx %d)", pos0, pos0 + n, kv->max_ctx);
+    if (n == 0) return FF_OK;
+    size_t plane = (size_t)kv->max_ctx * c.head_dim;
+    bf16_t* base = kv->dev.base + (((size_t)layer * kv->batch + seq) * c.n_kv_heads) * 2 * plane;
+    size_t tot = (size_t)n * c.n_kv_heads * c.head_dim;
+    int grid = (int)std::min<size_t>((tot + 255) / 256, 2048);
+    k_kv_copy<<<grid, 256, 0, (hipStream_t)stream>>>(kv->dev, 0, c.n_kv_heads, c.head_dim, base, base + plane, 2 * plane, pos0, n,
+                                                     (bf16_t*)k, (bf16_t*)v, dir);
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+int ff_kv_fill(ff_kv* kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, const void* k_dev, const void* v_dev, void* stream) {
+    return kv_copy(kv, layer, seq, pos0, n, (void*)k_dev, (void*)v_dev, stream, 0);
+}
+int ff_kv_read(ff_kv* kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, void* k_dev, void* v_dev, void* stream) {
+    return kv_copy(kv, layer, seq, pos0, n, k_dev, v_dev, stream, 1);
+}
+int ff_kv_free(ff_kv* kv) {
+    delete kv;
+    return FF_OK;
+}
+
+int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch,
+                   void* stream) {
+    int rc = check_step_args(m, tokens_dev, positions_dev, kv, logits_dev, batch);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    int bt = batch == 1 ? 1 : batch == 2 ? 2 : 4;
+#define FF_FUSED(WD)                                                                                         \
+    (bt == 1   ? launch_fused<WD, 1>(m, tokens_dev, positions_dev, kv, logits_dev, batch, st)                 \
+     : bt == 2 ? launch_fused<WD, 2>(m, tokens_dev, positions_dev, kv, logits_dev, batch, st)                 \
+               : launch_fused<WD, 4>(m, tokens_dev, positions_dev, kv, logits_dev, batch, st))
+    switch (m->cfg.wdtype) {
+        case W_BF16: return FF_FUSED(W_BF16);
+        case W_INT8: return FF_FUSED(W_INT8);
+        default: return FF_FUSED(W_INT4);
+    }
+#undef FF_FUSED
+}
+
+int ff_decode_step_perop(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev,
+                         int32_t batch, void* stream) {
+    int rc = check_step_args(m, tokens_dev, positions_dev, kv, logits_dev, batch);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const DevModel& D = m->dev;
+    const ff_config& c = m->cfg;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if ((rc = set_lds(op_attn_partial, m->lds_bytes))) return rc;
+        attr_set = true;
+    }
+    const int qd = c.n_q_heads * c.head_dim, qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const int share = std::max(1, m->n_cta / (batch * c.n_kv_heads));
+    const int ew_grid = 64;
+    op_embed<<<ew_grid, kThreads, 0, st>>>(D, kv->dev, tokens_dev, positions_dev, batch);
+    for (int l = 0; l < c.n_layers; l++) {
+        const PLayer& L = m->host_layers[l];
+        op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, L.g1, D.xn, c.d_model, c.rms_eps);
+        if ((rc = gemv_op(m, L.qkv, D.xn, c.d_model, D.y, batch, EPI_STORE, st))) return rc;
+        op_rope_append<<<ew_grid, kThreads, 0, st>>>(D, kv->dev, tokens_dev, positions_dev, batch, l);
+        op_attn_partial<<<m->n_cta, kThreads, m->lds_bytes, st>>>(D, kv->dev, tokens_dev, positions_dev, batch, l);
+        op_attn_merge<<<batch * c.n_kv_heads, kThreads, 0, st>>>(D, kv->dev, tokens_dev, positions_dev, batch, share);
+        if ((rc = gemv_op(m, L.o, D.attn_o, qd, D.x, batch, EPI_RESIDUAL, st))) return rc;
+        op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, L.g2, D.xn, c.d_model, c.rms_eps);
+        if ((rc = gemv_op(m, L.gu, D.xn, c.d_model, D.y, batch, EPI_STORE, st))) return rc;
+        op_swiglu<<<ew_grid, kThreads, 0, st>>>(D, batch);
+        if ((rc = gemv_op(m, L.down, D.h, c.d_ffn, D.x, batch, EPI_RESIDUAL, st))) return rc;
+    }
+    op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, D.gf, D.xn, c.d_model, c.rms_eps);
+    if ((rc = gemv_op(m, D.lm, D.xn, c.d_model, logits_dev, batch, EPI_STORE, st))) return rc;
+    (void)qkv_rows;
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+
+int ff_status(ff_model* m, void* stream) {
+    if (!m) return fail(FF_ERR_ARG, "null argument");
+    hipStream_t st = (hipStream_t)stream;
+    HIPCHK(hipStreamSynchronize(st));
+    int s = 0;
+    HIPCHK(hipMemcpy(&s, m->dev.status, sizeof(int), hipMemcpyDeviceToHost));
+    if (s != 0) {
+        HIPCHK(hipMemset(m->dev.status, 0, sizeof(int)));
+        if (s == kStatusRange) return fail(FF_ERR_RANGE, "a decode step saw a position >= max_ctx or a token id >= vocab and was skipped");
+        if (s == kStatusTimeout) return fail(FF_ERR_TIMEOUT, "grid barrier timed out: workgroups were not co-resident");
+        return fail(FF_ERR_HIP, "unknown device status %d", s);
+    }
+    return FF_OK;
+}
+
+int ff_debug_dequant(const ff_model* m, int32_t layer, int32_t which, float* out_dev, void* stream) {
+    if (!m || !out_dev) return fail(FF_ERR_ARG, "null argument");
+    const ff_config& c = m->cfg;
+    if (which != FF_MAT_LMHEAD && (layer < 0 || layer >= c.n_layers)) return fail(FF_ERR_ARG, "layer %d out of range", layer);
+    int qr = c.n_q_heads * c.head_dim, kr = c.n_kv_heads * c.head_dim;
+    PMat W;
+    int n_can, map = 0, parity = 0, row_off = 0;
+    const PLayer* L = which == FF_MAT_LMHEAD ? nullptr : &m->host_layers[layer];
+    switch (which) {
+        case FF_MAT_WQ: W = L->qkv; n_can = qr; map = 1; break;
+        case FF_MAT_WK: W = L->qkv; n_can = kr; map = 1; row_off = qr; break;
+        case FF_MAT_WV: W = L->qkv; n_can = kr; row_off = qr + kr; break;
+        case FF_MAT_WO: W = L->o; n_can = c.d_model; break;
+        case FF_MAT_WGATE: W = L->gu; n_can = c.d_ffn; map = 2; parity = 0; break;
+        case FF_MAT_WUP: W = L->gu; n_can = c.d_ffn; map = 2; parity = 1; break;
+        case FF_MAT_WDOWN: W = L->down; n_can = c.d_model; break;
+        case FF_MAT_LMHEAD: W = m->dev.lm; n_can = c.vocab; break;
+        default: return fail(FF_ERR_ARG, "unknown matrix id %d", which);
+    }
+    k_dequant<<<2048, 256, 0, (hipStream_t)stream>>>(W, out_dev, n_can, map, parity, row_off, c.head_dim);
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+
+int ff_fused_schedule(const ff_model* m, int32_t* barriers_per_step, int32_t* n_workgroups, int32_t* threads_per_workgroup) {
+    if (!m) return fail(FF_ERR_ARG, "null argument");
+    if (barriers_per_step) *barriers_per_step = kBarriersPerLayer * m->cfg.n_layers;
+    if (n_workgroups) *n_workgroups = m->n_cta;
+    if (threads_per_workgroup) *threads_per_workgroup = kThreads;
+    return FF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+"""GPU parity: the HIP decode step (fused whole-model kernel and per-op baseline, both through
+the C ABI) against the CPU oracle, element by element, on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_22758_amd import synth
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, positions_offset=None):
+    from paper_2505_22758_amd import binding
+    from oracle import oracle
+    max_ctx = T0 + steps + 3
+    M, okv = helpers.oracle_side(shape, seed, wdtype, batch, T0, max_ctx)
+    dec, caches = helpers.hip_side(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2)
+    toks = synth.make_tokens(shape, seed, steps, batch)
+    logits_f = torch.zeros(batch, shape.vocab, dtype=torch.float32, device="cuda:0")
+    logits_p = torch.zeros_like(logits_f)
+    worst = {"fused": [0.0, 0.0], "perop": [0.0, 0.0]}
+    agree = {"fused": [], "perop": []}
+    for s in range(steps):
+        pos = np.full(batch, T0 + s, dtype=np.int32)
+        ref = M.decode_step(toks[s].numpy(), pos, okv)
+        tok_d = toks[s].to("cuda:0")
+        pos_d = torch.from_numpy(pos).to("cuda:0")
+        binding.ff_decode_step(dec.model, tok_d, pos_d, caches[0][0], logits_f, batch)
+        binding.ff_decode_step_perop(dec.model, tok_d, pos_d, caches[1][0], logits_p, batch)
+        binding.ff_status(dec.model)
+        for name, lg in (("fused", logits_f), ("perop", logits_p)):
+            ma, rl, same = helpers.compare_logits(lg.cpu().numpy(), ref)
+            worst[name][0] = max(worst[name][0], ma)
+            worst[name][1] = max(worst[name][1], rl)
+            agree[name].extend(same.tolist())
+    print(f"\n[{shape.name} wd={wdtype} B={batch} T0={T0} steps={steps}] worst (max_abs, rel_l2): {worst}")
+    for name in ("fused", "perop"):
+        assert worst[name][0] <= helpers.MAX_ABS_TOL, (name, worst)
+        assert worst[name][1] <= helpers.REL_L2_TOL, (name, worst)
+        assert np.mean(agree[name]) >= helpers.ARGMAX_MIN_AGREE, (name, np.mean(agree[name]))
+    if check_kv:
+        # rows appended by the kernel: bf16 bits equal to the oracle's except for rare 1-ulp flips
+        # (the two sides round values that differ by summation order)
+        for ci in range(2):
+            mism = tot = 0
+            for l in range(shape.n_layers):
+                for b in range(batch):
+                    k = torch.empty(steps, shape.n_kv_heads, shape.head_dim, dtype=torch.bfloat16, device="cuda:0")
+                    v = torch.empty_like(k)
+                    binding.ff_kv_read(caches[ci][0], l, b, T0, k, v)
+                    for kv_i, t in ((0, k), (1, v)):
+                        got = t.cpu().view(torch.int16).numpy().view(np.uint16)
+                        want = okv[l, b, kv_i, T0:T0 + steps]
+                        gv, wv = oracle.bf16_bits_to_f64(got), oracle.bf16_bits_to_f64(want)
+                        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(wv), 1e-30))) - 7)
+                        assert np.all(np.abs(gv - wv) <= np.maximum(ulp, 1e-5)), "appended cache row is off by more than one bf16 step"
+                        mism += int((got != want).sum())
+                        tot += got.size
+            assert mism <= max(2, tot // 200), (mism, tot)
+    dec.close()
+    return worst
+
+
+def test_generators_are_bit_identical_on_cpu_and_gpu():
+    a = synth.normal_bf16(11, "w", (300, 512), 0.02, "cpu")
+    b = synth.normal_bf16(11, "w", (300, 512), 0.02, "cuda:0").cpu()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    for wd in (synth.WDTYPE_INT8, synth.WDTYPE_INT4):
+        ma = synth.make_matrix(synth.TINY, 3, "m", "wq", wd, "cpu")
+        mb = synth.make_matrix(synth.TINY, 3, "m", "wq", wd, "cuda:0")
+        for key in ma:
+            assert torch.equal(ma[key].view(torch.uint8) if ma[key].dtype == torch.int8 else ma[key].view(torch.int16) if ma[key].dtype == torch.float16 else ma[key],
+                               (mb[key].cpu().view(torch.uint8) if mb[key].dtype == torch.int8 else mb[key].cpu().view(torch.int16) if mb[key].dtype == torch.float16 else mb[key].cpu()))
+
+
+def test_tiny_bf16_batch1_teacher_forced_16_steps():
+    """The small benchmark configuration: 4 layers, d 512, 8q/2kv heads, ctx 128, 16 steps."""
+    _run_teacher_forced(synth.TINY, 0x2505, synth.WDTYPE_BF16, batch=1, T0=128, steps=16)
+
+
+def test_tiny_bf16_empty_cache_and_ragged_lengths():
+    # T0 = 0: first step attends only to itself; lengths that are not multiples of a wave's rows
+    _run_teacher_forced(synth.TINY, 7, synth.WDTYPE_BF16, batch=1, T0=0, steps=5)
+    _run_teacher_forced(synth.TINY, 8, synth.WDTYPE_BF16, batch=1, T0=77, steps=3)
+    _run_teacher_forced(synth.TINY, 9, synth.WDTYPE_BF16, batch=1, T0=1031, steps=2)
+
+
+def test_tiny_bf16_batches_2_3_4():
+    for b in (2, 3, 4):
+        _run_teacher_forced(synth.TINY, 20 + b, synth.WDTYPE_BF16, batch=b, T0=40, steps=3)
