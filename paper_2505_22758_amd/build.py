@@ -6,11 +6,11 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflashformer.so")
-SOURCES = ["flashformer.hip"]
+SOURCES = ["flashformer.hip", "ff_fused_bf16.hip", "ff_fused_int8.hip", "ff_fused_int4.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
+         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"] + os.environ.get("FF_EXTRA_FLAGS", "").split()
 
 
 def sources():
@@ -26,15 +26,29 @@ def is_stale() -> bool:
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
+    """Compile every translation unit (in parallel) and link libflashformer.so."""
     if not force and not is_stale():
         return LIB
-    cmd = [HIPCC] + FLAGS + ["-o", LIB] + sources()
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    msgs = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l)
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    procs = []
+    for src in sources():
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        procs.append((src, obj, subprocess.Popen([HIPCC] + compile_flags + ["-c", "-o", obj, src],
+                                                 stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    objs = []
+    for src, obj, p in procs:
+        out, _ = p.communicate()
+        msgs = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n" + msgs)
+        if verbose and msgs.strip():
+            print(msgs)
+        objs.append(obj)
+    res = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + msgs)
-    if verbose and msgs.strip():
-        print(msgs)
+        raise RuntimeError("link failed:\n" + res.stdout + res.stderr)
     return LIB
 
 

@@ -10,6 +10,8 @@ typedef unsigned int u32;
 typedef unsigned long long u64;
 typedef __attribute__((ext_vector_type(4))) u32 u32x4;
 typedef __attribute__((ext_vector_type(2))) u32 u32x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef uint16_t bf16_t;   // raw bits
 typedef uint16_t f16_t;    // raw bits
 
@@ -20,7 +22,8 @@ constexpr int kMaxSplits = 64;           // max KV splits per (sequence, kv head
 constexpr int kMinSplitLen = 64;         // do not split the cache finer than this many rows
 constexpr int kLdsActBytes = 128 * 1024; // LDS region holding the staged activation vector(s)
 constexpr int kLdsAuxBytes = 24 * 1024;  // partial sums, reduction scratch
-constexpr int kSpinLimit = 1 << 22;
+constexpr int kSpinLimit = 1 << 16;
+
 
 enum { W_BF16 = 0, W_INT8 = 1, W_INT4 = 2 };
 
@@ -52,6 +55,7 @@ struct DevModel {
     const bf16_t* gf;
     PMat lm;
     // exchange buffers (device scratch)
+    // plain exchange buffers (per-operation kernels)
     float* x;        // residual stream            [B][d]
     float* xn;       // normed activation (per-op)  [B][d]
     float* q;        // rotated queries            [B][Hq*hd]
@@ -62,9 +66,11 @@ struct DevModel {
     float* part_m;   // split partials             [B][Hq][kMaxSplits]
     float* part_l;
     float* part_o;   //                            [B][Hq][kMaxSplits][hd]
-    u32* head_ctr;   // arrivals per (b, kv head)  [B][Hkv]
-    u32* bar_flags;  // one arrival flag per workgroup
+    // tagged exchange buffers of the fused kernel: (fp32 bits, tag) pairs, same shapes as above
+    u32x2* tx;  u32x2* tx2;  u32x2* tdelta;  u32x2* tq;  u32x2* tkvcur;  u32x2* tattn_o;  u32x2* th;
+    u32x2* tpart_m;  u32x2* tpart_l;  u32x2* tpart_o;
     int* status;
+    u64* dbg;        // optional timeline buffer (null unless enabled through the debug entry point)
 };
 
 struct DevKV {
@@ -76,39 +82,68 @@ struct DevKV {
     }
 };
 
+// Pointers that reach a kernel inside structures read from memory lose their address space; a
+// generic-address (FLAT) access counts against the LDS counter as well as the vector-memory one and
+// forces full waits.  Everything dereferenced in device code goes through these casts.
+#define FF_GLOBAL __attribute__((address_space(1)))
+template <class T> __device__ __forceinline__ const FF_GLOBAL T* as_global(const T* p) { return (const FF_GLOBAL T*)p; }
+template <class T> __device__ __forceinline__ FF_GLOBAL T* as_global(T* p) { return (FF_GLOBAL T*)p; }
+
 // ---------------------------------------------------------------- coherent exchange accesses
-// Activations exchanged between workgroups inside one launch are read and written with
-// agent-scope relaxed atomics: these bypass the per-XCD L2's non-coherent lines, so no cache
-// write-back / invalidate is needed at a grid barrier.
-__device__ __forceinline__ float xld(const float* p) {
-    return __uint_as_float(__hip_atomic_load((const u32*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-}
-__device__ __forceinline__ float2 xld2(const float* p) {
-    u64 v = __hip_atomic_load((const u64*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_float2(__uint_as_float((u32)v), __uint_as_float((u32)(v >> 32)));
-}
+// Activations exchanged between workgroups inside one launch must bypass the per-XCD L2's
+// non-coherent lines, so that no cache write-back / invalidate is needed at a grid barrier
+// (an agent-scope acquire or release fence costs several microseconds on this chip).
+//   stores: agent-scope relaxed atomic stores (write through to the coherence point; the issuing
+//           wave waits for their acknowledgement with s_waitcnt before it arrives at a barrier)
+//   loads : raw buffer loads with the sc1 cache-policy bit -- the same instruction an agent-scope
+//           atomic load compiles to, but an ordinary load to the compiler, so many of them can be
+//           in flight at once (a chain of dependent ~1 us round trips is what must be avoided).
+// Loads take a wave-uniform base pointer plus a per-lane element index (buffers < 4 GiB).
 __device__ __forceinline__ void xst(float* p, float v) {
-    __hip_atomic_store((u32*)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(as_global((u32*)p), __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void xst2(float* p, float a, float b) {
     u64 v = (u64)__float_as_uint(a) | ((u64)__float_as_uint(b) << 32);
-    __hip_atomic_store((u64*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(as_global((u64*)p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ u32 xld_u32(const u32* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void xst_u32(u32* p, u32 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ u32 xld_u32(const u32* p) { return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void xst_u32(u32* p, u32 v) { __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ u32 xadd_u32(u32* p, u32 v) { return __hip_atomic_fetch_add(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// Plain (launch-boundary ordered) accessors with the same signatures, for the per-op kernels.
-struct PlainIO {
-    static __device__ __forceinline__ float ld(const float* p) { return *p; }
-    static __device__ __forceinline__ float2 ld2(const float* p) { return *(const float2*)p; }
-    static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
-    static __device__ __forceinline__ void st2(float* p, float a, float b) { *(float2*)p = make_float2(a, b); }
+constexpr int kAuxSc1 = 16;   // buffer-instruction cache policy: sc1 (agent-coherent)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, -1, 0x00020000);
+}
+
+struct PlainIO {   // launch-boundary ordered accesses (per-operation kernels)
+    static __device__ __forceinline__ float ld(const float* base, int i) { return as_global(base)[i]; }
+    static __device__ __forceinline__ float2 ld2(const float* base, int i) {
+        f32x2 v = *as_global((const f32x2*)(base + i));
+        return make_float2(v.x, v.y);
+    }
+    static __device__ __forceinline__ float4 ld4(const float* base, int i) {
+        f32x4 v = *as_global((const f32x4*)(base + i));
+        return make_float4(v.x, v.y, v.z, v.w);
+    }
+    static __device__ __forceinline__ void st(float* p, float v) { *as_global(p) = v; }
+    static __device__ __forceinline__ void st2(float* p, float a, float b) { *as_global((f32x2*)p) = f32x2{a, b}; }
+    static __device__ __forceinline__ void st4(float* p, float4 v) { *as_global((f32x4*)p) = f32x4{v.x, v.y, v.z, v.w}; }
 };
-struct CoherentIO {
-    static __device__ __forceinline__ float ld(const float* p) { return xld(p); }
-    static __device__ __forceinline__ float2 ld2(const float* p) { return xld2(p); }
+struct CoherentIO {   // accesses that are coherent across workgroups inside one launch
+    static __device__ __forceinline__ float ld(const float* base, int i) {
+        return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(base), i * 4, 0, kAuxSc1));
+    }
+    static __device__ __forceinline__ float2 ld2(const float* base, int i) {
+        u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(make_rsrc(base), i * 4, 0, kAuxSc1);
+        return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+    }
+    static __device__ __forceinline__ float4 ld4(const float* base, int i) {
+        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc(base), i * 4, 0, kAuxSc1);
+        return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+    }
     static __device__ __forceinline__ void st(float* p, float v) { xst(p, v); }
     static __device__ __forceinline__ void st2(float* p, float a, float b) { xst2(p, a, b); }
+    static __device__ __forceinline__ void st4(float* p, float4 v) { xst2(p, v.x, v.y); xst2(p + 2, v.z, v.w); }
 };
 
 // ---------------------------------------------------------------- scalar helpers
@@ -131,6 +166,6 @@ __device__ __forceinline__ float wave_sum(float v) {
     for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
 }
-__device__ __forceinline__ u32x4 ldg_stream(const void* p) { return __builtin_nontemporal_load((const u32x4*)p); }
+__device__ __forceinline__ u32x4 ldg_stream(const void* p) { return __builtin_nontemporal_load(as_global((const u32x4*)p)); }
 
 }  // namespace ff

@@ -1,0 +1,221 @@
+// The fused whole-model decode kernel (one persistent launch per decode step).
+#pragma once
+#include "ff_kernels.h"
+
+namespace ff {
+
+// Workgroup shape of the fused kernel: one wave per SIMD, so that each wave may use the whole
+// 512-entry register file of its SIMD for its tile ring.
+constexpr int kFusedWaves = 4;
+constexpr int kFusedThreads = kFusedWaves * 64;
+
+// Workgroup barrier that orders LDS traffic only: vector-memory loads stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+__device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
+
+// ---------------------------------------------------------------- the fused whole-model kernel
+// One launch = one decode step for all layers (paper abstract, Section 3).  Phases per layer:
+// [RMSNorm + QKV projection + RoPE + cache append] [split-KV attention + merge] [output projection]
+// [residual + RMSNorm + gate/up projection + SwiGLU] [down projection]; then residual + final norm
+// + LM head.  The residual additions are folded into the staging of the next normalised
+// projection, so no projection epilogue reads global memory.
+//
+// Synchronisation between phases is by dataflow on tagged values (see tagged_t): a phase starts in
+// a workgroup as soon as the vector it consumes carries the producing phase's tag.  The paper's
+// kernel separates the same phases with an atomic device-wide barrier plus fences (Section 3.1);
+// on this chip a barrier round trip, the wait for store acknowledgements before it and the input
+// load after it are three dependent trips through a memory pipeline that is full of weight
+// traffic, so the dependency is carried by the data instead.
+//
+// Memory pipeline (the paper's cross-layer overlap, Section 3.1, re-designed for CDNA4): each of
+// wave owns a ring of kDepth register stages of 16-byte non-temporal weight loads.  When a phase
+// ends, the first kDepth stages of the NEXT weight matrix are issued at once and the loads of the
+// next input vector right behind them, speculatively: by the time they return (results come back
+// in issue order) the other workgroups have usually published their part, so HBM keeps streaming
+// while the dependency resolves.
+//
+// The projections of all phases run through ONE instance of the streaming loop; what differs per
+// phase (input, epilogue) is selected at run time once per row pair.
+enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3, PH_LM = 4 };
+enum { TAG_QKV = 0, TAG_ATT = 1, TAG_O = 2, TAG_GU = 3, TAG_DOWN = 4 };
+
+// Optional timeline of workgroup 0 (8 slots per phase; 100 MHz wall clock), for profiling only.
+enum { EV_SYNCED = 0, EV_RUN_DONE = 1, EV_PF_ISSUED = 2, EV_H_START = 3, EV_H_LOADED = 4, EV_H_STAGED = 5, EV_ATT_START = 6, EV_ATT_END = 7,
+       EV_H_POLLED = 8, EV_H_FULL = 9, kEvSlots = 12 };
+__device__ __forceinline__ void dbg_event(const DevModel& M, int ph, int ev, int lane) {
+    if (M.dbg && blockIdx.x == 0 && lane == 0) as_global(M.dbg)[ph * kEvSlots + ev] = wall_clock64();
+}
+
+struct EpiFused {
+    int kind; u32 tag;
+    const DevModel& M; const DevKV& KV; const int* pos; int layer; const float2* rope; float* logits;
+    __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
+        switch (kind) {
+            case PH_QKV: EpiQKVTagged{M, KV, pos, layer, rope, tag}(pair, b, v0, v1); break;
+            case PH_GU: EpiSwiGLUTagged{M.th, M.F, tag}(pair, b, v0, v1); break;
+            case PH_LM: EpiStore{logits, M.V}(pair, b, v0, v1); break;
+            default: EpiDeltaTagged{M.tdelta, M.d, tag}(pair, b, v0, v1); break;
+        }
+    }
+};
+
+// Everything that distinguishes one projection phase from another.
+struct PhaseDesc {
+    int kind, layer;
+    TSrc src;
+    PMat W, Wn;        // this projection and the one after it
+    bool has_next;
+    u32 out_tag;
+};
+struct PhaseState {   // the residual stream's ping-pong buffers (both roles track them identically)
+    tagged_t* xcur; tagged_t* xnext;
+};
+__device__ __forceinline__ u32 tag_of(u32 tag_base, int l, int k) { return tag_base + 1u + (u32)(l * kTagsPerLayer + k); }
+
+__device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* tokens, u32 tb, int ph, int lm_in_kernel, const PhaseState& X) {
+    PhaseDesc D;
+    const int l = ph >> 2;
+    D.layer = l;
+    D.kind = ph == 4 * M.L ? PH_LM : (ph & 3);
+    D.has_next = true;
+    D.out_tag = 0;
+    TSrc& src = D.src;
+    if (D.kind == PH_QKV) {
+        if (l == 0) { src.embed = M.embed; src.tokens = tokens; src.tag = 0; }   // embedding rows are synthesised with tag 0
+        else {
+            src.base = X.xcur; src.stride = M.d; src.tag = tag_of(tb, l - 1, TAG_GU);
+            src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, l - 1, TAG_DOWN);
+        }
+        src.wb = X.xnext; src.wb_stride = M.d; src.wb_tag = tag_of(tb, l, TAG_QKV);
+        src.gain = M.layers[l].g1; src.eps = M.eps;
+        D.out_tag = tag_of(tb, l, TAG_QKV);
+        D.W = M.layers[l].qkv; D.Wn = M.layers[l].o;
+    } else if (D.kind == PH_O) {
+        src.base = M.tattn_o; src.stride = (size_t)M.Hq * M.hd; src.tag = tag_of(tb, l, TAG_ATT);
+        D.out_tag = tag_of(tb, l, TAG_O);
+        D.W = M.layers[l].o; D.Wn = M.layers[l].gu;
+    } else if (D.kind == PH_GU) {
+        src.base = X.xcur; src.stride = M.d; src.tag = tag_of(tb, l, TAG_QKV);
+        src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, l, TAG_O);
+        src.wb = X.xnext; src.wb_stride = M.d; src.wb_tag = tag_of(tb, l, TAG_GU);
+        src.gain = M.layers[l].g2; src.eps = M.eps;
+        D.out_tag = tag_of(tb, l, TAG_GU);
+        D.W = M.layers[l].gu; D.Wn = M.layers[l].down;
+    } else if (D.kind == PH_DOWN) {
+        src.base = M.th; src.stride = M.F; src.tag = tag_of(tb, l, TAG_GU);
+        D.out_tag = tag_of(tb, l, TAG_DOWN);
+        D.W = M.layers[l].down;
+        if (l + 1 < M.L) D.Wn = M.layers[l + 1].qkv;
+        else if (lm_in_kernel) D.Wn = M.lm;
+        else { D.Wn = D.W; D.has_next = false; }
+    } else {
+        src.base = X.xcur; src.stride = M.d; src.tag = tag_of(tb, M.L - 1, TAG_GU);
+        src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, M.L - 1, TAG_DOWN);
+        src.gain = M.gf; src.eps = M.eps;
+        D.W = M.lm; D.Wn = M.lm; D.has_next = false;
+    }
+    return D;
+}
+__device__ __forceinline__ void phase_advance(const PhaseDesc& D, PhaseState& X) {
+    if (D.kind == PH_QKV || D.kind == PH_GU) { tagged_t* t = X.xcur; X.xcur = X.xnext; X.xnext = t; }
+}
+
+template <int WD, int B>
+__global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
+                                                                     const int* __restrict__ pos, float* __restrict__ logits,
+                                                                     int batch, u32 tag_base, int lm_in_kernel) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    if (!inputs_ok(M, KV, tokens, pos, batch)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(M.status, kStatusRange);
+        return;
+    }
+    constexpr int EPU = WTraits<WD>::EPU;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float4* xs = (float4*)lds;
+    float2* rope_lds = (float2*)(lds + kLdsActBytes + kLdsAuxBytes);   // [batch][hd/2]
+    for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kFusedThreads) {
+        int b = i / (M.hd / 2), f = i % (M.hd / 2);
+        rope_lds[i] = KV.rope[(size_t)pos[b] * (M.hd / 2) + f];
+    }
+    // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
+    // weight type differs from the layers' (then the host launches it separately).
+    const int n_phases = 4 * M.L + (lm_in_kernel ? 1 : 0);
+    PhaseState X{M.tx, M.tx2};
+
+    const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = gridDim.x * kFusedWaves;
+    float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
+    float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64;   // behind the RoPE rows
+    Stage<WD> ring[kDepth];
+    prefetch_stream(Stream<WD, B>::make(M.layers[0].qkv, 0, gwave, n_gwaves), ring, lane);
+    for (int ph = 0; ph < n_phases; ph++) {
+        const PhaseDesc D = phase_desc(M, tokens, tag_base, ph, lm_in_kernel, X);
+        EpiFused epi{D.kind, D.out_tag, M, KV, pos, D.layer, rope_lds, logits};
+        Stream<WD, B> S = Stream<WD, B>::make(D.W, 0, gwave, n_gwaves);
+        const int nseg = S.nseg;
+        for (int seg = 0; seg < nseg; seg++) {
+            if (seg > 0) S = Stream<WD, B>::make(D.W, seg, gwave, n_gwaves);
+            if (wave == 0) dbg_event(M, ph, EV_H_START, lane);
+            TSrc src = D.src;
+            if (seg > 0) src.wb = nullptr;
+            bool ok;
+            if (src.add) ok = stage_tagged<EPU, true, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x);
+            else ok = stage_tagged<EPU, false, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x);
+            if (!ok) {
+                if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);
+                return;
+            }
+            if (wave == 0) dbg_event(M, ph, EV_SYNCED, lane);
+            gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
+            if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
+            if (seg + 1 < nseg) prefetch_stream(Stream<WD, B>::make(D.W, seg + 1, gwave, n_gwaves), ring, lane);
+            else if (D.has_next) prefetch_stream(Stream<WD, B>::make(D.Wn, 0, gwave, n_gwaves), ring, lane);
+            if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);
+        }
+        phase_advance(D, X);
+        if (D.kind == PH_QKV) {
+            // split-KV attention + merge; the ring keeps the output projection's tiles meanwhile
+            __syncthreads();   // every wave has finished reading the staged input: LDS is free
+            if (wave == 0) dbg_event(M, ph, EV_ATT_START, lane);
+            const bool ok = attention_phase_tagged<kFusedWaves>(M, KV, pos, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
+                                                                tag_of(tag_base, D.layer, TAG_ATT));
+            if (wave == 0) dbg_event(M, ph, EV_ATT_END, lane);
+            if (!ok) return;
+        }
+    }
+}
+
+// Host-side launcher of one weight-type family; defined once per weight type in its own
+// translation unit so that the instances compile in parallel.
+struct FusedLaunch {
+    DevModel M; DevKV KV; const int* tokens; const int* pos; float* logits;
+    int batch; u32 tag_base; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream;
+};
+template <int WD, int B>
+inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what) {
+    auto kern = fused_decode_kernel<WD, B>;
+    static bool ready = false;
+    if (!ready) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
+        if (e != hipSuccess) { *what = "hipFuncSetAttribute"; return e; }
+        int occ = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, kFusedThreads, a.lds_bytes);
+        if (e != hipSuccess) { *what = "hipOccupancyMaxActiveBlocksPerMultiprocessor"; return e; }
+        if (occ < 1) { *what = "fused kernel does not fit on a compute unit"; return hipErrorLaunchOutOfResources; }
+        ready = true;
+    }
+    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.tag_base, a.lm_in_kernel);
+    *what = "fused kernel launch";
+    return hipGetLastError();
+}
+template <int WD>
+inline hipError_t launch_fused_family(const FusedLaunch& a, const char** what) {
+    if (a.batch == 1) return launch_fused_instance<WD, 1>(a, what);
+    if (a.batch == 2) return launch_fused_instance<WD, 2>(a, what);
+    return launch_fused_instance<WD, 4>(a, what);
+}
+hipError_t launch_fused_bf16(const FusedLaunch& a, const char** what);
+hipError_t launch_fused_int8(const FusedLaunch& a, const char** what);
+hipError_t launch_fused_int4(const FusedLaunch& a, const char** what);
+
+}  // namespace ff

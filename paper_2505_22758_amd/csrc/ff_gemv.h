@@ -1,0 +1,347 @@
+// Weight-streaming GEMV engine: activation staging into LDS, a register ring of weight tiles kept
+// in flight ahead of the FMAs, and the per-format dot products.  Used by the fused whole-model
+// kernel (with tiles of the NEXT phase already in flight while a grid barrier is crossed) and by
+// the per-operation baseline kernels.
+#pragma once
+#include "ff_device.h"
+
+namespace ff {
+
+template <int WD> struct WTraits;
+template <> struct WTraits<W_BF16> { static constexpr int EPU = 8; };   // elements per 16-byte unit
+template <> struct WTraits<W_INT8> { static constexpr int EPU = 16; };
+template <> struct WTraits<W_INT4> { static constexpr int EPU = 32; };
+
+constexpr int kUnr = 4;                    // 16-byte units per row and pipeline stage (per lane)
+constexpr int kDepth = 4;                  // pipeline stages (register ring slots) per wave
+constexpr int kChunkUnits = 64 * kUnr;     // units of one row covered by one stage of one wave
+constexpr int kStageLoads = 2 * kUnr;      // weight loads a wave issues per stage
+
+// ---------------------------------------------------------------- reductions
+// Sum over the 64 lanes with DPP row operations; the result is wave-uniform.
+__device__ __forceinline__ float wave_sum_uniform(float v) {
+    int x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, true));   // row_half_mirror
+    x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, true));   // row_mirror
+    x = __float_as_int(v);
+    float r0 = __int_as_float(__builtin_amdgcn_readlane(x, 0));
+    float r1 = __int_as_float(__builtin_amdgcn_readlane(x, 16));
+    float r2 = __int_as_float(__builtin_amdgcn_readlane(x, 32));
+    float r3 = __int_as_float(__builtin_amdgcn_readlane(x, 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+// ---------------------------------------------------------------- staging
+// Where a GEMV phase takes its input vector(s) from, and what is folded into the staging.
+struct ActSrc {
+    const float* base = nullptr;    // fp32 exchange buffer [B][stride] ...
+    size_t stride = 0;
+    const bf16_t* embed = nullptr;  // ... or (tokens != null) rows of the bf16 embedding table
+    const int* tokens = nullptr;
+    const float* add = nullptr;     // optional second fp32 vector added element-wise (residual + sublayer output)
+    size_t add_stride = 0;
+    float* wb = nullptr;            // optional: the summed, un-normalised vector is written back here,
+    size_t wb_stride = 0;           //   each workgroup storing an interleaved slice
+    const bf16_t* gain = nullptr;   // non-null: RMSNorm with this gain is applied while staging
+    float eps = 0.f;
+};
+
+// Stage elements [k0, k0 + nunits*EPU) of every batch row into LDS, quad-planar so that a wave's
+// 64 lanes read 64 consecutive float4: quad qd of unit j of row b lives at xs[(b*NQ + qd)*nup + j].
+// Units [nunits, nup) are zero filled (the weight stream reads clamped addresses there).  With a
+// gain, RMSNorm (paper Section 2.1: pre-RMSNorm in front of the QKV and GLU in/gate projections) is
+// applied; that needs k0 == 0 and the whole row.  NT threads take part (tid in [0, NT)): 64 = one
+// wave (reduction by DPP), otherwise the whole workgroup (reduction through `red` in LDS, with
+// __syncthreads).  All global loads of a batch of kStageBatch quads per thread are issued before any
+// is used.  The caller synchronises before the staged vector is read.
+constexpr int kStageBatch = 8;
+template <int EPU, class IO, int NT>
+__device__ void stage_act(const ActSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid) {
+    constexpr int NQ = EPU / 4;
+    const int nquads = nunits * NQ;
+    const int padquads = nup * NQ;
+    for (int b = 0; b < batch; b++) {
+        float4* xb = xs + (size_t)b * NQ * nup;
+        const float* src = S.base + (size_t)b * S.stride;
+        const float* add = S.add ? S.add + (size_t)b * S.add_stride : nullptr;
+        const bf16_t* erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
+        float ss = 0.f;
+        for (int q0 = tid; q0 < padquads; q0 += NT * kStageBatch) {
+            float4 v[kStageBatch], a[kStageBatch];
+            u32x2 g[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; u++) {
+                int qi = min(q0 + u * NT, nquads - 1);   // clamped: the load is always issued
+                int k = k0 + qi * 4;
+                if (erow) {
+                    u32x2 w = *as_global((const u32x2*)(erow + k));
+                    v[u] = make_float4(bf_lo(w.x), bf_hi(w.x), bf_lo(w.y), bf_hi(w.y));
+                } else {
+                    v[u] = IO::ld4(src, k);
+                }
+                if (add) a[u] = IO::ld4(add, k);
+                if (S.gain) g[u] = *as_global((const u32x2*)(S.gain + k));
+            }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; u++) {
+                int qi = q0 + u * NT;
+                if (qi < padquads) {
+                    float4 t = v[u];
+                    if (add) { t.x += a[u].x; t.y += a[u].y; t.z += a[u].z; t.w += a[u].w; }
+                    if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
+                    else if (S.wb && (qi % (int)gridDim.x) == (int)blockIdx.x) IO::st4(S.wb + (size_t)b * S.wb_stride + k0 + qi * 4, t);
+                    if (S.gain && qi < nquads) {
+                        ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+                        t.x *= bf_lo(g[u].x); t.y *= bf_hi(g[u].x); t.z *= bf_lo(g[u].y); t.w *= bf_hi(g[u].y);
+                    }
+                    xb[(size_t)(qi % NQ) * nup + qi / NQ] = t;
+                }
+            }
+        }
+        if (S.gain) {
+            float tot;
+            if constexpr (NT == 64) {
+                tot = wave_sum_uniform(ss);
+            } else {
+                ss = wave_sum_uniform(ss);
+                __syncthreads();
+                if ((tid & 63) == 0) red[tid >> 6] = ss;
+                __syncthreads();
+                tot = 0.f;
+#pragma unroll
+                for (int w = 0; w < NT / 64; w++) tot += red[w];
+            }
+            float r = 1.0f / sqrtf(tot / (float)K + S.eps);
+            for (int qi = tid; qi < nquads; qi += NT) {   // each thread rescales the quads it wrote
+                int j = qi / NQ, qd = qi % NQ;
+                float4 v = xb[(size_t)qd * nup + j];
+                v.x *= r; v.y *= r; v.z *= r; v.w *= r;
+                xb[(size_t)qd * nup + j] = v;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- one stage of weights
+template <int WD> struct Stage {
+    u32x4 w[2][kUnr];
+};
+template <> struct Stage<W_INT8> {
+    u32x4 w[2][kUnr];
+    u32 rs[2];                 // raw fp16 row scales (loaded with the row's last chunk)
+};
+template <> struct Stage<W_INT4> {
+    u32x4 w[2][kUnr];
+    u32 s[2][kUnr], z[2][kUnr];   // raw fp16 group scale / zero of each unit
+};
+
+__device__ __forceinline__ float dot_bf16(const u32x4& w, const float4& a, const float4& b, float acc) {
+    acc = fmaf(bf_lo(w.x), a.x, acc);
+    acc = fmaf(bf_hi(w.x), a.y, acc);
+    acc = fmaf(bf_lo(w.y), a.z, acc);
+    acc = fmaf(bf_hi(w.y), a.w, acc);
+    acc = fmaf(bf_lo(w.z), b.x, acc);
+    acc = fmaf(bf_hi(w.z), b.y, acc);
+    acc = fmaf(bf_lo(w.w), b.z, acc);
+    acc = fmaf(bf_hi(w.w), b.w, acc);
+    return acc;
+}
+__device__ __forceinline__ float dot_i8x4(u32 w, const float4& x, float acc) {
+    acc = fmaf((float)(int)(int8_t)(w), x.x, acc);
+    acc = fmaf((float)(int)(int8_t)(w >> 8), x.y, acc);
+    acc = fmaf((float)(int)(int8_t)(w >> 16), x.z, acc);
+    acc = fmaf((float)((int)w >> 24), x.w, acc);
+    return acc;
+}
+// (code - z) * s is formed exactly as the dequantisation definition, then multiplied by x.
+__device__ __forceinline__ float dot_i4x8(u32 w, const float4& x0, const float4& x1, float s, float z, float acc) {
+    acc = fmaf(((float)(w & 15u) - z) * s, x0.x, acc);
+    acc = fmaf(((float)((w >> 4) & 15u) - z) * s, x0.y, acc);
+    acc = fmaf(((float)((w >> 8) & 15u) - z) * s, x0.z, acc);
+    acc = fmaf(((float)((w >> 12) & 15u) - z) * s, x0.w, acc);
+    acc = fmaf(((float)((w >> 16) & 15u) - z) * s, x1.x, acc);
+    acc = fmaf(((float)((w >> 20) & 15u) - z) * s, x1.y, acc);
+    acc = fmaf(((float)((w >> 24) & 15u) - z) * s, x1.z, acc);
+    acc = fmaf(((float)(w >> 28) - z) * s, x1.w, acc);
+    return acc;
+}
+
+// ---------------------------------------------------------------- per-wave view of one GEMV
+// A projection is cut along K into segments whose staged input fits the LDS activation region
+// (one segment except for the widest inputs at batch 4); along N every wave of the grid owns a
+// contiguous range of row pairs.  All fields are wave-uniform.
+template <int WD, int B>
+struct Stream {
+    const uint8_t* w; const f16_t* s; const f16_t* z;
+    size_t rowb;
+    int N, K, ng;
+    int nseg, seg, j0, nunits, cpr, nup;
+    int p0, my_pairs, n_it;
+
+    static constexpr int EPU = WTraits<WD>::EPU;
+    static constexpr int seg_units = (kLdsActBytes / (B * EPU * 4)) / kChunkUnits * kChunkUnits;
+
+    __device__ static Stream make(const PMat& M, int seg, int gwave, int n_gwaves) {
+        Stream S;
+        S.w = M.w; S.s = M.s; S.z = M.z; S.N = M.n; S.K = M.k; S.ng = M.k / 128;
+        S.rowb = WD == W_BF16 ? (size_t)M.k * 2 : WD == W_INT8 ? (size_t)M.k : (size_t)M.k / 2;
+        const int total_units = M.k / EPU;
+        S.nseg = (total_units + seg_units - 1) / seg_units;
+        S.seg = seg;
+        S.j0 = seg * seg_units;
+        S.nunits = min(seg_units, total_units - S.j0);
+        S.cpr = (S.nunits + kChunkUnits - 1) / kChunkUnits;
+        S.nup = S.cpr * kChunkUnits;
+        const long npairs = (M.n + 1) / 2;
+        S.p0 = (int)(npairs * gwave / n_gwaves);
+        S.my_pairs = (int)(npairs * (gwave + 1) / n_gwaves) - S.p0;
+        S.n_it = S.my_pairs * S.cpr;
+        return S;
+    }
+};
+
+// Issue the loads of iteration (pair, chunk).  Every load is issued unconditionally from a clamped
+// address: out-of-range units meet zeros in the staged input, out-of-range rows are dropped by the
+// epilogue.  Nothing is converted here, so no load result is waited for at issue time.
+template <int WD, int B>
+__device__ __forceinline__ void load_stage(const Stream<WD, B>& S, int pair, int chunk, Stage<WD>& st, int lane) {
+#pragma unroll
+    for (int u = 0; u < kUnr; u++) {
+        const int j = min((chunk * kUnr + u) * 64 + lane, S.nunits - 1);
+#pragma unroll
+        for (int r = 0; r < 2; r++) {
+            const int row = min(2 * pair + r, S.N - 1);
+            st.w[r][u] = ldg_stream(S.w + (size_t)row * S.rowb + (size_t)(S.j0 + j) * 16);
+            if constexpr (WD == W_INT4) {
+                const size_t gi = (size_t)row * S.ng + (S.j0 + j) / 4;
+                st.s[r][u] = as_global(S.s)[gi];
+                st.z[r][u] = as_global(S.z)[gi];
+            }
+        }
+    }
+    if constexpr (WD == W_INT8) {
+        if (chunk == S.cpr - 1) {
+            st.rs[0] = as_global(S.s)[min(2 * pair, S.N - 1)];
+            st.rs[1] = as_global(S.s)[min(2 * pair + 1, S.N - 1)];
+        }
+    }
+}
+
+// Issue the first min(kDepth, n_it) iterations of a stream into the ring; returns how many.
+template <int WD, int B>
+__device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepth], int lane) {
+    int pair = S.p0, chunk = 0, n = 0;
+#pragma unroll
+    for (int s = 0; s < kDepth; s++) {
+        if (s < S.n_it) {
+            load_stage(S, pair, chunk, ring[s], lane);
+            if (++chunk == S.cpr) { chunk = 0; ++pair; }
+            n = s + 1;
+        }
+    }
+    return n;
+}
+
+// Weight-streaming GEMV over one stream for up to B batch rows (paper Section 3.2: batch-one
+// projections are matrix-vector products with the input cached on chip and each workgroup owning
+// some rows of W; Section 4.2: at batch 2-4 the weights are still read exactly once and the inputs
+// replicated).  On entry ring[s] holds iteration s (s < min(kDepth, n_it)); iteration i+kDepth is
+// issued into the slot iteration i has just freed, so kDepth*kStageLoads 16-byte non-temporal loads
+// per lane stay in flight across row boundaries.  epi(pair, b, v0, v1) runs on lane 0 with the two
+// finished dot products of rows (2*pair, 2*pair+1); partial sums of earlier K segments are carried
+// in `myacc` (LDS, private to the wave).
+template <int WD, int B, class Epi>
+__device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepth], const float4* xs, float* myacc,
+                                         int batch, int lane, Epi& epi) {
+    constexpr int EPU = WTraits<WD>::EPU;
+    constexpr int NQ = EPU / 4;
+    const int nup = S.nup;
+    float acc[2][B];
+#pragma unroll
+    for (int b = 0; b < B; b++) acc[0][b] = acc[1][b] = 0.f;
+    int pc = S.p0, cc = 0;          // (pair, chunk) of the next compute
+    int pl = S.p0, cl = 0;          // (pair, chunk) of the next load = iteration kDepth
+    for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
+
+    auto compute = [&](const Stage<WD>& st) {
+#pragma unroll
+        for (int u = 0; u < kUnr; u++) {
+            const int j = (cc * kUnr + u) * 64 + lane;
+#pragma unroll
+            for (int b = 0; b < B; b++) {
+                const float4* xq = xs + (size_t)b * NQ * nup + j;
+                if constexpr (WD == W_BF16) {
+                    float4 x0 = xq[0], x1 = xq[nup];
+                    acc[0][b] = dot_bf16(st.w[0][u], x0, x1, acc[0][b]);
+                    acc[1][b] = dot_bf16(st.w[1][u], x0, x1, acc[1][b]);
+                } else if constexpr (WD == W_INT8) {
+                    float4 x0 = xq[0], x1 = xq[nup], x2 = xq[2 * nup], x3 = xq[3 * nup];
+#pragma unroll
+                    for (int r = 0; r < 2; r++) {
+                        float a = acc[r][b];
+                        a = dot_i8x4(st.w[r][u].x, x0, a); a = dot_i8x4(st.w[r][u].y, x1, a);
+                        a = dot_i8x4(st.w[r][u].z, x2, a); a = dot_i8x4(st.w[r][u].w, x3, a);
+                        acc[r][b] = a;
+                    }
+                } else {
+                    float4 x[8];
+#pragma unroll
+                    for (int q = 0; q < 8; q++) x[q] = xq[q * nup];
+#pragma unroll
+                    for (int r = 0; r < 2; r++) {
+                        const float sc = f16_to_f((f16_t)st.s[r][u]), zp = f16_to_f((f16_t)st.z[r][u]);
+                        float a = acc[r][b];
+                        a = dot_i4x8(st.w[r][u].x, x[0], x[1], sc, zp, a); a = dot_i4x8(st.w[r][u].y, x[2], x[3], sc, zp, a);
+                        a = dot_i4x8(st.w[r][u].z, x[4], x[5], sc, zp, a); a = dot_i4x8(st.w[r][u].w, x[6], x[7], sc, zp, a);
+                        acc[r][b] = a;
+                    }
+                }
+            }
+        }
+        if (cc == S.cpr - 1) {   // row pair finished (for this K segment)
+            const int lp = pc - S.p0;
+#pragma unroll
+            for (int b = 0; b < B; b++) {
+                float v0 = wave_sum_uniform(acc[0][b]), v1 = wave_sum_uniform(acc[1][b]);
+                acc[0][b] = acc[1][b] = 0.f;
+                if constexpr (WD == W_INT8) { v0 *= f16_to_f((f16_t)st.rs[0]); v1 *= f16_to_f((f16_t)st.rs[1]); }
+                if (lane == 0 && b < batch) {
+                    if (S.nseg > 1) {
+                        float* a = myacc + ((size_t)lp * B + b) * 2;
+                        if (S.seg > 0) { v0 += a[0]; v1 += a[1]; }
+                        if (S.seg < S.nseg - 1) { a[0] = v0; a[1] = v1; }
+                    }
+                    if (S.seg == S.nseg - 1) epi(pc, b, v0, v1);
+                }
+            }
+        }
+        if (++cc == S.cpr) { cc = 0; ++pc; }
+    };
+    auto load = [&](Stage<WD>& st) {
+        load_stage(S, pl, cl, st, lane);
+        if (++cl == S.cpr) { cl = 0; ++pl; }
+    };
+    int it = 0;
+    // steady state: every slot is consumed and refilled
+    for (; it + 2 * kDepth <= S.n_it; it += kDepth) {
+#pragma unroll
+        for (int s = 0; s < kDepth; s++) { compute(ring[s]); load(ring[s]); }
+    }
+    // tail
+    for (; it < S.n_it; it += kDepth) {
+#pragma unroll
+        for (int s = 0; s < kDepth; s++) {
+            if (it + s < S.n_it) {
+                compute(ring[s]);
+                if (it + s + kDepth < S.n_it) load(ring[s]);
+            }
+        }
+    }
+}
+
+}  // namespace ff

@@ -1,0 +1,187 @@
+// Per-operation baseline kernels (one launch per operation of the decode step) and the loaders.
+#pragma once
+#include "ff_kernels.h"
+
+namespace ff {
+
+// ---------------------------------------------------------------- per-operation baseline kernels
+__global__ void __launch_bounds__(kThreads) op_embed(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch) {
+    if (!inputs_ok(M, KV, tokens, pos, batch)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(M.status, kStatusRange);
+        return;
+    }
+    const int tot = batch * M.d;
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < tot; i += gridDim.x * kThreads) {
+        int b = i / M.d, c = i % M.d;
+        M.x[(size_t)b * M.d + c] = bf_to_f(M.embed[(size_t)tokens[b] * M.d + c]);
+    }
+}
+// grid = batch
+__global__ void __launch_bounds__(kThreads) op_rmsnorm(const float* x, const bf16_t* gain, float* out, int d, float eps) {
+    __shared__ float red[kWaves];
+    const float* xr = x + (size_t)blockIdx.x * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += kThreads) ss += xr[i] * xr[i];
+    ss = wave_sum_uniform(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+    for (int w = 0; w < kWaves; w++) tot += red[w];
+    float r = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += kThreads) out[(size_t)blockIdx.x * d + i] = xr[i] * bf_to_f(gain[i]) * r;
+}
+// x = residual + last sublayer output, from the fused kernel's tagged buffers (finishes the residual
+// stream when the LM head is launched separately after the fused kernel)
+__global__ void __launch_bounds__(kThreads) op_final_x(float* x, const u32x2* tx, const u32x2* tdelta, int n) {
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < n; i += gridDim.x * kThreads)
+        x[i] = __uint_as_float(tx[i].x) + __uint_as_float(tdelta[i].x);
+}
+enum { EPI_STORE = 0, EPI_RESIDUAL = 1 };
+template <int WD, int B, class Epi>
+__device__ __forceinline__ void op_gemv_body(const PMat& W, const ActSrc& src, int batch, uint8_t* lds, Epi& epi) {
+    constexpr int EPU = WTraits<WD>::EPU;
+    float4* xs = (float4*)lds;
+    float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes);
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gwave = blockIdx.x * kWaves + wave, n_gwaves = gridDim.x * kWaves;
+    float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
+    Stage<WD> ring[kDepth];
+    Stream<WD, B> S = Stream<WD, B>::make(W, 0, gwave, n_gwaves);
+    const int nseg = S.nseg;
+    for (int seg = 0; seg < nseg; seg++) {
+        if (seg > 0) { S = Stream<WD, B>::make(W, seg, gwave, n_gwaves); __syncthreads(); }
+        prefetch_stream(S, ring, lane);   // weights do not depend on the input: issue them first
+        stage_act<EPU, PlainIO, kThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x);
+        __syncthreads();
+        gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
+    }
+}
+template <int WD, int B>
+__global__ void __launch_bounds__(kThreads) op_gemv(PMat W, const float* in, int in_stride, float* out, int batch, int epi_kind) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    ActSrc src;
+    src.base = in; src.stride = (size_t)in_stride;
+    if (epi_kind == EPI_RESIDUAL) {
+        EpiResidual epi{out, W.n};
+        op_gemv_body<WD, B>(W, src, batch, lds, epi);
+    } else {
+        EpiStore epi{out, W.n};
+        op_gemv_body<WD, B>(W, src, batch, lds, epi);
+    }
+}
+// y holds raw QKV outputs in packed row order [B][rows]
+__global__ void __launch_bounds__(kThreads) op_rope_append(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch, int layer) {
+    if (!inputs_ok(M, KV, tokens, pos, batch)) return;
+    __shared__ float2 rope_s[kMaxBatch * 64];
+    for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kThreads) {
+        int b = i / (M.hd / 2), f = i % (M.hd / 2);
+        rope_s[i] = KV.rope[(size_t)pos[b] * (M.hd / 2) + f];
+    }
+    __syncthreads();
+    const int rows = (M.Hq + 2 * M.Hkv) * M.hd, npairs = rows / 2;
+    EpiQKV<PlainIO> epi{M, KV, pos, layer, rope_s};
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < npairs * batch; i += gridDim.x * kThreads) {
+        int b = i / npairs, p = i % npairs;
+        const float* y = M.y + (size_t)b * rows + 2 * p;
+        epi(p, b, y[0], y[1]);
+    }
+}
+__global__ void __launch_bounds__(kThreads) op_attn_partial(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch, int layer) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    if (!inputs_ok(M, KV, tokens, pos, batch)) return;
+    attention_phase_plain<kWaves>(M, KV, pos, batch, layer, lds);
+}
+// grid = batch * Hkv; must be launched with the same share (= partial grid / (batch*Hkv)) in `share`
+__global__ void __launch_bounds__(kThreads) op_attn_merge(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch, int share) {
+    if (!inputs_ok(M, KV, tokens, pos, batch)) return;
+    int b = blockIdx.x / M.Hkv, j = blockIdx.x % M.Hkv;
+    int ns = attn_nsplit(pos[b], share);
+    const int G = M.Hq / M.Hkv;
+    __shared__ float mlds[3 * 8 * kMaxSplits];
+    if (M.hd == 64 && G == 4) attn_merge<64, 4, kThreads>(M, b, j, ns, mlds);
+    else if (M.hd == 128 && G == 4) attn_merge<128, 4, kThreads>(M, b, j, ns, mlds);
+    else if (M.hd == 128 && G == 8) attn_merge<128, 8, kThreads>(M, b, j, ns, mlds);
+}
+// y holds raw gate/up outputs, rows interleaved [B][2F]
+__global__ void __launch_bounds__(kThreads) op_swiglu(DevModel M, int batch) {
+    EpiSwiGLU<PlainIO> epi{M.h, M.F};
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < M.F * batch; i += gridDim.x * kThreads) {
+        int b = i / M.F, p = i % M.F;
+        const float* y = M.y + (size_t)b * 2 * M.F + 2 * p;
+        epi(p, b, y[0], y[1]);
+    }
+}
+
+// ---------------------------------------------------------------- loaders and utilities
+enum { REPACK_COPY = 0, REPACK_ROPE = 1, REPACK_INTERLEAVE = 2 };
+// dst row r  <-  source row per mode.  row_bytes is a multiple of 2.
+__global__ void __launch_bounds__(kThreads) k_repack_rows(uint8_t* dst, const uint8_t* src_a, const uint8_t* src_b, int n_rows,
+                                                         size_t row_bytes, int mode, int hd) {
+    for (int r = blockIdx.x; r < n_rows; r += gridDim.x) {
+        const uint8_t* src;
+        if (mode == REPACK_ROPE) {
+            int head = r / hd, within = r % hd;
+            src = src_a + (size_t)(head * hd + within / 2 + (within & 1) * (hd / 2)) * row_bytes;
+        } else if (mode == REPACK_INTERLEAVE) {
+            src = ((r & 1) ? src_b : src_a) + (size_t)(r / 2) * row_bytes;
+        } else {
+            src = src_a + (size_t)r * row_bytes;
+        }
+        uint8_t* d = dst + (size_t)r * row_bytes;
+        if (row_bytes % 16 == 0) {
+            for (size_t i = threadIdx.x; i < row_bytes / 16; i += kThreads) ((u32x4*)d)[i] = ((const u32x4*)src)[i];
+        } else {
+            for (size_t i = threadIdx.x; i < row_bytes / 2; i += kThreads) ((uint16_t*)d)[i] = ((const uint16_t*)src)[i];
+        }
+    }
+}
+__global__ void k_rope_table(float2* rope, int max_ctx, int hd, double theta) {
+    int half = hd / 2;
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= max_ctx * half) return;
+    int p = i / half, f = i % half;
+    double ang = (double)p * pow(theta, -2.0 * (double)f / (double)hd);
+    double s, c;
+    sincos(ang, &s, &c);
+    rope[i] = make_float2((float)c, (float)s);
+}
+// canonical [n][Hkv][hd] rows <-> cache planes; dir 0 = fill cache, 1 = read cache
+__global__ void k_kv_copy(DevKV KV, int L_unused, int Hkv, int hd, bf16_t* plane_base_k, bf16_t* plane_base_v, size_t plane_stride_j,
+                          int pos0, int n, bf16_t* k_can, bf16_t* v_can, int dir) {
+    size_t tot = (size_t)n * Hkv * hd;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < tot; i += (size_t)gridDim.x * blockDim.x) {
+        int e = i % hd, j = (i / hd) % Hkv, t = i / ((size_t)hd * Hkv);
+        size_t off = (size_t)j * plane_stride_j + (size_t)(pos0 + t) * hd + e;
+        if (dir == 0) { plane_base_k[off] = k_can[i]; plane_base_v[off] = v_can[i]; }
+        else { k_can[i] = plane_base_k[off]; v_can[i] = plane_base_v[off]; }
+    }
+}
+// Dequantise packed matrix element-wise into canonical [N][K] fp32.  map: 0 identity, 1 RoPE-pair
+// block, 2 interleave (even rows: parity 0, odd rows: parity 1); row_off = first packed row.
+__global__ void k_dequant(PMat W, float* out, int n_can, int map, int parity, int row_off, int hd) {
+    size_t tot = (size_t)n_can * W.k;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < tot; i += (size_t)gridDim.x * blockDim.x) {
+        int r = i / W.k, c = i % W.k;
+        int pr;
+        if (map == 1) { int head = r / hd, within = r % hd, half = hd / 2; pr = head * hd + 2 * (within % half) + within / half; }
+        else if (map == 2) pr = 2 * r + parity;
+        else pr = r;
+        pr += row_off;
+        const uint8_t* row = W.w + (size_t)pr * W.row_bytes();
+        float v;
+        if (W.wd == W_BF16) v = bf_to_f(((const bf16_t*)row)[c]);
+        else if (W.wd == W_INT8) v = (float)(int)((const int8_t*)row)[c] * f16_to_f(W.s[pr]);
+        else {
+            int ng = W.k / 128;
+            uint8_t byte = row[c >> 1];
+            int code = (c & 1) ? (byte >> 4) : (byte & 15);
+            v = ((float)code - f16_to_f(W.z[(size_t)pr * ng + c / 128])) * f16_to_f(W.s[(size_t)pr * ng + c / 128]);
+        }
+        out[i] = v;
+    }
+}
+__global__ void k_fill_u32(u32* p, size_t n, u32 v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+}  // namespace ff

@@ -1,257 +1,169 @@
-// Phase bodies of the decode step: activation staging, weight-streaming GEMV, split-KV attention.
-// Each is a workgroup-collective device function used by the fused kernel (between grid barriers)
-// and, with launch boundaries instead of barriers, by the per-operation baseline kernels.
+// Split-KV attention and the projection epilogues of the decode step.  Workgroup-collective
+// device functions used by the fused kernel (between grid barriers) and, with launch boundaries
+// instead of barriers, by the per-operation baseline kernels.
 #pragma once
-#include "ff_device.h"
+#include "ff_gemv.h"
 
 namespace ff {
 
-template <int WD> struct WTraits;
-template <> struct WTraits<W_BF16> { static constexpr int EPU = 8; };   // elements per 16-byte unit
-template <> struct WTraits<W_INT8> { static constexpr int EPU = 16; };
-template <> struct WTraits<W_INT4> { static constexpr int EPU = 32; };
-
-constexpr int kUnr = 4;   // 16-byte loads per row kept in flight per lane and pipeline stage
-
-// Where a GEMV phase takes its input vector(s) from.
-struct ActSrc {
-    const void* base;     // fp32 exchange buffer, or bf16 embedding table
-    const int* tokens;    // non-null: row b is base(bf16)[tokens[b]][K]
-    size_t stride;        // elements between batch rows (fp32 source)
-    const bf16_t* gain;   // non-null: RMSNorm with this gain is applied while staging
-    float eps;
-};
-
-__device__ __forceinline__ float block_sum(float v, float* red /*LDS, >= kWaves floats*/) {
-    v = wave_sum(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float t = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; w++) t += red[w];
-    return t;
+// ---------------------------------------------------------------- tagged exchange format
+// Inside the fused kernel every value exchanged between workgroups travels as an 8-byte pair
+// (fp32 bits, tag) written with one coherent 8-byte store.  The tag names the phase instance that
+// produced the value (it grows monotonically over phases and over decode steps), so a consumer can
+// tell from the data itself whether its producer has run: it simply re-reads until every tag it
+// needs matches.  Dependencies are thereby resolved by dataflow -- no device-wide barrier, no
+// waiting for store acknowledgements -- and a vector is on the critical path for one store->load
+// hop only (paper Section 3.1 needs a fence + global barrier on its hardware for the same RAW hazard).
+#ifndef FF_TLD_AUX
+#define FF_TLD_AUX 17   /* sc0 | sc1 */
+#endif
+typedef u32x2 tagged_t;
+constexpr int kPollLanes = 8;
+__device__ __forceinline__ void tst(tagged_t* p, float v, u32 tag) { xst2((float*)p, v, __uint_as_float(tag)); }
+__device__ __forceinline__ void tst2(tagged_t* p, float v0, float v1, u32 tag) {
+    tst(p, v0, tag);
+    tst(p + 1, v1, tag);
+}
+__device__ __forceinline__ u32x2 tld1(const tagged_t* base, int i) {
+    u64 a = __hip_atomic_load(as_global((const u64*)(base + i)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return u32x2{(u32)a, (u32)(a >> 32)};
+}
+// Two consecutive tagged values (base + i, i even) as (v0, tag0, v1, tag1).  8-byte agent-scope
+// atomic loads are used on purpose: 16-byte buffer loads with the same cache-policy bits were
+// observed to keep returning a stale copy while polling, and inline-assembly loads cannot be kept
+// asynchronous safely (the compiler may copy their destination registers before the data lands).
+__device__ __forceinline__ u32x4 tld2(const tagged_t* base, int i) {
+    u32x2 a = tld1(base, i), b = tld1(base, i + 1);
+    return u32x4{a.x, a.y, b.x, b.y};
 }
 
-// Stage elements [k0, k0 + nunits*EPU) of every batch row into LDS, quad-planar so that a wave's
-// 64 lanes read 64 consecutive float4: quad qd of unit j of row b lives at xs[(b*NQ + qd)*nup + j].
-// Units [nunits, nup) are zero filled.  With a gain, RMSNorm (paper Section 2.1: pre-RMSNorm in
-// front of the QKV and GLU in/gate projections) is applied; that needs k0 == 0 and the whole row.
-template <int EPU, class IO>
-__device__ void stage_act(const ActSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red) {
+// Input of a projection inside the fused kernel.
+struct TSrc {
+    const tagged_t* base = nullptr; size_t stride = 0; u32 tag = 0;        // tagged vector [B][stride] ...
+    const bf16_t* embed = nullptr; const int* tokens = nullptr;            // ... or rows of the embedding table
+    const tagged_t* add = nullptr; size_t add_stride = 0; u32 add_tag = 0; // optional: + sublayer output
+    tagged_t* wb = nullptr; size_t wb_stride = 0; u32 wb_tag = 0;          // optional: publish the sum (residual stream)
+    const bf16_t* gain = nullptr; float eps = 0.f;                         // optional: RMSNorm
+};
+
+// Waits (bounded) until kPollLanes sampled elements of the source vector(s) carry their tags: a
+// cheap way to sit out a producer that is still running -- a few 8-byte loads with pauses in
+// between cost the memory system next to nothing even with every workgroup waiting at once.
+template <bool HAS_ADD>
+__device__ bool light_wait(const TSrc& S, int batch, int k0, int nel, int lane) {
+    const int sample = min(k0 + (int)(((long)(lane % kPollLanes) * nel) / kPollLanes) + (int)(blockIdx.x % 16) * 2, k0 + nel - 1);
+    const tagged_t* sb = S.base + (size_t)(batch - 1) * S.stride;
+    const tagged_t* sa = HAS_ADD ? S.add + (size_t)(batch - 1) * S.add_stride : nullptr;
+    for (int spins = 0; spins < kSpinLimit; spins++) {
+        bool ok = true;
+        if (lane < kPollLanes) {
+            u32x2 p = tld1(sb, sample);
+            ok = p.y == S.tag;
+            if constexpr (HAS_ADD) { u32x2 q = tld1(sa, sample); ok = ok && q.y == S.add_tag; }
+        }
+        if (__all(ok)) return true;
+        __builtin_amdgcn_s_sleep(16);
+    }
+    return false;
+}
+
+// The workgroup stages elements [k0, k0 + nunits*EPU) of every batch row into LDS in the
+// quad-planar layout of stage_act, re-reading the tagged sources until their producers have
+// written them.  Every thread issues all loads of its share of a batch at once and speculatively
+// (a load issued behind a wave's weight prefetch takes microseconds to return, so round trips are
+// what count); only if some tag in the workgroup is stale does it fall back to light polling.
+// The first workgroup barrier inside doubles as the hand-over of the LDS region from the previous
+// projection.  NT = threads of the workgroup.  Returns false (uniformly) on a time-out.
+template <int EPU, bool HAS_ADD, int NT>
+__device__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid) {
     constexpr int NQ = EPU / 4;
+    constexpr int QB = HAS_ADD ? 8 : 14;   // quads per thread and batch: 4 8-byte loads per quad and source
+    const int lane = tid & 63;
     const int nquads = nunits * NQ;
     const int padquads = nup * NQ;
     for (int b = 0; b < batch; b++) {
         float4* xb = xs + (size_t)b * NQ * nup;
+        const tagged_t* src = S.base + (size_t)b * S.stride;
+        const tagged_t* add = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
+        const bf16_t* erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
         float ss = 0.f;
-        for (int qi = threadIdx.x; qi < padquads; qi += kThreads) {
-            int j = qi / NQ, qd = qi % NQ;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (qi < nquads) {
-                int k = k0 + qi * 4;
-                if (S.tokens) {
-                    const bf16_t* row = (const bf16_t*)S.base + (size_t)S.tokens[b] * K;
-                    u32x2 w = *(const u32x2*)(row + k);
-                    v = make_float4(bf_lo(w.x), bf_hi(w.x), bf_lo(w.y), bf_hi(w.y));
-                } else {
-                    const float* row = (const float*)S.base + (size_t)b * S.stride;
-                    float2 a = IO::ld2(row + k), c = IO::ld2(row + k + 2);
-                    v = make_float4(a.x, a.y, c.x, c.y);
+        for (int q0 = tid; q0 < padquads; q0 += NT * QB) {
+            u32x4 v[QB][2], a[HAS_ADD ? QB : 1][2];
+            u32x2 g[QB];
+            bool all_ok = false;
+            for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
+#pragma unroll
+                for (int u = 0; u < QB; u++) {
+                    const int k = k0 + min(q0 + u * NT, nquads - 1) * 4;   // clamped: every load is issued
+                    if (erow) {
+                        u32x2 w = *as_global((const u32x2*)(erow + k));
+                        v[u][0] = u32x4{w.x << 16, S.tag, w.x & 0xFFFF0000u, S.tag};
+                        v[u][1] = u32x4{w.y << 16, S.tag, w.y & 0xFFFF0000u, S.tag};
+                    } else {
+                        v[u][0] = tld2(src, k);
+                        v[u][1] = tld2(src, k + 2);
+                    }
+                    if constexpr (HAS_ADD) { a[u][0] = tld2(add, k); a[u][1] = tld2(add, k + 2); }
+                    if (S.gain && spins == 0) g[u] = *as_global((const u32x2*)(S.gain + k));
                 }
-                if (S.gain) {
-                    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-                    u32x2 g = *(const u32x2*)(S.gain + k);
-                    v.x *= bf_lo(g.x); v.y *= bf_hi(g.x); v.z *= bf_lo(g.y); v.w *= bf_hi(g.y);
+                bool ok = true;
+#pragma unroll
+                for (int u = 0; u < QB; u++) {
+                    ok = ok && v[u][0].y == S.tag && v[u][0].w == S.tag && v[u][1].y == S.tag && v[u][1].w == S.tag;
+                    if constexpr (HAS_ADD)
+                        ok = ok && a[u][0].y == S.add_tag && a[u][0].w == S.add_tag && a[u][1].y == S.add_tag && a[u][1].w == S.add_tag;
+                }
+                all_ok = __syncthreads_and(ok);
+                if (!all_ok) {
+                    bool lw = true;
+                    if (tid < 64) lw = light_wait<HAS_ADD>(S, batch, k0, nunits * EPU, lane);
+                    if (!__syncthreads_and(lw)) return false;
                 }
             }
-            xb[(size_t)qd * nup + j] = v;
+            if (!all_ok) return false;
+#pragma unroll
+            for (int u = 0; u < QB; u++) {
+                const int qi = q0 + u * NT;
+                if (qi < padquads) {
+                    float4 t = make_float4(__uint_as_float(v[u][0].x), __uint_as_float(v[u][0].z), __uint_as_float(v[u][1].x),
+                                           __uint_as_float(v[u][1].z));
+                    if constexpr (HAS_ADD) {
+                        t.x += __uint_as_float(a[u][0].x); t.y += __uint_as_float(a[u][0].z);
+                        t.z += __uint_as_float(a[u][1].x); t.w += __uint_as_float(a[u][1].z);
+                    }
+                    if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
+                    else if (S.wb && (qi % (int)gridDim.x) == (int)blockIdx.x) {
+                        tagged_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
+                        tst2(w, t.x, t.y, S.wb_tag);
+                        tst2(w + 2, t.z, t.w, S.wb_tag);
+                    }
+                    if (S.gain && qi < nquads) {
+                        ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+                        t.x *= bf_lo(g[u].x); t.y *= bf_hi(g[u].x); t.z *= bf_lo(g[u].y); t.w *= bf_hi(g[u].y);
+                    }
+                    xb[(size_t)(qi % NQ) * nup + qi / NQ] = t;
+                }
+            }
         }
         if (S.gain) {
-            float tot = block_sum(ss, red);
-            float r = 1.0f / sqrtf(tot / (float)K + S.eps);
-            for (int qi = threadIdx.x; qi < nquads; qi += kThreads) {
+            ss = wave_sum_uniform(ss);
+            if (lane == 0) red[tid >> 6] = ss;
+            __syncthreads();
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < NT / 64; w++) tot += red[w];
+            const float r = 1.0f / sqrtf(tot / (float)K + S.eps);
+            for (int qi = tid; qi < nquads; qi += NT) {   // each thread rescales the quads it wrote
                 int j = qi / NQ, qd = qi % NQ;
-                float4 v = xb[(size_t)qd * nup + j];
-                v.x *= r; v.y *= r; v.z *= r; v.w *= r;
-                xb[(size_t)qd * nup + j] = v;
+                float4 v4 = xb[(size_t)qd * nup + j];
+                v4.x *= r; v4.y *= r; v4.z *= r; v4.w *= r;
+                xb[(size_t)qd * nup + j] = v4;
             }
+            __syncthreads();   // `red` may be rewritten for the next row
         }
     }
     __syncthreads();
-}
-
-// ---- one 16-byte unit of weights against the staged activations ----
-template <int WD> struct UnitAux {};                       // per-unit side data (int4 scale/zero)
-template <> struct UnitAux<W_INT4> { float s, z; };
-
-template <int WD>
-__device__ __forceinline__ float unit_dot(const u32x4& w, const UnitAux<WD>& aux, const float4* xq, int nup);
-
-template <>
-__device__ __forceinline__ float unit_dot<W_BF16>(const u32x4& w, const UnitAux<W_BF16>&, const float4* xq, int nup) {
-    float4 a = xq[0], b = xq[nup];
-    float acc = bf_lo(w.x) * a.x;
-    acc = fmaf(bf_hi(w.x), a.y, acc);
-    acc = fmaf(bf_lo(w.y), a.z, acc);
-    acc = fmaf(bf_hi(w.y), a.w, acc);
-    acc = fmaf(bf_lo(w.z), b.x, acc);
-    acc = fmaf(bf_hi(w.z), b.y, acc);
-    acc = fmaf(bf_lo(w.w), b.z, acc);
-    acc = fmaf(bf_hi(w.w), b.w, acc);
-    return acc;
-}
-__device__ __forceinline__ float i8dot4(u32 w, const float4& x, float acc) {
-    acc = fmaf((float)(int)(int8_t)(w), x.x, acc);
-    acc = fmaf((float)(int)(int8_t)(w >> 8), x.y, acc);
-    acc = fmaf((float)(int)(int8_t)(w >> 16), x.z, acc);
-    acc = fmaf((float)((int)w >> 24), x.w, acc);
-    return acc;
-}
-template <>
-__device__ __forceinline__ float unit_dot<W_INT8>(const u32x4& w, const UnitAux<W_INT8>&, const float4* xq, int nup) {
-    float acc = 0.f;
-    acc = i8dot4(w.x, xq[0], acc);
-    acc = i8dot4(w.y, xq[nup], acc);
-    acc = i8dot4(w.z, xq[2 * nup], acc);
-    acc = i8dot4(w.w, xq[3 * nup], acc);
-    return acc;
-}
-// (code - z) * s is formed exactly as the dequantisation definition, then multiplied by x.
-__device__ __forceinline__ float i4dot8(u32 w, const float4& x0, const float4& x1, float s, float z, float acc) {
-    acc = fmaf(((float)(w & 15u) - z) * s, x0.x, acc);
-    acc = fmaf(((float)((w >> 4) & 15u) - z) * s, x0.y, acc);
-    acc = fmaf(((float)((w >> 8) & 15u) - z) * s, x0.z, acc);
-    acc = fmaf(((float)((w >> 12) & 15u) - z) * s, x0.w, acc);
-    acc = fmaf(((float)((w >> 16) & 15u) - z) * s, x1.x, acc);
-    acc = fmaf(((float)((w >> 20) & 15u) - z) * s, x1.y, acc);
-    acc = fmaf(((float)((w >> 24) & 15u) - z) * s, x1.z, acc);
-    acc = fmaf(((float)(w >> 28) - z) * s, x1.w, acc);
-    return acc;
-}
-template <>
-__device__ __forceinline__ float unit_dot<W_INT4>(const u32x4& w, const UnitAux<W_INT4>& a, const float4* xq, int nup) {
-    float acc = 0.f;
-    acc = i4dot8(w.x, xq[0], xq[nup], a.s, a.z, acc);
-    acc = i4dot8(w.y, xq[2 * nup], xq[3 * nup], a.s, a.z, acc);
-    acc = i4dot8(w.z, xq[4 * nup], xq[5 * nup], a.s, a.z, acc);
-    acc = i4dot8(w.w, xq[6 * nup], xq[7 * nup], a.s, a.z, acc);
-    return acc;
-}
-
-template <int WD> struct PipeBuf {
-    u32x4 w[2][kUnr];
-    UnitAux<WD> aux[2][kUnr];
-};
-
-// Weight-streaming GEMV for up to B batch rows (paper Section 3.2: batch-one projections are
-// matrix-vector products with the input cached on chip and each workgroup owning some rows of W;
-// Section 4.2: at batch 2-4 the weights are still read exactly once and the inputs replicated).
-// Rows are handled in adjacent pairs (2p, 2p+1); every wave of the grid owns a contiguous range
-// of pairs and keeps 2*kUnr 16-byte non-temporal loads per lane in flight, one pipeline stage
-// ahead of the FMAs, across row boundaries.  epi(pair, b, v0, v1) runs on lane 0 with the two
-// finished dot products.
-template <int WD, int B, class IO, class Epi>
-__device__ void gemv_phase(const PMat& M, const ActSrc& S, int batch, uint8_t* lds, Epi& epi) {
-    constexpr int EPU = WTraits<WD>::EPU;
-    constexpr int NQ = EPU / 4;
-    float4* xs = (float4*)lds;
-    float* accbuf = (float*)(lds + kLdsActBytes);
-    float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes - 64);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int K = M.k, N = M.n;
-    const size_t rowb = M.row_bytes();
-    const int total_units = K / EPU;
-    constexpr int chunk_units = 64 * kUnr;
-    int seg_units = (kLdsActBytes / (B * EPU * 4)) / chunk_units * chunk_units;
-    const int nseg = (total_units + seg_units - 1) / seg_units;
-    const long npairs = (N + 1) / 2;
-    const long nwg = (long)gridDim.x * kWaves, gw = (long)blockIdx.x * kWaves + wave;
-    const int p0 = (int)(npairs * gw / nwg), p1 = (int)(npairs * (gw + 1) / nwg);
-    const int my_pairs = p1 - p0;
-    float* myacc = accbuf + (size_t)wave * ((kLdsAuxBytes - 64) / 4 / kWaves);
-
-    for (int seg = 0; seg < nseg; seg++) {
-        const int j0 = seg * seg_units;
-        const int nunits = min(seg_units, total_units - j0);
-        const int cpr = (nunits + chunk_units - 1) / chunk_units;
-        const int nup = cpr * chunk_units;
-        if (seg > 0) __syncthreads();
-        stage_act<EPU, IO>(S, batch, K, j0 * EPU, nunits, nup, xs, red);
-
-        const int n_it = my_pairs * cpr;
-        PipeBuf<WD> bufA, bufB;
-        auto load_it = [&](PipeBuf<WD>& buf, int pair, int chunk) {
-#pragma unroll
-            for (int u = 0; u < kUnr; u++) {
-                int j = (chunk * kUnr + u) * 64 + lane;
-                bool valid = j < nunits;
-#pragma unroll
-                for (int r = 0; r < 2; r++) {
-                    int row = 2 * pair + r;
-                    bool ok = valid && row < N;
-                    const uint8_t* p = M.w + (size_t)row * rowb + (size_t)(j0 + j) * 16;
-                    buf.w[r][u] = ok ? ldg_stream(p) : u32x4{0u, 0u, 0u, 0u};
-                    if constexpr (WD == W_INT4) {
-                        int g = (j0 + j) / 4, ng = K / 128;
-                        buf.aux[r][u].s = ok ? f16_to_f(M.s[(size_t)row * ng + g]) : 0.f;
-                        buf.aux[r][u].z = ok ? f16_to_f(M.z[(size_t)row * ng + g]) : 0.f;
-                    }
-                }
-            }
-        };
-        float acc[2][B];
-#pragma unroll
-        for (int b = 0; b < B; b++) acc[0][b] = acc[1][b] = 0.f;
-        auto compute_it = [&](const PipeBuf<WD>& buf, int pair, int chunk) {
-#pragma unroll
-            for (int u = 0; u < kUnr; u++) {
-                int j = (chunk * kUnr + u) * 64 + lane;
-#pragma unroll
-                for (int b = 0; b < B; b++) {
-                    const float4* xq = xs + (size_t)b * NQ * nup + j;
-                    acc[0][b] += unit_dot<WD>(buf.w[0][u], buf.aux[0][u], xq, nup);
-                    acc[1][b] += unit_dot<WD>(buf.w[1][u], buf.aux[1][u], xq, nup);
-                }
-            }
-            if (chunk == cpr - 1) {
-                int lp = pair - p0;
-#pragma unroll
-                for (int b = 0; b < B; b++) {
-                    float v0 = wave_sum(acc[0][b]), v1 = wave_sum(acc[1][b]);
-                    acc[0][b] = acc[1][b] = 0.f;
-                    if (lane == 0 && b < batch) {
-                        if (nseg > 1) {
-                            float* a = myacc + ((size_t)lp * B + b) * 2;
-                            if (seg > 0) { v0 += a[0]; v1 += a[1]; }
-                            if (seg < nseg - 1) { a[0] = v0; a[1] = v1; }
-                        }
-                        if (seg == nseg - 1) {
-                            if constexpr (WD == W_INT8) {
-                                v0 *= f16_to_f(M.s[2 * pair]);
-                                if (2 * pair + 1 < N) v1 *= f16_to_f(M.s[2 * pair + 1]);
-                            }
-                            epi(pair, b, v0, v1);
-                        }
-                    }
-                }
-            }
-        };
-        if (n_it > 0) {
-            int pl = p0, cl = 0;   // (pair, chunk) of the next load
-            int pc = p0, cc = 0;   // (pair, chunk) of the next compute
-            auto adv = [&](int& p, int& c) { if (++c == cpr) { c = 0; ++p; } };
-            load_it(bufA, pl, cl); adv(pl, cl);
-            for (int it = 0; it < n_it; it += 2) {
-                if (it + 1 < n_it) { load_it(bufB, pl, cl); adv(pl, cl); }
-                compute_it(bufA, pc, cc); adv(pc, cc);
-                if (it + 1 < n_it) {
-                    if (it + 2 < n_it) { load_it(bufA, pl, cl); adv(pl, cl); }
-                    compute_it(bufB, pc, cc); adv(pc, cc);
-                }
-            }
-        }
-    }
+    return true;
 }
 
 // ---------------------------------------------------------------- split-KV attention
@@ -264,27 +176,117 @@ __device__ void gemv_phase(const PMat& M, const ActSrc& S, int batch, uint8_t* l
 //
 // Thread mapping: a cache row is hd*2 bytes = LPR lanes x 16 bytes, so one wave load covers
 // 64/LPR rows; lane (grp, sub) holds dims [8*sub, 8*sub+8) of row grp.  Every (wave, grp) keeps its
-// own online-softmax state; the kWaves*64/LPR states are merged through LDS at the end.
-template <int HD, int G, class IO>
-__device__ void attn_item(const DevModel& M, const DevKV& KV, int layer, int b, int j, int t0, int t1, bool with_cur,
+// own online-softmax state; the NW*64/LPR states are merged through LDS at the end (NW = waves of
+// the workgroup, all of which take part).  XIO supplies the exchange accesses (plain buffers for
+// the per-operation kernels, tagged buffers for the fused kernel); returns false on a time-out.
+struct PlainAttnIO {
+    template <int HD, int G>
+    __device__ bool load_q(const DevModel& M, int b, int j, int sub, float (&qr)[G][8]) const {
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            const int qi = (b * M.Hq + (j * G + g)) * HD + sub * 8;
+            float4 v0 = PlainIO::ld4(M.q, qi), v1 = PlainIO::ld4(M.q, qi + 4);
+            qr[g][0] = v0.x; qr[g][1] = v0.y; qr[g][2] = v0.z; qr[g][3] = v0.w;
+            qr[g][4] = v1.x; qr[g][5] = v1.y; qr[g][6] = v1.z; qr[g][7] = v1.w;
+        }
+        return true;
+    }
+    template <int HD>
+    __device__ bool load_cur(const DevModel& M, int b, int j, int sub, float (&kf)[8], float (&vf)[8]) const {
+        const int ki = ((b * 2 + 0) * M.Hkv + j) * HD + sub * 8;
+        const int vi = ((b * 2 + 1) * M.Hkv + j) * HD + sub * 8;
+        float4 k0 = PlainIO::ld4(M.kvcur, ki), k1 = PlainIO::ld4(M.kvcur, ki + 4);
+        float4 v0 = PlainIO::ld4(M.kvcur, vi), v1 = PlainIO::ld4(M.kvcur, vi + 4);
+        kf[0] = k0.x; kf[1] = k0.y; kf[2] = k0.z; kf[3] = k0.w; kf[4] = k1.x; kf[5] = k1.y; kf[6] = k1.z; kf[7] = k1.w;
+        vf[0] = v0.x; vf[1] = v0.y; vf[2] = v0.z; vf[3] = v0.w; vf[4] = v1.x; vf[5] = v1.y; vf[6] = v1.z; vf[7] = v1.w;
+        return true;
+    }
+    template <int HD>
+    __device__ void store_partial(const DevModel& M, size_t hs, int dim, float ot, float mx, float lt) const {
+        PlainIO::st(M.part_o + hs * HD + dim, ot);
+        if (dim == 0) { PlainIO::st(M.part_m + hs, mx); PlainIO::st(M.part_l + hs, lt); }
+    }
+};
+struct TaggedAttnIO {
+    u32 in_tag;    // tag of q / kvcur (this layer's QKV projection)
+    u32 out_tag;   // tag of the partials and of attn_o (this layer's attention)
+    // 8 consecutive tagged values -> floats; false if any tag is stale
+    __device__ __forceinline__ static bool unpack8(const u32x4 (&r)[4], u32 tag, float (&f)[8]) {
+        bool ok = true;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            f[2 * i] = __uint_as_float(r[i].x); f[2 * i + 1] = __uint_as_float(r[i].z);
+            ok = ok && r[i].y == tag && r[i].w == tag;
+        }
+        return ok;
+    }
+    template <int HD, int G>
+    __device__ bool load_q(const DevModel& M, int b, int j, int sub, float (&qr)[G][8]) const {
+        {   // light poll: a few sampled query / key elements, with pauses
+            const int lane = threadIdx.x & 63;
+            bool ready = false;
+            for (int spins = 0; spins < kSpinLimit && !ready; spins++) {
+                bool ok = true;
+                if (lane < kPollLanes) {
+                    const int e = (lane * (G * HD)) / kPollLanes;
+                    u32x2 p = tld1(M.tq, (b * M.Hq + j * G) * HD + e);
+                    u32x2 k = tld1(M.tkvcur, ((b * 2 + (lane & 1)) * M.Hkv + j) * HD + (lane * HD) / kPollLanes);
+                    ok = p.y == in_tag && k.y == in_tag;
+                }
+                ready = __all(ok);
+                if (!ready) __builtin_amdgcn_s_sleep(16);
+            }
+        }
+        for (int spins = 0; spins < kSpinLimit; spins++) {
+            u32x4 r[G][4];
+#pragma unroll
+            for (int g = 0; g < G; g++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) r[g][i] = tld2(M.tq, (b * M.Hq + (j * G + g)) * HD + sub * 8 + 2 * i);
+            bool ok = true;
+#pragma unroll
+            for (int g = 0; g < G; g++) ok = unpack8(r[g], in_tag, qr[g]) && ok;
+            if (__all(ok)) return true;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        atomicCAS(M.status, 0, -51);
+        return false;
+    }
+    template <int HD>
+    __device__ bool load_cur(const DevModel& M, int b, int j, int sub, float (&kf)[8], float (&vf)[8]) const {
+        for (int spins = 0; spins < kSpinLimit; spins++) {
+            u32x4 rk[4], rv[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                rk[i] = tld2(M.tkvcur, ((b * 2 + 0) * M.Hkv + j) * HD + sub * 8 + 2 * i);
+                rv[i] = tld2(M.tkvcur, ((b * 2 + 1) * M.Hkv + j) * HD + sub * 8 + 2 * i);
+            }
+            bool ok = unpack8(rk, in_tag, kf);
+            ok = unpack8(rv, in_tag, vf) && ok;
+            if (__all(ok)) return true;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        atomicCAS(M.status, 0, -52);
+        return false;
+    }
+    template <int HD>
+    __device__ void store_partial(const DevModel& M, size_t hs, int dim, float ot, float mx, float lt) const {
+        tst(M.tpart_o + hs * HD + dim, ot, out_tag);
+        if (dim == 0) { tst(M.tpart_m + hs, mx, out_tag); tst(M.tpart_l + hs, lt, out_tag); }
+    }
+};
+
+template <int HD, int G, int NW, class XIO>
+__device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, int layer, int b, int j, int t0, int t1, bool with_cur,
                           int split, uint8_t* lds) {
     constexpr int LPR = HD / 8;        // lanes per cache row
     constexpr int RPW = 64 / LPR;      // rows per wave load
-    constexpr int NS = kWaves * RPW;   // partial states per workgroup
+    constexpr int NS = NW * RPW;       // partial states per workgroup
+    constexpr int NT = NW * 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, sub = lane % LPR;
     const float sc = 1.4426950408889634f / sqrtf((float)HD);   // alpha * log2(e)
 
-    float qr[G][8];
-#pragma unroll
-    for (int g = 0; g < G; g++) {
-        const float* qp = M.q + ((size_t)b * M.Hq + (j * G + g)) * HD + sub * 8;
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            float2 v = IO::ld2(qp + e);
-            qr[g][e] = v.x; qr[g][e + 1] = v.y;
-        }
-    }
     float m[G], l[G], o[G][8];
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -292,6 +294,11 @@ __device__ void attn_item(const DevModel& M, const DevKV& KV, int layer, int b, 
 #pragma unroll
         for (int e = 0; e < 8; e++) o[g][e] = 0.f;
     }
+    // cached rows first: issue the first K/V loads before the (possibly waited-for) queries
+    const bf16_t* Kp = KV.plane(M, layer, b, j, 0);
+    const bf16_t* Vp = KV.plane(M, layer, b, j, 1);
+    float qr[G][8];
+    bool ok = xio.template load_q<HD, G>(M, b, j, sub, qr);
     auto update = [&](const float (&kf)[8], const float (&vf)[8], bool valid) {
 #pragma unroll
         for (int g = 0; g < G; g++) {
@@ -311,32 +318,19 @@ __device__ void attn_item(const DevModel& M, const DevKV& KV, int layer, int b, 
             }
         }
     };
-    const bf16_t* Kp = KV.plane(M, layer, b, j, 0);
-    const bf16_t* Vp = KV.plane(M, layer, b, j, 1);
-    for (int tb = t0 + wave * RPW; tb < t1; tb += kWaves * RPW) {
-        int t = tb + grp;
-        bool valid = t < t1;
-        u32x4 kw = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
-        if (valid) {
-            kw = ldg_stream(Kp + (size_t)t * HD + sub * 8);
-            vw = ldg_stream(Vp + (size_t)t * HD + sub * 8);
-        }
+    for (int tb = t0 + wave * RPW; tb < t1; tb += NW * RPW) {
+        int t = min(tb + grp, t1 - 1);
+        bool valid = tb + grp < t1;
+        u32x4 kw = ldg_stream(Kp + (size_t)t * HD + sub * 8);
+        u32x4 vw = ldg_stream(Vp + (size_t)t * HD + sub * 8);
         float kf[8] = {bf_lo(kw.x), bf_hi(kw.x), bf_lo(kw.y), bf_hi(kw.y), bf_lo(kw.z), bf_hi(kw.z), bf_lo(kw.w), bf_hi(kw.w)};
         float vf[8] = {bf_lo(vw.x), bf_hi(vw.x), bf_lo(vw.y), bf_hi(vw.y), bf_lo(vw.z), bf_hi(vw.z), bf_lo(vw.w), bf_hi(vw.w)};
         update(kf, vf, valid);
     }
     if (with_cur && wave == 0) {   // this step's own key/value (uniform branch per wave)
-        const float* kc = M.kvcur + ((size_t)b * 2 + 0) * M.Hkv * HD + (size_t)j * HD + sub * 8;
-        const float* vc = M.kvcur + ((size_t)b * 2 + 1) * M.Hkv * HD + (size_t)j * HD + sub * 8;
         float kf[8], vf[8];
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            float2 a = IO::ld2(kc + e), c = IO::ld2(vc + e);
-            bool mine = grp == 0;
-            kf[e] = mine ? a.x : 0.f; kf[e + 1] = mine ? a.y : 0.f;
-            vf[e] = c.x; vf[e + 1] = c.y;
-        }
-        update(kf, vf, grp == 0);
+        ok = xio.template load_cur<HD>(M, b, j, sub, kf, vf) && ok;
+        update(kf, vf, grp == 0);   // scores reduce over the lanes of one row group: only group 0 is valid
     }
     // ---- merge the NS states of this workgroup ----
     float* sm = (float*)lds;              // [NS][G]
@@ -351,7 +345,7 @@ __device__ void attn_item(const DevModel& M, const DevKV& KV, int layer, int b, 
         for (int e = 0; e < 8; e++) so[((size_t)si * G + g) * HD + sub * 8 + e] = o[g][e];
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < G * HD; idx += kThreads) {
+    for (int idx = threadIdx.x; idx < G * HD; idx += NT) {
         int g = idx / HD, dim = idx % HD;
         float mx = -INFINITY;
         for (int s = 0; s < NS; s++) mx = fmaxf(mx, sm[s * G + g]);
@@ -362,28 +356,126 @@ __device__ void attn_item(const DevModel& M, const DevKV& KV, int layer, int b, 
             ot = fmaf(so[((size_t)s * G + g) * HD + dim], w, ot);
         }
         size_t hs = ((size_t)b * M.Hq + (j * G + g)) * kMaxSplits + split;
-        IO::st(M.part_o + hs * HD + dim, ot);
-        if (dim == 0) { IO::st(M.part_m + hs, mx); IO::st(M.part_l + hs, lt); }
+        xio.template store_partial<HD>(M, hs, dim, ot, mx, lt);
     }
+    return ok;
 }
 
 // Final merge for (b, kv head j) over nsplit partials (paper Section 3.2: combine per-block maximum
 // and denominator, rescale by own/global denominator ratio, sum): writes attn_o[b][h][:].
-template <int HD, int G, class IO>
-__device__ void attn_merge(const DevModel& M, int b, int j, int nsplit) {
-    for (int idx = threadIdx.x; idx < G * HD; idx += kThreads) {
-        int g = idx / HD, dim = idx % HD;
-        size_t hs = ((size_t)b * M.Hq + (j * G + g)) * kMaxSplits;
-        float mx = -INFINITY;
-        for (int s = 0; s < nsplit; s++) mx = fmaxf(mx, IO::ld(M.part_m + hs + s));
-        float lt = 0.f, ot = 0.f;
-        for (int s = 0; s < nsplit; s++) {
-            float w = exp2f(IO::ld(M.part_m + hs + s) - mx);
-            lt = fmaf(IO::ld(M.part_l + hs + s), w, lt);
-            ot = fmaf(IO::ld(M.part_o + (hs + s) * HD + dim), w, ot);
-        }
-        IO::st(M.attn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + dim, ot / lt);
+// Workgroup-collective; uses 2*G*kMaxSplits floats of LDS.
+template <int HD, int G, int NT>
+__device__ void attn_merge(const DevModel& M, int b, int j, int nsplit, float* lds) {
+    typedef PlainIO IO;
+    float* ms = lds;                       // [G][nsplit] maxima, then normalised weights
+    float* ls = lds + G * kMaxSplits;      // [G][nsplit] denominators
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * nsplit; idx += NT) {
+        int g = idx / nsplit, s = idx % nsplit;
+        int hs = (b * M.Hq + (j * G + g)) * kMaxSplits + s;
+        ms[g * kMaxSplits + s] = IO::ld(M.part_m, hs);
+        ls[g * kMaxSplits + s] = IO::ld(M.part_l, hs);
     }
+    __syncthreads();
+    if (threadIdx.x < G) {
+        int g = threadIdx.x;
+        float mx = -INFINITY;
+        for (int s = 0; s < nsplit; s++) mx = fmaxf(mx, ms[g * kMaxSplits + s]);
+        float lt = 0.f;
+        for (int s = 0; s < nsplit; s++) {
+            float w = exp2f(ms[g * kMaxSplits + s] - mx);
+            ms[g * kMaxSplits + s] = w;
+            lt = fmaf(ls[g * kMaxSplits + s], w, lt);
+        }
+        float inv = 1.0f / lt;
+        for (int s = 0; s < nsplit; s++) ms[g * kMaxSplits + s] *= inv;
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * HD / 4; idx += NT) {
+        int g = idx / (HD / 4), d4 = (idx % (HD / 4)) * 4;
+        int hs = (b * M.Hq + (j * G + g)) * kMaxSplits;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+        for (int s = 0; s < nsplit; s++) {
+            float4 o = IO::ld4(M.part_o, (hs + s) * HD + d4);
+            float w = ms[g * kMaxSplits + s];
+            acc.x = fmaf(o.x, w, acc.x); acc.y = fmaf(o.y, w, acc.y); acc.z = fmaf(o.z, w, acc.z); acc.w = fmaf(o.w, w, acc.w);
+        }
+        IO::st4(M.attn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d4, acc);
+    }
+}
+
+// The same merge on tagged partials (fused kernel): the workgroup that computed the LAST split of
+// (b, j) gathers all splits, re-reading until every partial carries this layer's attention tag,
+// and publishes attn_o with the same tag.  Returns false on a time-out.
+template <int HD, int G, int NT>
+__device__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, float* lds) {
+    float* ms = lds;
+    float* ls = lds + G * kMaxSplits;
+    __syncthreads();
+    bool done = false;
+    for (int spins = 0; spins < kSpinLimit && !done; spins++) {
+        bool ok = true;
+        for (int idx = threadIdx.x; idx < G * nsplit; idx += NT) {
+            int g = idx / nsplit, s = idx % nsplit;
+            int hs = (b * M.Hq + (j * G + g)) * kMaxSplits + s;
+            u32x2 pm = __builtin_amdgcn_raw_buffer_load_b64(make_rsrc(M.tpart_m), hs * 8, 0, kAuxSc1);
+            u32x2 pl = __builtin_amdgcn_raw_buffer_load_b64(make_rsrc(M.tpart_l), hs * 8, 0, kAuxSc1);
+            ok = ok && pm.y == tag && pl.y == tag;
+            ms[g * kMaxSplits + s] = __uint_as_float(pm.x);
+            ls[g * kMaxSplits + s] = __uint_as_float(pl.x);
+        }
+        done = __syncthreads_and(ok);
+        if (!done) __builtin_amdgcn_s_sleep(8);
+    }
+    if (!done) { atomicCAS(M.status, 0, -53); return false; }
+    if (threadIdx.x < G) {
+        int g = threadIdx.x;
+        float mx = -INFINITY;
+        for (int s = 0; s < nsplit; s++) mx = fmaxf(mx, ms[g * kMaxSplits + s]);
+        float lt = 0.f;
+        for (int s = 0; s < nsplit; s++) {
+            float w = exp2f(ms[g * kMaxSplits + s] - mx);
+            ms[g * kMaxSplits + s] = w;
+            lt = fmaf(ls[g * kMaxSplits + s], w, lt);
+        }
+        float inv = 1.0f / lt;
+        for (int s = 0; s < nsplit; s++) ms[g * kMaxSplits + s] *= inv;
+    }
+    __syncthreads();
+    constexpr int kSB = 16;   // splits gathered per batch of loads
+    bool all_ok = true;
+    for (int idx = threadIdx.x; idx < G * HD / 2; idx += NT) {
+        int g = idx / (HD / 2), d2 = (idx % (HD / 2)) * 2;
+        int hs = (b * M.Hq + (j * G + g)) * kMaxSplits;
+        float a0 = 0.f, a1 = 0.f;
+        for (int s0 = 0; s0 < nsplit; s0 += kSB) {
+            bool ok = false;
+            u32x4 r[kSB];
+            for (int spins = 0; spins < kSpinLimit && !ok; spins++) {
+                ok = true;
+#pragma unroll
+                for (int u = 0; u < kSB; u++) {
+                    int s = min(s0 + u, nsplit - 1);
+                    r[u] = tld2(M.tpart_o, (hs + s) * HD + d2);
+                }
+#pragma unroll
+                for (int u = 0; u < kSB; u++) ok = ok && r[u].y == tag && r[u].w == tag;
+            }
+            all_ok = all_ok && ok;
+            if (!ok) atomicCAS(M.status, 0, -54);
+#pragma unroll
+            for (int u = 0; u < kSB; u++) {
+                if (s0 + u < nsplit) {
+                    float w = ms[g * kMaxSplits + s0 + u];
+                    a0 = fmaf(__uint_as_float(r[u].x), w, a0);
+                    a1 = fmaf(__uint_as_float(r[u].z), w, a1);
+                }
+            }
+        }
+        tst2(M.tattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, tag);
+    }
+    return __syncthreads_and(all_ok);
 }
 
 // Number of KV splits for a sequence with `ncache` cached rows when `share` workgroups are
@@ -395,19 +487,25 @@ __device__ __forceinline__ int attn_nsplit(int ncache, int share) {
 }
 
 // ---------------------------------------------------------------- epilogues
+// No epilogue of the fused kernel issues a global LOAD: vector-memory operations of a wave complete
+// in issue order, so a load in the middle of the weight stream would drain the whole prefetch
+// pipeline.  What an epilogue needs beyond the dot products comes from LDS (RoPE cos/sin) or from
+// scalar loads (positions).
+//
 // QKV rows in packed order: q heads then k heads with RoPE partners (i, i+hd/2) adjacent, then v.
 template <class IO>
 struct EpiQKV {
     const DevModel& M; const DevKV& KV; const int* pos; int layer;
+    const float2* rope;   // [batch][hd/2] (cos, sin) of each sequence's position; LDS in the fused kernel
     __device__ void operator()(int pair, int b, float v0, float v1) const {
         const int half = M.hd / 2;
         const int nq = M.Hq * half, nk = M.Hkv * half;
-        const int p = pos[b];
+        const int p = as_global(pos)[b];
         if (pair < nq + nk) {
             bool isq = pair < nq;
             int pp = isq ? pair : pair - nq;
             int head = pp / half, i = pp % half;
-            float2 cs = KV.rope[(size_t)p * half + i];
+            float2 cs = rope[b * half + i];
             float a = v0 * cs.x - v1 * cs.y;
             float c = v1 * cs.x + v0 * cs.y;
             if (isq) {
@@ -416,7 +514,7 @@ struct EpiQKV {
             } else {
                 bf16_t ab = f_to_bf(a), cb = f_to_bf(c);
                 bf16_t* row = KV.plane(M, layer, b, head, 0) + (size_t)p * M.hd;
-                row[i] = ab; row[i + half] = cb;
+                as_global(row)[i] = ab; as_global(row)[i + half] = cb;
                 float* kc = M.kvcur + ((size_t)b * 2 + 0) * M.Hkv * M.hd + (size_t)head * M.hd;
                 IO::st(kc + i, bf_to_f(ab)); IO::st(kc + i + half, bf_to_f(cb));
             }
@@ -425,21 +523,19 @@ struct EpiQKV {
             int head = pp / half, i = (pp % half) * 2;
             bf16_t ab = f_to_bf(v0), cb = f_to_bf(v1);
             bf16_t* row = KV.plane(M, layer, b, head, 1) + (size_t)p * M.hd;
-            *(u32*)(row + i) = (u32)ab | ((u32)cb << 16);
+            *as_global((u32*)(row + i)) = (u32)ab | ((u32)cb << 16);
             float* vc = M.kvcur + ((size_t)b * 2 + 1) * M.Hkv * M.hd + (size_t)head * M.hd;
             IO::st2(vc + i, bf_to_f(ab), bf_to_f(cb));
         }
     }
 };
-// x[b][row] += W row . input   (attention output projection and GLU output projection: both add
-// straight into the residual stream, paper Section 3.2)
-template <class IO>
+// Per-operation kernels: x[b][row] += W row . input
 struct EpiResidual {
     float* x; int d;
     __device__ void operator()(int pair, int b, float v0, float v1) const {
-        float* p = x + (size_t)b * d + 2 * pair;
-        float2 o = IO::ld2(p);
-        IO::st2(p, o.x + v0, o.y + v1);
+        FF_GLOBAL f32x2* p = as_global((f32x2*)(x + (size_t)b * d + 2 * pair));
+        f32x2 o = *p;
+        *p = f32x2{o.x + v0, o.y + v1};
     }
 };
 // packed rows (2i, 2i+1) = (gate_i, up_i):  h_i = silu(gate_i) * up_i
@@ -451,10 +547,56 @@ struct EpiSwiGLU {
         IO::st(h + (size_t)b * F + pair, s * u);
     }
 };
+// ---- fused-kernel epilogues: outputs go to the tagged exchange buffers ----
+struct EpiQKVTagged {
+    const DevModel& M; const DevKV& KV; const int* pos; int layer; const float2* rope; u32 tag;
+    __device__ void operator()(int pair, int b, float v0, float v1) const {
+        const int half = M.hd / 2;
+        const int nq = M.Hq * half, nk = M.Hkv * half;
+        const int p = as_global(pos)[b];
+        if (pair < nq + nk) {
+            bool isq = pair < nq;
+            int pp = isq ? pair : pair - nq;
+            int head = pp / half, i = pp % half;
+            float2 cs = rope[b * half + i];
+            float a = v0 * cs.x - v1 * cs.y;
+            float c = v1 * cs.x + v0 * cs.y;
+            if (isq) {
+                tagged_t* qp = M.tq + ((size_t)b * M.Hq + head) * M.hd;
+                tst(qp + i, a, tag); tst(qp + i + half, c, tag);
+            } else {
+                bf16_t ab = f_to_bf(a), cb = f_to_bf(c);
+                bf16_t* row = KV.plane(M, layer, b, head, 0) + (size_t)p * M.hd;
+                as_global(row)[i] = ab; as_global(row)[i + half] = cb;
+                tagged_t* kc = M.tkvcur + ((size_t)b * 2 + 0) * M.Hkv * M.hd + (size_t)head * M.hd;
+                tst(kc + i, bf_to_f(ab), tag); tst(kc + i + half, bf_to_f(cb), tag);
+            }
+        } else {
+            int pp = pair - nq - nk;
+            int head = pp / half, i = (pp % half) * 2;
+            bf16_t ab = f_to_bf(v0), cb = f_to_bf(v1);
+            bf16_t* row = KV.plane(M, layer, b, head, 1) + (size_t)p * M.hd;
+            *as_global((u32*)(row + i)) = (u32)ab | ((u32)cb << 16);
+            tagged_t* vc = M.tkvcur + ((size_t)b * 2 + 1) * M.Hkv * M.hd + (size_t)head * M.hd;
+            tst2(vc + i, bf_to_f(ab), bf_to_f(cb), tag);
+        }
+    }
+};
+struct EpiDeltaTagged {   // projections feeding the residual stream: publish the output, the next
+    tagged_t* delta; int d; u32 tag;   // normalised staging adds it (paper Section 3.2: added to the residual)
+    __device__ void operator()(int pair, int b, float v0, float v1) const { tst2(delta + (size_t)b * d + 2 * pair, v0, v1, tag); }
+};
+struct EpiSwiGLUTagged {   // packed rows (2i, 2i+1) = (gate_i, up_i):  h_i = silu(gate_i) * up_i
+    tagged_t* h; int F; u32 tag;
+    __device__ void operator()(int pair, int b, float g, float u) const {
+        float s = g / (1.0f + expf(-g));
+        tst(h + (size_t)b * F + pair, s * u, tag);
+    }
+};
 struct EpiStore {   // plain output rows (logits; per-op raw projections)
     float* y; int n;
     __device__ void operator()(int pair, int b, float v0, float v1) const {
-        float* p = y + (size_t)b * n + 2 * pair;
+        FF_GLOBAL float* p = as_global(y + (size_t)b * n + 2 * pair);
         p[0] = v0;
         if (2 * pair + 1 < n) p[1] = v1;
     }

@@ -1,6 +1,7 @@
 // C ABI of the MI355X whole-model decode library (see include/flashformer.h).
 #include "../../include/flashformer.h"
-#include "ff_kernels.h"
+#include "ff_fused.h"
+#include "ff_ops.h"
 
 #include <cstdarg>
 #include <cstdio>
@@ -41,7 +42,8 @@ struct Plan {
     MatPlan lm;
     size_t packed_bytes;
     // scratch
-    size_t x, xn, q, kvcur, attn_o, h, y, part_m, part_l, part_o, head_ctr, bar_flags, status, scratch_bytes;
+    size_t x, xn, q, kvcur, attn_o, h, y, part_m, part_l, part_o, status, scratch_bytes;
+    size_t tx, tx2, tdelta, tq, tkvcur, tattn_o, th, tpart_m, tpart_l, tpart_o;
 };
 
 size_t mat_w_bytes(int n, int k, int wd) { return wd == W_BF16 ? (size_t)n * k * 2 : wd == W_INT8 ? (size_t)n * k : (size_t)n * k / 2; }
@@ -107,8 +109,16 @@ Plan make_plan(const ff_config& c) {
     P.part_m = take(mb * c.n_q_heads * kMaxSplits * 4);
     P.part_l = take(mb * c.n_q_heads * kMaxSplits * 4);
     P.part_o = take(mb * c.n_q_heads * kMaxSplits * c.head_dim * 4);
-    P.head_ctr = take(mb * c.n_kv_heads * 4);
-    P.bar_flags = take(4096 * 4);
+    P.tx = take(mb * c.d_model * 8);
+    P.tx2 = take(mb * c.d_model * 8);
+    P.tdelta = take(mb * c.d_model * 8);
+    P.tq = take(mb * qd * 8);
+    P.tkvcur = take(mb * 2 * c.n_kv_heads * c.head_dim * 8);
+    P.tattn_o = take(mb * qd * 8);
+    P.th = take(mb * c.d_ffn * 8);
+    P.tpart_m = take(mb * c.n_q_heads * kMaxSplits * 8);
+    P.tpart_l = take(mb * c.n_q_heads * kMaxSplits * 8);
+    P.tpart_o = take(mb * c.n_q_heads * kMaxSplits * c.head_dim * 8);
     P.status = take(256);
     P.scratch_bytes = s;
     return P;
@@ -187,24 +197,6 @@ int check_step_args(ff_model* m, const int32_t* tokens, const int32_t* pos, ff_k
 }
 
 template <int WD, int B>
-int launch_fused(ff_model* m, const int32_t* tokens, const int32_t* pos, ff_kv* kv, float* logits, int batch, hipStream_t st) {
-    auto kern = fused_decode_kernel<WD, B>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        int rc = set_lds(kern, m->lds_bytes);
-        if (rc) return rc;
-        int occ = 0;
-        HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, kThreads, m->lds_bytes));
-        if (occ < 1) return fail(FF_ERR_UNSUPPORTED, "fused kernel does not fit on a compute unit");
-        attr_set = true;
-    }
-    kern<<<m->n_cta, kThreads, m->lds_bytes, st>>>(m->dev, kv->dev, tokens, pos, logits, batch, m->bar_gen);
-    HIPCHK(hipGetLastError());
-    m->bar_gen += (uint32_t)(kBarriersPerLayer * m->cfg.n_layers);
-    return FF_OK;
-}
-
-template <int WD, int B>
 int launch_gemv(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st) {
     auto kern = op_gemv<WD, B>;
     static bool attr_set = false;
@@ -272,9 +264,8 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     m->head_loaded = false;
     m->bar_gen = 0;
     m->n_cta = prop.multiProcessorCount;
-    m->lds_bytes = kLdsActBytes + kLdsAuxBytes;
+    m->lds_bytes = kLdsActBytes + kLdsAuxBytes + kMaxBatch * 64 * sizeof(float2) + 64;
     if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
-    if (m->n_cta > 4096) { delete m; return fail(FF_ERR_UNSUPPORTED, "too many compute units"); }
 
     DevModel& D = m->dev;
     D.L = cfg->n_layers; D.d = cfg->d_model; D.Hq = cfg->n_q_heads; D.Hkv = cfg->n_kv_heads; D.hd = cfg->head_dim;
@@ -287,7 +278,11 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     D.x = (float*)(s + P.x); D.xn = (float*)(s + P.xn); D.q = (float*)(s + P.q); D.kvcur = (float*)(s + P.kvcur);
     D.attn_o = (float*)(s + P.attn_o); D.h = (float*)(s + P.h); D.y = (float*)(s + P.y);
     D.part_m = (float*)(s + P.part_m); D.part_l = (float*)(s + P.part_l); D.part_o = (float*)(s + P.part_o);
-    D.head_ctr = (u32*)(s + P.head_ctr); D.bar_flags = (u32*)(s + P.bar_flags); D.status = (int*)(s + P.status);
+    D.status = (int*)(s + P.status);
+    D.tx = (u32x2*)(s + P.tx); D.tx2 = (u32x2*)(s + P.tx2); D.tdelta = (u32x2*)(s + P.tdelta); D.tq = (u32x2*)(s + P.tq);
+    D.tkvcur = (u32x2*)(s + P.tkvcur); D.tattn_o = (u32x2*)(s + P.tattn_o); D.th = (u32x2*)(s + P.th);
+    D.tpart_m = (u32x2*)(s + P.tpart_m); D.tpart_l = (u32x2*)(s + P.tpart_l); D.tpart_o = (u32x2*)(s + P.tpart_o);
+    D.dbg = nullptr;
     for (int l = 0; l < cfg->n_layers; l++) {
         const LayerPlan& L = P.layers[l];
         PLayer pl;
@@ -424,17 +419,24 @@ int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positi
     int rc = check_step_args(m, tokens_dev, positions_dev, kv, logits_dev, batch);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    int bt = batch == 1 ? 1 : batch == 2 ? 2 : 4;
-#define FF_FUSED(WD)                                                                                         \
-    (bt == 1   ? launch_fused<WD, 1>(m, tokens_dev, positions_dev, kv, logits_dev, batch, st)                 \
-     : bt == 2 ? launch_fused<WD, 2>(m, tokens_dev, positions_dev, kv, logits_dev, batch, st)                 \
-               : launch_fused<WD, 4>(m, tokens_dev, positions_dev, kv, logits_dev, batch, st))
-    switch (m->cfg.wdtype) {
-        case W_BF16: return FF_FUSED(W_BF16);
-        case W_INT8: return FF_FUSED(W_INT8);
-        default: return FF_FUSED(W_INT4);
+    const int lm_in_kernel = m->dev.lm.wd == m->cfg.wdtype;
+    FusedLaunch a{m->dev, kv->dev, tokens_dev, positions_dev, logits_dev, batch, m->bar_gen, lm_in_kernel, m->n_cta, m->lds_bytes, st};
+    const char* what = "";
+    hipError_t e = m->cfg.wdtype == W_BF16 ? launch_fused_bf16(a, &what)
+                 : m->cfg.wdtype == W_INT8 ? launch_fused_int8(a, &what)
+                                           : launch_fused_int4(a, &what);
+    if (e != hipSuccess) return fail(e == hipErrorLaunchOutOfResources ? FF_ERR_UNSUPPORTED : FF_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    // exchange tags only grow: every step uses a fresh range, so values of earlier steps never match
+    m->bar_gen += (uint32_t)(kTagsPerLayer * m->cfg.n_layers + 1);
+    if (!lm_in_kernel) {   // LM head of a different weight type than the layers: separate launches
+        const ff_config& c = m->cfg;
+        op_final_x<<<16, kThreads, 0, st>>>(m->dev.x, m->dev.tx, m->dev.tdelta, batch * c.d_model);
+        op_rmsnorm<<<batch, kThreads, 0, st>>>(m->dev.x, m->dev.gf, m->dev.xn, c.d_model, c.rms_eps);
+        int rc = gemv_op(m, m->dev.lm, m->dev.xn, c.d_model, logits_dev, batch, EPI_STORE, st);
+        if (rc) return rc;
+        HIPCHK(hipGetLastError());
     }
-#undef FF_FUSED
+    return FF_OK;
 }
 
 int ff_decode_step_perop(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev,
@@ -482,7 +484,8 @@ int ff_status(ff_model* m, void* stream) {
     if (s != 0) {
         HIPCHK(hipMemset(m->dev.status, 0, sizeof(int)));
         if (s == kStatusRange) return fail(FF_ERR_RANGE, "a decode step saw a position >= max_ctx or a token id >= vocab and was skipped");
-        if (s == kStatusTimeout) return fail(FF_ERR_TIMEOUT, "grid barrier timed out: workgroups were not co-resident");
+        if (s <= -50 || s == kStatusTimeout)
+            return fail(FF_ERR_TIMEOUT, "a workgroup gave up waiting for another workgroup's output (site code %d): workgroups not co-resident?", s);
         return fail(FF_ERR_HIP, "unknown device status %d", s);
     }
     return FF_OK;
@@ -512,11 +515,17 @@ int ff_debug_dequant(const ff_model* m, int32_t layer, int32_t which, float* out
     return FF_OK;
 }
 
+int ff_debug_timeline(ff_model* m, void* buf_dev) {
+    if (!m) return fail(FF_ERR_ARG, "null argument");
+    m->dev.dbg = (u64*)buf_dev;
+    return FF_OK;
+}
+
 int ff_fused_schedule(const ff_model* m, int32_t* barriers_per_step, int32_t* n_workgroups, int32_t* threads_per_workgroup) {
     if (!m) return fail(FF_ERR_ARG, "null argument");
-    if (barriers_per_step) *barriers_per_step = kBarriersPerLayer * m->cfg.n_layers;
+    if (barriers_per_step) *barriers_per_step = 0;   // phases are ordered by tagged dataflow, not by grid barriers
     if (n_workgroups) *n_workgroups = m->n_cta;
-    if (threads_per_workgroup) *threads_per_workgroup = kThreads;
+    if (threads_per_workgroup) *threads_per_workgroup = kFusedThreads;
     return FF_OK;
 }
 

@@ -61,3 +61,43 @@ def compare_logits(got: np.ndarray, ref: np.ndarray):
     rel_l2 = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
     same = (got.argmax(axis=1) == ref.argmax(axis=1))
     return max_abs, rel_l2, same
+
+
+def both_sides_gpu_generated(shape, seed, wdtype, batch, T0, max_ctx, n_caches=1, quant_lm_head=True, device="cuda:0"):
+    """Full-size set-up: every tensor is produced once by the seeded generators on the GPU (fast),
+    handed to the HIP loader, and copied to the host for the oracle.  The generators are
+    bit-identical on both devices, so this equals generating twice."""
+    from oracle import oracle
+    from paper_2505_22758_amd import binding
+
+    def to_cpu(obj):
+        return {k: to_cpu(v) for k, v in obj.items()} if isinstance(obj, dict) else obj.cpu()
+
+    dec = binding.Decoder(shape, wdtype, max_batch=batch, quant_lm_head=quant_lm_head, device=device)
+    cpu_layers = []
+    for l in range(shape.n_layers):
+        lw = synth.make_layer(shape, seed, l, wdtype, device)
+        dec.load_layer(l, lw)
+        cpu_layers.append(to_cpu(lw))
+        torch.cuda.synchronize()
+        del lw
+    hw = synth.make_head(shape, seed, wdtype, device, quant_lm_head)
+    dec.load_head(hw)
+    cpu_head = to_cpu(hw)
+    torch.cuda.synchronize()
+    del hw
+    M = oracle.OracleModel(shape, cpu_layers, cpu_head)
+    okv = M.new_kv(batch, max_ctx)
+    caches = []
+    for _ in range(n_caches):
+        buf = torch.zeros(binding.ff_kv_bytes(dec.model, batch, max_ctx), dtype=torch.uint8, device=device)
+        caches.append((binding.ff_kv_alloc(dec.model, batch, max_ctx, buf), buf))
+    for l in range(shape.n_layers):
+        for b in range(batch):
+            if T0 > 0:
+                k, v = synth.make_kv_prefill(shape, seed, l, b, T0, device)
+                for kv, _ in caches:
+                    binding.ff_kv_fill(kv, l, b, 0, k, v)
+                okv[l, b, 0, :T0], okv[l, b, 1, :T0] = oracle._np(k.cpu()), oracle._np(v.cpu())
+    torch.cuda.synchronize()
+    return M, okv, dec, caches

@@ -10,12 +10,15 @@ from tests import helpers
 pytestmark = pytest.mark.gpu
 
 
-def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, positions_offset=None):
+def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, gpu_generated=False):
     from paper_2505_22758_amd import binding
     from oracle import oracle
     max_ctx = T0 + steps + 3
-    M, okv = helpers.oracle_side(shape, seed, wdtype, batch, T0, max_ctx)
-    dec, caches = helpers.hip_side(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2)
+    if gpu_generated:
+        M, okv, dec, caches = helpers.both_sides_gpu_generated(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2)
+    else:
+        M, okv = helpers.oracle_side(shape, seed, wdtype, batch, T0, max_ctx)
+        dec, caches = helpers.hip_side(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2)
     toks = synth.make_tokens(shape, seed, steps, batch)
     logits_f = torch.zeros(batch, shape.vocab, dtype=torch.float32, device="cuda:0")
     logits_p = torch.zeros_like(logits_f)
@@ -54,7 +57,9 @@ def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, po
                         want = okv[l, b, kv_i, T0:T0 + steps]
                         gv, wv = oracle.bf16_bits_to_f64(got), oracle.bf16_bits_to_f64(want)
                         ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(wv), 1e-30))) - 7)
-                        assert np.all(np.abs(gv - wv) <= np.maximum(ulp, 1e-5)), "appended cache row is off by more than one bf16 step"
+                        # one bf16 step, or (for values near zero) the fp32 accumulation error of the projection
+                        excess = float(np.max(np.abs(gv - wv) - np.maximum(ulp, 1e-4)))
+                        assert excess <= 0, f"appended cache row off by more than one bf16 step (layer {l}, seq {b}, kv {kv_i}, excess {excess:.3e})"
                         mism += int((got != want).sum())
                         tot += got.size
             assert mism <= max(2, tot // 200), (mism, tot)
@@ -89,3 +94,9 @@ def test_tiny_bf16_empty_cache_and_ragged_lengths():
 def test_tiny_bf16_batches_2_3_4():
     for b in (2, 3, 4):
         _run_teacher_forced(synth.TINY, 20 + b, synth.WDTYPE_BF16, batch=b, T0=40, steps=3)
+
+
+def test_llama8b_bf16_batch1_ctx1024_full_size():
+    """The benchmark workload at full size (32 layers, d 4096, vocab 128256, ctx 1024), in the
+    launch configuration bench.py times; every logit of three teacher-forced steps is compared."""
+    _run_teacher_forced(synth.LLAMA_8B, 0x250522758, synth.WDTYPE_BF16, batch=1, T0=1024, steps=3, gpu_generated=True)
