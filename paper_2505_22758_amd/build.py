@@ -6,7 +6,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflashformer.so")
-SOURCES = ["flashformer.hip", "ff_fused_bf16.hip", "ff_fused_int8.hip", "ff_fused_int4.hip"]
+SOURCES = ["flashformer.hip"] + [f"ff_fused_{w}_hd{h}_g{g}.hip" for w in ("bf16", "int8", "int4")
+                               for h, g in ((64, 4), (128, 4), (128, 8))]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -120,7 +120,7 @@ __device__ __forceinline__ void phase_advance(const PhaseDesc& D, PhaseState& X)
     if (D.kind == PH_QKV || D.kind == PH_GU) { tagged_t* t = X.xcur; X.xcur = X.xnext; X.xnext = t; }
 }
 
-template <int WD, int B>
+template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
                                                                      int batch, u32 tag_base, int lm_in_kernel) {
@@ -177,7 +177,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             // split-KV attention + merge; the ring keeps the output projection's tiles meanwhile
             __syncthreads();   // every wave has finished reading the staged input: LDS is free
             if (wave == 0) dbg_event(M, ph, EV_ATT_START, lane);
-            const bool ok = attention_phase_tagged<kFusedWaves>(M, KV, pos, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
                                                                 tag_of(tag_base, D.layer, TAG_ATT));
             if (wave == 0) dbg_event(M, ph, EV_ATT_END, lane);
             if (!ok) return;
@@ -191,9 +191,9 @@ struct FusedLaunch {
     DevModel M; DevKV KV; const int* tokens; const int* pos; float* logits;
     int batch; u32 tag_base; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream;
 };
-template <int WD, int B>
+template <int WD, int B, int HD, int G>
 inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what) {
-    auto kern = fused_decode_kernel<WD, B>;
+    auto kern = fused_decode_kernel<WD, B, HD, G>;
     static bool ready = false;
     if (!ready) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
@@ -208,14 +208,19 @@ inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what)
     *what = "fused kernel launch";
     return hipGetLastError();
 }
-template <int WD>
+template <int WD, int HD, int G>
 inline hipError_t launch_fused_family(const FusedLaunch& a, const char** what) {
-    if (a.batch == 1) return launch_fused_instance<WD, 1>(a, what);
-    if (a.batch == 2) return launch_fused_instance<WD, 2>(a, what);
-    return launch_fused_instance<WD, 4>(a, what);
+    if (a.batch == 1) return launch_fused_instance<WD, 1, HD, G>(a, what);
+    if (a.batch == 2) return launch_fused_instance<WD, 2, HD, G>(a, what);
+    return launch_fused_instance<WD, 4, HD, G>(a, what);
 }
-hipError_t launch_fused_bf16(const FusedLaunch& a, const char** what);
-hipError_t launch_fused_int8(const FusedLaunch& a, const char** what);
-hipError_t launch_fused_int4(const FusedLaunch& a, const char** what);
+// One definition per (weight type, head geometry), each in its own translation unit.
+#define FF_FUSED_FAMILIES(X) \
+    X(bf16, W_BF16, 64, 4) X(bf16, W_BF16, 128, 4) X(bf16, W_BF16, 128, 8) \
+    X(int8, W_INT8, 64, 4) X(int8, W_INT8, 128, 4) X(int8, W_INT8, 128, 8) \
+    X(int4, W_INT4, 64, 4) X(int4, W_INT4, 128, 4) X(int4, W_INT4, 128, 8)
+#define FF_DECLARE_FAMILY(name, wd, hd, g) hipError_t launch_fused_##name##_hd##hd##_g##g(const FusedLaunch& a, const char** what);
+FF_FUSED_FAMILIES(FF_DECLARE_FAMILY)
+#undef FF_DECLARE_FAMILY
 
 }  // namespace ff

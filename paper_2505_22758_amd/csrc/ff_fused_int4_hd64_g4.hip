@@ -1,0 +1,5 @@
+// Fused decode kernel instances: int4 weights, head_dim 64, 4 query heads per kv head.
+#include "ff_fused.h"
+namespace ff {
+hipError_t launch_fused_int4_hd64_g4(const FusedLaunch& a, const char** what) { return launch_fused_family<W_INT4, 64, 4>(a, what); }
+}  // namespace ff

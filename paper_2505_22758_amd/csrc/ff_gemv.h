@@ -330,7 +330,14 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
     // steady state: every slot is consumed and refilled
     for (; it + 2 * kDepth <= S.n_it; it += kDepth) {
 #pragma unroll
-        for (int s = 0; s < kDepth; s++) { compute(ring[s]); load(ring[s]); }
+        for (int s = 0; s < kDepth; s++) {
+            // keep the instruction scheduler from hoisting a slot's refill above the FMAs that
+            // still read the slot: that doubles the live tile registers and ends in spills
+            compute(ring[s]);
+            __builtin_amdgcn_sched_barrier(0);
+            load(ring[s]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     // tail
     for (; it < S.n_it; it += kDepth) {
@@ -338,7 +345,9 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
         for (int s = 0; s < kDepth; s++) {
             if (it + s < S.n_it) {
                 compute(ring[s]);
+                __builtin_amdgcn_sched_barrier(0);
                 if (it + s + kDepth < S.n_it) load(ring[s]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }

@@ -48,12 +48,13 @@ __device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const 
 
 // Fused kernel: queries / current k,v are awaited through their tags; the workgroup that owns the
 // last split of (b, j) also merges all splits of that head group (paper Section 3.2: the reduction
-// is fused into the attention pass instead of a separate kernel).
-template <int NW>
-__device__ __noinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
-                                                    uint8_t* lds, u32 in_tag, u32 out_tag) {
+// is fused into the attention pass instead of a separate kernel).  The head geometry is a template
+// parameter here (one kernel instance per geometry) to keep the register footprint of the fused
+// kernel down to what the model at hand needs.
+template <int NW, int HD, int G>
+__device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
+                                                       uint8_t* lds, u32 in_tag, u32 out_tag) {
     constexpr int NT = NW * 64;
-    const int G = M.Hq / M.Hkv;
     const int share = max(1, (int)gridDim.x / (batch * M.Hkv));
     int base = 0;
     bool ok = true;
@@ -68,14 +69,8 @@ __device__ __noinline__ bool attention_phase_tagged(const DevModel& M, const Dev
             int j = it / ns, s = it % ns;
             int t0 = (int)((long)T * s / ns), t1 = (int)((long)T * (s + 1) / ns);
             bool cur = s == ns - 1;
-            if (M.hd == 64 && G == 4) ok = attn_item<64, 4, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds) && ok;
-            else if (M.hd == 128 && G == 4) ok = attn_item<128, 4, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds) && ok;
-            else if (M.hd == 128 && G == 8) ok = attn_item<128, 8, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds) && ok;
-            if (cur) {
-                if (M.hd == 64 && G == 4) ok = attn_merge_tagged<64, 4, NT>(M, b, j, ns, out_tag, (float*)lds) && ok;
-                else if (M.hd == 128 && G == 4) ok = attn_merge_tagged<128, 4, NT>(M, b, j, ns, out_tag, (float*)lds) && ok;
-                else if (M.hd == 128 && G == 8) ok = attn_merge_tagged<128, 8, NT>(M, b, j, ns, out_tag, (float*)lds) && ok;
-            }
+            ok = attn_item<HD, G, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds) && ok;
+            if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, (float*)lds) && ok;
         }
         base = (base + nitems) % (int)gridDim.x;
     }

@@ -220,23 +220,25 @@ struct TaggedAttnIO {
         }
         return ok;
     }
+    // a few sampled query / key elements, with pauses: sits out a QKV projection that is still running
+    template <int HD, int G>
+    __device__ void light_poll(const DevModel& M, int b, int j) const {
+        const int lane = threadIdx.x & 63;
+        bool ready = false;
+        for (int spins = 0; spins < kSpinLimit && !ready; spins++) {
+            bool ok = true;
+            if (lane < kPollLanes) {
+                const int e = (lane * (G * HD)) / kPollLanes;
+                u32x2 p = tld1(M.tq, (b * M.Hq + j * G) * HD + e);
+                u32x2 k = tld1(M.tkvcur, ((b * 2 + (lane & 1)) * M.Hkv + j) * HD + (lane * HD) / kPollLanes);
+                ok = p.y == in_tag && k.y == in_tag;
+            }
+            ready = __all(ok);
+            if (!ready) __builtin_amdgcn_s_sleep(8);
+        }
+    }
     template <int HD, int G>
     __device__ bool load_q(const DevModel& M, int b, int j, int sub, float (&qr)[G][8]) const {
-        {   // light poll: a few sampled query / key elements, with pauses
-            const int lane = threadIdx.x & 63;
-            bool ready = false;
-            for (int spins = 0; spins < kSpinLimit && !ready; spins++) {
-                bool ok = true;
-                if (lane < kPollLanes) {
-                    const int e = (lane * (G * HD)) / kPollLanes;
-                    u32x2 p = tld1(M.tq, (b * M.Hq + j * G) * HD + e);
-                    u32x2 k = tld1(M.tkvcur, ((b * 2 + (lane & 1)) * M.Hkv + j) * HD + (lane * HD) / kPollLanes);
-                    ok = p.y == in_tag && k.y == in_tag;
-                }
-                ready = __all(ok);
-                if (!ready) __builtin_amdgcn_s_sleep(16);
-            }
-        }
         for (int spins = 0; spins < kSpinLimit; spins++) {
             u32x4 r[G][4];
 #pragma unroll
@@ -247,7 +249,7 @@ struct TaggedAttnIO {
 #pragma unroll
             for (int g = 0; g < G; g++) ok = unpack8(r[g], in_tag, qr[g]) && ok;
             if (__all(ok)) return true;
-            __builtin_amdgcn_s_sleep(8);
+            light_poll<HD, G>(M, b, j);
         }
         atomicCAS(M.status, 0, -51);
         return false;
@@ -294,11 +296,10 @@ __device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, in
 #pragma unroll
         for (int e = 0; e < 8; e++) o[g][e] = 0.f;
     }
-    // cached rows first: issue the first K/V loads before the (possibly waited-for) queries
     const bf16_t* Kp = KV.plane(M, layer, b, j, 0);
     const bf16_t* Vp = KV.plane(M, layer, b, j, 1);
     float qr[G][8];
-    bool ok = xio.template load_q<HD, G>(M, b, j, sub, qr);
+    bool ok = true, have_q = false;
     auto update = [&](const float (&kf)[8], const float (&vf)[8], bool valid) {
 #pragma unroll
         for (int g = 0; g < G; g++) {
@@ -318,15 +319,27 @@ __device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, in
             }
         }
     };
-    for (int tb = t0 + wave * RPW; tb < t1; tb += NW * RPW) {
-        int t = min(tb + grp, t1 - 1);
-        bool valid = tb + grp < t1;
-        u32x4 kw = ldg_stream(Kp + (size_t)t * HD + sub * 8);
-        u32x4 vw = ldg_stream(Vp + (size_t)t * HD + sub * 8);
-        float kf[8] = {bf_lo(kw.x), bf_hi(kw.x), bf_lo(kw.y), bf_hi(kw.y), bf_lo(kw.z), bf_hi(kw.z), bf_lo(kw.w), bf_hi(kw.w)};
-        float vf[8] = {bf_lo(vw.x), bf_hi(vw.x), bf_lo(vw.y), bf_hi(vw.y), bf_lo(vw.z), bf_hi(vw.z), bf_lo(vw.w), bf_hi(vw.w)};
-        update(kf, vf, valid);
+    // Cached rows do not depend on this step: their loads are issued (kAttnBatch wave-loads at a
+    // time) BEFORE the queries are waited for, so the wait for the QKV projection overlaps them.
+    constexpr int kAttnBatch = 4;
+    for (int tb0 = t0 + wave * RPW; tb0 < t1; tb0 += NW * RPW * kAttnBatch) {
+        u32x4 kw[kAttnBatch], vw[kAttnBatch];
+#pragma unroll
+        for (int i = 0; i < kAttnBatch; i++) {
+            const int t = min(tb0 + i * NW * RPW + grp, t1 - 1);   // clamped: every load is issued
+            kw[i] = ldg_stream(Kp + (size_t)t * HD + sub * 8);
+            vw[i] = ldg_stream(Vp + (size_t)t * HD + sub * 8);
+        }
+        if (!have_q) { ok = xio.template load_q<HD, G>(M, b, j, sub, qr); have_q = true; }
+#pragma unroll
+        for (int i = 0; i < kAttnBatch; i++) {
+            const bool valid = tb0 + i * NW * RPW + grp < t1;
+            float kf[8] = {bf_lo(kw[i].x), bf_hi(kw[i].x), bf_lo(kw[i].y), bf_hi(kw[i].y), bf_lo(kw[i].z), bf_hi(kw[i].z), bf_lo(kw[i].w), bf_hi(kw[i].w)};
+            float vf[8] = {bf_lo(vw[i].x), bf_hi(vw[i].x), bf_lo(vw[i].y), bf_hi(vw[i].y), bf_lo(vw[i].z), bf_hi(vw[i].z), bf_lo(vw[i].w), bf_hi(vw[i].w)};
+            update(kf, vf, valid);
+        }
     }
+    if (!have_q) ok = xio.template load_q<HD, G>(M, b, j, sub, qr);
     if (with_cur && wave == 0) {   // this step's own key/value (uniform branch per wave)
         float kf[8], vf[8];
         ok = xio.template load_cur<HD>(M, b, j, sub, kf, vf) && ok;

@@ -422,9 +422,13 @@ int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positi
     const int lm_in_kernel = m->dev.lm.wd == m->cfg.wdtype;
     FusedLaunch a{m->dev, kv->dev, tokens_dev, positions_dev, logits_dev, batch, m->bar_gen, lm_in_kernel, m->n_cta, m->lds_bytes, st};
     const char* what = "";
-    hipError_t e = m->cfg.wdtype == W_BF16 ? launch_fused_bf16(a, &what)
-                 : m->cfg.wdtype == W_INT8 ? launch_fused_int8(a, &what)
-                                           : launch_fused_int4(a, &what);
+    const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
+    hipError_t e = hipErrorInvalidValue;
+    what = "no fused kernel instance for this configuration";
+#define FF_TRY_FAMILY(name, wd, hd, g) \
+    if (m->cfg.wdtype == wd && m->cfg.head_dim == hd && G == g) e = launch_fused_##name##_hd##hd##_g##g(a, &what);
+    FF_FUSED_FAMILIES(FF_TRY_FAMILY)
+#undef FF_TRY_FAMILY
     if (e != hipSuccess) return fail(e == hipErrorLaunchOutOfResources ? FF_ERR_UNSUPPORTED : FF_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
     // exchange tags only grow: every step uses a fresh range, so values of earlier steps never match
     m->bar_gen += (uint32_t)(kTagsPerLayer * m->cfg.n_layers + 1);
