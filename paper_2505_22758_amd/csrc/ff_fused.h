@@ -166,8 +166,14 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
                 return;
             }
             if (wave == 0) dbg_event(M, ph, EV_SYNCED, lane);
+            if (M.dbg && D.layer == 1 && lane == 0 && D.kind == PH_GU)
+                as_global(M.dbg)[(size_t)n_phases * kEvSlots + ((size_t)blockIdx.x * kFusedWaves + wave) * 8 + 6] = wall_clock64();
             gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
             if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
+            if (M.dbg && D.layer == 1 && lane == 0) {   // per-wave completion times of layer 1 (load-balance profile)
+                as_global(M.dbg)[(size_t)n_phases * kEvSlots + ((size_t)blockIdx.x * kFusedWaves + wave) * 8 + D.kind] = wall_clock64();
+                if (D.kind == PH_QKV) as_global(M.dbg)[(size_t)n_phases * kEvSlots + ((size_t)blockIdx.x * kFusedWaves + wave) * 8 + 5] = 0;
+            }
             if (seg + 1 < nseg) prefetch_stream(Stream<WD, B>::make(D.W, seg + 1, gwave, n_gwaves), ring, lane);
             else if (D.has_next) prefetch_stream(Stream<WD, B>::make(D.Wn, 0, gwave, n_gwaves), ring, lane);
             if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);

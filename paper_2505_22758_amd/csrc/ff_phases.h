@@ -62,7 +62,7 @@ __device__ bool light_wait(const TSrc& S, int batch, int k0, int nel, int lane) 
             if constexpr (HAS_ADD) { u32x2 q = tld1(sa, sample); ok = ok && q.y == S.add_tag; }
         }
         if (__all(ok)) return true;
-        __builtin_amdgcn_s_sleep(16);
+        __builtin_amdgcn_s_sleep(4);
     }
     return false;
 }
@@ -234,7 +234,7 @@ struct TaggedAttnIO {
                 ok = p.y == in_tag && k.y == in_tag;
             }
             ready = __all(ok);
-            if (!ready) __builtin_amdgcn_s_sleep(8);
+            if (!ready) __builtin_amdgcn_s_sleep(4);
         }
     }
     template <int HD, int G>
@@ -439,7 +439,7 @@ __device__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u
             ls[g * kMaxSplits + s] = __uint_as_float(pl.x);
         }
         done = __syncthreads_and(ok);
-        if (!done) __builtin_amdgcn_s_sleep(8);
+        if (!done) __builtin_amdgcn_s_sleep(4);
     }
     if (!done) { atomicCAS(M.status, 0, -53); return false; }
     if (threadIdx.x < G) {

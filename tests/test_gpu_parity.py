@@ -100,3 +100,59 @@ def test_llama8b_bf16_batch1_ctx1024_full_size():
     """The benchmark workload at full size (32 layers, d 4096, vocab 128256, ctx 1024), in the
     launch configuration bench.py times; every logit of three teacher-forced steps is compared."""
     _run_teacher_forced(synth.LLAMA_8B, 0x250522758, synth.WDTYPE_BF16, batch=1, T0=1024, steps=3, gpu_generated=True)
+
+
+def test_int8_and_int4_dequantised_weights_are_bit_exact():
+    """ff_debug_dequant (packed copy, kernel arithmetic) against the oracle's dequantised matrices."""
+    from paper_2505_22758_amd import binding
+    from oracle import oracle
+    S = synth.TINY.replace(n_layers=2, d_ffn=1408)   # int4 groups need K % 128 == 0
+    for wd in (synth.WDTYPE_BF16, synth.WDTYPE_INT8, synth.WDTYPE_INT4):
+        dec = binding.Decoder(S, wd, max_batch=1)
+        layers = [synth.make_layer(S, 31, l, wd, "cuda:0") for l in range(S.n_layers)]
+        head = synth.make_head(S, 31, wd, "cuda:0")
+        for l, lw in enumerate(layers):
+            dec.load_layer(l, lw)
+        dec.load_head(head)
+        for l in (0, 1):
+            for which in synth.LAYER_MATS:
+                n, k = synth.mat_shape(S, which)
+                out = torch.empty(n, k, dtype=torch.float32, device="cuda:0")
+                binding.ff_debug_dequant(dec.model, l, which, out)
+                ref = oracle.dequant_matrix({kk: v.cpu() for kk, v in layers[l][which].items()})
+                assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32)), (wd, l, which)
+        out = torch.empty(S.vocab, S.d_model, dtype=torch.float32, device="cuda:0")
+        binding.ff_debug_dequant(dec.model, 0, "lm_head", out)
+        ref = oracle.dequant_matrix({kk: v.cpu() for kk, v in head["lm_head"].items()})
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32)), (wd, "lm_head")
+        dec.close()
+
+
+def test_tiny_shaped_int8_and_int4_steps():
+    S = synth.TINY.replace(d_ffn=1408)
+    for wd in (synth.WDTYPE_INT8, synth.WDTYPE_INT4):
+        _run_teacher_forced(S, 40 + wd, wd, batch=1, T0=70, steps=4)
+        _run_teacher_forced(S, 50 + wd, wd, batch=4, T0=33, steps=2)
+
+
+def test_out_of_range_position_is_reported_and_skipped():
+    from paper_2505_22758_amd import binding
+    S = synth.TINY
+    dec, caches = helpers.hip_side(S, 3, synth.WDTYPE_BF16, 1, 4, max_ctx=8)
+    tok = torch.tensor([1], dtype=torch.int32, device="cuda:0")
+    logits = torch.zeros(1, S.vocab, dtype=torch.float32, device="cuda:0")
+    for fn in (binding.ff_decode_step, binding.ff_decode_step_perop):
+        pos = torch.tensor([8], dtype=torch.int32, device="cuda:0")     # == max_ctx
+        fn(dec.model, tok, pos, caches[0][0], logits, 1)
+        with pytest.raises(binding.FFError) as e:
+            binding.ff_status(dec.model)
+        assert e.value.code == binding.FF_ERR_RANGE
+        bad_tok = torch.tensor([S.vocab], dtype=torch.int32, device="cuda:0")
+        fn(dec.model, bad_tok, torch.tensor([4], dtype=torch.int32, device="cuda:0"), caches[0][0], logits, 1)
+        with pytest.raises(binding.FFError):
+            binding.ff_status(dec.model)
+    # the model is still usable afterwards
+    binding.ff_decode_step(dec.model, tok, torch.tensor([4], dtype=torch.int32, device="cuda:0"), caches[0][0], logits, 1)
+    binding.ff_status(dec.model)
+    assert torch.isfinite(logits).all()
+    dec.close()
