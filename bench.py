@@ -19,6 +19,19 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per fused launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
+# a plain copy of known size); the summary under profiles/ gives the commands and the raw figures.
+TRAFFIC_FILES = {"llama3-8b-bf16-b1-ctx1024": "profiles/fused_decode_kernel_llama3-8b-bf16-b1-ctx1024.md"}
+
+
+def measured_traffic(workload):
+    path = os.path.join(ROOT, TRAFFIC_FILES.get(workload, ""))
+    if not os.path.isfile(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch="):
+            return float(line.split("=", 1)[1])
+    return None
 
 WORKLOADS = {
     # name: (shape, wdtype, batch, context)
@@ -76,6 +89,8 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-bf16-b1-ctx1024", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-perop", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-traffic kernel to scale rocprofv3 --pmc counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the paper's kernel is single-GPU); --gpus must be 1",
@@ -133,6 +148,15 @@ def main():
         wall = (time.perf_counter() - t0) * 1e3
         return wall, [evs[i].elapsed_time(evs[i + 1]) for i in range(n)]
 
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB read + 1 GiB written
+        b = torch.empty_like(a)
+        a.fill_(1.0)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
+
     kv, kv_buf = new_cache()
     run(binding.ff_decode_step, kv, 0, args.warmup)
     wall_ms, per_step_ms = run(binding.ff_decode_step, kv, args.warmup, args.steps)
@@ -156,7 +180,7 @@ def main():
         "tokens_per_s": batch / (ms_per_step * 1e-3),
         "latency_us_p10_p50_p90": [float(np.percentile(per_step_ms, q)) * 1e3 for q in (10, 50, 90)],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "kernel": "fused_decode_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": alg_bytes},
     }
 
