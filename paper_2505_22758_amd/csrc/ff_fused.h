@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = gridDim.x * kFusedWaves;
     float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64;   // behind the RoPE rows
-    Stage<WD> ring[kDepth];
+    Stage<WD> ring[kDepthOf<WD>];
     prefetch_stream(Stream<WD, B>::make(M.layers[0].qkv, 0, gwave, n_gwaves), ring, lane);
     for (int ph = 0; ph < n_phases; ph++) {
         const PhaseDesc D = phase_desc(M, tokens, tag_base, ph, lm_in_kernel, X);

@@ -13,7 +13,10 @@ template <> struct WTraits<W_INT8> { static constexpr int EPU = 16; };
 template <> struct WTraits<W_INT4> { static constexpr int EPU = 32; };
 
 constexpr int kUnr = 4;                    // 16-byte units per row and pipeline stage (per lane)
-constexpr int kDepth = 4;                  // pipeline stages (register ring slots) per wave
+// Pipeline stages (register ring slots) per wave.  An int4 stage carries its group scales and
+// zeros as well (48 registers instead of 32), so its ring is one stage shorter: the ring has to
+// fit the register file next to the attention code without spilling.
+template <int WD> constexpr int kDepthOf = WD == W_INT4 ? 3 : 4;
 constexpr int kChunkUnits = 64 * kUnr;     // units of one row covered by one stage of one wave
 constexpr int kStageLoads = 2 * kUnr;      // weight loads a wave issues per stage
 
@@ -234,7 +237,8 @@ __device__ __forceinline__ void load_stage(const Stream<WD, B>& S, int pair, int
 
 // Issue the first min(kDepth, n_it) iterations of a stream into the ring; returns how many.
 template <int WD, int B>
-__device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepth], int lane) {
+__device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], int lane) {
+    constexpr int kDepth = kDepthOf<WD>;
     int pair = S.p0, chunk = 0, n = 0;
 #pragma unroll
     for (int s = 0; s < kDepth; s++) {
@@ -256,8 +260,9 @@ __device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD>
 // finished dot products of rows (2*pair, 2*pair+1); partial sums of earlier K segments are carried
 // in `myacc` (LDS, private to the wave).
 template <int WD, int B, class Epi>
-__device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepth], const float4* xs, float* myacc,
+__device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs, float* myacc,
                                          int batch, int lane, Epi& epi) {
+    constexpr int kDepth = kDepthOf<WD>;
     constexpr int EPU = WTraits<WD>::EPU;
     constexpr int NQ = EPU / 4;
     const int nup = S.nup;
