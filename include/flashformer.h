@@ -139,12 +139,14 @@ int ff_status(ff_model *m, void *stream);
  * [N][K] order, dequantised from the PACKED copy exactly as the decode kernels dequantise it. */
 int ff_debug_dequant(const ff_model *m, int32_t layer, int32_t which, float *out_dev, void *stream);
 
-/* Profiling aid: when buf_dev is non-NULL, workgroup 0 of every following fused step writes a
- * timeline of 100 MHz wall-clock stamps into it: 12 uint64 slots per projection phase
- * (4*n_layers+1 phases; slot meaning: 0 input in LDS seen by compute wave 0, 1 projection done,
- * 2 next tiles issued, 3 helper starts, 4 helper at the workgroup hand-over, 5 helper staged,
- * 6/7 attention start/end, 8 helper's light poll succeeded, 9 helper's full load verified).
- * NULL switches it off.  The buffer must hold 12*(4*n_layers+1) uint64. */
+/* Profiling aid: when buf_dev is non-NULL, every following fused step writes 100 MHz wall-clock
+ * stamps into it; NULL switches it off.  With P = 4*n_layers+1 projection phases and W workgroups
+ * (see ff_fused_schedule) the buffer must hold 12*P + 64*W uint64:
+ *   [0, 12P)          workgroup 0: 12 slots per phase (0 input staged, 1 projection done, 2 first
+ *                     tiles requested, 3 staging starts, 6/7 attention start/end)
+ *   [12P, 12P+32W)    layer 1, 8 per wave: projection end of QKV/O/GU/DOWN, then their starts
+ *   [12P+32W, +32W)   layer 1, 8 per workgroup and projection: input staging entered, first load
+ *                     checked, last light wait done, all fresh, staged, number of stale passes */
 int ff_debug_timeline(ff_model *m, void *buf_dev);
 
 /* Number of grid barriers one fused step executes (for tests of the schedule), and the number of

@@ -36,6 +36,7 @@ struct PMat {
     int wd;
     __host__ __device__ size_t row_bytes() const { return wd == W_BF16 ? (size_t)k * 2 : wd == W_INT8 ? (size_t)k : (size_t)k / 2; }
 };
+#define FF_PMAT_FIELDS(p) PMat{(p).w, (p).s, (p).z, (p).n, (p).k, (p).wd}
 
 struct PLayer {
     const bf16_t* g1;   // attention pre-norm gain
@@ -88,6 +89,10 @@ struct DevKV {
 #define FF_GLOBAL __attribute__((address_space(1)))
 template <class T> __device__ __forceinline__ const FF_GLOBAL T* as_global(const T* p) { return (const FF_GLOBAL T*)p; }
 template <class T> __device__ __forceinline__ FF_GLOBAL T* as_global(T* p) { return (FF_GLOBAL T*)p; }
+// Read-only data that no kernel writes (the layer descriptors): uniform loads through the constant
+// address space are scalar loads, which do not queue behind the wave's vector loads and stores.
+#define FF_CONST __attribute__((address_space(4)))
+template <class T> __device__ __forceinline__ const FF_CONST T* as_const(const T* p) { return (const FF_CONST T*)p; }
 
 // ---------------------------------------------------------------- coherent exchange accesses
 // Activations exchanged between workgroups inside one launch must bypass the per-XCD L2's

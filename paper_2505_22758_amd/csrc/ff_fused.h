@@ -39,11 +39,24 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3, PH_LM = 4 };
 enum { TAG_QKV = 0, TAG_ATT = 1, TAG_O = 2, TAG_GU = 3, TAG_DOWN = 4 };
 
-// Optional timeline of workgroup 0 (8 slots per phase; 100 MHz wall clock), for profiling only.
-enum { EV_SYNCED = 0, EV_RUN_DONE = 1, EV_PF_ISSUED = 2, EV_H_START = 3, EV_H_LOADED = 4, EV_H_STAGED = 5, EV_ATT_START = 6, EV_ATT_END = 7,
-       EV_H_POLLED = 8, EV_H_FULL = 9, kEvSlots = 12 };
+// Optional profile (100 MHz wall clock), written only while a buffer is set through the debug entry
+// point.  Layout in uint64 words, P = number of projection phases, W = workgroups:
+//   [0, 12P)             workgroup 0, wave 0: kEvSlots stamps per phase (EV_* below)
+//   [12P, 12P + 32W)     layer 1, every wave: 8 words per wave = run end of QKV/O/GU/DOWN (0..3),
+//                        run start of the same (4..7)
+//   [.. , .. + 32W)      layer 1, every workgroup: 8 words per projection kind about the staging of
+//                        its input: 0 entered, 1 first load checked, 2 last light wait done,
+//                        3 all tags fresh, 4 staged, 5 number of stale passes
+enum { EV_SYNCED = 0, EV_RUN_DONE = 1, EV_PF_ISSUED = 2, EV_H_START = 3, EV_ATT_START = 6, EV_ATT_END = 7, kEvSlots = 12 };
 __device__ __forceinline__ void dbg_event(const DevModel& M, int ph, int ev, int lane) {
     if (M.dbg && blockIdx.x == 0 && lane == 0) as_global(M.dbg)[ph * kEvSlots + ev] = wall_clock64();
+}
+__device__ __forceinline__ u64* dbg_wave_slots(const DevModel& M, int n_phases, int layer, int wave) {
+    return M.dbg && layer == 1 ? M.dbg + (size_t)n_phases * kEvSlots + ((size_t)blockIdx.x * kFusedWaves + wave) * 8 : nullptr;
+}
+__device__ __forceinline__ u64* dbg_stage_slots(const DevModel& M, int n_phases, int ncta, int layer, int kind) {
+    return M.dbg && layer == 1 && kind < 4 ? M.dbg + (size_t)n_phases * kEvSlots + (size_t)ncta * kFusedWaves * 8 + ((size_t)blockIdx.x * 4 + kind) * 8
+                                           : nullptr;
 }
 
 struct EpiFused {
@@ -63,8 +76,7 @@ struct EpiFused {
 struct PhaseDesc {
     int kind, layer;
     TSrc src;
-    PMat W, Wn;        // this projection and the one after it
-    bool has_next;
+    PMat W;
     u32 out_tag;
 };
 struct PhaseState {   // the residual stream's ping-pong buffers (both roles track them identically)
@@ -75,9 +87,9 @@ __device__ __forceinline__ u32 tag_of(u32 tag_base, int l, int k) { return tag_b
 __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* tokens, u32 tb, int ph, int lm_in_kernel, const PhaseState& X) {
     PhaseDesc D;
     const int l = ph >> 2;
+    const FF_CONST PLayer* Lp = as_const(M.layers) + min(l, M.L - 1);   // scalar loads (see as_const)
     D.layer = l;
     D.kind = ph == 4 * M.L ? PH_LM : (ph & 3);
-    D.has_next = true;
     D.out_tag = 0;
     TSrc& src = D.src;
     if (D.kind == PH_QKV) {
@@ -87,32 +99,29 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
             src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, l - 1, TAG_DOWN);
         }
         src.wb = X.xnext; src.wb_stride = M.d; src.wb_tag = tag_of(tb, l, TAG_QKV);
-        src.gain = M.layers[l].g1; src.eps = M.eps;
+        src.gain = Lp->g1; src.eps = M.eps;
         D.out_tag = tag_of(tb, l, TAG_QKV);
-        D.W = M.layers[l].qkv; D.Wn = M.layers[l].o;
+        D.W = FF_PMAT_FIELDS(Lp->qkv);
     } else if (D.kind == PH_O) {
         src.base = M.tattn_o; src.stride = (size_t)M.Hq * M.hd; src.tag = tag_of(tb, l, TAG_ATT);
         D.out_tag = tag_of(tb, l, TAG_O);
-        D.W = M.layers[l].o; D.Wn = M.layers[l].gu;
+        D.W = FF_PMAT_FIELDS(Lp->o);
     } else if (D.kind == PH_GU) {
         src.base = X.xcur; src.stride = M.d; src.tag = tag_of(tb, l, TAG_QKV);
         src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, l, TAG_O);
         src.wb = X.xnext; src.wb_stride = M.d; src.wb_tag = tag_of(tb, l, TAG_GU);
-        src.gain = M.layers[l].g2; src.eps = M.eps;
+        src.gain = Lp->g2; src.eps = M.eps;
         D.out_tag = tag_of(tb, l, TAG_GU);
-        D.W = M.layers[l].gu; D.Wn = M.layers[l].down;
+        D.W = FF_PMAT_FIELDS(Lp->gu);
     } else if (D.kind == PH_DOWN) {
         src.base = M.th; src.stride = M.F; src.tag = tag_of(tb, l, TAG_GU);
         D.out_tag = tag_of(tb, l, TAG_DOWN);
-        D.W = M.layers[l].down;
-        if (l + 1 < M.L) D.Wn = M.layers[l + 1].qkv;
-        else if (lm_in_kernel) D.Wn = M.lm;
-        else { D.Wn = D.W; D.has_next = false; }
+        D.W = FF_PMAT_FIELDS(Lp->down);
     } else {
         src.base = X.xcur; src.stride = M.d; src.tag = tag_of(tb, M.L - 1, TAG_GU);
         src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, M.L - 1, TAG_DOWN);
         src.gain = M.gf; src.eps = M.eps;
-        D.W = M.lm; D.Wn = M.lm; D.has_next = false;
+        D.W = M.lm;
     }
     return D;
 }
@@ -123,7 +132,7 @@ __device__ __forceinline__ void phase_advance(const PhaseDesc& D, PhaseState& X)
 template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
-                                                                     int batch, u32 tag_base, int lm_in_kernel) {
+                                                                     int batch, u32 tag_base, int lm_in_kernel, int ncta) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     if (!inputs_ok(M, KV, tokens, pos, batch)) {
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(M.status, kStatusRange);
@@ -138,56 +147,72 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         int b = i / (M.hd / 2), f = i % (M.hd / 2);
         rope_lds[i] = KV.rope[(size_t)pos[b] * (M.hd / 2) + f];
     }
+    // Launch dimensions and positions are read again and again below; a vector load of them would
+    // make the wave wait for everything it has in flight (its prefetched weight tiles included), so
+    // the grid size is a kernel argument and the positions are staged in LDS once.
+    int* pos_lds = (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64 + 8);
+    if (threadIdx.x < batch) pos_lds[threadIdx.x] = pos[threadIdx.x];
+    __syncthreads();
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
     // weight type differs from the layers' (then the host launches it separately).
     const int n_phases = 4 * M.L + (lm_in_kernel ? 1 : 0);
     PhaseState X{M.tx, M.tx2};
 
-    const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = gridDim.x * kFusedWaves;
+    const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = ncta * kFusedWaves;
     float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64;   // behind the RoPE rows
-    Stage<WD> ring[kDepthOf<WD>];
-    prefetch_stream(Stream<WD, B>::make(M.layers[0].qkv, 0, gwave, n_gwaves), ring, lane);
-    for (int ph = 0; ph < n_phases; ph++) {
-        const PhaseDesc D = phase_desc(M, tokens, tag_base, ph, lm_in_kernel, X);
-        EpiFused epi{D.kind, D.out_tag, M, KV, pos, D.layer, rope_lds, logits};
-        Stream<WD, B> S = Stream<WD, B>::make(D.W, 0, gwave, n_gwaves);
-        const int nseg = S.nseg;
-        for (int seg = 0; seg < nseg; seg++) {
-            if (seg > 0) S = Stream<WD, B>::make(D.W, seg, gwave, n_gwaves);
-            if (wave == 0) dbg_event(M, ph, EV_H_START, lane);
-            TSrc src = D.src;
-            if (seg > 0) src.wb = nullptr;
-            bool ok;
-            if (src.add) ok = stage_tagged<EPU, true, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x);
-            else ok = stage_tagged<EPU, false, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x);
-            if (!ok) {
-                if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);
-                return;
-            }
-            if (wave == 0) dbg_event(M, ph, EV_SYNCED, lane);
-            if (M.dbg && D.layer == 1 && lane == 0 && D.kind == PH_GU)
-                as_global(M.dbg)[(size_t)n_phases * kEvSlots + ((size_t)blockIdx.x * kFusedWaves + wave) * 8 + 6] = wall_clock64();
-            gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
-            if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
-            if (M.dbg && D.layer == 1 && lane == 0) {   // per-wave completion times of layer 1 (load-balance profile)
-                as_global(M.dbg)[(size_t)n_phases * kEvSlots + ((size_t)blockIdx.x * kFusedWaves + wave) * 8 + D.kind] = wall_clock64();
-                if (D.kind == PH_QKV) as_global(M.dbg)[(size_t)n_phases * kEvSlots + ((size_t)blockIdx.x * kFusedWaves + wave) * 8 + 5] = 0;
-            }
-            if (seg + 1 < nseg) prefetch_stream(Stream<WD, B>::make(D.W, seg + 1, gwave, n_gwaves), ring, lane);
-            else if (D.has_next) prefetch_stream(Stream<WD, B>::make(D.Wn, 0, gwave, n_gwaves), ring, lane);
-            if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);
-        }
-        phase_advance(D, X);
-        if (D.kind == PH_QKV) {
-            // split-KV attention + merge; the ring keeps the output projection's tiles meanwhile
+    // One iteration = one K segment of one projection.
+    int ph = 0;
+    PhaseDesc D = phase_desc(M, tokens, tag_base, 0, lm_in_kernel, X);
+    Stream<WD, B> S = Stream<WD, B>::make(D.W, 0, gwave, n_gwaves);
+    for (;;) {
+        const int seg = S.seg;
+        EpiFused epi{D.kind, D.out_tag, M, KV, pos_lds, D.layer, rope_lds, logits};
+        // The wave's first tiles of this projection are requested before anything it has to wait
+        // for (its input vector; for the output projection the whole attention), so the memory
+        // pipe has work while the dependency resolves.  The ring lives from here to the end of
+        // gemv_run only: keeping it out of the loop-carried state lets it stay in the registers
+        // the loads were issued to (a copy would have to wait for the data).
+        TSrc src = D.src;
+        src.ncta = ncta;
+        if (seg > 0) src.wb = nullptr;
+        const bool att_first = D.kind == PH_O && seg == 0;
+        Stage<WD> ring[kDepthOf<WD>];
+        prefetch_stream(S, ring, lane);
+        if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);
+        if (att_first) {
+            // split-KV attention + merge of this layer (the ring holds the output projection's tiles)
             __syncthreads();   // every wave has finished reading the staged input: LDS is free
             if (wave == 0) dbg_event(M, ph, EV_ATT_START, lane);
-            const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
-                                                                tag_of(tag_base, D.layer, TAG_ATT));
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
+                                                                tag_of(tag_base, D.layer, TAG_ATT), ncta);
             if (wave == 0) dbg_event(M, ph, EV_ATT_END, lane);
             if (!ok) return;
         }
+        if (wave == 0) dbg_event(M, ph, EV_H_START, lane);
+        bool ok;
+        u64* ev = dbg_stage_slots(M, n_phases, ncta, D.layer, D.kind);
+        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, ev);
+        else ok = stage_tagged<EPU, false, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, ev);
+        if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
+        if (!ok) {
+            if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);
+            return;
+        }
+        if (wave == 0) dbg_event(M, ph, EV_SYNCED, lane);
+        u64* wv = D.kind < 4 ? dbg_wave_slots(M, n_phases, D.layer, wave) : nullptr;
+        if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
+        gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
+        if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
+        if (wv && lane == 0) as_global(wv)[D.kind] = wall_clock64();
+        // next iteration: further K segment of the same projection, or the next projection
+        if (seg + 1 < S.nseg) S = Stream<WD, B>::make(D.W, seg + 1, gwave, n_gwaves);
+        else if (ph + 1 < n_phases) {
+            phase_advance(D, X);
+            ++ph;
+            D = phase_desc(M, tokens, tag_base, ph, lm_in_kernel, X);
+            S = Stream<WD, B>::make(D.W, 0, gwave, n_gwaves);
+        } else break;
     }
 }
 
@@ -210,7 +235,7 @@ inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what)
         if (occ < 1) { *what = "fused kernel does not fit on a compute unit"; return hipErrorLaunchOutOfResources; }
         ready = true;
     }
-    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.tag_base, a.lm_in_kernel);
+    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.tag_base, a.lm_in_kernel, a.n_cta);
     *what = "fused kernel launch";
     return hipGetLastError();
 }

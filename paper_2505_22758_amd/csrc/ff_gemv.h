@@ -13,10 +13,14 @@ template <> struct WTraits<W_INT8> { static constexpr int EPU = 16; };
 template <> struct WTraits<W_INT4> { static constexpr int EPU = 32; };
 
 constexpr int kUnr = 4;                    // 16-byte units per row and pipeline stage (per lane)
-// Pipeline stages (register ring slots) per wave.  An int4 stage carries its group scales and
-// zeros as well (48 registers instead of 32), so its ring is one stage shorter: the ring has to
-// fit the register file next to the attention code without spilling.
-template <int WD> constexpr int kDepthOf = WD == W_INT4 ? 3 : 4;
+// Pipeline stages (register ring slots) per wave.  Two stages (16 loads of 16 bytes per lane) keep
+// the memory pipe full; deeper rings measured slower in the fused kernel, because every byte
+// prefetched across a projection boundary queues in front of the loads of the next input vector
+// (a wave's loads return in issue order).  FF_DEPTH can be overridden at build time for sweeps.
+#ifndef FF_DEPTH
+#define FF_DEPTH 2
+#endif
+template <int WD> constexpr int kDepthOf = FF_DEPTH;
 constexpr int kChunkUnits = 64 * kUnr;     // units of one row covered by one stage of one wave
 constexpr int kStageLoads = 2 * kUnr;      // weight loads a wave issues per stage
 
@@ -259,9 +263,11 @@ __device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD>
 // per lane stay in flight across row boundaries.  epi(pair, b, v0, v1) runs on lane 0 with the two
 // finished dot products of rows (2*pair, 2*pair+1); partial sums of earlier K segments are carried
 // in `myacc` (LDS, private to the wave).
-template <int WD, int B, class Epi>
+// on_tail() is called once, when the last few iterations remain: a place to request small data needed
+// right after the projection (the request queues behind tiles the wave waits for anyway).
+template <int WD, int B, class Epi, class Tail>
 __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs, float* myacc,
-                                         int batch, int lane, Epi& epi) {
+                                         int batch, int lane, Epi& epi, Tail&& on_tail) {
     constexpr int kDepth = kDepthOf<WD>;
     constexpr int EPU = WTraits<WD>::EPU;
     constexpr int NQ = EPU / 4;
@@ -344,6 +350,7 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    on_tail();
     // tail
     for (; it < S.n_it; it += kDepth) {
 #pragma unroll
@@ -356,6 +363,12 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
             }
         }
     }
+}
+
+template <int WD, int B, class Epi>
+__device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs, float* myacc,
+                                         int batch, int lane, Epi& epi) {
+    gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi, [] {});
 }
 
 }  // namespace ff

@@ -50,12 +50,14 @@ __device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const 
 // last split of (b, j) also merges all splits of that head group (paper Section 3.2: the reduction
 // is fused into the attention pass instead of a separate kernel).  The head geometry is a template
 // parameter here (one kernel instance per geometry) to keep the register footprint of the fused
-// kernel down to what the model at hand needs.
+// kernel down to what the model at hand needs.  `pos` points to the positions staged in LDS and
+// ncta is the grid size: both are read often, and fetching them from global memory here would make
+// the wave wait for every load it has in flight, weight tiles included.
 template <int NW, int HD, int G>
 __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
-                                                       uint8_t* lds, u32 in_tag, u32 out_tag) {
+                                                       uint8_t* lds, u32 in_tag, u32 out_tag, int ncta) {
     constexpr int NT = NW * 64;
-    const int share = max(1, (int)gridDim.x / (batch * M.Hkv));
+    const int share = max(1, ncta / (batch * M.Hkv));
     int base = 0;
     bool ok = true;
     TaggedAttnIO xio{in_tag, out_tag};
@@ -63,16 +65,16 @@ __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const 
         const int T = pos[b];
         const int ns = attn_nsplit(T, share);
         const int nitems = M.Hkv * ns;
-        int first = ((int)blockIdx.x - base) % (int)gridDim.x;
-        if (first < 0) first += gridDim.x;
-        for (int it = first; it < nitems; it += gridDim.x) {
+        int first = ((int)blockIdx.x - base) % ncta;
+        if (first < 0) first += ncta;
+        for (int it = first; it < nitems; it += ncta) {
             int j = it / ns, s = it % ns;
             int t0 = (int)((long)T * s / ns), t1 = (int)((long)T * (s + 1) / ns);
             bool cur = s == ns - 1;
             ok = attn_item<HD, G, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds) && ok;
             if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, (float*)lds) && ok;
         }
-        base = (base + nitems) % (int)gridDim.x;
+        base = (base + nitems) % ncta;
     }
     return ok;
 }

@@ -44,6 +44,7 @@ struct TSrc {
     const tagged_t* add = nullptr; size_t add_stride = 0; u32 add_tag = 0; // optional: + sublayer output
     tagged_t* wb = nullptr; size_t wb_stride = 0; u32 wb_tag = 0;          // optional: publish the sum (residual stream)
     const bf16_t* gain = nullptr; float eps = 0.f;                         // optional: RMSNorm
+    int ncta = 1;                                                          // workgroups in the grid (each publishes 1/ncta of wb)
 };
 
 // Waits (bounded) until kPollLanes sampled elements of the source vector(s) carry their tags: a
@@ -74,10 +75,13 @@ __device__ bool light_wait(const TSrc& S, int batch, int k0, int nel, int lane) 
 // what count); only if some tag in the workgroup is stale does it fall back to light polling.
 // The first workgroup barrier inside doubles as the hand-over of the LDS region from the previous
 // projection.  NT = threads of the workgroup.  Returns false (uniformly) on a time-out.
-template <int EPU, bool HAS_ADD, int NT>
-__device__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid) {
+// QB = quads per thread and pass (4 8-byte loads per quad and source, all in flight at once; their
+// 8*QB destination registers per source must fit beside the wave's prefetched weight tiles, or the
+// compiler parks those tiles elsewhere and has to wait for them first).
+template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB>
+__device__ bool stage_tagged_impl(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, u64* ev) {
     constexpr int NQ = EPU / 4;
-    constexpr int QB = HAS_ADD ? 8 : 14;   // quads per thread and batch: 4 8-byte loads per quad and source
+    if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
     const int lane = tid & 63;
     const int nquads = nunits * NQ;
     const int padquads = nup * NQ;
@@ -85,42 +89,52 @@ __device__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits
         float4* xb = xs + (size_t)b * NQ * nup;
         const tagged_t* src = S.base + (size_t)b * S.stride;
         const tagged_t* add = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
-        const bf16_t* erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
+        const bf16_t* erow = nullptr;   // embedding rows only come through the (no add, gain) instance
+        if constexpr (!HAS_ADD && HAS_GAIN) erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
         float ss = 0.f;
         for (int q0 = tid; q0 < padquads; q0 += NT * QB) {
             u32x4 v[QB][2], a[HAS_ADD ? QB : 1][2];
-            u32x2 g[QB];
+            u32x2 g[HAS_GAIN ? QB : 1];
             bool all_ok = false;
+            u32 stale = (1u << QB) - 1;   // quads (bit u) this lane still has to (re)load
             for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
+                // first pass: every quad of every lane; later passes: only what came back stale, so
+                // a vector that was mostly complete is not fetched twice
 #pragma unroll
                 for (int u = 0; u < QB; u++) {
                     const int k = k0 + min(q0 + u * NT, nquads - 1) * 4;   // clamped: every load is issued
-                    if (erow) {
-                        u32x2 w = *as_global((const u32x2*)(erow + k));
-                        v[u][0] = u32x4{w.x << 16, S.tag, w.x & 0xFFFF0000u, S.tag};
-                        v[u][1] = u32x4{w.y << 16, S.tag, w.y & 0xFFFF0000u, S.tag};
-                    } else {
-                        v[u][0] = tld2(src, k);
-                        v[u][1] = tld2(src, k + 2);
+                    if (spins == 0 || ((stale >> u) & 1)) {
+                        if (erow) {
+                            u32x2 w = *as_global((const u32x2*)(erow + k));
+                            v[u][0] = u32x4{w.x << 16, S.tag, w.x & 0xFFFF0000u, S.tag};
+                            v[u][1] = u32x4{w.y << 16, S.tag, w.y & 0xFFFF0000u, S.tag};
+                        } else {
+                            v[u][0] = tld2(src, k);
+                            v[u][1] = tld2(src, k + 2);
+                        }
+                        if constexpr (HAS_ADD) { a[u][0] = tld2(add, k); a[u][1] = tld2(add, k + 2); }
                     }
-                    if constexpr (HAS_ADD) { a[u][0] = tld2(add, k); a[u][1] = tld2(add, k + 2); }
-                    if (S.gain && spins == 0) g[u] = *as_global((const u32x2*)(S.gain + k));
+                    if constexpr (HAS_GAIN) { if (spins == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
                 }
-                bool ok = true;
+                stale = 0;
 #pragma unroll
                 for (int u = 0; u < QB; u++) {
-                    ok = ok && v[u][0].y == S.tag && v[u][0].w == S.tag && v[u][1].y == S.tag && v[u][1].w == S.tag;
+                    bool ok = v[u][0].y == S.tag && v[u][0].w == S.tag && v[u][1].y == S.tag && v[u][1].w == S.tag;
                     if constexpr (HAS_ADD)
                         ok = ok && a[u][0].y == S.add_tag && a[u][0].w == S.add_tag && a[u][1].y == S.add_tag && a[u][1].w == S.add_tag;
+                    if (!ok) stale |= 1u << u;
                 }
-                all_ok = __syncthreads_and(ok);
+                all_ok = __syncthreads_and(stale == 0);
+                if (ev && tid == 0 && spins == 0 && b == 0) as_global(ev)[1] = wall_clock64();
                 if (!all_ok) {
                     bool lw = true;
                     if (tid < 64) lw = light_wait<HAS_ADD>(S, batch, k0, nunits * EPU, lane);
                     if (!__syncthreads_and(lw)) return false;
+                    if (ev && tid == 0) { as_global(ev)[2] = wall_clock64(); as_global(ev)[5] += 1; }
                 }
             }
             if (!all_ok) return false;
+            if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
 #pragma unroll
             for (int u = 0; u < QB; u++) {
                 const int qi = q0 + u * NT;
@@ -132,20 +146,22 @@ __device__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits
                         t.z += __uint_as_float(a[u][1].x); t.w += __uint_as_float(a[u][1].z);
                     }
                     if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
-                    else if (S.wb && (qi % (int)gridDim.x) == (int)blockIdx.x) {
+                    else if (S.wb && (qi % S.ncta) == (int)blockIdx.x) {
                         tagged_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
                         tst2(w, t.x, t.y, S.wb_tag);
                         tst2(w + 2, t.z, t.w, S.wb_tag);
                     }
-                    if (S.gain && qi < nquads) {
-                        ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
-                        t.x *= bf_lo(g[u].x); t.y *= bf_hi(g[u].x); t.z *= bf_lo(g[u].y); t.w *= bf_hi(g[u].y);
+                    if constexpr (HAS_GAIN) {
+                        if (qi < nquads) {
+                            ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+                            t.x *= bf_lo(g[u].x); t.y *= bf_hi(g[u].x); t.z *= bf_lo(g[u].y); t.w *= bf_hi(g[u].y);
+                        }
                     }
                     xb[(size_t)(qi % NQ) * nup + qi / NQ] = t;
                 }
             }
         }
-        if (S.gain) {
+        if constexpr (HAS_GAIN) {
             ss = wave_sum_uniform(ss);
             if (lane == 0) red[tid >> 6] = ss;
             __syncthreads();
@@ -164,6 +180,23 @@ __device__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits
     }
     __syncthreads();
     return true;
+}
+
+// Picks the pass size that covers the vector in one pass with the fewest registers.
+template <int EPU, bool HAS_ADD, int NT>
+__device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
+                                             u64* ev) {
+    const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
+    if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
+        if (per_thread <= 4) return stage_tagged_impl<EPU, true, true, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+        return stage_tagged_impl<EPU, true, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+    } else if (S.gain) {       // embedding rows
+        return stage_tagged_impl<EPU, false, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+    } else {
+        if (per_thread <= 4) return stage_tagged_impl<EPU, false, false, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+        if (per_thread <= 8) return stage_tagged_impl<EPU, false, false, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+        return stage_tagged_impl<EPU, false, false, NT, 14>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+    }
 }
 
 // ---------------------------------------------------------------- split-KV attention
@@ -561,12 +594,12 @@ struct EpiSwiGLU {
     }
 };
 // ---- fused-kernel epilogues: outputs go to the tagged exchange buffers ----
-struct EpiQKVTagged {
+struct EpiQKVTagged {   // pos: positions of this step, staged in LDS
     const DevModel& M; const DevKV& KV; const int* pos; int layer; const float2* rope; u32 tag;
     __device__ void operator()(int pair, int b, float v0, float v1) const {
         const int half = M.hd / 2;
         const int nq = M.Hq * half, nk = M.Hkv * half;
-        const int p = as_global(pos)[b];
+        const int p = pos[b];
         if (pair < nq + nk) {
             bool isq = pair < nq;
             int pp = isq ? pair : pair - nq;
