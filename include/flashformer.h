@@ -141,12 +141,14 @@ int ff_debug_dequant(const ff_model *m, int32_t layer, int32_t which, float *out
 
 /* Profiling aid: when buf_dev is non-NULL, every following fused step writes 100 MHz wall-clock
  * stamps into it; NULL switches it off.  With P = 4*n_layers+1 projection phases and W workgroups
- * (see ff_fused_schedule) the buffer must hold 12*P + 64*W uint64:
+ * (see ff_fused_schedule) the buffer must hold 12*P + 72*W uint64:
  *   [0, 12P)          workgroup 0: 12 slots per phase (0 input staged, 1 projection done, 2 first
  *                     tiles requested, 3 staging starts, 6/7 attention start/end)
  *   [12P, 12P+32W)    layer 1, 8 per wave: projection end of QKV/O/GU/DOWN, then their starts
- *   [12P+32W, +32W)   layer 1, 8 per workgroup and projection: input staging entered, first load
- *                     checked, last light wait done, all fresh, staged, number of stale passes */
+ *   [12P+32W, +40W)   layer 1, per workgroup: 8 per projection (input staging entered, first load
+ *                     checked, last light wait done, all fresh, staged, number of stale passes),
+ *                     then 8 about its attention work (start, queries seen, rows done, partial
+ *                     stored, split maxima seen and merged output stored if it merges, end) */
 int ff_debug_timeline(ff_model *m, void *buf_dev);
 
 /* Number of grid barriers one fused step executes (for tests of the schedule), and the number of

@@ -44,9 +44,11 @@ enum { TAG_QKV = 0, TAG_ATT = 1, TAG_O = 2, TAG_GU = 3, TAG_DOWN = 4 };
 //   [0, 12P)             workgroup 0, wave 0: kEvSlots stamps per phase (EV_* below)
 //   [12P, 12P + 32W)     layer 1, every wave: 8 words per wave = run end of QKV/O/GU/DOWN (0..3),
 //                        run start of the same (4..7)
-//   [.. , .. + 32W)      layer 1, every workgroup: 8 words per projection kind about the staging of
+//   [.. , .. + 40W)      layer 1, every workgroup: 8 words per projection kind about the staging of
 //                        its input: 0 entered, 1 first load checked, 2 last light wait done,
-//                        3 all tags fresh, 4 staged, 5 number of stale passes
+//                        3 all tags fresh, 4 staged, 5 number of stale passes; then 8 words about
+//                        its attention work: 0 start, 1 queries seen, 2 rows done, 3 partial stored,
+//                        4 (merging workgroups) split maxima seen, 5 merged output stored, 6 end
 enum { EV_SYNCED = 0, EV_RUN_DONE = 1, EV_PF_ISSUED = 2, EV_H_START = 3, EV_ATT_START = 6, EV_ATT_END = 7, kEvSlots = 12 };
 __device__ __forceinline__ void dbg_event(const DevModel& M, int ph, int ev, int lane) {
     if (M.dbg && blockIdx.x == 0 && lane == 0) as_global(M.dbg)[ph * kEvSlots + ev] = wall_clock64();
@@ -55,7 +57,7 @@ __device__ __forceinline__ u64* dbg_wave_slots(const DevModel& M, int n_phases, 
     return M.dbg && layer == 1 ? M.dbg + (size_t)n_phases * kEvSlots + ((size_t)blockIdx.x * kFusedWaves + wave) * 8 : nullptr;
 }
 __device__ __forceinline__ u64* dbg_stage_slots(const DevModel& M, int n_phases, int ncta, int layer, int kind) {
-    return M.dbg && layer == 1 && kind < 4 ? M.dbg + (size_t)n_phases * kEvSlots + (size_t)ncta * kFusedWaves * 8 + ((size_t)blockIdx.x * 4 + kind) * 8
+    return M.dbg && layer == 1 && kind < 5 ? M.dbg + (size_t)n_phases * kEvSlots + (size_t)ncta * kFusedWaves * 8 + ((size_t)blockIdx.x * 5 + kind) * 8
                                            : nullptr;
 }
 
@@ -184,8 +186,11 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             // split-KV attention + merge of this layer (the ring holds the output projection's tiles)
             __syncthreads();   // every wave has finished reading the staged input: LDS is free
             if (wave == 0) dbg_event(M, ph, EV_ATT_START, lane);
+            u64* aev = dbg_stage_slots(M, n_phases, ncta, D.layer, 4);
+            if (aev && threadIdx.x == 0) { as_global(aev)[0] = wall_clock64(); as_global(aev)[4] = 0; as_global(aev)[5] = 0; }
             const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
-                                                                tag_of(tag_base, D.layer, TAG_ATT), ncta);
+                                                                tag_of(tag_base, D.layer, TAG_ATT), ncta, aev);
+            if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
             if (wave == 0) dbg_event(M, ph, EV_ATT_END, lane);
             if (!ok) return;
         }

@@ -43,6 +43,24 @@ __device__ __forceinline__ float wave_sum_uniform(float v) {
     return (r0 + r1) + (r2 + r3);
 }
 
+// Sum over aligned groups of W lanes (W = 8 or 16), every lane of a group receiving the group's sum:
+// DPP steps inside one 16-lane row, no LDS permute traffic.
+template <int W>
+__device__ __forceinline__ float group_sum(float v) {
+    static_assert(W == 8 || W == 16, "group width");
+    int x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, true));   // row_half_mirror
+    if constexpr (W == 16) {
+        x = __float_as_int(v);
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, true));   // row_mirror
+    }
+    return v;
+}
+
 // ---------------------------------------------------------------- staging
 // Where a GEMV phase takes its input vector(s) from, and what is folded into the staging.
 struct ActSrc {

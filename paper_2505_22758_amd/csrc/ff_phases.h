@@ -185,7 +185,7 @@ __device__ bool stage_tagged_impl(const TSrc& S, int batch, int K, int k0, int n
 // Picks the pass size that covers the vector in one pass with the fewest registers.
 template <int EPU, bool HAS_ADD, int NT>
 __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
-                                             u64* ev) {
+                                             u64* ev = nullptr) {
     const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
     if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
         if (per_thread <= 4) return stage_tagged_impl<EPU, true, true, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
@@ -213,25 +213,18 @@ __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, in
 // the workgroup, all of which take part).  XIO supplies the exchange accesses (plain buffers for
 // the per-operation kernels, tagged buffers for the fused kernel); returns false on a time-out.
 struct PlainAttnIO {
-    template <int HD, int G>
-    __device__ bool load_q(const DevModel& M, int b, int j, int sub, float (&qr)[G][8]) const {
-#pragma unroll
-        for (int g = 0; g < G; g++) {
-            const int qi = (b * M.Hq + (j * G + g)) * HD + sub * 8;
-            float4 v0 = PlainIO::ld4(M.q, qi), v1 = PlainIO::ld4(M.q, qi + 4);
-            qr[g][0] = v0.x; qr[g][1] = v0.y; qr[g][2] = v0.z; qr[g][3] = v0.w;
-            qr[g][4] = v1.x; qr[g][5] = v1.y; qr[g][6] = v1.z; qr[g][7] = v1.w;
+    // Workgroup-collective: the G query rows of kv head j, then (with_cur) this step's own key and
+    // value row, as floats into dst[G*HD + 2*HD] (LDS); ends with a workgroup barrier.
+    template <int HD, int G, int NT>
+    __device__ bool stage_inputs(const DevModel& M, int b, int j, bool with_cur, float* dst) const {
+        const int nq = G * HD, n = nq + (with_cur ? 2 * HD : 0);
+        for (int e = threadIdx.x; e < n; e += NT) {
+            float v;
+            if (e < nq) v = PlainIO::ld(M.q, (b * M.Hq + j * G) * HD + e);
+            else v = PlainIO::ld(M.kvcur, ((b * 2 + (e - nq) / HD) * M.Hkv + j) * HD + (e - nq) % HD);
+            dst[e] = v;
         }
-        return true;
-    }
-    template <int HD>
-    __device__ bool load_cur(const DevModel& M, int b, int j, int sub, float (&kf)[8], float (&vf)[8]) const {
-        const int ki = ((b * 2 + 0) * M.Hkv + j) * HD + sub * 8;
-        const int vi = ((b * 2 + 1) * M.Hkv + j) * HD + sub * 8;
-        float4 k0 = PlainIO::ld4(M.kvcur, ki), k1 = PlainIO::ld4(M.kvcur, ki + 4);
-        float4 v0 = PlainIO::ld4(M.kvcur, vi), v1 = PlainIO::ld4(M.kvcur, vi + 4);
-        kf[0] = k0.x; kf[1] = k0.y; kf[2] = k0.z; kf[3] = k0.w; kf[4] = k1.x; kf[5] = k1.y; kf[6] = k1.z; kf[7] = k1.w;
-        vf[0] = v0.x; vf[1] = v0.y; vf[2] = v0.z; vf[3] = v0.w; vf[4] = v1.x; vf[5] = v1.y; vf[6] = v1.z; vf[7] = v1.w;
+        __syncthreads();
         return true;
     }
     template <int HD>
@@ -243,66 +236,40 @@ struct PlainAttnIO {
 struct TaggedAttnIO {
     u32 in_tag;    // tag of q / kvcur (this layer's QKV projection)
     u32 out_tag;   // tag of the partials and of attn_o (this layer's attention)
-    // 8 consecutive tagged values -> floats; false if any tag is stale
-    __device__ __forceinline__ static bool unpack8(const u32x4 (&r)[4], u32 tag, float (&f)[8]) {
-        bool ok = true;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            f[2 * i] = __uint_as_float(r[i].x); f[2 * i + 1] = __uint_as_float(r[i].z);
-            ok = ok && r[i].y == tag && r[i].w == tag;
-        }
-        return ok;
-    }
-    // a few sampled query / key elements, with pauses: sits out a QKV projection that is still running
-    template <int HD, int G>
-    __device__ void light_poll(const DevModel& M, int b, int j) const {
-        const int lane = threadIdx.x & 63;
-        bool ready = false;
-        for (int spins = 0; spins < kSpinLimit && !ready; spins++) {
-            bool ok = true;
-            if (lane < kPollLanes) {
-                const int e = (lane * (G * HD)) / kPollLanes;
-                u32x2 p = tld1(M.tq, (b * M.Hq + j * G) * HD + e);
-                u32x2 k = tld1(M.tkvcur, ((b * 2 + (lane & 1)) * M.Hkv + j) * HD + (lane * HD) / kPollLanes);
-                ok = p.y == in_tag && k.y == in_tag;
-            }
-            ready = __all(ok);
-            if (!ready) __builtin_amdgcn_s_sleep(4);
-        }
-    }
-    template <int HD, int G>
-    __device__ bool load_q(const DevModel& M, int b, int j, int sub, float (&qr)[G][8]) const {
-        for (int spins = 0; spins < kSpinLimit; spins++) {
-            u32x4 r[G][4];
-#pragma unroll
-            for (int g = 0; g < G; g++)
-#pragma unroll
-                for (int i = 0; i < 4; i++) r[g][i] = tld2(M.tq, (b * M.Hq + (j * G + g)) * HD + sub * 8 + 2 * i);
+    // Workgroup-collective, same contract as PlainAttnIO::stage_inputs.  The whole input of an
+    // item is a few kilobytes (one or two 16-byte pairs per thread), so the workgroup simply
+    // re-reads it until the QKV projection's tag is on every element; returns false on a time-out.
+    template <int HD, int G, int NT>
+    __device__ bool stage_inputs(const DevModel& M, int b, int j, bool with_cur, float* dst) const {
+        constexpr int NQ2 = G * HD / 2, NK2 = HD / 2;       // pairs of queries, of one k or v row
+        constexpr int PP = (NQ2 + 2 * NK2 + NT - 1) / NT;   // pairs per thread
+        const int np = NQ2 + (with_cur ? 2 * NK2 : 0);
+        const tagged_t* qb = M.tq + (size_t)(b * M.Hq + j * G) * HD;
+        const tagged_t* kb = M.tkvcur + (size_t)((b * 2 + 0) * M.Hkv + j) * HD;
+        const tagged_t* vb = M.tkvcur + (size_t)((b * 2 + 1) * M.Hkv + j) * HD;
+        u32x4 r[PP];
+        bool done = false;
+        for (int spins = 0; spins < kSpinLimit && !done; spins++) {
             bool ok = true;
 #pragma unroll
-            for (int g = 0; g < G; g++) ok = unpack8(r[g], in_tag, qr[g]) && ok;
-            if (__all(ok)) return true;
-            light_poll<HD, G>(M, b, j);
-        }
-        atomicCAS(M.status, 0, -51);
-        return false;
-    }
-    template <int HD>
-    __device__ bool load_cur(const DevModel& M, int b, int j, int sub, float (&kf)[8], float (&vf)[8]) const {
-        for (int spins = 0; spins < kSpinLimit; spins++) {
-            u32x4 rk[4], rv[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                rk[i] = tld2(M.tkvcur, ((b * 2 + 0) * M.Hkv + j) * HD + sub * 8 + 2 * i);
-                rv[i] = tld2(M.tkvcur, ((b * 2 + 1) * M.Hkv + j) * HD + sub * 8 + 2 * i);
+            for (int u = 0; u < PP; u++) {
+                const int p = min((int)threadIdx.x + u * NT, np - 1);   // clamped: every load is issued
+                const tagged_t* src = p < NQ2 ? qb + 2 * p : p < NQ2 + NK2 ? kb + 2 * (p - NQ2) : vb + 2 * (p - NQ2 - NK2);
+                r[u] = tld2(src, 0);
             }
-            bool ok = unpack8(rk, in_tag, kf);
-            ok = unpack8(rv, in_tag, vf) && ok;
-            if (__all(ok)) return true;
-            __builtin_amdgcn_s_sleep(8);
+#pragma unroll
+            for (int u = 0; u < PP; u++) ok = ok && r[u].y == in_tag && r[u].w == in_tag;
+            done = __syncthreads_and(ok);
+            if (!done) __builtin_amdgcn_s_sleep(2);
         }
-        atomicCAS(M.status, 0, -52);
-        return false;
+        if (!done) { atomicCAS(M.status, 0, -51); return false; }
+#pragma unroll
+        for (int u = 0; u < PP; u++) {
+            const int p = (int)threadIdx.x + u * NT;
+            if (p < np) { dst[2 * p] = __uint_as_float(r[u].x); dst[2 * p + 1] = __uint_as_float(r[u].z); }
+        }
+        __syncthreads();
+        return true;
     }
     template <int HD>
     __device__ void store_partial(const DevModel& M, size_t hs, int dim, float ot, float mx, float lt) const {
@@ -313,7 +280,7 @@ struct TaggedAttnIO {
 
 template <int HD, int G, int NW, class XIO>
 __device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, int layer, int b, int j, int t0, int t1, bool with_cur,
-                          int split, uint8_t* lds) {
+                          int split, uint8_t* lds, u64* ev = nullptr) {
     constexpr int LPR = HD / 8;        // lanes per cache row
     constexpr int RPW = 64 / LPR;      // rows per wave load
     constexpr int NS = NW * RPW;       // partial states per workgroup
@@ -332,16 +299,13 @@ __device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, in
     const bf16_t* Kp = KV.plane(M, layer, b, j, 0);
     const bf16_t* Vp = KV.plane(M, layer, b, j, 1);
     float qr[G][8];
-    bool ok = true, have_q = false;
     auto update = [&](const float (&kf)[8], const float (&vf)[8], bool valid) {
 #pragma unroll
         for (int g = 0; g < G; g++) {
             float s = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; e++) s = fmaf(qr[g][e], kf[e], s);
-#pragma unroll
-            for (int off = LPR / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-            s *= sc;
+            s = group_sum<LPR>(s) * sc;
             if (valid) {
                 float mn = fmaxf(m[g], s);
                 float corr = exp2f(m[g] - mn), p = exp2f(s - mn);
@@ -352,18 +316,35 @@ __device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, in
             }
         }
     };
-    // Cached rows do not depend on this step: their loads are issued (kAttnBatch wave-loads at a
-    // time) BEFORE the queries are waited for, so the wait for the QKV projection overlaps them.
+    // Cached rows do not depend on this step: the first kAttnBatch wave-loads are issued BEFORE the
+    // queries are waited for, so the wait for the QKV projection overlaps them.
     constexpr int kAttnBatch = 4;
-    for (int tb0 = t0 + wave * RPW; tb0 < t1; tb0 += NW * RPW * kAttnBatch) {
-        u32x4 kw[kAttnBatch], vw[kAttnBatch];
+    constexpr int kStride = NW * RPW * kAttnBatch;
+    u32x4 kw[kAttnBatch], vw[kAttnBatch];
+    auto issue = [&](int tb0) {
 #pragma unroll
         for (int i = 0; i < kAttnBatch; i++) {
             const int t = min(tb0 + i * NW * RPW + grp, t1 - 1);   // clamped: every load is issued
             kw[i] = ldg_stream(Kp + (size_t)t * HD + sub * 8);
             vw[i] = ldg_stream(Vp + (size_t)t * HD + sub * 8);
         }
-        if (!have_q) { ok = xio.template load_q<HD, G>(M, b, j, sub, qr); have_q = true; }
+    };
+    int tb0 = t0 + wave * RPW;
+    if (tb0 < t1) issue(tb0);
+    // queries of the G heads and this step's own k, v: staged once per workgroup behind the state
+    // merge area, then read by every lane from LDS
+    float* xin = (float*)lds + 2 * NS * G + (size_t)NS * G * HD;
+    const bool ok = xio.template stage_inputs<HD, G, NT>(M, b, j, with_cur, xin);
+    if (ev && threadIdx.x == 0) as_global(ev)[1] = wall_clock64();
+    if (!ok) return false;   // uniform
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        const float4 q0 = *(const float4*)(xin + g * HD + sub * 8), q1 = *(const float4*)(xin + g * HD + sub * 8 + 4);
+        qr[g][0] = q0.x; qr[g][1] = q0.y; qr[g][2] = q0.z; qr[g][3] = q0.w;
+        qr[g][4] = q1.x; qr[g][5] = q1.y; qr[g][6] = q1.z; qr[g][7] = q1.w;
+    }
+    for (bool first = true; tb0 < t1; tb0 += kStride, first = false) {
+        if (!first) issue(tb0);
 #pragma unroll
         for (int i = 0; i < kAttnBatch; i++) {
             const bool valid = tb0 + i * NW * RPW + grp < t1;
@@ -372,10 +353,12 @@ __device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, in
             update(kf, vf, valid);
         }
     }
-    if (!have_q) ok = xio.template load_q<HD, G>(M, b, j, sub, qr);
     if (with_cur && wave == 0) {   // this step's own key/value (uniform branch per wave)
         float kf[8], vf[8];
-        ok = xio.template load_cur<HD>(M, b, j, sub, kf, vf) && ok;
+        const float* kc = xin + G * HD + sub * 8;
+        const float* vc = kc + HD;
+#pragma unroll
+        for (int e = 0; e < 8; e++) { kf[e] = kc[e]; vf[e] = vc[e]; }
         update(kf, vf, grp == 0);   // scores reduce over the lanes of one row group: only group 0 is valid
     }
     // ---- merge the NS states of this workgroup ----
@@ -383,6 +366,7 @@ __device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, in
     float* sl = sm + NS * G;              // [NS][G]
     float* so = sl + NS * G;              // [NS][G][HD]
     const int si = wave * RPW + grp;
+    if (ev && threadIdx.x == 0) as_global(ev)[2] = wall_clock64();
     __syncthreads();
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -404,6 +388,7 @@ __device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, in
         size_t hs = ((size_t)b * M.Hq + (j * G + g)) * kMaxSplits + split;
         xio.template store_partial<HD>(M, hs, dim, ot, mx, lt);
     }
+    if (ev && threadIdx.x == 0) as_global(ev)[3] = wall_clock64();
     return ok;
 }
 
@@ -455,9 +440,29 @@ __device__ void attn_merge(const DevModel& M, int b, int j, int nsplit, float* l
 // (b, j) gathers all splits, re-reading until every partial carries this layer's attention tag,
 // and publishes attn_o with the same tag.  Returns false on a time-out.
 template <int HD, int G, int NT>
-__device__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, float* lds) {
+__device__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, float* lds, u64* ev = nullptr) {
     float* ms = lds;
     float* ls = lds + G * kMaxSplits;
+    constexpr int kSB = 16;   // splits gathered per batch of loads
+    constexpr u32 kAll = (1u << kSB) - 1;
+    // (re)loads the partial outputs of splits s0.. (bit u of mask = split s0+u) for output pair d2
+    auto issue = [&](u32x4 (&r)[kSB], int hs, int d2, int s0, u32 mask) {
+#pragma unroll
+        for (int u = 0; u < kSB; u++)
+            if ((mask >> u) & 1) r[u] = tld2(M.tpart_o, (hs + min(s0 + u, nsplit - 1)) * HD + d2);
+    };
+    auto stale_of = [&](const u32x4 (&r)[kSB]) {
+        u32 m = 0;
+#pragma unroll
+        for (int u = 0; u < kSB; u++) if (!(r[u].y == tag && r[u].w == tag)) m |= 1u << u;
+        return m;
+    };
+    // The first batch of partial outputs is requested before the maxima and denominators are
+    // waited for: all partials of a head group arrive in one round trip, and whatever is still
+    // stale (the last split's rows, typically) is re-read selectively.
+    u32x4 r[kSB];
+    const bool pre = (int)threadIdx.x < G * HD / 2;
+    if (pre) issue(r, (b * M.Hq + (j * G + (int)threadIdx.x / (HD / 2))) * kMaxSplits, ((int)threadIdx.x % (HD / 2)) * 2, 0, kAll);
     __syncthreads();
     bool done = false;
     for (int spins = 0; spins < kSpinLimit && !done; spins++) {
@@ -465,62 +470,59 @@ __device__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u
         for (int idx = threadIdx.x; idx < G * nsplit; idx += NT) {
             int g = idx / nsplit, s = idx % nsplit;
             int hs = (b * M.Hq + (j * G + g)) * kMaxSplits + s;
-            u32x2 pm = __builtin_amdgcn_raw_buffer_load_b64(make_rsrc(M.tpart_m), hs * 8, 0, kAuxSc1);
-            u32x2 pl = __builtin_amdgcn_raw_buffer_load_b64(make_rsrc(M.tpart_l), hs * 8, 0, kAuxSc1);
+            u32x2 pm = tld1(M.tpart_m, hs), pl = tld1(M.tpart_l, hs);
             ok = ok && pm.y == tag && pl.y == tag;
             ms[g * kMaxSplits + s] = __uint_as_float(pm.x);
             ls[g * kMaxSplits + s] = __uint_as_float(pl.x);
         }
         done = __syncthreads_and(ok);
-        if (!done) __builtin_amdgcn_s_sleep(4);
+        if (!done) __builtin_amdgcn_s_sleep(2);
     }
     if (!done) { atomicCAS(M.status, 0, -53); return false; }
-    if (threadIdx.x < G) {
-        int g = threadIdx.x;
-        float mx = -INFINITY;
-        for (int s = 0; s < nsplit; s++) mx = fmaxf(mx, ms[g * kMaxSplits + s]);
-        float lt = 0.f;
-        for (int s = 0; s < nsplit; s++) {
-            float w = exp2f(ms[g * kMaxSplits + s] - mx);
-            ms[g * kMaxSplits + s] = w;
-            lt = fmaf(ls[g * kMaxSplits + s], w, lt);
-        }
-        float inv = 1.0f / lt;
-        for (int s = 0; s < nsplit; s++) ms[g * kMaxSplits + s] *= inv;
-    }
-    __syncthreads();
-    constexpr int kSB = 16;   // splits gathered per batch of loads
+    if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
     bool all_ok = true;
     for (int idx = threadIdx.x; idx < G * HD / 2; idx += NT) {
         int g = idx / (HD / 2), d2 = (idx % (HD / 2)) * 2;
         int hs = (b * M.Hq + (j * G + g)) * kMaxSplits;
+        // every thread reduces the maxima and denominators of its head itself (independent LDS
+        // reads; no serial section, no further barrier)
+        float mx = -INFINITY;
+        for (int s0 = 0; s0 < nsplit; s0 += kSB) {
+#pragma unroll
+            for (int u = 0; u < kSB; u++) mx = fmaxf(mx, ms[g * kMaxSplits + min(s0 + u, nsplit - 1)]);   // batched LDS reads
+        }
+        float lt = 0.f;
+        for (int s0 = 0; s0 < nsplit; s0 += kSB) {
+#pragma unroll
+            for (int u = 0; u < kSB; u++) {
+                const int s = min(s0 + u, nsplit - 1);
+                const float w = exp2f(ms[g * kMaxSplits + s] - mx);
+                lt = fmaf(ls[g * kMaxSplits + s], s0 + u < nsplit ? w : 0.f, lt);
+            }
+        }
+        const float inv = 1.0f / lt;
         float a0 = 0.f, a1 = 0.f;
         for (int s0 = 0; s0 < nsplit; s0 += kSB) {
+            u32 need = (idx == (int)threadIdx.x && s0 == 0) ? 0u : kAll;   // the first batch is already in flight
             bool ok = false;
-            u32x4 r[kSB];
             for (int spins = 0; spins < kSpinLimit && !ok; spins++) {
-                ok = true;
-#pragma unroll
-                for (int u = 0; u < kSB; u++) {
-                    int s = min(s0 + u, nsplit - 1);
-                    r[u] = tld2(M.tpart_o, (hs + s) * HD + d2);
-                }
-#pragma unroll
-                for (int u = 0; u < kSB; u++) ok = ok && r[u].y == tag && r[u].w == tag;
+                issue(r, hs, d2, s0, need);
+                need = stale_of(r);
+                ok = need == 0;
             }
             all_ok = all_ok && ok;
             if (!ok) atomicCAS(M.status, 0, -54);
 #pragma unroll
             for (int u = 0; u < kSB; u++) {
-                if (s0 + u < nsplit) {
-                    float w = ms[g * kMaxSplits + s0 + u];
-                    a0 = fmaf(__uint_as_float(r[u].x), w, a0);
-                    a1 = fmaf(__uint_as_float(r[u].z), w, a1);
-                }
+                const float mu = ms[g * kMaxSplits + min(s0 + u, nsplit - 1)];
+                const float w = s0 + u < nsplit ? exp2f(mu - mx) * inv : 0.f;
+                a0 = fmaf(__uint_as_float(r[u].x), w, a0);
+                a1 = fmaf(__uint_as_float(r[u].z), w, a1);
             }
         }
         tst2(M.tattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, tag);
     }
+    if (ev && threadIdx.x == 0) as_global(ev)[5] = wall_clock64();
     return __syncthreads_and(all_ok);
 }
 
