@@ -58,7 +58,7 @@ typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
     float rms_eps, rope_theta;
     int32_t wdtype;        /* FF_W_* for the seven per-layer projections */
-    int32_t max_batch;     /* largest batch any step will use (1..4) */
+    int32_t max_batch;     /* largest batch any step will use (1..16) */
     int32_t quant_lm_head; /* nonzero: LM head uses wdtype too; zero: LM head is bf16 */
 } ff_config;
 
@@ -123,7 +123,10 @@ int ff_kv_free(ff_kv *kv);
  *                                 rows 0..position inclusive.  The caller advances positions.
  *   logits_dev    fp32  [batch][vocab]   valid once `stream` has synchronised.
  * Asynchronous; an out-of-range position or token makes the kernel skip the step and record
- * FF_ERR_RANGE in the model's status word (see ff_status).  Steps on one model must not overlap. */
+ * FF_ERR_RANGE in the model's status word (see ff_status).  Steps on one model must not overlap.
+ * One kernel pass serves up to 4 sequences (paper Section 4.2: batches 2-4 replicate the inputs and
+ * read every weight once); a larger batch runs as consecutive passes of 4 on the stream, each
+ * streaming the weights again. */
 int ff_decode_step(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
                    float *logits_dev, int32_t batch, void *stream);
 

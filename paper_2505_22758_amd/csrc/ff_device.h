@@ -17,7 +17,8 @@ typedef uint16_t f16_t;    // raw bits
 
 constexpr int kThreads = 256;            // threads per workgroup (4 waves, one per SIMD)
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxBatch = 4;
+constexpr int kMaxBatch = 4;        // sequences one kernel pass works on
+constexpr int kMaxBatchApi = 16;    // sequences one decode step accepts (run as passes of kMaxBatch)
 constexpr int kMaxSplits = 64;           // max KV splits per (sequence, kv head)
 constexpr int kMinSplitLen = 64;         // do not split the cache finer than this many rows
 constexpr int kLdsActBytes = 128 * 1024; // LDS region holding the staged activation vector(s)
@@ -78,8 +79,9 @@ struct DevKV {
     bf16_t* base;        // [L][batch][Hkv][2][max_ctx][hd]
     const float2* rope;  // [max_ctx][hd/2] (cos, sin)
     int max_ctx, batch;
+    int seq0;            // first sequence of the current pass (kernels number their sequences from 0)
     __device__ bf16_t* plane(const DevModel& M, int l, int b, int j, int kv) const {
-        return base + ((((size_t)l * batch + b) * M.Hkv + j) * 2 + kv) * (size_t)max_ctx * M.hd;
+        return base + ((((size_t)l * batch + (seq0 + b)) * M.Hkv + j) * 2 + kv) * (size_t)max_ctx * M.hd;
     }
 };
 

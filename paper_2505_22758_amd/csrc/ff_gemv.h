@@ -281,11 +281,9 @@ __device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD>
 // per lane stay in flight across row boundaries.  epi(pair, b, v0, v1) runs on lane 0 with the two
 // finished dot products of rows (2*pair, 2*pair+1); partial sums of earlier K segments are carried
 // in `myacc` (LDS, private to the wave).
-// on_tail() is called once, when the last few iterations remain: a place to request small data needed
-// right after the projection (the request queues behind tiles the wave waits for anyway).
-template <int WD, int B, class Epi, class Tail>
+template <int WD, int B, class Epi>
 __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs, float* myacc,
-                                         int batch, int lane, Epi& epi, Tail&& on_tail) {
+                                         int batch, int lane, Epi& epi) {
     constexpr int kDepth = kDepthOf<WD>;
     constexpr int EPU = WTraits<WD>::EPU;
     constexpr int NQ = EPU / 4;
@@ -368,7 +366,6 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    on_tail();
     // tail
     for (; it < S.n_it; it += kDepth) {
 #pragma unroll
@@ -381,12 +378,6 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
             }
         }
     }
-}
-
-template <int WD, int B, class Epi>
-__device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs, float* myacc,
-                                         int batch, int lane, Epi& epi) {
-    gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi, [] {});
 }
 
 }  // namespace ff

@@ -3,6 +3,7 @@
 #include "ff_fused.h"
 #include "ff_ops.h"
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -61,7 +62,7 @@ int check_config(const ff_config* c) {
     if (!c) return fail(FF_ERR_ARG, "config is null");
     if (c->n_layers < 1 || c->d_model < 8 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 8 || c->vocab < 2)
         return fail(FF_ERR_ARG, "non-positive model dimension");
-    if (c->max_batch < 1 || c->max_batch > kMaxBatch) return fail(FF_ERR_ARG, "max_batch %d outside [1,%d]", c->max_batch, kMaxBatch);
+    if (c->max_batch < 1 || c->max_batch > kMaxBatchApi) return fail(FF_ERR_ARG, "max_batch %d outside [1,%d]", c->max_batch, kMaxBatchApi);
     if (c->wdtype < 0 || c->wdtype > 2) return fail(FF_ERR_ARG, "unknown wdtype %d", c->wdtype);
     if (c->n_q_heads % c->n_kv_heads) return fail(FF_ERR_UNSUPPORTED, "n_q_heads must be a multiple of n_kv_heads");
     int G = c->n_q_heads / c->n_kv_heads;
@@ -72,6 +73,8 @@ int check_config(const ff_config* c) {
     if (c->d_model % epu || qd % epu || c->d_ffn % epu)
         return fail(FF_ERR_UNSUPPORTED, "d_model, n_q_heads*head_dim and d_ffn must be multiples of %d for this weight type", epu);
     if (c->d_model % 8 || c->d_ffn % 2 || c->vocab < 2) return fail(FF_ERR_UNSUPPORTED, "d_model must be a multiple of 8");
+    if ((size_t)c->d_model * 4 * std::min(c->max_batch, kMaxBatch) > (size_t)kLdsActBytes)
+        return fail(FF_ERR_UNSUPPORTED, "d_model %d x max_batch %d does not fit the on-chip input buffer (RMSNorm needs the whole row)", c->d_model, c->max_batch);
     return FF_OK;
 }
 
@@ -96,7 +99,7 @@ Plan make_plan(const ff_config& c) {
     P.packed_bytes = off;
 
     size_t s = 0;
-    size_t mb = c.max_batch;
+    size_t mb = std::min(c.max_batch, kMaxBatch);   // exchange buffers hold one pass
     auto take = [&](size_t bytes) { size_t o = s; s = align256(s + bytes); return o; };
     P.x = take(mb * c.d_model * 4);
     P.xn = take(mb * c.d_model * 4);
@@ -379,7 +382,7 @@ int ff_kv_alloc(ff_model* m, int32_t batch, int32_t max_ctx, void* kv_dev, size_
     size_t cache = align256((size_t)c.n_layers * batch * c.n_kv_heads * 2 * (size_t)max_ctx * c.head_dim * 2);
     kv->dev.base = (bf16_t*)kv_dev;
     kv->dev.rope = (const float2*)((uint8_t*)kv_dev + cache);
-    kv->dev.max_ctx = max_ctx; kv->dev.batch = batch;
+    kv->dev.max_ctx = max_ctx; kv->dev.batch = batch; kv->dev.seq0 = 0;
     int n = max_ctx * (c.head_dim / 2);
     k_rope_table<<<(n + 255) / 256, 256, 0, (hipStream_t)stream>>>((float2*)kv->dev.rope, max_ctx, c.head_dim, (double)c.rope_theta);
     hipError_t e = hipGetLastError();
@@ -414,13 +417,14 @@ int ff_kv_free(ff_kv* kv) {
     return FF_OK;
 }
 
-int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch,
-                   void* stream) {
-    int rc = check_step_args(m, tokens_dev, positions_dev, kv, logits_dev, batch);
-    if (rc) return rc;
-    hipStream_t st = (hipStream_t)stream;
+namespace {
+// One pass of the fused kernel over sequences [seq0, seq0 + batch), batch <= kMaxBatch.
+int fused_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch, int seq0,
+               hipStream_t st) {
     const int lm_in_kernel = m->dev.lm.wd == m->cfg.wdtype;
-    FusedLaunch a{m->dev, kv->dev, tokens_dev, positions_dev, logits_dev, batch, m->bar_gen, lm_in_kernel, m->n_cta, m->lds_bytes, st};
+    DevKV kvd = kv->dev;
+    kvd.seq0 = seq0;
+    FusedLaunch a{m->dev, kvd, tokens_dev, positions_dev, logits_dev, batch, m->bar_gen, lm_in_kernel, m->n_cta, m->lds_bytes, st};
     const char* what = "";
     const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     hipError_t e = hipErrorInvalidValue;
@@ -442,12 +446,28 @@ int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positi
     }
     return FF_OK;
 }
+}  // namespace
 
-int ff_decode_step_perop(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev,
-                         int32_t batch, void* stream) {
+// Batches above kMaxBatch run as consecutive passes of at most kMaxBatch sequences on the stream
+// (every pass streams the weights again; the exchange buffers are reused pass after pass).
+int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch,
+                   void* stream) {
     int rc = check_step_args(m, tokens_dev, positions_dev, kv, logits_dev, batch);
     if (rc) return rc;
-    hipStream_t st = (hipStream_t)stream;
+    for (int s0 = 0; s0 < batch; s0 += kMaxBatch) {
+        rc = fused_pass(m, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(kMaxBatch, batch - s0), s0,
+                        (hipStream_t)stream);
+        if (rc) return rc;
+    }
+    return FF_OK;
+}
+
+namespace {
+int perop_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch, int seq0,
+               hipStream_t st) {
+    int rc = 0;
+    DevKV kvd = kv->dev;
+    kvd.seq0 = seq0;
     const DevModel& D = m->dev;
     const ff_config& c = m->cfg;
     static bool attr_set = false;
@@ -458,14 +478,14 @@ int ff_decode_step_perop(ff_model* m, const int32_t* tokens_dev, const int32_t* 
     const int qd = c.n_q_heads * c.head_dim, qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     const int share = std::max(1, m->n_cta / (batch * c.n_kv_heads));
     const int ew_grid = 64;
-    op_embed<<<ew_grid, kThreads, 0, st>>>(D, kv->dev, tokens_dev, positions_dev, batch);
+    op_embed<<<ew_grid, kThreads, 0, st>>>(D, kvd, tokens_dev, positions_dev, batch);
     for (int l = 0; l < c.n_layers; l++) {
         const PLayer& L = m->host_layers[l];
         op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, L.g1, D.xn, c.d_model, c.rms_eps);
         if ((rc = gemv_op(m, L.qkv, D.xn, c.d_model, D.y, batch, EPI_STORE, st))) return rc;
-        op_rope_append<<<ew_grid, kThreads, 0, st>>>(D, kv->dev, tokens_dev, positions_dev, batch, l);
-        op_attn_partial<<<m->n_cta, kThreads, m->lds_bytes, st>>>(D, kv->dev, tokens_dev, positions_dev, batch, l);
-        op_attn_merge<<<batch * c.n_kv_heads, kThreads, 0, st>>>(D, kv->dev, tokens_dev, positions_dev, batch, share);
+        op_rope_append<<<ew_grid, kThreads, 0, st>>>(D, kvd, tokens_dev, positions_dev, batch, l);
+        op_attn_partial<<<m->n_cta, kThreads, m->lds_bytes, st>>>(D, kvd, tokens_dev, positions_dev, batch, l);
+        op_attn_merge<<<batch * c.n_kv_heads, kThreads, 0, st>>>(D, kvd, tokens_dev, positions_dev, batch, share);
         if ((rc = gemv_op(m, L.o, D.attn_o, qd, D.x, batch, EPI_RESIDUAL, st))) return rc;
         op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, L.g2, D.xn, c.d_model, c.rms_eps);
         if ((rc = gemv_op(m, L.gu, D.xn, c.d_model, D.y, batch, EPI_STORE, st))) return rc;
@@ -476,6 +496,19 @@ int ff_decode_step_perop(ff_model* m, const int32_t* tokens_dev, const int32_t* 
     if ((rc = gemv_op(m, D.lm, D.xn, c.d_model, logits_dev, batch, EPI_STORE, st))) return rc;
     (void)qkv_rows;
     HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+}  // namespace
+
+int ff_decode_step_perop(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev,
+                         int32_t batch, void* stream) {
+    int rc = check_step_args(m, tokens_dev, positions_dev, kv, logits_dev, batch);
+    if (rc) return rc;
+    for (int s0 = 0; s0 < batch; s0 += kMaxBatch) {
+        rc = perop_pass(m, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(kMaxBatch, batch - s0), s0,
+                        (hipStream_t)stream);
+        if (rc) return rc;
+    }
     return FF_OK;
 }
 

@@ -41,7 +41,7 @@ def test_argument_validation_needs_no_device():
     with pytest.raises(binding.FFError) as e:
         binding.ff_model_bytes(bad)
     assert e.value.code == binding.FF_ERR_UNSUPPORTED
-    bad = binding.make_config(synth.TINY, max_batch=9)
+    bad = binding.make_config(synth.TINY, max_batch=17)
     with pytest.raises(binding.FFError) as e:
         binding.ff_model_bytes(bad)
     assert e.value.code == binding.FF_ERR_ARG

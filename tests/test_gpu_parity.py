@@ -103,6 +103,14 @@ def test_tiny_bf16_batches_2_3_4():
         _run_teacher_forced(synth.TINY, 20 + b, synth.WDTYPE_BF16, batch=b, T0=40, steps=3)
 
 
+def test_tiny_batches_above_one_pass():
+    """Batches 5..16 run as passes of four sequences: ragged last pass (5, 7), full passes (8, 16),
+    with bf16 and with int8 weights."""
+    for b in (5, 7, 8, 16):
+        _run_teacher_forced(synth.TINY, 40 + b, synth.WDTYPE_BF16, batch=b, T0=24, steps=2)
+    _run_teacher_forced(synth.TINY.replace(d_ffn=1408), 61, synth.WDTYPE_INT8, batch=6, T0=24, steps=2)
+
+
 def test_llama8b_bf16_batch1_ctx1024_full_size():
     """The benchmark workload at full size (32 layers, d 4096, vocab 128256, ctx 1024), in the
     launch configuration bench.py times; every logit of three teacher-forced steps is compared."""
@@ -179,3 +187,8 @@ def test_llama70b_shaped_layers_batch1_ctx2048():
     parameter per step): exercises the d_model 8192 / d_ffn 28672 / 8-queries-per-kv-head instances."""
     _run_teacher_forced(synth.LLAMA_70B.replace(n_layers=2), 0x250522763, synth.WDTYPE_BF16, batch=1, T0=2048, steps=2, gpu_generated=True)
     _run_teacher_forced(synth.LLAMA_70B.replace(n_layers=2), 0x250522764, synth.WDTYPE_BF16, batch=2, T0=300, steps=1, gpu_generated=True)
+
+
+def test_llama70b_shaped_one_layer_batch16():
+    """Batch 16 at the 70B width (one layer, short context so that the oracle finishes in seconds)."""
+    _run_teacher_forced(synth.LLAMA_70B.replace(n_layers=1), 0x250522765, synth.WDTYPE_BF16, batch=16, T0=64, steps=1, gpu_generated=True)
