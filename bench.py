@@ -194,7 +194,8 @@ def main():
         # the same launches replayed from a HIP graph (the paper's baselines ran with graphs enabled)
         try:
             g = torch.cuda.CUDAGraph()
-            st_tok, st_pos = toks[args.warmup + n_po].clone(), pos[args.warmup + n_po].clone()
+            gi = min(args.warmup + n_po, total_steps - 1)
+            st_tok, st_pos = toks[gi].clone(), pos[gi].clone()
             with torch.cuda.graph(g):
                 binding.ff_decode_step_perop(dec.model, st_tok, st_pos, kv2, logits, batch)
             torch.cuda.synchronize()

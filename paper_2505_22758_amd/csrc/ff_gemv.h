@@ -12,7 +12,10 @@ template <> struct WTraits<W_BF16> { static constexpr int EPU = 8; };   // eleme
 template <> struct WTraits<W_INT8> { static constexpr int EPU = 16; };
 template <> struct WTraits<W_INT4> { static constexpr int EPU = 32; };
 
-constexpr int kUnr = 4;                    // 16-byte units per row and pipeline stage (per lane)
+// 16-byte units per row and pipeline stage (per lane).  A unit of int4 weights spans 32 columns, so
+// four units per lane would cover 8192 columns per stage: rows of 4096 columns would leave half
+// the lanes multiplying padding.  int4 stages are therefore half as wide and its ring twice as deep.
+template <int WD> constexpr int kUnrOf = WD == W_INT4 ? 2 : 4;
 // Pipeline stages (register ring slots) per wave.  Two stages (16 loads of 16 bytes per lane) keep
 // the memory pipe full; deeper rings measured slower in the fused kernel, because every byte
 // prefetched across a projection boundary queues in front of the loads of the next input vector
@@ -20,9 +23,8 @@ constexpr int kUnr = 4;                    // 16-byte units per row and pipeline
 #ifndef FF_DEPTH
 #define FF_DEPTH 2
 #endif
-template <int WD> constexpr int kDepthOf = FF_DEPTH;
-constexpr int kChunkUnits = 64 * kUnr;     // units of one row covered by one stage of one wave
-constexpr int kStageLoads = 2 * kUnr;      // weight loads a wave issues per stage
+template <int WD> constexpr int kDepthOf = WD == W_INT4 ? 2 * FF_DEPTH : FF_DEPTH;
+template <int WD> constexpr int kChunkUnitsOf = 64 * kUnrOf<WD>;   // units of one row covered by one stage of one wave
 
 // ---------------------------------------------------------------- reductions
 // Sum over the 64 lanes with DPP row operations; the result is wave-uniform.
@@ -154,15 +156,15 @@ __device__ void stage_act(const ActSrc& S, int batch, int K, int k0, int nunits,
 
 // ---------------------------------------------------------------- one stage of weights
 template <int WD> struct Stage {
-    u32x4 w[2][kUnr];
+    u32x4 w[2][kUnrOf<WD>];
 };
 template <> struct Stage<W_INT8> {
-    u32x4 w[2][kUnr];
+    u32x4 w[2][kUnrOf<W_INT8>];
     u32 rs[2];                 // raw fp16 row scales (loaded with the row's last chunk)
 };
 template <> struct Stage<W_INT4> {
-    u32x4 w[2][kUnr];
-    u32 s[2][kUnr], z[2][kUnr];   // raw fp16 group scale / zero of each unit
+    u32x4 w[2][kUnrOf<W_INT4>];
+    u32 s[2][kUnrOf<W_INT4>], z[2][kUnrOf<W_INT4>];   // raw fp16 group scale / zero of each unit
 };
 
 __device__ __forceinline__ float dot_bf16(const u32x4& w, const float4& a, const float4& b, float acc) {
@@ -183,18 +185,28 @@ __device__ __forceinline__ float dot_i8x4(u32 w, const float4& x, float acc) {
     acc = fmaf((float)((int)w >> 24), x.w, acc);
     return acc;
 }
-// (code - z) * s is formed exactly as the dequantisation definition, then multiplied by x.
-__device__ __forceinline__ float dot_i4x8(u32 w, const float4& x0, const float4& x1, float s, float z, float acc) {
-    acc = fmaf(((float)(w & 15u) - z) * s, x0.x, acc);
-    acc = fmaf(((float)((w >> 4) & 15u) - z) * s, x0.y, acc);
-    acc = fmaf(((float)((w >> 8) & 15u) - z) * s, x0.z, acc);
-    acc = fmaf(((float)((w >> 12) & 15u) - z) * s, x0.w, acc);
-    acc = fmaf(((float)((w >> 16) & 15u) - z) * s, x1.x, acc);
-    acc = fmaf(((float)((w >> 20) & 15u) - z) * s, x1.y, acc);
-    acc = fmaf(((float)((w >> 24) & 15u) - z) * s, x1.z, acc);
-    acc = fmaf(((float)(w >> 28) - z) * s, x1.w, acc);
+// int4 group-128: a 16-byte unit holds 32 codes of ONE group, so its contribution is
+//   sum_i (code_i - z) s x_i  =  s (sum_i code_i x_i  -  z sum_i x_i):
+// the inner loop only converts codes and multiplies (about 2.4 operations per weight); scale and
+// zero are applied once per unit.  Even codes of a word are isolated with one mask, odd ones with a
+// shift and the same mask, and the byte-to-float conversions pick them up.
+__device__ __forceinline__ float dot_i4x8_codes(u32 w, const float4& x0, const float4& x1, float acc) {
+    u32 e = w & 0x0F0F0F0Fu, o = (w >> 4) & 0x0F0F0F0Fu;
+    // value barriers (no instruction): keep the compiler from folding the masks back into one
+    // bit-field extract per code, which would cost an extra operation per weight
+    asm("" : "+v"(e));
+    asm("" : "+v"(o));
+    acc = fmaf((float)(e & 0xFFu), x0.x, acc);
+    acc = fmaf((float)(o & 0xFFu), x0.y, acc);
+    acc = fmaf((float)((e >> 8) & 0xFFu), x0.z, acc);
+    acc = fmaf((float)((o >> 8) & 0xFFu), x0.w, acc);
+    acc = fmaf((float)((e >> 16) & 0xFFu), x1.x, acc);
+    acc = fmaf((float)((o >> 16) & 0xFFu), x1.y, acc);
+    acc = fmaf((float)(e >> 24), x1.z, acc);
+    acc = fmaf((float)(o >> 24), x1.w, acc);
     return acc;
 }
+__device__ __forceinline__ float sum4(const float4& v) { return (v.x + v.y) + (v.z + v.w); }
 
 // ---------------------------------------------------------------- per-wave view of one GEMV
 // A projection is cut along K into segments whose staged input fits the LDS activation region
@@ -209,6 +221,7 @@ struct Stream {
     int p0, my_pairs, n_it;
 
     static constexpr int EPU = WTraits<WD>::EPU;
+    static constexpr int kChunkUnits = kChunkUnitsOf<WD>;
     static constexpr int seg_units = (kLdsActBytes / (B * EPU * 4)) / kChunkUnits * kChunkUnits;
 
     __device__ static Stream make(const PMat& M, int seg, int gwave, int n_gwaves) {
@@ -235,6 +248,7 @@ struct Stream {
 // epilogue.  Nothing is converted here, so no load result is waited for at issue time.
 template <int WD, int B>
 __device__ __forceinline__ void load_stage(const Stream<WD, B>& S, int pair, int chunk, Stage<WD>& st, int lane) {
+    constexpr int kUnr = kUnrOf<WD>;
 #pragma unroll
     for (int u = 0; u < kUnr; u++) {
         const int j = min((chunk * kUnr + u) * 64 + lane, S.nunits - 1);
@@ -277,7 +291,7 @@ __device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD>
 // projections are matrix-vector products with the input cached on chip and each workgroup owning
 // some rows of W; Section 4.2: at batch 2-4 the weights are still read exactly once and the inputs
 // replicated).  On entry ring[s] holds iteration s (s < min(kDepth, n_it)); iteration i+kDepth is
-// issued into the slot iteration i has just freed, so kDepth*kStageLoads 16-byte non-temporal loads
+// issued into the slot iteration i has just freed, so 2*kDepth*kUnr 16-byte non-temporal loads
 // per lane stay in flight across row boundaries.  epi(pair, b, v0, v1) runs on lane 0 with the two
 // finished dot products of rows (2*pair, 2*pair+1); partial sums of earlier K segments are carried
 // in `myacc` (LDS, private to the wave).
@@ -285,6 +299,7 @@ template <int WD, int B, class Epi>
 __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs, float* myacc,
                                          int batch, int lane, Epi& epi) {
     constexpr int kDepth = kDepthOf<WD>;
+    constexpr int kUnr = kUnrOf<WD>;
     constexpr int EPU = WTraits<WD>::EPU;
     constexpr int NQ = EPU / 4;
     const int nup = S.nup;
@@ -319,13 +334,15 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
                     float4 x[8];
 #pragma unroll
                     for (int q = 0; q < 8; q++) x[q] = xq[q * nup];
+                    const float xsum = ((sum4(x[0]) + sum4(x[1])) + (sum4(x[2]) + sum4(x[3]))) + ((sum4(x[4]) + sum4(x[5])) + (sum4(x[6]) + sum4(x[7])));
 #pragma unroll
                     for (int r = 0; r < 2; r++) {
                         const float sc = f16_to_f((f16_t)st.s[r][u]), zp = f16_to_f((f16_t)st.z[r][u]);
-                        float a = acc[r][b];
-                        a = dot_i4x8(st.w[r][u].x, x[0], x[1], sc, zp, a); a = dot_i4x8(st.w[r][u].y, x[2], x[3], sc, zp, a);
-                        a = dot_i4x8(st.w[r][u].z, x[4], x[5], sc, zp, a); a = dot_i4x8(st.w[r][u].w, x[6], x[7], sc, zp, a);
-                        acc[r][b] = a;
+                        float t = dot_i4x8_codes(st.w[r][u].x, x[0], x[1], 0.f);
+                        t = dot_i4x8_codes(st.w[r][u].y, x[2], x[3], t);
+                        t = dot_i4x8_codes(st.w[r][u].z, x[4], x[5], t);
+                        t = dot_i4x8_codes(st.w[r][u].w, x[6], x[7], t);
+                        acc[r][b] = fmaf(sc, fmaf(-zp, xsum, t), acc[r][b]);
                     }
                 }
             }
