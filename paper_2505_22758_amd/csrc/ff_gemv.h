@@ -224,7 +224,7 @@ struct Stream {
     static constexpr int kChunkUnits = kChunkUnitsOf<WD>;
     static constexpr int seg_units = (kLdsActBytes / (B * EPU * 4)) / kChunkUnits * kChunkUnits;
 
-    __device__ static Stream make(const PMat& M, int seg, int gwave, int n_gwaves) {
+    __device__ __forceinline__ static Stream make(const PMat& M, int seg, int gwave, int n_gwaves) {
         Stream S;
         S.w = M.w; S.s = M.s; S.z = M.z; S.N = M.n; S.K = M.k; S.ng = M.k / 128;
         S.rowb = WD == W_BF16 ? (size_t)M.k * 2 : WD == W_INT8 ? (size_t)M.k : (size_t)M.k / 2;
@@ -287,6 +287,49 @@ __device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD>
     return n;
 }
 
+// The multiply-accumulates of one stage: chunk cc of a row pair against the staged input.
+template <int WD, int B>
+__device__ __forceinline__ void stage_fma(const Stage<WD>& st, const float4* xs, int nup, int cc, int lane, float (&acc)[2][B]) {
+    constexpr int kUnr = kUnrOf<WD>;
+    constexpr int NQ = WTraits<WD>::EPU / 4;
+#pragma unroll
+    for (int u = 0; u < kUnr; u++) {
+        const int j = (cc * kUnr + u) * 64 + lane;
+#pragma unroll
+        for (int b = 0; b < B; b++) {
+            const float4* xq = xs + (size_t)b * NQ * nup + j;
+            if constexpr (WD == W_BF16) {
+                float4 x0 = xq[0], x1 = xq[nup];
+                acc[0][b] = dot_bf16(st.w[0][u], x0, x1, acc[0][b]);
+                acc[1][b] = dot_bf16(st.w[1][u], x0, x1, acc[1][b]);
+            } else if constexpr (WD == W_INT8) {
+                float4 x0 = xq[0], x1 = xq[nup], x2 = xq[2 * nup], x3 = xq[3 * nup];
+#pragma unroll
+                for (int r = 0; r < 2; r++) {
+                    float a = acc[r][b];
+                    a = dot_i8x4(st.w[r][u].x, x0, a); a = dot_i8x4(st.w[r][u].y, x1, a);
+                    a = dot_i8x4(st.w[r][u].z, x2, a); a = dot_i8x4(st.w[r][u].w, x3, a);
+                    acc[r][b] = a;
+                }
+            } else {
+                float4 x[8];
+#pragma unroll
+                for (int q = 0; q < 8; q++) x[q] = xq[q * nup];
+                const float xsum = ((sum4(x[0]) + sum4(x[1])) + (sum4(x[2]) + sum4(x[3]))) + ((sum4(x[4]) + sum4(x[5])) + (sum4(x[6]) + sum4(x[7])));
+#pragma unroll
+                for (int r = 0; r < 2; r++) {
+                    const float sc = f16_to_f((f16_t)st.s[r][u]), zp = f16_to_f((f16_t)st.z[r][u]);
+                    float t = dot_i4x8_codes(st.w[r][u].x, x[0], x[1], 0.f);
+                    t = dot_i4x8_codes(st.w[r][u].y, x[2], x[3], t);
+                    t = dot_i4x8_codes(st.w[r][u].z, x[4], x[5], t);
+                    t = dot_i4x8_codes(st.w[r][u].w, x[6], x[7], t);
+                    acc[r][b] = fmaf(sc, fmaf(-zp, xsum, t), acc[r][b]);
+                }
+            }
+        }
+    }
+}
+
 // Weight-streaming GEMV over one stream for up to B batch rows (paper Section 3.2: batch-one
 // projections are matrix-vector products with the input cached on chip and each workgroup owning
 // some rows of W; Section 4.2: at batch 2-4 the weights are still read exactly once and the inputs
@@ -311,42 +354,7 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
     for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
 
     auto compute = [&](const Stage<WD>& st) {
-#pragma unroll
-        for (int u = 0; u < kUnr; u++) {
-            const int j = (cc * kUnr + u) * 64 + lane;
-#pragma unroll
-            for (int b = 0; b < B; b++) {
-                const float4* xq = xs + (size_t)b * NQ * nup + j;
-                if constexpr (WD == W_BF16) {
-                    float4 x0 = xq[0], x1 = xq[nup];
-                    acc[0][b] = dot_bf16(st.w[0][u], x0, x1, acc[0][b]);
-                    acc[1][b] = dot_bf16(st.w[1][u], x0, x1, acc[1][b]);
-                } else if constexpr (WD == W_INT8) {
-                    float4 x0 = xq[0], x1 = xq[nup], x2 = xq[2 * nup], x3 = xq[3 * nup];
-#pragma unroll
-                    for (int r = 0; r < 2; r++) {
-                        float a = acc[r][b];
-                        a = dot_i8x4(st.w[r][u].x, x0, a); a = dot_i8x4(st.w[r][u].y, x1, a);
-                        a = dot_i8x4(st.w[r][u].z, x2, a); a = dot_i8x4(st.w[r][u].w, x3, a);
-                        acc[r][b] = a;
-                    }
-                } else {
-                    float4 x[8];
-#pragma unroll
-                    for (int q = 0; q < 8; q++) x[q] = xq[q * nup];
-                    const float xsum = ((sum4(x[0]) + sum4(x[1])) + (sum4(x[2]) + sum4(x[3]))) + ((sum4(x[4]) + sum4(x[5])) + (sum4(x[6]) + sum4(x[7])));
-#pragma unroll
-                    for (int r = 0; r < 2; r++) {
-                        const float sc = f16_to_f((f16_t)st.s[r][u]), zp = f16_to_f((f16_t)st.z[r][u]);
-                        float t = dot_i4x8_codes(st.w[r][u].x, x[0], x[1], 0.f);
-                        t = dot_i4x8_codes(st.w[r][u].y, x[2], x[3], t);
-                        t = dot_i4x8_codes(st.w[r][u].z, x[4], x[5], t);
-                        t = dot_i4x8_codes(st.w[r][u].w, x[6], x[7], t);
-                        acc[r][b] = fmaf(sc, fmaf(-zp, xsum, t), acc[r][b]);
-                    }
-                }
-            }
-        }
+        stage_fma<WD, B>(st, xs, nup, cc, lane, acc);
         if (cc == S.cpr - 1) {   // row pair finished (for this K segment)
             const int lp = pc - S.p0;
 #pragma unroll

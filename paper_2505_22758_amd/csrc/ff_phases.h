@@ -51,7 +51,7 @@ struct TSrc {
 // cheap way to sit out a producer that is still running -- a few 8-byte loads with pauses in
 // between cost the memory system next to nothing even with every workgroup waiting at once.
 template <bool HAS_ADD>
-__device__ bool light_wait(const TSrc& S, int batch, int k0, int nel, int lane) {
+__device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int nel, int lane) {
     const int sample = min(k0 + (int)(((long)(lane % kPollLanes) * nel) / kPollLanes) + (int)(blockIdx.x % 16) * 2, k0 + nel - 1);
     const tagged_t* sb = S.base + (size_t)(batch - 1) * S.stride;
     const tagged_t* sa = HAS_ADD ? S.add + (size_t)(batch - 1) * S.add_stride : nullptr;
@@ -79,7 +79,7 @@ __device__ bool light_wait(const TSrc& S, int batch, int k0, int nel, int lane) 
 // 8*QB destination registers per source must fit beside the wave's prefetched weight tiles, or the
 // compiler parks those tiles elsewhere and has to wait for them first).
 template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB>
-__device__ bool stage_tagged_impl(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, u64* ev) {
+__device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, u64* ev) {
     constexpr int NQ = EPU / 4;
     if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
     const int lane = tid & 63;
@@ -216,7 +216,7 @@ struct PlainAttnIO {
     // Workgroup-collective: the G query rows of kv head j, then (with_cur) this step's own key and
     // value row, as floats into dst[G*HD + 2*HD] (LDS); ends with a workgroup barrier.
     template <int HD, int G, int NT>
-    __device__ bool stage_inputs(const DevModel& M, int b, int j, bool with_cur, float* dst) const {
+    __device__ __forceinline__ bool stage_inputs(const DevModel& M, int b, int j, bool with_cur, float* dst) const {
         const int nq = G * HD, n = nq + (with_cur ? 2 * HD : 0);
         for (int e = threadIdx.x; e < n; e += NT) {
             float v;
@@ -228,7 +228,7 @@ struct PlainAttnIO {
         return true;
     }
     template <int HD>
-    __device__ void store_partial(const DevModel& M, size_t hs, int dim, float ot, float mx, float lt) const {
+    __device__ __forceinline__ void store_partial(const DevModel& M, size_t hs, int dim, float ot, float mx, float lt) const {
         PlainIO::st(M.part_o + hs * HD + dim, ot);
         if (dim == 0) { PlainIO::st(M.part_m + hs, mx); PlainIO::st(M.part_l + hs, lt); }
     }
@@ -240,7 +240,7 @@ struct TaggedAttnIO {
     // item is a few kilobytes (one or two 16-byte pairs per thread), so the workgroup simply
     // re-reads it until the QKV projection's tag is on every element; returns false on a time-out.
     template <int HD, int G, int NT>
-    __device__ bool stage_inputs(const DevModel& M, int b, int j, bool with_cur, float* dst) const {
+    __device__ __forceinline__ bool stage_inputs(const DevModel& M, int b, int j, bool with_cur, float* dst) const {
         constexpr int NQ2 = G * HD / 2, NK2 = HD / 2;       // pairs of queries, of one k or v row
         constexpr int PP = (NQ2 + 2 * NK2 + NT - 1) / NT;   // pairs per thread
         const int np = NQ2 + (with_cur ? 2 * NK2 : 0);
@@ -272,14 +272,14 @@ struct TaggedAttnIO {
         return true;
     }
     template <int HD>
-    __device__ void store_partial(const DevModel& M, size_t hs, int dim, float ot, float mx, float lt) const {
+    __device__ __forceinline__ void store_partial(const DevModel& M, size_t hs, int dim, float ot, float mx, float lt) const {
         tst(M.tpart_o + hs * HD + dim, ot, out_tag);
         if (dim == 0) { tst(M.tpart_m + hs, mx, out_tag); tst(M.tpart_l + hs, lt, out_tag); }
     }
 };
 
 template <int HD, int G, int NW, class XIO>
-__device__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, int layer, int b, int j, int t0, int t1, bool with_cur,
+__device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, int layer, int b, int j, int t0, int t1, bool with_cur,
                           int split, uint8_t* lds, u64* ev = nullptr) {
     constexpr int LPR = HD / 8;        // lanes per cache row
     constexpr int RPW = 64 / LPR;      // rows per wave load
@@ -440,7 +440,7 @@ __device__ void attn_merge(const DevModel& M, int b, int j, int nsplit, float* l
 // (b, j) gathers all splits, re-reading until every partial carries this layer's attention tag,
 // and publishes attn_o with the same tag.  Returns false on a time-out.
 template <int HD, int G, int NT>
-__device__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, float* lds, u64* ev = nullptr) {
+__device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, float* lds, u64* ev = nullptr) {
     float* ms = lds;
     float* ls = lds + G * kMaxSplits;
     constexpr int kSB = 16;   // splits gathered per batch of loads
@@ -545,7 +545,7 @@ template <class IO>
 struct EpiQKV {
     const DevModel& M; const DevKV& KV; const int* pos; int layer;
     const float2* rope;   // [batch][hd/2] (cos, sin) of each sequence's position; LDS in the fused kernel
-    __device__ void operator()(int pair, int b, float v0, float v1) const {
+    __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         const int half = M.hd / 2;
         const int nq = M.Hq * half, nk = M.Hkv * half;
         const int p = as_global(pos)[b];
@@ -580,7 +580,7 @@ struct EpiQKV {
 // Per-operation kernels: x[b][row] += W row . input
 struct EpiResidual {
     float* x; int d;
-    __device__ void operator()(int pair, int b, float v0, float v1) const {
+    __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         FF_GLOBAL f32x2* p = as_global((f32x2*)(x + (size_t)b * d + 2 * pair));
         f32x2 o = *p;
         *p = f32x2{o.x + v0, o.y + v1};
@@ -590,7 +590,7 @@ struct EpiResidual {
 template <class IO>
 struct EpiSwiGLU {
     float* h; int F;
-    __device__ void operator()(int pair, int b, float g, float u) const {
+    __device__ __forceinline__ void operator()(int pair, int b, float g, float u) const {
         float s = g / (1.0f + expf(-g));
         IO::st(h + (size_t)b * F + pair, s * u);
     }
@@ -598,7 +598,7 @@ struct EpiSwiGLU {
 // ---- fused-kernel epilogues: outputs go to the tagged exchange buffers ----
 struct EpiQKVTagged {   // pos: positions of this step, staged in LDS
     const DevModel& M; const DevKV& KV; const int* pos; int layer; const float2* rope; u32 tag;
-    __device__ void operator()(int pair, int b, float v0, float v1) const {
+    __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         const int half = M.hd / 2;
         const int nq = M.Hq * half, nk = M.Hkv * half;
         const int p = pos[b];
@@ -632,18 +632,18 @@ struct EpiQKVTagged {   // pos: positions of this step, staged in LDS
 };
 struct EpiDeltaTagged {   // projections feeding the residual stream: publish the output, the next
     tagged_t* delta; int d; u32 tag;   // normalised staging adds it (paper Section 3.2: added to the residual)
-    __device__ void operator()(int pair, int b, float v0, float v1) const { tst2(delta + (size_t)b * d + 2 * pair, v0, v1, tag); }
+    __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const { tst2(delta + (size_t)b * d + 2 * pair, v0, v1, tag); }
 };
 struct EpiSwiGLUTagged {   // packed rows (2i, 2i+1) = (gate_i, up_i):  h_i = silu(gate_i) * up_i
     tagged_t* h; int F; u32 tag;
-    __device__ void operator()(int pair, int b, float g, float u) const {
+    __device__ __forceinline__ void operator()(int pair, int b, float g, float u) const {
         float s = g / (1.0f + expf(-g));
         tst(h + (size_t)b * F + pair, s * u, tag);
     }
 };
 struct EpiStore {   // plain output rows (logits; per-op raw projections)
     float* y; int n;
-    __device__ void operator()(int pair, int b, float v0, float v1) const {
+    __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         FF_GLOBAL float* p = as_global(y + (size_t)b * n + 2 * pair);
         p[0] = v0;
         if (2 * pair + 1 < n) p[1] = v1;
