@@ -43,12 +43,13 @@ WORKLOADS = {
 }
 
 
-def cpu_baseline(shape, wdtype, ctx, seed, n_layers_sample=4, steps=1, gen_device="cpu"):
+def cpu_baseline(shape, wdtype, ctx, seed, n_layers_sample=16, steps=16, gen_device="cpu"):
     """Times the CPU oracle (as it stands) on a bounded sample: `steps` decode steps of an
     n_layers_sample-layer model of the same shape plus the LM head, scaled to the full depth."""
     import numpy as np
     from oracle import oracle
     from paper_2505_22758_amd import synth
+    n_layers_sample = min(n_layers_sample, shape.n_layers)   # 8B shape: about 10 s of CPU work on 16 cores
     sub = shape.replace(n_layers=n_layers_sample)
     def to_cpu(obj):
         return {k: to_cpu(v) for k, v in obj.items()} if isinstance(obj, dict) else obj.cpu()
