@@ -44,7 +44,7 @@ enum {
     FF_ERR_UNSUPPORTED = -2, /* configuration has no compiled kernel instance */
     FF_ERR_RANGE = -3,       /* a position is >= max_ctx, or a token id >= vocab (seen on device) */
     FF_ERR_NOMEM = -4,       /* a caller-provided buffer is too small or misaligned */
-    FF_ERR_TIMEOUT = -5,     /* the in-kernel grid barrier gave up waiting (CTAs not co-resident) */
+    FF_ERR_TIMEOUT = -5,     /* a workgroup gave up waiting for another one's output (not co-resident?) */
     FF_ERR_HIP = -6          /* a HIP runtime call failed; text in ff_last_error() */
 };
 
@@ -154,7 +154,8 @@ int ff_debug_dequant(const ff_model *m, int32_t layer, int32_t which, float *out
  *                     stored, split maxima seen and merged output stored if it merges, end) */
 int ff_debug_timeline(ff_model *m, void *buf_dev);
 
-/* Number of grid barriers one fused step executes (for tests of the schedule), and the number of
+/* Number of device-wide barriers one fused step executes (0: phases are ordered by tagged dataflow;
+ * kept for tests of the schedule), and the number of
  * workgroups / threads per workgroup the fused kernel launches with. */
 int ff_fused_schedule(const ff_model *m, int32_t *barriers_per_step, int32_t *n_workgroups,
                       int32_t *threads_per_workgroup);

@@ -98,14 +98,11 @@ template <class T> __device__ __forceinline__ const FF_CONST T* as_const(const T
 
 // ---------------------------------------------------------------- coherent exchange accesses
 // Activations exchanged between workgroups inside one launch must bypass the per-XCD L2's
-// non-coherent lines, so that no cache write-back / invalidate is needed at a grid barrier
-// (an agent-scope acquire or release fence costs several microseconds on this chip).
-//   stores: agent-scope relaxed atomic stores (write through to the coherence point; the issuing
-//           wave waits for their acknowledgement with s_waitcnt before it arrives at a barrier)
-//   loads : raw buffer loads with the sc1 cache-policy bit -- the same instruction an agent-scope
-//           atomic load compiles to, but an ordinary load to the compiler, so many of them can be
-//           in flight at once (a chain of dependent ~1 us round trips is what must be avoided).
-// Loads take a wave-uniform base pointer plus a per-lane element index (buffers < 4 GiB).
+// non-coherent lines (an agent-scope acquire or release fence costs several microseconds on this
+// chip): they are written with agent-scope relaxed atomic stores (write through to the coherence
+// point) and read with agent-scope relaxed atomic loads of at most 8 bytes (see the tagged
+// exchange format).  Buffer loads with the matching cache-policy bit are not used: they were
+// observed to keep returning a stale copy while polling.
 __device__ __forceinline__ void xst(float* p, float v) {
     __hip_atomic_store(as_global((u32*)p), __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -116,11 +113,6 @@ __device__ __forceinline__ void xst2(float* p, float a, float b) {
 __device__ __forceinline__ u32 xld_u32(const u32* p) { return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void xst_u32(u32* p, u32 v) { __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ u32 xadd_u32(u32* p, u32 v) { return __hip_atomic_fetch_add(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-
-constexpr int kAuxSc1 = 16;   // buffer-instruction cache policy: sc1 (agent-coherent)
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
-    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, -1, 0x00020000);
-}
 
 struct PlainIO {   // launch-boundary ordered accesses (per-operation kernels)
     static __device__ __forceinline__ float ld(const float* base, int i) { return as_global(base)[i]; }
@@ -136,23 +128,6 @@ struct PlainIO {   // launch-boundary ordered accesses (per-operation kernels)
     static __device__ __forceinline__ void st2(float* p, float a, float b) { *as_global((f32x2*)p) = f32x2{a, b}; }
     static __device__ __forceinline__ void st4(float* p, float4 v) { *as_global((f32x4*)p) = f32x4{v.x, v.y, v.z, v.w}; }
 };
-struct CoherentIO {   // accesses that are coherent across workgroups inside one launch
-    static __device__ __forceinline__ float ld(const float* base, int i) {
-        return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(base), i * 4, 0, kAuxSc1));
-    }
-    static __device__ __forceinline__ float2 ld2(const float* base, int i) {
-        u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(make_rsrc(base), i * 4, 0, kAuxSc1);
-        return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
-    }
-    static __device__ __forceinline__ float4 ld4(const float* base, int i) {
-        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc(base), i * 4, 0, kAuxSc1);
-        return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
-    }
-    static __device__ __forceinline__ void st(float* p, float v) { xst(p, v); }
-    static __device__ __forceinline__ void st2(float* p, float a, float b) { xst2(p, a, b); }
-    static __device__ __forceinline__ void st4(float* p, float4 v) { xst2(p, v.x, v.y); xst2(p + 2, v.z, v.w); }
-};
-
 // ---------------------------------------------------------------- scalar helpers
 __device__ __forceinline__ float bf_lo(u32 w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(u32 w) { return __uint_as_float(w & 0xFFFF0000u); }

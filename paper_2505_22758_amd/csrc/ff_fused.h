@@ -9,8 +9,6 @@ namespace ff {
 constexpr int kFusedWaves = 4;
 constexpr int kFusedThreads = kFusedWaves * 64;
 
-// Workgroup barrier that orders LDS traffic only: vector-memory loads stay in flight across it.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
 
 // ---------------------------------------------------------------- the fused whole-model kernel

@@ -1,7 +1,7 @@
 // Weight-streaming GEMV engine: activation staging into LDS, a register ring of weight tiles kept
 // in flight ahead of the FMAs, and the per-format dot products.  Used by the fused whole-model
-// kernel (with tiles of the NEXT phase already in flight while a grid barrier is crossed) and by
-// the per-operation baseline kernels.
+// kernel (which requests a projection's first tiles before it waits for the projection's input)
+// and by the per-operation baseline kernels.
 #pragma once
 #include "ff_device.h"
 

@@ -1,6 +1,6 @@
 // Split-KV attention and the projection epilogues of the decode step.  Workgroup-collective
-// device functions used by the fused kernel (between grid barriers) and, with launch boundaries
-// instead of barriers, by the per-operation baseline kernels.
+// device functions used by the fused kernel (ordered by tagged dataflow) and, with launch
+// boundaries as the ordering, by the per-operation baseline kernels.
 #pragma once
 #include "ff_gemv.h"
 

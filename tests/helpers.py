@@ -14,17 +14,23 @@ REL_L2_TOL = 1e-2
 ARGMAX_MIN_AGREE = 0.99
 
 
+def prefill_lengths(T0, batch):
+    """T0 as one length for every sequence or one length per sequence."""
+    return [int(T0)] * batch if np.isscalar(T0) else [int(t) for t in T0]
+
+
 def oracle_side(shape, seed, wdtype, batch, T0, max_ctx, quant_lm_head=True):
     from oracle import oracle
     layers = [synth.make_layer(shape, seed, l, wdtype, "cpu") for l in range(shape.n_layers)]
     head = synth.make_head(shape, seed, wdtype, "cpu", quant_lm_head)
     M = oracle.OracleModel(shape, layers, head)
     kv = M.new_kv(batch, max_ctx)
+    T0s = prefill_lengths(T0, batch)
     for l in range(shape.n_layers):
         for b in range(batch):
-            if T0 > 0:
-                k, v = synth.make_kv_prefill(shape, seed, l, b, T0, "cpu")
-                kv[l, b, 0, :T0], kv[l, b, 1, :T0] = oracle._np(k), oracle._np(v)
+            if T0s[b] > 0:
+                k, v = synth.make_kv_prefill(shape, seed, l, b, T0s[b], "cpu")
+                kv[l, b, 0, :T0s[b]], kv[l, b, 1, :T0s[b]] = oracle._np(k), oracle._np(v)
     return M, kv
 
 
@@ -41,13 +47,14 @@ def hip_side(shape, seed, wdtype, batch, T0, max_ctx, n_caches=1, quant_lm_head=
     torch.cuda.synchronize()
     del hw
     caches = []
+    T0s = prefill_lengths(T0, batch)
     for _ in range(n_caches):
         buf = torch.zeros(binding.ff_kv_bytes(dec.model, batch, max_ctx), dtype=torch.uint8, device=device)
         kv = binding.ff_kv_alloc(dec.model, batch, max_ctx, buf)
         for l in range(shape.n_layers):
             for b in range(batch):
-                if T0 > 0:
-                    k, v = synth.make_kv_prefill(shape, seed, l, b, T0, device)
+                if T0s[b] > 0:
+                    k, v = synth.make_kv_prefill(shape, seed, l, b, T0s[b], device)
                     binding.ff_kv_fill(kv, l, b, 0, k, v)
         torch.cuda.synchronize()
         caches.append((kv, buf))
@@ -92,12 +99,13 @@ def both_sides_gpu_generated(shape, seed, wdtype, batch, T0, max_ctx, n_caches=1
     for _ in range(n_caches):
         buf = torch.zeros(binding.ff_kv_bytes(dec.model, batch, max_ctx), dtype=torch.uint8, device=device)
         caches.append((binding.ff_kv_alloc(dec.model, batch, max_ctx, buf), buf))
+    T0s = prefill_lengths(T0, batch)
     for l in range(shape.n_layers):
         for b in range(batch):
-            if T0 > 0:
-                k, v = synth.make_kv_prefill(shape, seed, l, b, T0, device)
+            if T0s[b] > 0:
+                k, v = synth.make_kv_prefill(shape, seed, l, b, T0s[b], device)
                 for kv, _ in caches:
                     binding.ff_kv_fill(kv, l, b, 0, k, v)
-                okv[l, b, 0, :T0], okv[l, b, 1, :T0] = oracle._np(k.cpu()), oracle._np(v.cpu())
+                okv[l, b, 0, :T0s[b]], okv[l, b, 1, :T0s[b]] = oracle._np(k.cpu()), oracle._np(v.cpu())
     torch.cuda.synchronize()
     return M, okv, dec, caches

@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, gpu_generated=False):
     from paper_2505_22758_amd import binding
     from oracle import oracle
-    max_ctx = T0 + steps + 3
+    T0s = helpers.prefill_lengths(T0, batch)   # one prefill length for all sequences, or one each
+    max_ctx = max(T0s) + steps + 3
     if gpu_generated:
         M, okv, dec, caches = helpers.both_sides_gpu_generated(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2)
     else:
@@ -25,7 +26,7 @@ def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, gp
     worst = {"fused": [0.0, 0.0], "perop": [0.0, 0.0]}
     agree = {"fused": [], "perop": []}
     for s in range(steps):
-        pos = np.full(batch, T0 + s, dtype=np.int32)
+        pos = np.array([t + s for t in T0s], dtype=np.int32)
         ref = M.decode_step(toks[s].numpy(), pos, okv)
         tok_d = toks[s].to("cuda:0")
         pos_d = torch.from_numpy(pos).to("cuda:0")
@@ -51,10 +52,10 @@ def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, gp
                 for b in range(batch):
                     k = torch.empty(steps, shape.n_kv_heads, shape.head_dim, dtype=torch.bfloat16, device="cuda:0")
                     v = torch.empty_like(k)
-                    binding.ff_kv_read(caches[ci][0], l, b, T0, k, v)
+                    binding.ff_kv_read(caches[ci][0], l, b, T0s[b], k, v)
                     for kv_i, t in ((0, k), (1, v)):
                         got = t.cpu().view(torch.int16).numpy().view(np.uint16)
-                        want = okv[l, b, kv_i, T0:T0 + steps]
+                        want = okv[l, b, kv_i, T0s[b]:T0s[b] + steps]
                         gv, wv = oracle.bf16_bits_to_f64(got), oracle.bf16_bits_to_f64(want)
                         ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(wv), 1e-30))) - 7)
                         # One bf16 step: the two sides round values that differ by summation order, so a
@@ -101,6 +102,14 @@ def test_tiny_bf16_empty_cache_and_ragged_lengths():
 def test_tiny_bf16_batches_2_3_4():
     for b in (2, 3, 4):
         _run_teacher_forced(synth.TINY, 20 + b, synth.WDTYPE_BF16, batch=b, T0=40, steps=3)
+
+
+def test_sequences_of_different_lengths_in_one_batch():
+    """Every sequence has its own position (the number of splits follows each sequence's length):
+    empty, shorter than one split, ragged and long caches side by side; then the 8B shape."""
+    _run_teacher_forced(synth.TINY, 71, synth.WDTYPE_BF16, batch=4, T0=[0, 5, 77, 300], steps=3)
+    _run_teacher_forced(synth.TINY, 72, synth.WDTYPE_BF16, batch=7, T0=[1, 0, 130, 64, 63, 65, 9], steps=2)
+    _run_teacher_forced(synth.LLAMA_8B, 0x250522766, synth.WDTYPE_BF16, batch=4, T0=[1024, 1000, 7, 2048], steps=1, gpu_generated=True)
 
 
 def test_tiny_batches_above_one_pass():
