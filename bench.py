@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="llama3-8b-bf16-b1-ctx1024", choices=sorted(WORKLOADS))
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (sweeps)")
+    ap.add_argument("--ctx", type=int, default=0, help="override the workload's KV context (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-perop", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -103,6 +105,7 @@ def main():
     from paper_2505_22758_amd import binding, synth
 
     shape_name, wdtype, batch, ctx = WORKLOADS[args.workload]
+    batch, ctx = args.batch or batch, args.ctx or ctx
     shape = synth.SHAPES[shape_name]
     seed = 0x250522758
     dev = "cuda:0"
@@ -176,12 +179,13 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "bf16", 1: "int8", 2: "int4"}[wdtype] + " weights, f32 activations/accumulate",
         "data": "synthetic",
-        "config": {"workload": args.workload, "batch": batch, "kv_context": ctx,
+        "config": {"workload": args.workload if not (args.batch or args.ctx) else f"{args.workload} with batch {batch}, ctx {ctx}",
+                   "batch": batch, "kv_context": ctx,
                    "weight_bytes_per_step": wbytes, "kv_bytes_per_step_mean": float(np.mean(kvb))},
         "tokens_per_s": batch / (ms_per_step * 1e-3),
         "latency_us_p10_p50_p90": [float(np.percentile(per_step_ms, q)) * 1e3 for q in (10, 50, 90)],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.batch or args.ctx) else measured_traffic(args.workload),
                      "kernel": "fused_decode_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": alg_bytes},
     }
 
