@@ -201,3 +201,40 @@ def test_llama70b_shaped_layers_batch1_ctx2048():
 def test_llama70b_shaped_one_layer_batch16():
     """Batch 16 at the 70B width (one layer, short context so that the oracle finishes in seconds)."""
     _run_teacher_forced(synth.LLAMA_70B.replace(n_layers=1), 0x250522765, synth.WDTYPE_BF16, batch=16, T0=64, steps=1, gpu_generated=True)
+
+
+def test_two_models_interleaved_on_a_side_stream():
+    """Two models of different geometry (head_dim 64 vs 128, bf16 vs int8) alive at once and stepped
+    alternately on a non-default stream: no state is shared between models, and a model's result does
+    not depend on what ran in between (compared with a run of the same model alone)."""
+    from paper_2505_22758_amd import binding
+    shapes = [(synth.TINY, synth.WDTYPE_BF16, 91), (synth.TINY.replace(head_dim=128, n_q_heads=4, n_kv_heads=1, d_ffn=1408), synth.WDTYPE_INT8, 92)]
+    T0, steps = 50, 3
+
+    def setup(shape, wd, seed):
+        dec, caches = helpers.hip_side(shape, seed, wd, 1, T0, T0 + steps + 2, n_caches=1)
+        toks = synth.make_tokens(shape, seed, steps, 1).to("cuda:0")
+        return dec, caches[0][0], caches, toks, torch.zeros(1, shape.vocab, device="cuda:0")
+
+    def run(models, stream):
+        outs = [[] for _ in models]
+        with torch.cuda.stream(stream):
+            for s in range(steps):
+                for i, (dec, kv, _, toks, lg) in enumerate(models):
+                    pos = torch.tensor([T0 + s], dtype=torch.int32, device="cuda:0")
+                    binding.ff_decode_step(dec.model, toks[s], pos, kv, lg, 1)
+                    stream.synchronize()
+                    binding.ff_status(dec.model)
+                    outs[i].append(lg.cpu().clone())
+        return outs
+
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    both = [setup(*a) for a in shapes]
+    together = run(both, side)
+    for i, a in enumerate(shapes):
+        alone = run([setup(*a)], torch.cuda.current_stream())[0]
+        for s in range(steps):
+            assert torch.equal(alone[s], together[i][s]), (i, s)
+    for m in both:
+        m[0].close()
