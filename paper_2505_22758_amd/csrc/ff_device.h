@@ -69,7 +69,12 @@ struct DevModel {
     float* part_l;
     float* part_o;   //                            [B][Hq][kMaxSplits][hd]
     // tagged exchange buffers of the fused kernel: (fp32 bits, tag) pairs, same shapes as above
-    u32x2* tx;  u32x2* tx2;  u32x2* tdelta;  u32x2* tq;  u32x2* tkvcur;  u32x2* tattn_o;  u32x2* th;
+    u32x2* tq;  u32x2* tkvcur;
+    // the vectors every workgroup reads whole, in the compact 4-byte format (value with a 4-bit write
+    // counter in its lowest mantissa bits): residual stream (two buffers), sublayer output, merged
+    // attention output, SwiGLU output
+    u32* cx;  u32* cx2;  u32* cdelta;  u32* cattn_o;  u32* ch;
+    u32* stepctr;    // number of fused steps executed so far on these buffers (skipped steps do not count)
     u32x2* tpart_m;  u32x2* tpart_l;  u32x2* tpart_o;
     int* status;
     u64* dbg;        // optional timeline buffer (null unless enabled through the debug entry point)

@@ -60,14 +60,14 @@ __device__ __forceinline__ u64* dbg_stage_slots(const DevModel& M, int n_phases,
 }
 
 struct EpiFused {
-    int kind; u32 tag;
+    int kind; u32 tag; u32 cnt;   // tag: 32-bit tag of q / k,v; cnt: write counter of the compact output vector
     const DevModel& M; const DevKV& KV; const int* pos; int layer; const float2* rope; float* logits;
     __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         switch (kind) {
             case PH_QKV: EpiQKVTagged{M, KV, pos, layer, rope, tag}(pair, b, v0, v1); break;
-            case PH_GU: EpiSwiGLUTagged{M.th, M.F, tag}(pair, b, v0, v1); break;
+            case PH_GU: EpiSwiGLUTagged{M.ch, M.F, cnt}(pair, b, v0, v1); break;
             case PH_LM: EpiStore{logits, M.V}(pair, b, v0, v1); break;
-            default: EpiDeltaTagged{M.tdelta, M.d, tag}(pair, b, v0, v1); break;
+            default: EpiDeltaTagged{M.cdelta, M.d, cnt}(pair, b, v0, v1); break;
         }
     }
 };
@@ -77,56 +77,60 @@ struct PhaseDesc {
     int kind, layer;
     TSrc src;
     PMat W;
-    u32 out_tag;
+    u32 out_tag;     // 32-bit tag of this phase's tagged outputs (q, k, v; attention partials)
+    u32 out_cnt;     // write counter of this phase's compact output vector
 };
 struct PhaseState {   // the residual stream's ping-pong buffers (both roles track them identically)
-    tagged_t* xcur; tagged_t* xnext;
+    cword_t* xcur; cword_t* xnext;
 };
 __device__ __forceinline__ u32 tag_of(u32 tag_base, int l, int k) { return tag_base + 1u + (u32)(l * kTagsPerLayer + k); }
 
-__device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* tokens, u32 tb, int ph, int lm_in_kernel, const PhaseState& X) {
+// `sl` = (steps executed so far) * L: the write counters of the compact vectors are sl + layer for the
+// buffers written once per layer and 2 * (sl + layer) + {0, 1} for the sublayer output (O, then DOWN).
+__device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* tokens, u32 tb, u32 sl, int ph, int lm_in_kernel, const PhaseState& X) {
     PhaseDesc D;
     const int l = ph >> 2;
     const FF_CONST PLayer* Lp = as_const(M.layers) + min(l, M.L - 1);   // scalar loads (see as_const)
     D.layer = l;
     D.kind = ph == 4 * M.L ? PH_LM : (ph & 3);
     D.out_tag = 0;
+    D.out_cnt = 0;
     TSrc& src = D.src;
     if (D.kind == PH_QKV) {
         if (l == 0) { src.embed = M.embed; src.tokens = tokens; src.tag = 0; }   // embedding rows are synthesised with tag 0
         else {
-            src.base = X.xcur; src.stride = M.d; src.tag = tag_of(tb, l - 1, TAG_GU);
-            src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, l - 1, TAG_DOWN);
+            src.base = X.xcur; src.stride = M.d; src.tag = sl + l - 1;
+            src.add = M.cdelta; src.add_stride = M.d; src.add_tag = 2 * (sl + l - 1) + 1;
         }
-        src.wb = X.xnext; src.wb_stride = M.d; src.wb_tag = tag_of(tb, l, TAG_QKV);
+        src.wb = X.xnext; src.wb_stride = M.d; src.wb_tag = sl + l;
         src.gain = Lp->g1; src.eps = M.eps;
         D.out_tag = tag_of(tb, l, TAG_QKV);
         D.W = FF_PMAT_FIELDS(Lp->qkv);
     } else if (D.kind == PH_O) {
-        src.base = M.tattn_o; src.stride = (size_t)M.Hq * M.hd; src.tag = tag_of(tb, l, TAG_ATT);
-        D.out_tag = tag_of(tb, l, TAG_O);
+        src.base = M.cattn_o; src.stride = (size_t)M.Hq * M.hd; src.tag = sl + l;
+        D.out_cnt = 2 * (sl + l);
         D.W = FF_PMAT_FIELDS(Lp->o);
     } else if (D.kind == PH_GU) {
-        src.base = X.xcur; src.stride = M.d; src.tag = tag_of(tb, l, TAG_QKV);
-        src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, l, TAG_O);
-        src.wb = X.xnext; src.wb_stride = M.d; src.wb_tag = tag_of(tb, l, TAG_GU);
+        src.base = X.xcur; src.stride = M.d; src.tag = sl + l;
+        src.add = M.cdelta; src.add_stride = M.d; src.add_tag = 2 * (sl + l);
+        src.wb = X.xnext; src.wb_stride = M.d; src.wb_tag = sl + l;
         src.gain = Lp->g2; src.eps = M.eps;
-        D.out_tag = tag_of(tb, l, TAG_GU);
+        D.out_cnt = sl + l;
         D.W = FF_PMAT_FIELDS(Lp->gu);
     } else if (D.kind == PH_DOWN) {
-        src.base = M.th; src.stride = M.F; src.tag = tag_of(tb, l, TAG_GU);
-        D.out_tag = tag_of(tb, l, TAG_DOWN);
+        src.base = M.ch; src.stride = M.F; src.tag = sl + l;
+        D.out_cnt = 2 * (sl + l) + 1;
         D.W = FF_PMAT_FIELDS(Lp->down);
     } else {
-        src.base = X.xcur; src.stride = M.d; src.tag = tag_of(tb, M.L - 1, TAG_GU);
-        src.add = M.tdelta; src.add_stride = M.d; src.add_tag = tag_of(tb, M.L - 1, TAG_DOWN);
+        src.base = X.xcur; src.stride = M.d; src.tag = sl + M.L - 1;
+        src.add = M.cdelta; src.add_stride = M.d; src.add_tag = 2 * (sl + M.L - 1) + 1;
         src.gain = M.gf; src.eps = M.eps;
         D.W = M.lm;
     }
     return D;
 }
 __device__ __forceinline__ void phase_advance(const PhaseDesc& D, PhaseState& X) {
-    if (D.kind == PH_QKV || D.kind == PH_GU) { tagged_t* t = X.xcur; X.xcur = X.xnext; X.xnext = t; }
+    if (D.kind == PH_QKV || D.kind == PH_GU) { cword_t* t = X.xcur; X.xcur = X.xnext; X.xnext = t; }
 }
 
 template <int WD, int B, int HD, int G>
@@ -156,18 +160,21 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
     // weight type differs from the layers' (then the host launches it separately).
     const int n_phases = 4 * M.L + (lm_in_kernel ? 1 : 0);
-    PhaseState X{M.tx, M.tx2};
+    PhaseState X{M.cx, M.cx2};
+    // steps executed so far on the compact buffers (kept on the device: a skipped step does not count)
+    const u32 steps_done = (u32)__builtin_amdgcn_readfirstlane(xld_u32(M.stepctr));
+    const u32 sl = steps_done * (u32)M.L;
 
     const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = ncta * kFusedWaves;
     float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64;   // behind the RoPE rows
     // One iteration = one K segment of one projection.
     int ph = 0;
-    PhaseDesc D = phase_desc(M, tokens, tag_base, 0, lm_in_kernel, X);
+    PhaseDesc D = phase_desc(M, tokens, tag_base, sl, 0, lm_in_kernel, X);
     Stream<WD, B> S = Stream<WD, B>::make(D.W, 0, gwave, n_gwaves);
     for (;;) {
         const int seg = S.seg;
-        EpiFused epi{D.kind, D.out_tag, M, KV, pos_lds, D.layer, rope_lds, logits};
+        EpiFused epi{D.kind, D.out_tag, D.out_cnt, M, KV, pos_lds, D.layer, rope_lds, logits};
         // The wave's first tiles of this projection are requested before anything it has to wait
         // for (its input vector; for the output projection the whole attention), so the memory
         // pipe has work while the dependency resolves.  The ring lives from here to the end of
@@ -187,7 +194,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             u64* aev = dbg_stage_slots(M, n_phases, ncta, D.layer, 4);
             if (aev && threadIdx.x == 0) { as_global(aev)[0] = wall_clock64(); as_global(aev)[4] = 0; as_global(aev)[5] = 0; }
             const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
-                                                                tag_of(tag_base, D.layer, TAG_ATT), ncta, aev);
+                                                                tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, ncta, aev);
             if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
             if (wave == 0) dbg_event(M, ph, EV_ATT_END, lane);
             if (!ok) return;
@@ -213,10 +220,13 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         else if (ph + 1 < n_phases) {
             phase_advance(D, X);
             ++ph;
-            D = phase_desc(M, tokens, tag_base, ph, lm_in_kernel, X);
+            D = phase_desc(M, tokens, tag_base, sl, ph, lm_in_kernel, X);
             S = Stream<WD, B>::make(D.W, 0, gwave, n_gwaves);
         } else break;
     }
+    // this step has been executed: the next one uses the next write counters (workgroup 0 can only
+    // get here after every workgroup has taken part in every phase, i.e. has read the counter)
+    if (blockIdx.x == 0 && threadIdx.x == 0) xst_u32(M.stepctr, steps_done + 1u);
 }
 
 // Host-side launcher of one weight-type family; defined once per weight type in its own

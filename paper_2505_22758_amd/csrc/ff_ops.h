@@ -32,9 +32,31 @@ __global__ void __launch_bounds__(kThreads) op_rmsnorm(const float* x, const bf1
 }
 // x = residual + last sublayer output, from the fused kernel's tagged buffers (finishes the residual
 // stream when the LM head is launched separately after the fused kernel)
-__global__ void __launch_bounds__(kThreads) op_final_x(float* x, const u32x2* tx, const u32x2* tdelta, int n) {
+// Re-initialises rows [row0, row1) of the compact exchange vectors so that their counter bits are
+// the ones just BEFORE each vector's first write of the next step: rows a smaller batch has left
+// untouched for a while could otherwise carry, by chance, the bits a later reader waits for.
+__global__ void __launch_bounds__(kThreads) k_scrub_rows(DevModel M, int row0, int row1) {
+    const u32 sl = as_global(M.stepctr)[0] * (u32)M.L;
+    const int qd = M.Hq * M.hd;
+    const size_t per_row = (size_t)3 * M.d + qd + M.F;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < per_row * (size_t)(row1 - row0); i += (size_t)gridDim.x * kThreads) {
+        const int r = row0 + (int)(i / per_row);
+        size_t e = i % per_row;
+        if (e < (size_t)M.d) { as_global(M.cx)[(size_t)r * M.d + e] = (sl - 1u) & 15u; continue; }
+        e -= M.d;
+        if (e < (size_t)M.d) { as_global(M.cx2)[(size_t)r * M.d + e] = (sl - 1u) & 15u; continue; }
+        e -= M.d;
+        if (e < (size_t)M.d) { as_global(M.cdelta)[(size_t)r * M.d + e] = (2u * sl - 1u) & 15u; continue; }
+        e -= M.d;
+        if (e < (size_t)qd) { as_global(M.cattn_o)[(size_t)r * qd + e] = (sl - 1u) & 15u; continue; }
+        e -= qd;
+        as_global(M.ch)[(size_t)r * M.F + e] = (sl - 1u) & 15u;
+    }
+}
+
+__global__ void __launch_bounds__(kThreads) op_final_x(float* x, const u32* tx, const u32* tdelta, int n) {
     for (int i = blockIdx.x * kThreads + threadIdx.x; i < n; i += gridDim.x * kThreads)
-        x[i] = __uint_as_float(tx[i].x) + __uint_as_float(tdelta[i].x);
+        x[i] = __uint_as_float(tx[i] & ~15u) + __uint_as_float(tdelta[i] & ~15u);
 }
 enum { EPI_STORE = 0, EPI_RESIDUAL = 1 };
 template <int WD, int B, class Epi>

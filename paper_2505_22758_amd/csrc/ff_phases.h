@@ -7,8 +7,9 @@
 namespace ff {
 
 // ---------------------------------------------------------------- tagged exchange format
-// Inside the fused kernel every value exchanged between workgroups travels as an 8-byte pair
-// (fp32 bits, tag) written with one coherent 8-byte store.  The tag names the phase instance that
+// Inside the fused kernel the small exchanged values (queries, the step's own k and v, attention
+// partials) travel as 8-byte pairs (fp32 bits, tag) written with one coherent 8-byte store; the big
+// vectors use the compact format further down.  The tag names the phase instance that
 // produced the value (it grows monotonically over phases and over decode steps), so a consumer can
 // tell from the data itself whether its producer has run: it simply re-reads until every tag it
 // needs matches.  Dependencies are thereby resolved by dataflow -- no device-wide barrier, no
@@ -37,12 +38,40 @@ __device__ __forceinline__ u32x4 tld2(const tagged_t* base, int i) {
     return u32x4{a.x, a.y, b.x, b.y};
 }
 
+// ---------------------------------------------------------------- compact exchange format
+// The vectors that every workgroup reads whole (residual stream, sublayer outputs, merged attention
+// output, SwiGLU output) travel as 4-byte words: the fp32 value rounded to 20 mantissa bits, with
+// the low 4 bits of a per-buffer WRITE COUNTER in the freed bits.  Every element of such a buffer
+// (for the sequences of the step) is rewritten each time the buffer is written, and the counter
+// grows by exactly one per write, so whatever a reader can find in a slot is either the value it
+// waits for or the previous write, whose 4 bits differ.  The counter is derived from the number of
+// steps EXECUTED on the buffers (kept on the device: a skipped step changes nothing), the layer and
+// the phase.  Rows of sequences beyond the previous step's batch are re-initialised by the host
+// side (a small fill) before a larger batch runs.  Two elements move per 8-byte coherent access.
+typedef u32 cword_t;
+__device__ __forceinline__ u32 cpack(float v, u32 cnt) {
+    const u32 b = __float_as_uint(v);
+    const u32 r = (b & 0x7F800000u) == 0x7F800000u ? b : b + 8u;   // round to nearest; infinities and NaNs keep their class
+    return (r & ~15u) | (cnt & 15u);
+}
+__device__ __forceinline__ float cvalue(u32 w) { return __uint_as_float(w & ~15u); }
+__device__ __forceinline__ bool cfresh(u32 w, u32 cnt) { return ((w ^ cnt) & 15u) == 0; }
+__device__ __forceinline__ void cst1(cword_t* p, float v, u32 cnt) { xst_u32(p, cpack(v, cnt)); }
+__device__ __forceinline__ void cst2(cword_t* p, float v0, float v1, u32 cnt) {   // p 8-byte aligned
+    xst2((float*)p, __uint_as_float(cpack(v0, cnt)), __uint_as_float(cpack(v1, cnt)));
+}
+__device__ __forceinline__ u32 cld1(const cword_t* base, int i) { return xld_u32(base + i); }
+__device__ __forceinline__ u32x2 cld2(const cword_t* base, int i) {   // elements i, i+1 (i even)
+    u64 a = __hip_atomic_load(as_global((const u64*)(base + i)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return u32x2{(u32)a, (u32)(a >> 32)};
+}
+
 // Input of a projection inside the fused kernel.
 struct TSrc {
-    const tagged_t* base = nullptr; size_t stride = 0; u32 tag = 0;        // tagged vector [B][stride] ...
+    const cword_t* base = nullptr; size_t stride = 0; u32 tag = 0;         // compact vector [B][stride] (tag = write counter) ...
     const bf16_t* embed = nullptr; const int* tokens = nullptr;            // ... or rows of the embedding table
-    const tagged_t* add = nullptr; size_t add_stride = 0; u32 add_tag = 0; // optional: + sublayer output
-    tagged_t* wb = nullptr; size_t wb_stride = 0; u32 wb_tag = 0;          // optional: publish the sum (residual stream)
+    const cword_t* add = nullptr; size_t add_stride = 0; u32 add_tag = 0;  // optional: + sublayer output
+    cword_t* wb = nullptr; size_t wb_stride = 0; u32 wb_tag = 0;           // optional: publish the sum (residual stream)
     const bf16_t* gain = nullptr; float eps = 0.f;                         // optional: RMSNorm
     int ncta = 1;                                                          // workgroups in the grid (each publishes 1/ncta of wb)
 };
@@ -53,14 +82,13 @@ struct TSrc {
 template <bool HAS_ADD>
 __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int nel, int lane) {
     const int sample = min(k0 + (int)(((long)(lane % kPollLanes) * nel) / kPollLanes) + (int)(blockIdx.x % 16) * 2, k0 + nel - 1);
-    const tagged_t* sb = S.base + (size_t)(batch - 1) * S.stride;
-    const tagged_t* sa = HAS_ADD ? S.add + (size_t)(batch - 1) * S.add_stride : nullptr;
+    const cword_t* sb = S.base + (size_t)(batch - 1) * S.stride;
+    const cword_t* sa = HAS_ADD ? S.add + (size_t)(batch - 1) * S.add_stride : nullptr;
     for (int spins = 0; spins < kSpinLimit; spins++) {
         bool ok = true;
         if (lane < kPollLanes) {
-            u32x2 p = tld1(sb, sample);
-            ok = p.y == S.tag;
-            if constexpr (HAS_ADD) { u32x2 q = tld1(sa, sample); ok = ok && q.y == S.add_tag; }
+            ok = cfresh(cld1(sb, sample), S.tag);
+            if constexpr (HAS_ADD) ok = ok && cfresh(cld1(sa, sample), S.add_tag);
         }
         if (__all(ok)) return true;
         __builtin_amdgcn_s_sleep(4);
@@ -75,8 +103,8 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 // what count); only if some tag in the workgroup is stale does it fall back to light polling.
 // The first workgroup barrier inside doubles as the hand-over of the LDS region from the previous
 // projection.  NT = threads of the workgroup.  Returns false (uniformly) on a time-out.
-// QB = quads per thread and pass (4 8-byte loads per quad and source, all in flight at once; their
-// 8*QB destination registers per source must fit beside the wave's prefetched weight tiles, or the
+// QB = quads per thread and pass (2 8-byte loads per quad and source, all in flight at once; their
+// 4*QB destination registers per source must fit beside the wave's prefetched weight tiles, or the
 // compiler parks those tiles elsewhere and has to wait for them first).
 template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB>
 __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, u64* ev) {
@@ -87,13 +115,13 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
     const int padquads = nup * NQ;
     for (int b = 0; b < batch; b++) {
         float4* xb = xs + (size_t)b * NQ * nup;
-        const tagged_t* src = S.base + (size_t)b * S.stride;
-        const tagged_t* add = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
+        const cword_t* src = S.base + (size_t)b * S.stride;
+        const cword_t* add = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
         const bf16_t* erow = nullptr;   // embedding rows only come through the (no add, gain) instance
         if constexpr (!HAS_ADD && HAS_GAIN) erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
         float ss = 0.f;
         for (int q0 = tid; q0 < padquads; q0 += NT * QB) {
-            u32x4 v[QB][2], a[HAS_ADD ? QB : 1][2];
+            u32x4 v[QB], a[HAS_ADD ? QB : 1];   // four compact words per quad and source
             u32x2 g[HAS_GAIN ? QB : 1];
             bool all_ok = false;
             u32 stale = (1u << QB) - 1;   // quads (bit u) this lane still has to (re)load
@@ -104,24 +132,27 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
                 for (int u = 0; u < QB; u++) {
                     const int k = k0 + min(q0 + u * NT, nquads - 1) * 4;   // clamped: every load is issued
                     if (spins == 0 || ((stale >> u) & 1)) {
-                        if (erow) {
+                        if (erow) {   // bf16 values are exact in the compact format: mark them fresh
                             u32x2 w = *as_global((const u32x2*)(erow + k));
-                            v[u][0] = u32x4{w.x << 16, S.tag, w.x & 0xFFFF0000u, S.tag};
-                            v[u][1] = u32x4{w.y << 16, S.tag, w.y & 0xFFFF0000u, S.tag};
+                            const u32 t = S.tag & 15u;
+                            v[u] = u32x4{(w.x << 16) | t, (w.x & 0xFFFF0000u) | t, (w.y << 16) | t, (w.y & 0xFFFF0000u) | t};
                         } else {
-                            v[u][0] = tld2(src, k);
-                            v[u][1] = tld2(src, k + 2);
+                            const u32x2 lo = cld2(src, k), hi = cld2(src, k + 2);
+                            v[u] = u32x4{lo.x, lo.y, hi.x, hi.y};
                         }
-                        if constexpr (HAS_ADD) { a[u][0] = tld2(add, k); a[u][1] = tld2(add, k + 2); }
+                        if constexpr (HAS_ADD) {
+                            const u32x2 lo = cld2(add, k), hi = cld2(add, k + 2);
+                            a[u] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                        }
                     }
                     if constexpr (HAS_GAIN) { if (spins == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
                 }
                 stale = 0;
 #pragma unroll
                 for (int u = 0; u < QB; u++) {
-                    bool ok = v[u][0].y == S.tag && v[u][0].w == S.tag && v[u][1].y == S.tag && v[u][1].w == S.tag;
+                    bool ok = cfresh(v[u].x, S.tag) && cfresh(v[u].y, S.tag) && cfresh(v[u].z, S.tag) && cfresh(v[u].w, S.tag);
                     if constexpr (HAS_ADD)
-                        ok = ok && a[u][0].y == S.add_tag && a[u][0].w == S.add_tag && a[u][1].y == S.add_tag && a[u][1].w == S.add_tag;
+                        ok = ok && cfresh(a[u].x, S.add_tag) && cfresh(a[u].y, S.add_tag) && cfresh(a[u].z, S.add_tag) && cfresh(a[u].w, S.add_tag);
                     if (!ok) stale |= 1u << u;
                 }
                 all_ok = __syncthreads_and(stale == 0);
@@ -139,17 +170,13 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
             for (int u = 0; u < QB; u++) {
                 const int qi = q0 + u * NT;
                 if (qi < padquads) {
-                    float4 t = make_float4(__uint_as_float(v[u][0].x), __uint_as_float(v[u][0].z), __uint_as_float(v[u][1].x),
-                                           __uint_as_float(v[u][1].z));
-                    if constexpr (HAS_ADD) {
-                        t.x += __uint_as_float(a[u][0].x); t.y += __uint_as_float(a[u][0].z);
-                        t.z += __uint_as_float(a[u][1].x); t.w += __uint_as_float(a[u][1].z);
-                    }
+                    float4 t = make_float4(cvalue(v[u].x), cvalue(v[u].y), cvalue(v[u].z), cvalue(v[u].w));
+                    if constexpr (HAS_ADD) { t.x += cvalue(a[u].x); t.y += cvalue(a[u].y); t.z += cvalue(a[u].z); t.w += cvalue(a[u].w); }
                     if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
                     else if (S.wb && (qi % S.ncta) == (int)blockIdx.x) {
-                        tagged_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
-                        tst2(w, t.x, t.y, S.wb_tag);
-                        tst2(w + 2, t.z, t.w, S.wb_tag);
+                        cword_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
+                        cst2(w, t.x, t.y, S.wb_tag);
+                        cst2(w + 2, t.z, t.w, S.wb_tag);
                     }
                     if constexpr (HAS_GAIN) {
                         if (qi < nquads) {
@@ -440,7 +467,7 @@ __device__ void attn_merge(const DevModel& M, int b, int j, int nsplit, float* l
 // (b, j) gathers all splits, re-reading until every partial carries this layer's attention tag,
 // and publishes attn_o with the same tag.  Returns false on a time-out.
 template <int HD, int G, int NT>
-__device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, float* lds, u64* ev = nullptr) {
+__device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, u32 out_cnt, float* lds, u64* ev = nullptr) {
     float* ms = lds;
     float* ls = lds + G * kMaxSplits;
     constexpr int kSB = 16;   // splits gathered per batch of loads
@@ -520,7 +547,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
                 a1 = fmaf(__uint_as_float(r[u].z), w, a1);
             }
         }
-        tst2(M.tattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, tag);
+        cst2(M.cattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, out_cnt);
     }
     if (ev && threadIdx.x == 0) as_global(ev)[5] = wall_clock64();
     return __syncthreads_and(all_ok);
@@ -631,14 +658,14 @@ struct EpiQKVTagged {   // pos: positions of this step, staged in LDS
     }
 };
 struct EpiDeltaTagged {   // projections feeding the residual stream: publish the output, the next
-    tagged_t* delta; int d; u32 tag;   // normalised staging adds it (paper Section 3.2: added to the residual)
-    __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const { tst2(delta + (size_t)b * d + 2 * pair, v0, v1, tag); }
+    cword_t* delta; int d; u32 tag;    // normalised staging adds it (paper Section 3.2: added to the residual)
+    __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const { cst2(delta + (size_t)b * d + 2 * pair, v0, v1, tag); }
 };
 struct EpiSwiGLUTagged {   // packed rows (2i, 2i+1) = (gate_i, up_i):  h_i = silu(gate_i) * up_i
-    tagged_t* h; int F; u32 tag;
+    cword_t* h; int F; u32 tag;
     __device__ __forceinline__ void operator()(int pair, int b, float g, float u) const {
         float s = g / (1.0f + expf(-g));
-        tst(h + (size_t)b * F + pair, s * u, tag);
+        cst1(h + (size_t)b * F + pair, s * u, tag);
     }
 };
 struct EpiStore {   // plain output rows (logits; per-op raw projections)

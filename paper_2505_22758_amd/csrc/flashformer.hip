@@ -44,7 +44,7 @@ struct Plan {
     size_t packed_bytes;
     // scratch
     size_t x, xn, q, kvcur, attn_o, h, y, part_m, part_l, part_o, status, scratch_bytes;
-    size_t tx, tx2, tdelta, tq, tkvcur, tattn_o, th, tpart_m, tpart_l, tpart_o;
+    size_t cx, cx2, cdelta, tq, tkvcur, cattn_o, ch, stepctr, tpart_m, tpart_l, tpart_o;
 };
 
 size_t mat_w_bytes(int n, int k, int wd) { return wd == W_BF16 ? (size_t)n * k * 2 : wd == W_INT8 ? (size_t)n * k : (size_t)n * k / 2; }
@@ -112,13 +112,14 @@ Plan make_plan(const ff_config& c) {
     P.part_m = take(mb * c.n_q_heads * kMaxSplits * 4);
     P.part_l = take(mb * c.n_q_heads * kMaxSplits * 4);
     P.part_o = take(mb * c.n_q_heads * kMaxSplits * c.head_dim * 4);
-    P.tx = take(mb * c.d_model * 8);
-    P.tx2 = take(mb * c.d_model * 8);
-    P.tdelta = take(mb * c.d_model * 8);
+    P.cx = take(mb * c.d_model * 4);
+    P.cx2 = take(mb * c.d_model * 4);
+    P.cdelta = take(mb * c.d_model * 4);
     P.tq = take(mb * qd * 8);
     P.tkvcur = take(mb * 2 * c.n_kv_heads * c.head_dim * 8);
-    P.tattn_o = take(mb * qd * 8);
-    P.th = take(mb * c.d_ffn * 8);
+    P.cattn_o = take(mb * qd * 4);
+    P.ch = take(mb * c.d_ffn * 4);
+    P.stepctr = take(256);
     P.tpart_m = take(mb * c.n_q_heads * kMaxSplits * 8);
     P.tpart_l = take(mb * c.n_q_heads * kMaxSplits * 8);
     P.tpart_o = take(mb * c.n_q_heads * kMaxSplits * c.head_dim * 8);
@@ -139,6 +140,7 @@ struct ff_model {
     std::vector<char> layer_loaded;
     bool head_loaded;
     uint32_t bar_gen;
+    int rows_clean = 0;   // sequences whose compact exchange rows the last fused launch wrote (or that were re-initialised since)
     int n_cta;
     size_t lds_bytes;
 };
@@ -282,8 +284,9 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     D.attn_o = (float*)(s + P.attn_o); D.h = (float*)(s + P.h); D.y = (float*)(s + P.y);
     D.part_m = (float*)(s + P.part_m); D.part_l = (float*)(s + P.part_l); D.part_o = (float*)(s + P.part_o);
     D.status = (int*)(s + P.status);
-    D.tx = (u32x2*)(s + P.tx); D.tx2 = (u32x2*)(s + P.tx2); D.tdelta = (u32x2*)(s + P.tdelta); D.tq = (u32x2*)(s + P.tq);
-    D.tkvcur = (u32x2*)(s + P.tkvcur); D.tattn_o = (u32x2*)(s + P.tattn_o); D.th = (u32x2*)(s + P.th);
+    D.cx = (u32*)(s + P.cx); D.cx2 = (u32*)(s + P.cx2); D.cdelta = (u32*)(s + P.cdelta); D.tq = (u32x2*)(s + P.tq);
+    D.tkvcur = (u32x2*)(s + P.tkvcur); D.cattn_o = (u32*)(s + P.cattn_o); D.ch = (u32*)(s + P.ch);
+    D.stepctr = (u32*)(s + P.stepctr);
     D.tpart_m = (u32x2*)(s + P.tpart_m); D.tpart_l = (u32x2*)(s + P.tpart_l); D.tpart_o = (u32x2*)(s + P.tpart_o);
     D.dbg = nullptr;
     for (int l = 0; l < cfg->n_layers; l++) {
@@ -424,6 +427,11 @@ int fused_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_
     const int lm_in_kernel = m->dev.lm.wd == m->cfg.wdtype;
     DevKV kvd = kv->dev;
     kvd.seq0 = seq0;
+    if (batch > m->rows_clean) {   // rows a smaller batch left behind: see k_scrub_rows
+        k_scrub_rows<<<64, kThreads, 0, st>>>(m->dev, m->rows_clean, batch);
+        HIPCHK(hipGetLastError());
+    }
+    m->rows_clean = batch;
     FusedLaunch a{m->dev, kvd, tokens_dev, positions_dev, logits_dev, batch, m->bar_gen, lm_in_kernel, m->n_cta, m->lds_bytes, st};
     const char* what = "";
     const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
@@ -438,7 +446,7 @@ int fused_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_
     m->bar_gen += (uint32_t)(kTagsPerLayer * m->cfg.n_layers + 1);
     if (!lm_in_kernel) {   // LM head of a different weight type than the layers: separate launches
         const ff_config& c = m->cfg;
-        op_final_x<<<16, kThreads, 0, st>>>(m->dev.x, m->dev.tx, m->dev.tdelta, batch * c.d_model);
+        op_final_x<<<16, kThreads, 0, st>>>(m->dev.x, m->dev.cx, m->dev.cdelta, batch * c.d_model);
         op_rmsnorm<<<batch, kThreads, 0, st>>>(m->dev.x, m->dev.gf, m->dev.xn, c.d_model, c.rms_eps);
         int rc = gemv_op(m, m->dev.lm, m->dev.xn, c.d_model, logits_dev, batch, EPI_STORE, st);
         if (rc) return rc;

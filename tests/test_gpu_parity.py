@@ -238,3 +238,39 @@ def test_two_models_interleaved_on_a_side_stream():
             assert torch.equal(alone[s], together[i][s]), (i, s)
     for m in both:
         m[0].close()
+
+
+def test_batch_size_changing_from_step_to_step():
+    """Steps of different batch sizes on one model and one cache: a sequence that sits out some steps
+    (among them exactly as many as make the exchange vectors' 4-bit write counters come round again:
+    with 4 layers, 4 steps) must not be served values its exchange rows kept from its last step."""
+    from paper_2505_22758_amd import binding
+    from oracle import oracle
+    shape, seed, T0 = synth.TINY, 0x77, 20
+    sizes = [4, 1, 1, 1, 1, 4, 2, 2, 2, 2, 3, 1, 4, 4, 1, 1, 1, 1, 1, 1, 1, 1, 2]
+    max_ctx = T0 + len(sizes) + 2
+    layers = [synth.make_layer(shape, seed, l, synth.WDTYPE_BF16, "cpu") for l in range(shape.n_layers)]
+    M = oracle.OracleModel(shape, layers, synth.make_head(shape, seed, synth.WDTYPE_BF16, "cpu"))
+    okv = []
+    for b in range(4):
+        kv = M.new_kv(1, max_ctx)
+        for l in range(shape.n_layers):
+            k, v = synth.make_kv_prefill(shape, seed, l, b, T0, "cpu")
+            kv[l, 0, 0, :T0], kv[l, 0, 1, :T0] = oracle._np(k), oracle._np(v)
+        okv.append(kv)
+    dec, caches = helpers.hip_side(shape, seed, synth.WDTYPE_BF16, 4, T0, max_ctx, n_caches=1)
+    toks = synth.make_tokens(shape, seed, len(sizes), 4)
+    pos = [T0] * 4
+    logits = torch.zeros(4, shape.vocab, dtype=torch.float32, device="cuda:0")
+    for s, b in enumerate(sizes):
+        tok_d = toks[s, :b].contiguous().to("cuda:0")
+        pos_d = torch.tensor(pos[:b], dtype=torch.int32, device="cuda:0")
+        binding.ff_decode_step(dec.model, tok_d, pos_d, caches[0][0], logits, b)
+        binding.ff_status(dec.model)
+        got = logits[:b].cpu().numpy()
+        for r in range(b):
+            ref = M.decode_step(toks[s, r:r + 1].numpy(), np.array([pos[r]], dtype=np.int32), okv[r])
+            ma, rl, same = helpers.compare_logits(got[r:r + 1], ref)
+            assert ma <= helpers.MAX_ABS_TOL and rl <= helpers.REL_L2_TOL and same.all(), (s, b, r, ma, rl)
+            pos[r] += 1
+    dec.close()
