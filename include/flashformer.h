@@ -135,7 +135,9 @@ int ff_decode_step_perop(ff_model *m, const int32_t *tokens_dev, const int32_t *
                          float *logits_dev, int32_t batch, void *stream);
 
 /* Synchronises `stream`, returns the device status word (FF_OK, FF_ERR_RANGE or FF_ERR_TIMEOUT)
- * recorded by the steps so far, and clears it. */
+ * recorded by the steps so far, and clears it.  A step that saw FF_ERR_RANGE was skipped as a whole
+ * and leaves model and cache unchanged.  After FF_ERR_TIMEOUT a step has stopped half-way: the
+ * model's exchange buffers are then undefined and the model must be created again. */
 int ff_status(ff_model *m, void *stream);
 
 /* Writes matrix `which` (FF_MAT_*) of `layer` (ignored for FF_MAT_LMHEAD) as fp32, canonical
