@@ -113,6 +113,7 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
     const int lane = tid & 63;
     const int nquads = nunits * NQ;
     const int padquads = nup * NQ;
+    const int wb_lo = (int)((long)nquads * blockIdx.x / S.ncta), wb_hi = (int)((long)nquads * (blockIdx.x + 1) / S.ncta);
     for (int b = 0; b < batch; b++) {
         float4* xb = xs + (size_t)b * NQ * nup;
         const cword_t* src = S.base + (size_t)b * S.stride;
@@ -173,7 +174,7 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
                     float4 t = make_float4(cvalue(v[u].x), cvalue(v[u].y), cvalue(v[u].z), cvalue(v[u].w));
                     if constexpr (HAS_ADD) { t.x += cvalue(a[u].x); t.y += cvalue(a[u].y); t.z += cvalue(a[u].z); t.w += cvalue(a[u].w); }
                     if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
-                    else if (S.wb && (qi % S.ncta) == (int)blockIdx.x) {
+                    else if (S.wb && qi >= wb_lo && qi < wb_hi) {   // this workgroup's slice of the published sum
                         cword_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
                         cst2(w, t.x, t.y, S.wb_tag);
                         cst2(w + 2, t.z, t.w, S.wb_tag);
@@ -195,14 +196,14 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
             float tot = 0.f;
 #pragma unroll
             for (int w = 0; w < NT / 64; w++) tot += red[w];
-            const float r = 1.0f / sqrtf(tot / (float)K + S.eps);
+            const float r = rsqrtf(tot / (float)K + S.eps);
             for (int qi = tid; qi < nquads; qi += NT) {   // each thread rescales the quads it wrote
                 int j = qi / NQ, qd = qi % NQ;
                 float4 v4 = xb[(size_t)qd * nup + j];
                 v4.x *= r; v4.y *= r; v4.z *= r; v4.w *= r;
                 xb[(size_t)qd * nup + j] = v4;
             }
-            __syncthreads();   // `red` may be rewritten for the next row
+            if (b + 1 < batch) __syncthreads();   // `red` is rewritten for the next row
         }
     }
     __syncthreads();
