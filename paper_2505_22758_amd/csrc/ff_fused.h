@@ -168,6 +168,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = ncta * kFusedWaves;
     float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64;   // behind the RoPE rows
+    WgVote vote{(u32*)(red + 16), 0u};   // behind the reduction scratch and the positions
     // One iteration = one K segment of one projection.
     int ph = 0;
     PhaseDesc D = phase_desc(M, tokens, tag_base, sl, 0, lm_in_kernel, X);
@@ -194,7 +195,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             u64* aev = dbg_stage_slots(M, n_phases, ncta, D.layer, 4);
             if (aev && threadIdx.x == 0) { as_global(aev)[0] = wall_clock64(); as_global(aev)[4] = 0; as_global(aev)[5] = 0; }
             const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
-                                                                tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, ncta, aev);
+                                                                tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, ncta, vote, aev);
             if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
             if (wave == 0) dbg_event(M, ph, EV_ATT_END, lane);
             if (!ok) return;
@@ -202,8 +203,8 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (wave == 0) dbg_event(M, ph, EV_H_START, lane);
         bool ok;
         u64* ev = dbg_stage_slots(M, n_phases, ncta, D.layer, D.kind);
-        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, ev);
-        else ok = stage_tagged<EPU, false, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, ev);
+        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
+        else ok = stage_tagged<EPU, false, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
         if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
         if (!ok) {
             if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);

@@ -55,12 +55,12 @@ __device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const 
 // the wave wait for every load it has in flight, weight tiles included.
 template <int NW, int HD, int G>
 __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
-                                                       uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, int ncta, u64* ev = nullptr) {
+                                                       uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, int ncta, WgVote& vote, u64* ev = nullptr) {
     constexpr int NT = NW * 64;
     const int share = max(1, ncta / (batch * M.Hkv));
     int base = 0;
     bool ok = true;
-    TaggedAttnIO xio{in_tag, out_tag};
+    TaggedAttnIO xio{in_tag, out_tag, &vote};
     for (int b = 0; b < batch; b++) {
         const int T = pos[b];
         const int ns = attn_nsplit(T, share);
@@ -72,7 +72,7 @@ __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const 
             int t0 = (int)((long)T * s / ns), t1 = (int)((long)T * (s + 1) / ns);
             bool cur = s == ns - 1;
             ok = attn_item<HD, G, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds, ev) && ok;
-            if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, out_cnt, (float*)lds, ev) && ok;
+            if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, out_cnt, (float*)lds, vote, ev) && ok;
         }
         base = (base + nitems) % ncta;
     }

@@ -66,6 +66,30 @@ __device__ __forceinline__ u32x2 cld2(const cword_t* base, int i) {   // element
     return u32x2{(u32)a, (u32)(a >> 32)};
 }
 
+// Workgroup-wide AND of a predicate with ONE barrier: every wave votes with a ballot, its first
+// lane drops the result into an LDS slot, and after the barrier every thread reads all slots.
+// Consecutive votes alternate between two sets of slots, so a wave that runs ahead to the next vote
+// cannot overwrite a slot another wave has yet to read (the vote after that lies behind the next
+// vote's barrier, which that other wave only reaches after its read).  All threads must take part
+// in every vote, in the same order.
+struct WgVote {
+    u32* slots;   // LDS, 2 * (waves per workgroup) words
+    u32 par;
+    template <int NT>
+    __device__ __forceinline__ bool all(bool ok) {
+        constexpr int NW = NT / 64;
+        const u32 w = __all(ok) ? 1u : 0u;
+        u32* f = slots + par * NW;
+        par ^= 1u;
+        if ((threadIdx.x & 63) == 0) f[threadIdx.x >> 6] = w;
+        __syncthreads();
+        u32 r = 1u;
+#pragma unroll
+        for (int i = 0; i < NW; i++) r &= f[i];
+        return __builtin_amdgcn_readfirstlane(r) != 0;
+    }
+};
+
 // Input of a projection inside the fused kernel.
 struct TSrc {
     const cword_t* base = nullptr; size_t stride = 0; u32 tag = 0;         // compact vector [B][stride] (tag = write counter) ...
@@ -107,13 +131,13 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 // 4*QB destination registers per source must fit beside the wave's prefetched weight tiles, or the
 // compiler parks those tiles elsewhere and has to wait for them first).
 template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB>
-__device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, u64* ev) {
+__device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, WgVote& vote, u64* ev) {
     constexpr int NQ = EPU / 4;
     if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
     const int lane = tid & 63;
     const int nquads = nunits * NQ;
     const int padquads = nup * NQ;
-    const int wb_lo = (int)((long)nquads * blockIdx.x / S.ncta), wb_hi = (int)((long)nquads * (blockIdx.x + 1) / S.ncta);
+    const u32 wb_lo = (u32)nquads * blockIdx.x / (u32)S.ncta, wb_hi = (u32)nquads * (blockIdx.x + 1) / (u32)S.ncta;
     for (int b = 0; b < batch; b++) {
         float4* xb = xs + (size_t)b * NQ * nup;
         const cword_t* src = S.base + (size_t)b * S.stride;
@@ -156,12 +180,12 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
                         ok = ok && cfresh(a[u].x, S.add_tag) && cfresh(a[u].y, S.add_tag) && cfresh(a[u].z, S.add_tag) && cfresh(a[u].w, S.add_tag);
                     if (!ok) stale |= 1u << u;
                 }
-                all_ok = __syncthreads_and(stale == 0);
+                all_ok = vote.all<NT>(stale == 0);
                 if (ev && tid == 0 && spins == 0 && b == 0) as_global(ev)[1] = wall_clock64();
                 if (!all_ok) {
                     bool lw = true;
                     if (tid < 64) lw = light_wait<HAS_ADD>(S, batch, k0, nunits * EPU, lane);
-                    if (!__syncthreads_and(lw)) return false;
+                    if (!vote.all<NT>(lw)) return false;
                     if (ev && tid == 0) { as_global(ev)[2] = wall_clock64(); as_global(ev)[5] += 1; }
                 }
             }
@@ -174,7 +198,7 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
                     float4 t = make_float4(cvalue(v[u].x), cvalue(v[u].y), cvalue(v[u].z), cvalue(v[u].w));
                     if constexpr (HAS_ADD) { t.x += cvalue(a[u].x); t.y += cvalue(a[u].y); t.z += cvalue(a[u].z); t.w += cvalue(a[u].w); }
                     if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
-                    else if (S.wb && qi >= wb_lo && qi < wb_hi) {   // this workgroup's slice of the published sum
+                    else if (S.wb && (u32)qi >= wb_lo && (u32)qi < wb_hi) {   // this workgroup's slice of the published sum
                         cword_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
                         cst2(w, t.x, t.y, S.wb_tag);
                         cst2(w + 2, t.z, t.w, S.wb_tag);
@@ -213,17 +237,17 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
 // Picks the pass size that covers the vector in one pass with the fewest registers.
 template <int EPU, bool HAS_ADD, int NT>
 __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
-                                             u64* ev = nullptr) {
+                                             WgVote& vote, u64* ev = nullptr) {
     const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
     if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
-        if (per_thread <= 4) return stage_tagged_impl<EPU, true, true, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
-        return stage_tagged_impl<EPU, true, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+        if (per_thread <= 4) return stage_tagged_impl<EPU, true, true, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        return stage_tagged_impl<EPU, true, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else if (S.gain) {       // embedding rows
-        return stage_tagged_impl<EPU, false, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+        return stage_tagged_impl<EPU, false, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else {
-        if (per_thread <= 4) return stage_tagged_impl<EPU, false, false, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
-        if (per_thread <= 8) return stage_tagged_impl<EPU, false, false, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
-        return stage_tagged_impl<EPU, false, false, NT, 14>(S, batch, K, k0, nunits, nup, xs, red, tid, ev);
+        if (per_thread <= 4) return stage_tagged_impl<EPU, false, false, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_impl<EPU, false, false, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        return stage_tagged_impl<EPU, false, false, NT, 14>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     }
 }
 
@@ -264,6 +288,7 @@ struct PlainAttnIO {
 struct TaggedAttnIO {
     u32 in_tag;    // tag of q / kvcur (this layer's QKV projection)
     u32 out_tag;   // tag of the partials and of attn_o (this layer's attention)
+    WgVote* vote;
     // Workgroup-collective, same contract as PlainAttnIO::stage_inputs.  The whole input of an
     // item is a few kilobytes (one or two 16-byte pairs per thread), so the workgroup simply
     // re-reads it until the QKV projection's tag is on every element; returns false on a time-out.
@@ -287,7 +312,7 @@ struct TaggedAttnIO {
             }
 #pragma unroll
             for (int u = 0; u < PP; u++) ok = ok && r[u].y == in_tag && r[u].w == in_tag;
-            done = __syncthreads_and(ok);
+            done = vote->all<NT>(ok);
             if (!done) __builtin_amdgcn_s_sleep(2);
         }
         if (!done) { atomicCAS(M.status, 0, -51); return false; }
@@ -468,7 +493,7 @@ __device__ void attn_merge(const DevModel& M, int b, int j, int nsplit, float* l
 // (b, j) gathers all splits, re-reading until every partial carries this layer's attention tag,
 // and publishes attn_o with the same tag.  Returns false on a time-out.
 template <int HD, int G, int NT>
-__device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, u32 out_cnt, float* lds, u64* ev = nullptr) {
+__device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, u32 out_cnt, float* lds, WgVote& vote, u64* ev = nullptr) {
     float* ms = lds;
     float* ls = lds + G * kMaxSplits;
     constexpr int kSB = 16;   // splits gathered per batch of loads
@@ -503,7 +528,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
             ms[g * kMaxSplits + s] = __uint_as_float(pm.x);
             ls[g * kMaxSplits + s] = __uint_as_float(pl.x);
         }
-        done = __syncthreads_and(ok);
+        done = vote.all<NT>(ok);
         if (!done) __builtin_amdgcn_s_sleep(2);
     }
     if (!done) { atomicCAS(M.status, 0, -53); return false; }
@@ -551,7 +576,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
         cst2(M.cattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, out_cnt);
     }
     if (ev && threadIdx.x == 0) as_global(ev)[5] = wall_clock64();
-    return __syncthreads_and(all_ok);
+    return vote.all<NT>(all_ok);
 }
 
 // Number of KV splits for a sequence with `ncache` cached rows when `share` workgroups are
