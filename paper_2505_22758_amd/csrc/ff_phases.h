@@ -73,19 +73,27 @@ __device__ __forceinline__ u32x2 cld2(const cword_t* base, int i) {   // element
 // vote's barrier, which that other wave only reaches after its read).  All threads must take part
 // in every vote, in the same order.
 struct WgVote {
-    u32* slots;   // LDS, 2 * (waves per workgroup) words
+    u32* slots;   // LDS, 4 * (waves per workgroup) words
     u32 par;
     template <int NT>
     __device__ __forceinline__ bool all(bool ok) {
+        float unused;
+        return all_sum<NT>(ok, 0.f, unused);
+    }
+    // The same vote, which also adds up one (wave-uniform) float per wave over the workgroup.
+    template <int NT>
+    __device__ __forceinline__ bool all_sum(bool ok, float part, float& total) {
         constexpr int NW = NT / 64;
         const u32 w = __all(ok) ? 1u : 0u;
-        u32* f = slots + par * NW;
+        u32* f = slots + par * 2 * NW;
         par ^= 1u;
-        if ((threadIdx.x & 63) == 0) f[threadIdx.x >> 6] = w;
+        if ((threadIdx.x & 63) == 0) { f[threadIdx.x >> 6] = w; f[NW + (threadIdx.x >> 6)] = __float_as_uint(part); }
         __syncthreads();
         u32 r = 1u;
+        float t = 0.f;
 #pragma unroll
-        for (int i = 0; i < NW; i++) r &= f[i];
+        for (int i = 0; i < NW; i++) { r &= f[i]; t += __uint_as_float(f[NW + i]); }
+        total = t;
         return __builtin_amdgcn_readfirstlane(r) != 0;
     }
 };
@@ -131,7 +139,7 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 // 4*QB destination registers per source must fit beside the wave's prefetched weight tiles, or the
 // compiler parks those tiles elsewhere and has to wait for them first).
 template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB>
-__device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, WgVote& vote, u64* ev) {
+__device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, WgVote& vote, u64* ev) {
     constexpr int NQ = EPU / 4;
     if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
     const int lane = tid & 63;
@@ -234,20 +242,120 @@ __device__ __forceinline__ bool stage_tagged_impl(const TSrc& S, int batch, int 
     return true;
 }
 
+// The common case, where one pass of QB quads per thread covers the whole vector (nup * EPU / 4 <=
+// NT * QB): every thread keeps its quads in registers from the load to the LDS write, and the sum
+// of squares of the normalisation travels with the freshness vote, so a batch row costs a single
+// workgroup barrier and the staged vector is written once, already scaled.
+template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB>
+__device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, int tid, WgVote& vote, u64* ev) {
+    constexpr int NQ = EPU / 4;
+    if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
+    const int lane = tid & 63;
+    const int nquads = nunits * NQ;
+    const int padquads = nup * NQ;
+    const u32 wb_lo = (u32)nquads * blockIdx.x / (u32)S.ncta, wb_hi = (u32)nquads * (blockIdx.x + 1) / (u32)S.ncta;
+    for (int b = 0; b < batch; b++) {
+        float4* xb = xs + (size_t)b * NQ * nup;
+        const cword_t* src = S.base + (size_t)b * S.stride;
+        const cword_t* add = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
+        const bf16_t* erow = nullptr;   // embedding rows only come through the (no add, gain) instance
+        if constexpr (!HAS_ADD && HAS_GAIN) erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
+        u32x4 v[QB], a[HAS_ADD ? QB : 1];   // four compact words per quad and source
+        u32x2 g[HAS_GAIN ? QB : 1];
+        bool all_ok = false;
+        float tot = 0.f;
+        u32 stale = (1u << QB) - 1;   // quads (bit u) this lane still has to (re)load
+        for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
+            // first round: every quad of every lane; later rounds: only what came back stale, so a
+            // vector that was mostly complete is not fetched twice
+#pragma unroll
+            for (int u = 0; u < QB; u++) {
+                const int k = k0 + min(tid + u * NT, nquads - 1) * 4;   // clamped: every load is issued
+                if (spins == 0 || ((stale >> u) & 1)) {
+                    if (erow) {   // bf16 values are exact in the compact format: mark them fresh
+                        u32x2 w = *as_global((const u32x2*)(erow + k));
+                        const u32 t = S.tag & 15u;
+                        v[u] = u32x4{(w.x << 16) | t, (w.x & 0xFFFF0000u) | t, (w.y << 16) | t, (w.y & 0xFFFF0000u) | t};
+                    } else {
+                        const u32x2 lo = cld2(src, k), hi = cld2(src, k + 2);
+                        v[u] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                    }
+                    if constexpr (HAS_ADD) {
+                        const u32x2 lo = cld2(add, k), hi = cld2(add, k + 2);
+                        a[u] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                    }
+                }
+                if constexpr (HAS_GAIN) { if (spins == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
+            }
+            stale = 0;
+            float ss = 0.f;   // only meaningful if the vote passes
+#pragma unroll
+            for (int u = 0; u < QB; u++) {
+                bool ok = cfresh(v[u].x, S.tag) && cfresh(v[u].y, S.tag) && cfresh(v[u].z, S.tag) && cfresh(v[u].w, S.tag);
+                if constexpr (HAS_ADD)
+                    ok = ok && cfresh(a[u].x, S.add_tag) && cfresh(a[u].y, S.add_tag) && cfresh(a[u].z, S.add_tag) && cfresh(a[u].w, S.add_tag);
+                if (!ok) stale |= 1u << u;
+                if constexpr (HAS_GAIN) {
+                    float4 t = make_float4(cvalue(v[u].x), cvalue(v[u].y), cvalue(v[u].z), cvalue(v[u].w));
+                    if constexpr (HAS_ADD) { t.x += cvalue(a[u].x); t.y += cvalue(a[u].y); t.z += cvalue(a[u].z); t.w += cvalue(a[u].w); }
+                    if (tid + u * NT < nquads) ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+                }
+            }
+            if constexpr (HAS_GAIN) all_ok = vote.all_sum<NT>(stale == 0, wave_sum_uniform(ss), tot);
+            else all_ok = vote.all<NT>(stale == 0);
+            if (ev && tid == 0 && spins == 0 && b == 0) as_global(ev)[1] = wall_clock64();
+            if (!all_ok) {
+                bool lw = true;
+                if (tid < 64) lw = light_wait<HAS_ADD>(S, batch, k0, nunits * EPU, lane);
+                if (!vote.all<NT>(lw)) return false;
+                if (ev && tid == 0) { as_global(ev)[2] = wall_clock64(); as_global(ev)[5] += 1; }
+            }
+        }
+        if (!all_ok) return false;
+        if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
+        const float r = HAS_GAIN ? rsqrtf(tot / (float)K + S.eps) : 1.f;
+#pragma unroll
+        for (int u = 0; u < QB; u++) {
+            const int qi = tid + u * NT;
+            if (qi < padquads) {
+                float4 t = make_float4(cvalue(v[u].x), cvalue(v[u].y), cvalue(v[u].z), cvalue(v[u].w));
+                if constexpr (HAS_ADD) { t.x += cvalue(a[u].x); t.y += cvalue(a[u].y); t.z += cvalue(a[u].z); t.w += cvalue(a[u].w); }
+                if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
+                else {
+                    if (S.wb && (u32)qi >= wb_lo && (u32)qi < wb_hi) {   // this workgroup's slice of the published sum
+                        cword_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
+                        cst2(w, t.x, t.y, S.wb_tag);
+                        cst2(w + 2, t.z, t.w, S.wb_tag);
+                    }
+                    if constexpr (HAS_GAIN) {
+                        t.x *= bf_lo(g[u].x) * r; t.y *= bf_hi(g[u].x) * r; t.z *= bf_lo(g[u].y) * r; t.w *= bf_hi(g[u].y) * r;
+                    }
+                }
+                xb[(size_t)(qi % NQ) * nup + qi / NQ] = t;
+            }
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
 // Picks the pass size that covers the vector in one pass with the fewest registers.
 template <int EPU, bool HAS_ADD, int NT>
 __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
                                              WgVote& vote, u64* ev = nullptr) {
     const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
     if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
-        if (per_thread <= 4) return stage_tagged_impl<EPU, true, true, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
-        return stage_tagged_impl<EPU, true, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        return stage_tagged_multipass<EPU, true, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else if (S.gain) {       // embedding rows
-        return stage_tagged_impl<EPU, false, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        return stage_tagged_multipass<EPU, false, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else {
-        if (per_thread <= 4) return stage_tagged_impl<EPU, false, false, NT, 4>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_impl<EPU, false, false, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
-        return stage_tagged_impl<EPU, false, false, NT, 14>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        return stage_tagged_multipass<EPU, false, false, NT, 14>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     }
 }
 
