@@ -80,14 +80,21 @@ struct PhaseDesc {
     u32 out_tag;     // 32-bit tag of this phase's tagged outputs (q, k, v; attention partials)
     u32 out_cnt;     // write counter of this phase's compact output vector
 };
-struct PhaseState {   // the residual stream's ping-pong buffers (both roles track them identically)
+struct PhaseState {   // the residual stream's ping-pong buffers
     cword_t* xcur; cword_t* xnext;
 };
+// The buffers swap roles after every QKV and every GU phase (each publishes the updated stream into
+// xnext), so which is which follows from the phase number alone.
+__device__ __forceinline__ PhaseState phase_state(const DevModel& M, int ph) {
+    const int k = ph & 3;
+    const bool odd = k == 1 || k == 2;
+    return odd ? PhaseState{M.cx2, M.cx} : PhaseState{M.cx, M.cx2};
+}
 __device__ __forceinline__ u32 tag_of(u32 tag_base, int l, int k) { return tag_base + 1u + (u32)(l * kTagsPerLayer + k); }
 
 // `sl` = (steps executed so far) * L: the write counters of the compact vectors are sl + layer for the
 // buffers written once per layer and 2 * (sl + layer) + {0, 1} for the sublayer output (O, then DOWN).
-__device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* tokens, u32 tb, u32 sl, int ph, int lm_in_kernel, const PhaseState& X) {
+__device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* tokens, u32 tb, u32 sl, int ph, int lm_in_kernel, const PhaseState& X, bool eager_attn) {
     PhaseDesc D;
     const int l = ph >> 2;
     const FF_CONST PLayer* Lp = as_const(M.layers) + min(l, M.L - 1);   // scalar loads (see as_const)
@@ -108,6 +115,7 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
         D.W = FF_PMAT_FIELDS(Lp->qkv);
     } else if (D.kind == PH_O) {
         src.base = M.cattn_o; src.stride = (size_t)M.Hq * M.hd; src.tag = sl + l;
+        src.eager = eager_attn;
         D.out_cnt = 2 * (sl + l);
         D.W = FF_PMAT_FIELDS(Lp->o);
     } else if (D.kind == PH_GU) {
@@ -128,9 +136,6 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
         D.W = M.lm;
     }
     return D;
-}
-__device__ __forceinline__ void phase_advance(const PhaseDesc& D, PhaseState& X) {
-    if (D.kind == PH_QKV || D.kind == PH_GU) { cword_t* t = X.xcur; X.xcur = X.xnext; X.xnext = t; }
 }
 
 template <int WD, int B, int HD, int G>
@@ -160,7 +165,6 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
     // weight type differs from the layers' (then the host launches it separately).
     const int n_phases = 4 * M.L + (lm_in_kernel ? 1 : 0);
-    PhaseState X{M.cx, M.cx2};
     // steps executed so far on the compact buffers (kept on the device: a skipped step does not count)
     const u32 steps_done = (u32)__builtin_amdgcn_readfirstlane(xld_u32(M.stepctr));
     const u32 sl = steps_done * (u32)M.L;
@@ -169,12 +173,24 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64;   // behind the RoPE rows
     WgVote vote{(u32*)(red + 16), 0u};   // behind the reduction scratch and the positions
-    // One iteration = one K segment of one projection.
-    int ph = 0;
-    PhaseDesc D = phase_desc(M, tokens, tag_base, sl, 0, lm_in_kernel, X);
-    Stream<WD, B> S = Stream<WD, B>::make(D.W, 0, gwave, n_gwaves);
+    // One iteration = one K segment of one projection; only (phase, segment) are carried from one
+    // iteration to the next.  With kScalarState they are pinned to scalar registers, so that all
+    // that derives from them (the layer's descriptor, the wave's share) is fetched and computed on
+    // the scalar unit, the next descriptor is touched ahead of time, and the wait for the merged
+    // attention output re-reads eagerly.  Each of the three shortens the path from the end of one
+    // projection to the first tile requests of the next; with several sequences per pass that
+    // pays (8B bf16, batch 4: 5.70 -> 5.61 ms); with a single one the step measured slower
+    // (3.26 -> 3.30 ms; presumably the earlier requests compete with the workgroups still finishing
+    // the previous projection), so batch 1 keeps the unpinned form.
+    constexpr bool kScalarState = B > 1;
+    int ph = 0, seg = 0;
     for (;;) {
-        const int seg = S.seg;
+        if constexpr (kScalarState) {
+            ph = __builtin_amdgcn_readfirstlane(ph);
+            seg = __builtin_amdgcn_readfirstlane(seg);
+        }
+        const PhaseDesc D = phase_desc(M, tokens, tag_base, sl, ph, lm_in_kernel, phase_state(M, ph), kScalarState);
+        const Stream<WD, B> S = Stream<WD, B>::make(D.W, seg, gwave, n_gwaves);
         EpiFused epi{D.kind, D.out_tag, D.out_cnt, M, KV, pos_lds, D.layer, rope_lds, logits};
         // The wave's first tiles of this projection are requested before anything it has to wait
         // for (its input vector; for the output projection the whole attention), so the memory
@@ -188,6 +204,13 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         Stage<WD> ring[kDepthOf<WD>];
         prefetch_stream(S, ring, lane);
         if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);
+        // Touch the descriptor the NEXT phase will fetch, so that it sits in the scalar cache by
+        // then instead of costing a trip to memory at the head of that phase.
+        u32 warm = 0;
+        if constexpr (kScalarState) {
+            const FF_CONST u32* nd = (const FF_CONST u32*)(as_const(M.layers) + min((ph + 1) >> 2, M.L - 1));
+            warm = nd[0] ^ nd[16] ^ nd[32] ^ nd[sizeof(PLayer) / 4 - 1];
+        }
         if (att_first) {
             // split-KV attention + merge of this layer (the ring holds the output projection's tiles)
             __syncthreads();   // every wave has finished reading the staged input: LDS is free
@@ -214,16 +237,13 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         u64* wv = D.kind < 4 ? dbg_wave_slots(M, n_phases, D.layer, wave) : nullptr;
         if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
         gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
+        asm volatile("" ::"s"(warm));   // keeps the touch alive
         if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
         if (wv && lane == 0) as_global(wv)[D.kind] = wall_clock64();
         // next iteration: further K segment of the same projection, or the next projection
-        if (seg + 1 < S.nseg) S = Stream<WD, B>::make(D.W, seg + 1, gwave, n_gwaves);
-        else if (ph + 1 < n_phases) {
-            phase_advance(D, X);
-            ++ph;
-            D = phase_desc(M, tokens, tag_base, sl, ph, lm_in_kernel, X);
-            S = Stream<WD, B>::make(D.W, 0, gwave, n_gwaves);
-        } else break;
+        if (seg + 1 < S.nseg) ++seg;
+        else if (ph + 1 < n_phases) { ++ph; seg = 0; }
+        else break;
     }
     // this step has been executed: the next one uses the next write counters (workgroup 0 can only
     // get here after every workgroup has taken part in every phase, i.e. has read the counter)

@@ -235,9 +235,10 @@ struct Stream {
         S.nunits = min(seg_units, total_units - S.j0);
         S.cpr = (S.nunits + kChunkUnits - 1) / kChunkUnits;
         S.nup = S.cpr * kChunkUnits;
-        const long npairs = (M.n + 1) / 2;
-        S.p0 = (int)(npairs * gwave / n_gwaves);
-        S.my_pairs = (int)(npairs * (gwave + 1) / n_gwaves) - S.p0;
+        // row pairs [p0, p0 + my_pairs) of this wave; the products fit 32 bits (rows * waves < 2^32)
+        const u32 npairs = (u32)(M.n + 1) / 2;
+        S.p0 = (int)(npairs * (u32)gwave / (u32)n_gwaves);
+        S.my_pairs = (int)(npairs * (u32)(gwave + 1) / (u32)n_gwaves) - S.p0;
         S.n_it = S.my_pairs * S.cpr;
         return S;
     }

@@ -106,6 +106,7 @@ struct TSrc {
     cword_t* wb = nullptr; size_t wb_stride = 0; u32 wb_tag = 0;           // optional: publish the sum (residual stream)
     const bf16_t* gain = nullptr; float eps = 0.f;                         // optional: RMSNorm
     int ncta = 1;                                                          // workgroups in the grid (each publishes 1/ncta of wb)
+    bool eager = false;   // re-read the whole vector while waiting instead of polling samples (see stage_tagged_onepass)
 };
 
 // Waits (bounded) until kPollLanes sampled elements of the source vector(s) carry their tags: a
@@ -304,7 +305,12 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
             if constexpr (HAS_GAIN) all_ok = vote.all_sum<NT>(stale == 0, wave_sum_uniform(ss), tot);
             else all_ok = vote.all<NT>(stale == 0);
             if (ev && tid == 0 && spins == 0 && b == 0) as_global(ev)[1] = wall_clock64();
-            if (!all_ok) {
+            if (!all_ok && !S.eager) {
+                // A producer that is still streaming weights should not have to compete with 256
+                // workgroups re-reading its output: wait on a few samples.  An eager source is
+                // written by a handful of workgroups while the rest of the chip idles (the merged
+                // attention output): there the stale quads are simply read again, which saves the
+                // round trip between "sample seen" and "vector loaded".
                 bool lw = true;
                 if (tid < 64) lw = light_wait<HAS_ADD>(S, batch, k0, nunits * EPU, lane);
                 if (!vote.all<NT>(lw)) return false;

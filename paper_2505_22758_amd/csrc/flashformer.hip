@@ -73,6 +73,9 @@ int check_config(const ff_config* c) {
     if (c->d_model % epu || qd % epu || c->d_ffn % epu)
         return fail(FF_ERR_UNSUPPORTED, "d_model, n_q_heads*head_dim and d_ffn must be multiples of %d for this weight type", epu);
     if (c->d_model % 8 || c->d_ffn % 2 || c->vocab < 2) return fail(FF_ERR_UNSUPPORTED, "d_model must be a multiple of 8");
+    // the row partition among waves is computed in 32 bits: (rows / 2) * (waves in the grid) < 2^32
+    if (c->vocab > (1 << 21) || c->d_ffn > (1 << 20) || c->d_model > (1 << 20) || qd > (1 << 20))
+        return fail(FF_ERR_UNSUPPORTED, "matrix with more than 2^21 rows");
     if ((size_t)c->d_model * 4 * std::min(c->max_batch, kMaxBatch) > (size_t)kLdsActBytes)
         return fail(FF_ERR_UNSUPPORTED, "d_model %d x max_batch %d does not fit the on-chip input buffer (RMSNorm needs the whole row)", c->d_model, c->max_batch);
     return FF_OK;
