@@ -183,6 +183,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // (3.26 -> 3.30 ms; presumably the earlier requests compete with the workgroups still finishing
     // the previous projection), so batch 1 keeps the unpinned form.
     constexpr bool kScalarState = B > 1;
+    constexpr bool kQuad = kQuadOf<WD, B>;   // matrix-core GEMV on groups of four rows, split-bf16 staged input
     int ph = 0, seg = 0;
     for (;;) {
         if constexpr (kScalarState) {
@@ -190,7 +191,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             seg = __builtin_amdgcn_readfirstlane(seg);
         }
         const PhaseDesc D = phase_desc(M, tokens, tag_base, sl, ph, lm_in_kernel, phase_state(M, ph), kScalarState);
-        const Stream<WD, B> S = Stream<WD, B>::make(D.W, seg, gwave, n_gwaves);
+        const Stream<WD, B> S = Stream<WD, B>::make(D.W, seg, gwave, n_gwaves, kQuad);
         EpiFused epi{D.kind, D.out_tag, D.out_cnt, M, KV, pos_lds, D.layer, rope_lds, logits};
         // The wave's first tiles of this projection are requested before anything it has to wait
         // for (its input vector; for the output projection the whole attention), so the memory
@@ -202,7 +203,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (seg > 0) src.wb = nullptr;
         const bool att_first = D.kind == PH_O && seg == 0;
         Stage<WD> ring[kDepthOf<WD>];
-        prefetch_stream(S, ring, lane);
+        prefetch_stream<kQuad>(S, ring, lane);
         if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);
         // Touch the descriptor the NEXT phase will fetch, so that it sits in the scalar cache by
         // then instead of costing a trip to memory at the head of that phase.
@@ -226,8 +227,8 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (wave == 0) dbg_event(M, ph, EV_H_START, lane);
         bool ok;
         u64* ev = dbg_stage_slots(M, n_phases, ncta, D.layer, D.kind);
-        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
-        else ok = stage_tagged<EPU, false, kFusedThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
+        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads, kQuad>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
+        else ok = stage_tagged<EPU, false, kFusedThreads, kQuad>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
         if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
         if (!ok) {
             if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);
@@ -236,7 +237,8 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (wave == 0) dbg_event(M, ph, EV_SYNCED, lane);
         u64* wv = D.kind < 4 ? dbg_wave_slots(M, n_phases, D.layer, wave) : nullptr;
         if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
-        gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
+        if constexpr (kQuad) gemv_run_quad<B>(S, ring, xs, myacc, batch, lane, epi);
+        else gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         asm volatile("" ::"s"(warm));   // keeps the touch alive
         if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
         if (wv && lane == 0) as_global(wv)[D.kind] = wall_clock64();

@@ -25,6 +25,10 @@ template <int WD> constexpr int kUnrOf = WD == W_INT4 ? 2 : 4;
 #endif
 template <int WD> constexpr int kDepthOf = WD == W_INT4 ? 2 * FF_DEPTH : FF_DEPTH;
 template <int WD> constexpr int kChunkUnitsOf = 64 * kUnrOf<WD>;   // units of one row covered by one stage of one wave
+// With two or more sequences per pass the bf16 projections run on the matrix cores in groups of
+// four rows (gemv_run_quad below) instead of row pairs on the vector ALUs.
+template <int WD, int B> constexpr bool kQuadOf = WD == W_BF16 && B > 1;
+constexpr int kQuadChunkUnits = 128;   // units of one row covered by one stage of one wave in that mode
 
 // ---------------------------------------------------------------- reductions
 // Sum over the 64 lanes with DPP row operations; the result is wave-uniform.
@@ -224,7 +228,9 @@ struct Stream {
     static constexpr int kChunkUnits = kChunkUnitsOf<WD>;
     static constexpr int seg_units = (kLdsActBytes / (B * EPU * 4)) / kChunkUnits * kChunkUnits;
 
-    __device__ __forceinline__ static Stream make(const PMat& M, int seg, int gwave, int n_gwaves) {
+    // quad: rows are dealt out in groups of four (p0, my_pairs count groups) and a stage covers
+    // kQuadChunkUnits units of each of the four rows instead of kChunkUnits units of two rows.
+    __device__ __forceinline__ static Stream make(const PMat& M, int seg, int gwave, int n_gwaves, bool quad = false) {
         Stream S;
         S.w = M.w; S.s = M.s; S.z = M.z; S.N = M.n; S.K = M.k; S.ng = M.k / 128;
         S.rowb = WD == W_BF16 ? (size_t)M.k * 2 : WD == W_INT8 ? (size_t)M.k : (size_t)M.k / 2;
@@ -233,10 +239,10 @@ struct Stream {
         S.seg = seg;
         S.j0 = seg * seg_units;
         S.nunits = min(seg_units, total_units - S.j0);
-        S.cpr = (S.nunits + kChunkUnits - 1) / kChunkUnits;
-        S.nup = S.cpr * kChunkUnits;
+        S.nup = (S.nunits + kChunkUnits - 1) / kChunkUnits * kChunkUnits;
+        S.cpr = S.nup / (quad ? kQuadChunkUnits : kChunkUnits);
         // row pairs [p0, p0 + my_pairs) of this wave; the products fit 32 bits (rows * waves < 2^32)
-        const u32 npairs = (u32)(M.n + 1) / 2;
+        const u32 npairs = quad ? (u32)(M.n + 3) / 4 : (u32)(M.n + 1) / 2;
         S.p0 = (int)(npairs * (u32)gwave / (u32)n_gwaves);
         S.my_pairs = (int)(npairs * (u32)(gwave + 1) / (u32)n_gwaves) - S.p0;
         S.n_it = S.my_pairs * S.cpr;
@@ -272,15 +278,29 @@ __device__ __forceinline__ void load_stage(const Stream<WD, B>& S, int pair, int
     }
 }
 
+// The same for a group of four rows: lane (blk = lane / 4, r = lane % 4) loads unit blk of row r of
+// each of the stage's eight 16-unit slices, i.e. a wave load covers 256 contiguous bytes of four rows.
+template <int B>
+__device__ __forceinline__ void load_stage_quad(const Stream<W_BF16, B>& S, int grp, int chunk, Stage<W_BF16>& st, int lane) {
+    const int row = min(4 * grp + (lane & 3), S.N - 1);
+    const uint8_t* rp = S.w + (size_t)row * S.rowb + (size_t)S.j0 * 16;
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+        const int j = min((chunk * 8 + u) * 16 + (lane >> 2), S.nunits - 1);
+        st.w[u >> 2][u & 3] = ldg_stream(rp + (size_t)j * 16);
+    }
+}
+
 // Issue the first min(kDepth, n_it) iterations of a stream into the ring; returns how many.
-template <int WD, int B>
+template <bool QUAD, int WD, int B>
 __device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], int lane) {
     constexpr int kDepth = kDepthOf<WD>;
     int pair = S.p0, chunk = 0, n = 0;
 #pragma unroll
     for (int s = 0; s < kDepth; s++) {
         if (s < S.n_it) {
-            load_stage(S, pair, chunk, ring[s], lane);
+            if constexpr (QUAD) load_stage_quad(S, pair, chunk, ring[s], lane);
+            else load_stage(S, pair, chunk, ring[s], lane);
             if (++chunk == S.cpr) { chunk = 0; ++pair; }
             n = s + 1;
         }
@@ -393,6 +413,103 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
         }
     }
     // tail
+    for (; it < S.n_it; it += kDepth) {
+#pragma unroll
+        for (int s = 0; s < kDepth; s++) {
+            if (it + s < S.n_it) {
+                compute(ring[s]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (it + s + kDepth < S.n_it) load(ring[s]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- matrix-core variant (bf16, batch >= 2)
+// The same stream for groups of FOUR rows on v_mfma_f32_4x4x4_16b_bf16, which multiplies sixteen
+// independent 4x4x4 blocks per wave: in block blk = lane / 4, lane r = lane % 4 supplies row r of
+// A (four k values) and column r of B, and receives column r of the 4x4 result (register i = row
+// i).  Here A = the four weight rows over four consecutive k (half of the lane's 16-byte unit) and
+// B = the staged inputs of sequences 0..3 over the same k, so one instruction does the 64
+// multiply-adds that cost 16 vector FMAs plus conversions in gemv_run, and the cost no longer
+// grows with the batch (paper Section 4.2 keeps the weights read once at batch 2-4; this keeps the
+// arithmetic from becoming the limit there).  The inputs stay fp32-accurate: staging splits every
+// value into a bf16 head and a bf16 remainder (two planes per sequence, see stage_store), and both
+// are multiplied.  Unit j of sequence b sits at index (j ^ (b << 2)) of its plane, which spreads
+// the four lanes of a block over different LDS banks.
+typedef short mfma_s4 __attribute__((ext_vector_type(4)));
+typedef float mfma_f4 __attribute__((ext_vector_type(4)));
+
+template <int B, class Epi>
+__device__ __forceinline__ void gemv_run_quad(const Stream<W_BF16, B>& S, Stage<W_BF16> (&ring)[kDepthOf<W_BF16>], const float4* xs,
+                                              float* myacc, int batch, int lane, Epi& epi) {
+    constexpr int kDepth = kDepthOf<W_BF16>;
+    const int nup = S.nup;
+    const int bl = min(lane & 3, B - 1);   // sequence whose inputs this lane feeds (columns >= B are never read back)
+    const u32x4* xh = (const u32x4*)xs + (size_t)(2 * bl) * nup + ((lane >> 2) ^ (bl << 2));
+    const u32x4* xl = xh + nup;
+    mfma_f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    int pc = S.p0, cc = 0;          // (group, chunk) of the next compute
+    int pl = S.p0, cl = 0;          // (group, chunk) of the next load = iteration kDepth
+    for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
+
+    auto half = [](u32 a, u32 b) { u32x2 v{a, b}; return __builtin_bit_cast(mfma_s4, v); };
+    auto compute = [&](const Stage<W_BF16>& st) {
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const int off = (cc * 8 + u) * 16;
+            const u32x4 h = xh[off], l = xl[off], w = st.w[u >> 2][u & 3];
+            acc0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(h.x, h.y), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(l.x, l.y), acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(h.z, h.w), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(l.z, l.w), acc1, 0, 0, 0);
+        }
+        if (cc == S.cpr - 1) {   // group finished (for this K segment): add up the sixteen blocks
+            float t[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                float v = acc0[i] + acc1[i];
+                v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xF, 0xF, true));   // row_ror:8
+                v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xF, 0xF, true));   // row_ror:4
+                v += __shfl_xor(v, 16);
+                v += __shfl_xor(v, 32);
+                t[i] = v;   // row 4*group + i, sequence lane % 4
+            }
+            acc0 = mfma_f4{0.f, 0.f, 0.f, 0.f};
+            acc1 = mfma_f4{0.f, 0.f, 0.f, 0.f};
+            if (lane < 4 && lane < batch) {   // lane b finishes sequence b
+                const int b = lane;
+                if (S.nseg > 1) {
+                    float* a = myacc + ((size_t)(pc - S.p0) * B + b) * 4;
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        if (S.seg > 0) t[i] += a[i];
+                        if (S.seg < S.nseg - 1) a[i] = t[i];
+                    }
+                }
+                if (S.seg == S.nseg - 1) {
+                    epi(2 * pc, b, t[0], t[1]);
+                    if (4 * pc + 2 < S.N) epi(2 * pc + 1, b, t[2], t[3]);
+                }
+            }
+        }
+        if (++cc == S.cpr) { cc = 0; ++pc; }
+    };
+    auto load = [&](Stage<W_BF16>& st) {
+        load_stage_quad(S, pl, cl, st, lane);
+        if (++cl == S.cpr) { cl = 0; ++pl; }
+    };
+    int it = 0;
+    for (; it + 2 * kDepth <= S.n_it; it += kDepth) {
+#pragma unroll
+        for (int s = 0; s < kDepth; s++) {
+            compute(ring[s]);
+            __builtin_amdgcn_sched_barrier(0);
+            load(ring[s]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
     for (; it < S.n_it; it += kDepth) {
 #pragma unroll
         for (int s = 0; s < kDepth; s++) {

@@ -72,7 +72,7 @@ __device__ __forceinline__ void op_gemv_body(const PMat& W, const ActSrc& src, i
     const int nseg = S.nseg;
     for (int seg = 0; seg < nseg; seg++) {
         if (seg > 0) { S = Stream<WD, B>::make(W, seg, gwave, n_gwaves); __syncthreads(); }
-        prefetch_stream(S, ring, lane);   // weights do not depend on the input: issue them first
+        prefetch_stream<false>(S, ring, lane);   // weights do not depend on the input: issue them first
         stage_act<EPU, PlainIO, kThreads>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x);
         __syncthreads();
         gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);

@@ -129,6 +129,33 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
     return false;
 }
 
+// Writes quad qi (elements 4*qi .. 4*qi+3) of sequence b into the staged vector.  Plain form: the
+// quad-planar fp32 layout of stage_act.  SPLIT form (input of gemv_run_quad): every value v is
+// stored as bf16 head h = v truncated and bf16 remainder of v - h (the pair carries 16 mantissa
+// bits), heads in plane 2b and remainders in plane 2b+1 of nup 16-byte units each, element order as
+// in a weight unit, unit j at index j ^ (b << 2).
+template <int EPU, bool SPLIT>
+__device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, const float4& t) {
+    constexpr int NQ = EPU / 4;
+    if constexpr (!SPLIT) {
+        xs[((size_t)b * NQ + qi % NQ) * nup + qi / NQ] = t;
+    } else {
+        static_assert(EPU == 8, "bf16 weights only");
+        const float v[4] = {t.x, t.y, t.z, t.w};
+        u32 h[4], l[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            h[e] = __float_as_uint(v[e]) & 0xFFFF0000u;
+            l[e] = __float_as_uint(v[e] - __uint_as_float(h[e]));
+        }
+        const int j = (qi >> 1) ^ (b << 2);
+        u32x2* ph = (u32x2*)(xs + (size_t)(2 * b) * nup + j) + (qi & 1);
+        u32x2* pl = (u32x2*)(xs + (size_t)(2 * b + 1) * nup + j) + (qi & 1);
+        *ph = u32x2{(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
+        *pl = u32x2{(l[0] >> 16) | (l[1] & 0xFFFF0000u), (l[2] >> 16) | (l[3] & 0xFFFF0000u)};
+    }
+}
+
 // The workgroup stages elements [k0, k0 + nunits*EPU) of every batch row into LDS in the
 // quad-planar layout of stage_act, re-reading the tagged sources until their producers have
 // written them.  Every thread issues all loads of its share of a batch at once and speculatively
@@ -139,7 +166,7 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 // QB = quads per thread and pass (2 8-byte loads per quad and source, all in flight at once; their
 // 4*QB destination registers per source must fit beside the wave's prefetched weight tiles, or the
 // compiler parks those tiles elsewhere and has to wait for them first).
-template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB>
+template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT>
 __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid, WgVote& vote, u64* ev) {
     constexpr int NQ = EPU / 4;
     if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
@@ -218,11 +245,12 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
                             t.x *= bf_lo(g[u].x); t.y *= bf_hi(g[u].x); t.z *= bf_lo(g[u].y); t.w *= bf_hi(g[u].y);
                         }
                     }
-                    xb[(size_t)(qi % NQ) * nup + qi / NQ] = t;
+                    stage_store<EPU, SPLIT>(xs, nup, b, qi, t);
                 }
             }
         }
         if constexpr (HAS_GAIN) {
+            static_assert(!SPLIT, "the rescaling pass below works on the fp32 layout");
             ss = wave_sum_uniform(ss);
             if (lane == 0) red[tid >> 6] = ss;
             __syncthreads();
@@ -247,7 +275,7 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
 // NT * QB): every thread keeps its quads in registers from the load to the LDS write, and the sum
 // of squares of the normalisation travels with the freshness vote, so a batch row costs a single
 // workgroup barrier and the staged vector is written once, already scaled.
-template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB>
+template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT>
 __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, int tid, WgVote& vote, u64* ev) {
     constexpr int NQ = EPU / 4;
     if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
@@ -337,7 +365,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                         t.x *= bf_lo(g[u].x) * r; t.y *= bf_hi(g[u].x) * r; t.z *= bf_lo(g[u].y) * r; t.w *= bf_hi(g[u].y) * r;
                     }
                 }
-                xb[(size_t)(qi % NQ) * nup + qi / NQ] = t;
+                stage_store<EPU, SPLIT>(xs, nup, b, qi, t);
             }
         }
     }
@@ -345,23 +373,27 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
     return true;
 }
 
-// Picks the pass size that covers the vector in one pass with the fewest registers.
-template <int EPU, bool HAS_ADD, int NT>
+// Picks the pass size that covers the vector in one pass with the fewest registers.  SPLIT selects
+// the staged format (see stage_store); a normalised vector too long for one pass has no SPLIT form
+// (the host rejects such configurations).
+template <int EPU, bool HAS_ADD, int NT, bool SPLIT>
 __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
                                              WgVote& vote, u64* ev = nullptr) {
     const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
     if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
-        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        return stage_tagged_multipass<EPU, true, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if constexpr (SPLIT) return false;
+        else return stage_tagged_multipass<EPU, true, true, NT, 8, false>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else if (S.gain) {       // embedding rows
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        return stage_tagged_multipass<EPU, false, true, NT, 8>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if constexpr (SPLIT) return false;
+        else return stage_tagged_multipass<EPU, false, true, NT, 8, false>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else {
-        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        return stage_tagged_multipass<EPU, false, false, NT, 14>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        return stage_tagged_multipass<EPU, false, false, NT, 14, SPLIT>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     }
 }
 
