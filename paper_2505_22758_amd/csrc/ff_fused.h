@@ -227,8 +227,8 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (wave == 0) dbg_event(M, ph, EV_H_START, lane);
         bool ok;
         u64* ev = dbg_stage_slots(M, n_phases, ncta, D.layer, D.kind);
-        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads, kQuad>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
-        else ok = stage_tagged<EPU, false, kFusedThreads, kQuad>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
+        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
+        else ok = stage_tagged<EPU, false, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
         if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
         if (!ok) {
             if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);

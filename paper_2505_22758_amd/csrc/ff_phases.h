@@ -73,27 +73,39 @@ __device__ __forceinline__ u32x2 cld2(const cword_t* base, int i) {   // element
 // vote's barrier, which that other wave only reaches after its read).  All threads must take part
 // in every vote, in the same order.
 struct WgVote {
-    u32* slots;   // LDS, 4 * (waves per workgroup) words
+    static constexpr int kMaxSums = 4;
+    u32* slots;   // LDS, 2 * (1 + kMaxSums) * (waves per workgroup) words
     u32 par;
     template <int NT>
     __device__ __forceinline__ bool all(bool ok) {
-        float unused;
-        return all_sum<NT>(ok, 0.f, unused);
+        const float none[1] = {0.f};
+        float unused[1];
+        return all_sum<NT, 1>(ok, none, unused);
     }
-    // The same vote, which also adds up one (wave-uniform) float per wave over the workgroup.
-    template <int NT>
-    __device__ __forceinline__ bool all_sum(bool ok, float part, float& total) {
+    // The same vote, which also adds up N (wave-uniform) floats per wave over the workgroup.
+    template <int NT, int N>
+    __device__ __forceinline__ bool all_sum(bool ok, const float (&part)[N], float (&total)[N]) {
+        static_assert(N <= kMaxSums, "too many sums");
         constexpr int NW = NT / 64;
         const u32 w = __all(ok) ? 1u : 0u;
-        u32* f = slots + par * 2 * NW;
+        u32* f = slots + par * (1 + kMaxSums) * NW;
         par ^= 1u;
-        if ((threadIdx.x & 63) == 0) { f[threadIdx.x >> 6] = w; f[NW + (threadIdx.x >> 6)] = __float_as_uint(part); }
+        if ((threadIdx.x & 63) == 0) {
+            f[threadIdx.x >> 6] = w;
+#pragma unroll
+            for (int n = 0; n < N; n++) f[(1 + n) * NW + (threadIdx.x >> 6)] = __float_as_uint(part[n]);
+        }
         __syncthreads();
         u32 r = 1u;
-        float t = 0.f;
 #pragma unroll
-        for (int i = 0; i < NW; i++) { r &= f[i]; t += __uint_as_float(f[NW + i]); }
-        total = t;
+        for (int i = 0; i < NW; i++) r &= f[i];
+#pragma unroll
+        for (int n = 0; n < N; n++) {
+            float t = 0.f;
+#pragma unroll
+            for (int i = 0; i < NW; i++) t += __uint_as_float(f[(1 + n) * NW + i]);
+            total[n] = t;
+        }
         return __builtin_amdgcn_readfirstlane(r) != 0;
     }
 };
@@ -272,10 +284,12 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
 }
 
 // The common case, where one pass of QB quads per thread covers the whole vector (nup * EPU / 4 <=
-// NT * QB): every thread keeps its quads in registers from the load to the LDS write, and the sum
-// of squares of the normalisation travels with the freshness vote, so a batch row costs a single
-// workgroup barrier and the staged vector is written once, already scaled.
-template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT>
+// NT * QB): every thread keeps its quads in registers from the load to the LDS write, and the sums
+// of squares of the normalisation travel with the freshness vote, so a group of RB batch rows costs
+// a single workgroup barrier and the staged vectors are written once, already scaled.  The loads
+// of all RB rows are in flight together: behind a wave's weight prefetch a round trip takes
+// microseconds, and one per row would make the hand-over grow with the batch.
+template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT, int RB>
 __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, int tid, WgVote& vote, u64* ev) {
     constexpr int NQ = EPU / 4;
     if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
@@ -283,56 +297,75 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
     const int nquads = nunits * NQ;
     const int padquads = nup * NQ;
     const u32 wb_lo = (u32)nquads * blockIdx.x / (u32)S.ncta, wb_hi = (u32)nquads * (blockIdx.x + 1) / (u32)S.ncta;
-    for (int b = 0; b < batch; b++) {
-        float4* xb = xs + (size_t)b * NQ * nup;
-        const cword_t* src = S.base + (size_t)b * S.stride;
-        const cword_t* add = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
-        const bf16_t* erow = nullptr;   // embedding rows only come through the (no add, gain) instance
-        if constexpr (!HAS_ADD && HAS_GAIN) erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
-        u32x4 v[QB], a[HAS_ADD ? QB : 1];   // four compact words per quad and source
+    for (int b0 = 0; b0 < batch; b0 += RB) {
+        // rows b0 .. b0+RB-1; a row past the batch repeats the last one (loaded and checked, never written)
+        const cword_t* src[RB];
+        const cword_t* add[RB];
+        const bf16_t* erow[RB];   // embedding rows only come through the (no add, gain) instance
+#pragma unroll
+        for (int r = 0; r < RB; r++) {
+            const int b = min(b0 + r, batch - 1);
+            src[r] = S.base + (size_t)b * S.stride;
+            add[r] = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
+            erow[r] = nullptr;
+            if constexpr (!HAS_ADD && HAS_GAIN) erow[r] = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
+        }
+        u32x4 v[RB][QB], a[HAS_ADD ? RB : 1][HAS_ADD ? QB : 1];   // four compact words per quad and source
         u32x2 g[HAS_GAIN ? QB : 1];
         bool all_ok = false;
-        float tot = 0.f;
-        u32 stale = (1u << QB) - 1;   // quads (bit u) this lane still has to (re)load
+        float tot[RB];
+        u32 stale[RB];   // quads (bit u) of row r this lane still has to (re)load
+#pragma unroll
+        for (int r = 0; r < RB; r++) { stale[r] = (1u << QB) - 1; tot[r] = 0.f; }
         for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
             // first round: every quad of every lane; later rounds: only what came back stale, so a
             // vector that was mostly complete is not fetched twice
 #pragma unroll
-            for (int u = 0; u < QB; u++) {
-                const int k = k0 + min(tid + u * NT, nquads - 1) * 4;   // clamped: every load is issued
-                if (spins == 0 || ((stale >> u) & 1)) {
-                    if (erow) {   // bf16 values are exact in the compact format: mark them fresh
-                        u32x2 w = *as_global((const u32x2*)(erow + k));
-                        const u32 t = S.tag & 15u;
-                        v[u] = u32x4{(w.x << 16) | t, (w.x & 0xFFFF0000u) | t, (w.y << 16) | t, (w.y & 0xFFFF0000u) | t};
-                    } else {
-                        const u32x2 lo = cld2(src, k), hi = cld2(src, k + 2);
-                        v[u] = u32x4{lo.x, lo.y, hi.x, hi.y};
-                    }
-                    if constexpr (HAS_ADD) {
-                        const u32x2 lo = cld2(add, k), hi = cld2(add, k + 2);
-                        a[u] = u32x4{lo.x, lo.y, hi.x, hi.y};
-                    }
-                }
-                if constexpr (HAS_GAIN) { if (spins == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
-            }
-            stale = 0;
-            float ss = 0.f;   // only meaningful if the vote passes
+            for (int r = 0; r < RB; r++) {
 #pragma unroll
-            for (int u = 0; u < QB; u++) {
-                bool ok = cfresh(v[u].x, S.tag) && cfresh(v[u].y, S.tag) && cfresh(v[u].z, S.tag) && cfresh(v[u].w, S.tag);
-                if constexpr (HAS_ADD)
-                    ok = ok && cfresh(a[u].x, S.add_tag) && cfresh(a[u].y, S.add_tag) && cfresh(a[u].z, S.add_tag) && cfresh(a[u].w, S.add_tag);
-                if (!ok) stale |= 1u << u;
-                if constexpr (HAS_GAIN) {
-                    float4 t = make_float4(cvalue(v[u].x), cvalue(v[u].y), cvalue(v[u].z), cvalue(v[u].w));
-                    if constexpr (HAS_ADD) { t.x += cvalue(a[u].x); t.y += cvalue(a[u].y); t.z += cvalue(a[u].z); t.w += cvalue(a[u].w); }
-                    if (tid + u * NT < nquads) ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+                for (int u = 0; u < QB; u++) {
+                    const int k = k0 + min(tid + u * NT, nquads - 1) * 4;   // clamped: every load is issued
+                    if (spins == 0 || ((stale[r] >> u) & 1)) {
+                        if (erow[r]) {   // bf16 values are exact in the compact format: mark them fresh
+                            u32x2 w = *as_global((const u32x2*)(erow[r] + k));
+                            const u32 t = S.tag & 15u;
+                            v[r][u] = u32x4{(w.x << 16) | t, (w.x & 0xFFFF0000u) | t, (w.y << 16) | t, (w.y & 0xFFFF0000u) | t};
+                        } else {
+                            const u32x2 lo = cld2(src[r], k), hi = cld2(src[r], k + 2);
+                            v[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                        }
+                        if constexpr (HAS_ADD) {
+                            const u32x2 lo = cld2(add[r], k), hi = cld2(add[r], k + 2);
+                            a[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                        }
+                    }
+                    if constexpr (HAS_GAIN) { if (spins == 0 && r == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
                 }
             }
-            if constexpr (HAS_GAIN) all_ok = vote.all_sum<NT>(stale == 0, wave_sum_uniform(ss), tot);
-            else all_ok = vote.all<NT>(stale == 0);
-            if (ev && tid == 0 && spins == 0 && b == 0) as_global(ev)[1] = wall_clock64();
+            float ss[RB];   // only meaningful if the vote passes
+            bool mine = true;
+#pragma unroll
+            for (int r = 0; r < RB; r++) {
+                stale[r] = 0;
+                ss[r] = 0.f;
+#pragma unroll
+                for (int u = 0; u < QB; u++) {
+                    bool ok = cfresh(v[r][u].x, S.tag) && cfresh(v[r][u].y, S.tag) && cfresh(v[r][u].z, S.tag) && cfresh(v[r][u].w, S.tag);
+                    if constexpr (HAS_ADD)
+                        ok = ok && cfresh(a[r][u].x, S.add_tag) && cfresh(a[r][u].y, S.add_tag) && cfresh(a[r][u].z, S.add_tag) && cfresh(a[r][u].w, S.add_tag);
+                    if (!ok) stale[r] |= 1u << u;
+                    if constexpr (HAS_GAIN) {
+                        float4 t = make_float4(cvalue(v[r][u].x), cvalue(v[r][u].y), cvalue(v[r][u].z), cvalue(v[r][u].w));
+                        if constexpr (HAS_ADD) { t.x += cvalue(a[r][u].x); t.y += cvalue(a[r][u].y); t.z += cvalue(a[r][u].z); t.w += cvalue(a[r][u].w); }
+                        if (tid + u * NT < nquads) ss[r] += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+                    }
+                }
+                mine = mine && stale[r] == 0;
+                if constexpr (HAS_GAIN) ss[r] = wave_sum_uniform(ss[r]);
+            }
+            if constexpr (HAS_GAIN) all_ok = vote.all_sum<NT, RB>(mine, ss, tot);
+            else all_ok = vote.all<NT>(mine);
+            if (ev && tid == 0 && spins == 0 && b0 == 0) as_global(ev)[1] = wall_clock64();
             if (!all_ok && !S.eager) {
                 // A producer that is still streaming weights should not have to compete with 256
                 // workgroups re-reading its output: wait on a few samples.  An eager source is
@@ -347,25 +380,31 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
         }
         if (!all_ok) return false;
         if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
-        const float r = HAS_GAIN ? rsqrtf(tot / (float)K + S.eps) : 1.f;
 #pragma unroll
-        for (int u = 0; u < QB; u++) {
-            const int qi = tid + u * NT;
-            if (qi < padquads) {
-                float4 t = make_float4(cvalue(v[u].x), cvalue(v[u].y), cvalue(v[u].z), cvalue(v[u].w));
-                if constexpr (HAS_ADD) { t.x += cvalue(a[u].x); t.y += cvalue(a[u].y); t.z += cvalue(a[u].z); t.w += cvalue(a[u].w); }
-                if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
-                else {
-                    if (S.wb && (u32)qi >= wb_lo && (u32)qi < wb_hi) {   // this workgroup's slice of the published sum
-                        cword_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
-                        cst2(w, t.x, t.y, S.wb_tag);
-                        cst2(w + 2, t.z, t.w, S.wb_tag);
-                    }
-                    if constexpr (HAS_GAIN) {
-                        t.x *= bf_lo(g[u].x) * r; t.y *= bf_hi(g[u].x) * r; t.z *= bf_lo(g[u].y) * r; t.w *= bf_hi(g[u].y) * r;
+        for (int r = 0; r < RB; r++) {
+            const int b = b0 + r;
+            if (b < batch) {
+                const float rs = HAS_GAIN ? rsqrtf(tot[r] / (float)K + S.eps) : 1.f;
+#pragma unroll
+                for (int u = 0; u < QB; u++) {
+                    const int qi = tid + u * NT;
+                    if (qi < padquads) {
+                        float4 t = make_float4(cvalue(v[r][u].x), cvalue(v[r][u].y), cvalue(v[r][u].z), cvalue(v[r][u].w));
+                        if constexpr (HAS_ADD) { t.x += cvalue(a[r][u].x); t.y += cvalue(a[r][u].y); t.z += cvalue(a[r][u].z); t.w += cvalue(a[r][u].w); }
+                        if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
+                        else {
+                            if (S.wb && (u32)qi >= wb_lo && (u32)qi < wb_hi) {   // this workgroup's slice of the published sum
+                                cword_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
+                                cst2(w, t.x, t.y, S.wb_tag);
+                                cst2(w + 2, t.z, t.w, S.wb_tag);
+                            }
+                            if constexpr (HAS_GAIN) {
+                                t.x *= bf_lo(g[u].x) * rs; t.y *= bf_hi(g[u].x) * rs; t.z *= bf_lo(g[u].y) * rs; t.w *= bf_hi(g[u].y) * rs;
+                            }
+                        }
+                        stage_store<EPU, SPLIT>(xs, nup, b, qi, t);
                     }
                 }
-                stage_store<EPU, SPLIT>(xs, nup, b, qi, t);
             }
         }
     }
@@ -373,26 +412,29 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
     return true;
 }
 
-// Picks the pass size that covers the vector in one pass with the fewest registers.  SPLIT selects
-// the staged format (see stage_store); a normalised vector too long for one pass has no SPLIT form
-// (the host rejects such configurations).
-template <int EPU, bool HAS_ADD, int NT, bool SPLIT>
+// Picks the pass size that covers the vector in one pass with the fewest registers, and how many
+// batch rows are loaded together (RBMAX = the kernel's batch capacity; four rows of a short
+// vector, two of a long one, to keep the quads of all rows in registers beside the weight tiles).
+// SPLIT selects the staged format (see stage_store); a normalised vector too long for one pass has
+// no SPLIT form (the host rejects such configurations).
+template <int EPU, bool HAS_ADD, int NT, bool SPLIT, int RBMAX>
 __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
                                              WgVote& vote, u64* ev = nullptr) {
+    constexpr int RB4 = RBMAX < 4 ? RBMAX : 4, RB2 = RBMAX < 2 ? RBMAX : 2;
     const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
     if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
-        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         if constexpr (SPLIT) return false;
         else return stage_tagged_multipass<EPU, true, true, NT, 8, false>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else if (S.gain) {       // embedding rows
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         if constexpr (SPLIT) return false;
         else return stage_tagged_multipass<EPU, false, true, NT, 8, false>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else {
-        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14, SPLIT>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         return stage_tagged_multipass<EPU, false, false, NT, 14, SPLIT>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     }
 }
