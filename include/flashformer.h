@@ -125,8 +125,8 @@ int ff_kv_free(ff_kv *kv);
  * Asynchronous; an out-of-range position or token makes the kernel skip the step and record
  * FF_ERR_RANGE in the model's status word (see ff_status).  Steps on one model must not overlap.
  * One kernel pass serves up to 4 sequences (paper Section 4.2: batches 2-4 replicate the inputs and
- * read every weight once); a larger batch runs as consecutive passes of 4 on the stream, each
- * streaming the weights again. */
+ * read every weight once), or up to 8 with bf16 weights when d_model <= 4096 and max_batch > 4;
+ * a larger batch runs as consecutive passes on the stream, each streaming the weights again. */
 int ff_decode_step(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
                    float *logits_dev, int32_t batch, void *stream);
 

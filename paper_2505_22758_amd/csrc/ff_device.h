@@ -18,6 +18,7 @@ typedef uint16_t f16_t;    // raw bits
 constexpr int kThreads = 256;            // threads per workgroup (4 waves, one per SIMD)
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxBatch = 4;        // sequences one kernel pass works on
+constexpr int kMaxBatchFused = 8;   // ... of the fused kernel with bf16 weights, if the input rows of 8 sequences fit in LDS
 constexpr int kMaxBatchApi = 16;    // sequences one decode step accepts (run as passes of kMaxBatch)
 constexpr int kMaxSplits = 64;           // max KV splits per (sequence, kv head)
 constexpr int kMinSplitLen = 64;         // do not split the cache finer than this many rows

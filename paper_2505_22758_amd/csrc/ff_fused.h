@@ -159,7 +159,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // Launch dimensions and positions are read again and again below; a vector load of them would
     // make the wave wait for everything it has in flight (its prefetched weight tiles included), so
     // the grid size is a kernel argument and the positions are staged in LDS once.
-    int* pos_lds = (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64 + 8);
+    int* pos_lds = (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64 + 8);
     if (threadIdx.x < batch) pos_lds[threadIdx.x] = pos[threadIdx.x];
     __syncthreads();
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
@@ -171,7 +171,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
 
     const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = ncta * kFusedWaves;
     float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
-    float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatch * 64;   // behind the RoPE rows
+    float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64;   // behind the RoPE rows
     WgVote vote{(u32*)(red + 16), 0u};   // behind the reduction scratch and the positions
     // One iteration = one K segment of one projection; only (phase, segment) are carried from one
     // iteration to the next.  With kScalarState they are pinned to scalar registers, so that all
@@ -279,6 +279,9 @@ template <int WD, int HD, int G>
 inline hipError_t launch_fused_family(const FusedLaunch& a, const char** what) {
     if (a.batch == 1) return launch_fused_instance<WD, 1, HD, G>(a, what);
     if (a.batch == 2) return launch_fused_instance<WD, 2, HD, G>(a, what);
+    if constexpr (kQuadOf<WD, kMaxBatchFused>) {
+        if (a.batch > kMaxBatch) return launch_fused_instance<WD, kMaxBatchFused, HD, G>(a, what);
+    }
     return launch_fused_instance<WD, 4, HD, G>(a, what);
 }
 // One definition per (weight type, head geometry), each in its own translation unit.

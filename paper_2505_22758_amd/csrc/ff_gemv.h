@@ -436,8 +436,9 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
 // grows with the batch (paper Section 4.2 keeps the weights read once at batch 2-4; this keeps the
 // arithmetic from becoming the limit there).  The inputs stay fp32-accurate: staging splits every
 // value into a bf16 head and a bf16 remainder (two planes per sequence, see stage_store), and both
-// are multiplied.  Unit j of sequence b sits at index (j ^ (b << 2)) of its plane, which spreads
-// the four lanes of a block over different LDS banks.
+// are multiplied.  Unit j of sequence b sits at index (j ^ ((b & 3) << 2)) of its plane, which spreads
+// the four lanes of a block over different LDS banks.  More than four sequences take one
+// accumulator pair per set of four (the weights in registers are reused).
 typedef short mfma_s4 __attribute__((ext_vector_type(4)));
 typedef float mfma_f4 __attribute__((ext_vector_type(4)));
 
@@ -445,11 +446,17 @@ template <int B, class Epi>
 __device__ __forceinline__ void gemv_run_quad(const Stream<W_BF16, B>& S, Stage<W_BF16> (&ring)[kDepthOf<W_BF16>], const float4* xs,
                                               float* myacc, int batch, int lane, Epi& epi) {
     constexpr int kDepth = kDepthOf<W_BF16>;
+    constexpr int NC = (B + 3) / 4;   // sets of four sequences (one accumulator pair each)
     const int nup = S.nup;
-    const int bl = min(lane & 3, B - 1);   // sequence whose inputs this lane feeds (columns >= B are never read back)
-    const u32x4* xh = (const u32x4*)xs + (size_t)(2 * bl) * nup + ((lane >> 2) ^ (bl << 2));
-    const u32x4* xl = xh + nup;
-    mfma_f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    const u32x4* xh[NC];
+#pragma unroll
+    for (int c = 0; c < NC; c++) {
+        const int bl = min(4 * c + (lane & 3), B - 1);   // sequence whose inputs this lane feeds (columns >= B are never read back)
+        xh[c] = (const u32x4*)xs + (size_t)(2 * bl) * nup + ((lane >> 2) ^ ((bl & 3) << 2));
+    }
+    mfma_f4 acc0[NC], acc1[NC];
+#pragma unroll
+    for (int c = 0; c < NC; c++) { acc0[c] = mfma_f4{0.f, 0.f, 0.f, 0.f}; acc1[c] = mfma_f4{0.f, 0.f, 0.f, 0.f}; }
     int pc = S.p0, cc = 0;          // (group, chunk) of the next compute
     int pl = S.p0, cl = 0;          // (group, chunk) of the next load = iteration kDepth
     for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
@@ -459,38 +466,45 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<W_BF16, B>& S, Stage<
 #pragma unroll
         for (int u = 0; u < 8; u++) {
             const int off = (cc * 8 + u) * 16;
-            const u32x4 h = xh[off], l = xl[off], w = st.w[u >> 2][u & 3];
-            acc0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(h.x, h.y), acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(l.x, l.y), acc1, 0, 0, 0);
-            acc0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(h.z, h.w), acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(l.z, l.w), acc1, 0, 0, 0);
+            const u32x4 w = st.w[u >> 2][u & 3];
+#pragma unroll
+            for (int c = 0; c < NC; c++) {
+                const u32x4 h = xh[c][off], l = xh[c][off + nup];
+                acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(h.x, h.y), acc0[c], 0, 0, 0);
+                acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(l.x, l.y), acc1[c], 0, 0, 0);
+                acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(h.z, h.w), acc0[c], 0, 0, 0);
+                acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(l.z, l.w), acc1[c], 0, 0, 0);
+            }
         }
         if (cc == S.cpr - 1) {   // group finished (for this K segment): add up the sixteen blocks
-            float t[4];
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                float v = acc0[i] + acc1[i];
-                v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xF, 0xF, true));   // row_ror:8
-                v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xF, 0xF, true));   // row_ror:4
-                v += __shfl_xor(v, 16);
-                v += __shfl_xor(v, 32);
-                t[i] = v;   // row 4*group + i, sequence lane % 4
-            }
-            acc0 = mfma_f4{0.f, 0.f, 0.f, 0.f};
-            acc1 = mfma_f4{0.f, 0.f, 0.f, 0.f};
-            if (lane < 4 && lane < batch) {   // lane b finishes sequence b
-                const int b = lane;
-                if (S.nseg > 1) {
-                    float* a = myacc + ((size_t)(pc - S.p0) * B + b) * 4;
+            for (int c = 0; c < NC; c++) {
+                float t[4];
 #pragma unroll
-                    for (int i = 0; i < 4; i++) {
-                        if (S.seg > 0) t[i] += a[i];
-                        if (S.seg < S.nseg - 1) a[i] = t[i];
-                    }
+                for (int i = 0; i < 4; i++) {
+                    float v = acc0[c][i] + acc1[c][i];
+                    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xF, 0xF, true));   // row_ror:8
+                    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xF, 0xF, true));   // row_ror:4
+                    v += __shfl_xor(v, 16);
+                    v += __shfl_xor(v, 32);
+                    t[i] = v;   // row 4*group + i, sequence 4*c + lane % 4
                 }
-                if (S.seg == S.nseg - 1) {
-                    epi(2 * pc, b, t[0], t[1]);
-                    if (4 * pc + 2 < S.N) epi(2 * pc + 1, b, t[2], t[3]);
+                acc0[c] = mfma_f4{0.f, 0.f, 0.f, 0.f};
+                acc1[c] = mfma_f4{0.f, 0.f, 0.f, 0.f};
+                const int b = 4 * c + lane;
+                if (lane < 4 && b < batch) {   // lanes 0..3 finish one sequence each
+                    if (S.nseg > 1) {
+                        float* a = myacc + ((size_t)(pc - S.p0) * B + b) * 4;
+#pragma unroll
+                        for (int i = 0; i < 4; i++) {
+                            if (S.seg > 0) t[i] += a[i];
+                            if (S.seg < S.nseg - 1) a[i] = t[i];
+                        }
+                    }
+                    if (S.seg == S.nseg - 1) {
+                        epi(2 * pc, b, t[0], t[1]);
+                        if (4 * pc + 2 < S.N) epi(2 * pc + 1, b, t[2], t[3]);
+                    }
                 }
             }
         }

@@ -145,7 +145,7 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 // quad-planar fp32 layout of stage_act.  SPLIT form (input of gemv_run_quad): every value v is
 // stored as bf16 head h = v truncated and bf16 remainder of v - h (the pair carries 16 mantissa
 // bits), heads in plane 2b and remainders in plane 2b+1 of nup 16-byte units each, element order as
-// in a weight unit, unit j at index j ^ (b << 2).
+// in a weight unit, unit j at index j ^ ((b & 3) << 2).
 template <int EPU, bool SPLIT>
 __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, const float4& t) {
     constexpr int NQ = EPU / 4;
@@ -160,7 +160,7 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
             h[e] = __float_as_uint(v[e]) & 0xFFFF0000u;
             l[e] = __float_as_uint(v[e] - __uint_as_float(h[e]));
         }
-        const int j = (qi >> 1) ^ (b << 2);
+        const int j = (qi >> 1) ^ ((b & 3) << 2);
         u32x2* ph = (u32x2*)(xs + (size_t)(2 * b) * nup + j) + (qi & 1);
         u32x2* pl = (u32x2*)(xs + (size_t)(2 * b + 1) * nup + j) + (qi & 1);
         *ph = u32x2{(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};

@@ -85,6 +85,13 @@ int check_config(const ff_config* c) {
     return FF_OK;
 }
 
+// Sequences one pass of the fused kernel serves: 8 with bf16 weights when their input rows fit the
+// on-chip buffer together (and the model is created for that many), else up to 4.
+int fused_pass_rows(const ff_config& c) {
+    if (c.wdtype == W_BF16 && c.max_batch > kMaxBatch && (size_t)c.d_model * 4 * kMaxBatchFused <= (size_t)kLdsActBytes) return kMaxBatchFused;
+    return std::min(c.max_batch, kMaxBatch);
+}
+
 Plan make_plan(const ff_config& c) {
     Plan P;
     size_t off = 0;
@@ -106,7 +113,7 @@ Plan make_plan(const ff_config& c) {
     P.packed_bytes = off;
 
     size_t s = 0;
-    size_t mb = std::min(c.max_batch, kMaxBatch);   // exchange buffers hold one pass
+    size_t mb = fused_pass_rows(c);   // exchange buffers hold one pass
     auto take = [&](size_t bytes) { size_t o = s; s = align256(s + bytes); return o; };
     P.x = take(mb * c.d_model * 4);
     P.xn = take(mb * c.d_model * 4);
@@ -276,7 +283,7 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     m->head_loaded = false;
     m->bar_gen = 0;
     m->n_cta = prop.multiProcessorCount;
-    m->lds_bytes = kLdsActBytes + kLdsAuxBytes + kMaxBatch * 64 * sizeof(float2) + 256;
+    m->lds_bytes = kLdsActBytes + kLdsAuxBytes + kMaxBatchFused * 64 * sizeof(float2) + 256;
     if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
 
     DevModel& D = m->dev;
@@ -428,7 +435,7 @@ int ff_kv_free(ff_kv* kv) {
 }
 
 namespace {
-// One pass of the fused kernel over sequences [seq0, seq0 + batch), batch <= kMaxBatch.
+// One pass of the fused kernel over sequences [seq0, seq0 + batch), batch <= fused_pass_rows.
 int fused_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch, int seq0,
                hipStream_t st) {
     const int lm_in_kernel = m->dev.lm.wd == m->cfg.wdtype;
@@ -463,14 +470,15 @@ int fused_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_
 }
 }  // namespace
 
-// Batches above kMaxBatch run as consecutive passes of at most kMaxBatch sequences on the stream
-// (every pass streams the weights again; the exchange buffers are reused pass after pass).
+// Batches above one pass run as consecutive passes on the stream (every pass streams the weights
+// again; the exchange buffers are reused pass after pass).
 int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch,
                    void* stream) {
     int rc = check_step_args(m, tokens_dev, positions_dev, kv, logits_dev, batch);
     if (rc) return rc;
-    for (int s0 = 0; s0 < batch; s0 += kMaxBatch) {
-        rc = fused_pass(m, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(kMaxBatch, batch - s0), s0,
+    const int rows = fused_pass_rows(m->cfg);
+    for (int s0 = 0; s0 < batch; s0 += rows) {
+        rc = fused_pass(m, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(rows, batch - s0), s0,
                         (hipStream_t)stream);
         if (rc) return rc;
     }

@@ -113,8 +113,8 @@ def test_sequences_of_different_lengths_in_one_batch():
 
 
 def test_tiny_batches_above_one_pass():
-    """Batches 5..16 run as passes of four sequences: ragged last pass (5, 7), full passes (8, 16),
-    with bf16 and with int8 weights."""
+    """Batches 5..16: with bf16 weights one pass serves up to eight sequences (5, 7, 8 in one pass,
+    16 in two), with int8 weights four (6 = a full and a ragged pass)."""
     for b in (5, 7, 8, 16):
         _run_teacher_forced(synth.TINY, 40 + b, synth.WDTYPE_BF16, batch=b, T0=24, steps=2)
     _run_teacher_forced(synth.TINY.replace(d_ffn=1408), 61, synth.WDTYPE_INT8, batch=6, T0=24, steps=2)
@@ -201,6 +201,13 @@ def test_llama70b_shaped_layers_batch1_ctx2048():
 def test_llama70b_shaped_one_layer_batch16():
     """Batch 16 at the 70B width (one layer, short context so that the oracle finishes in seconds)."""
     _run_teacher_forced(synth.LLAMA_70B.replace(n_layers=1), 0x250522765, synth.WDTYPE_BF16, batch=16, T0=64, steps=1, gpu_generated=True)
+
+
+def test_llama8b_shaped_one_layer_batch8_single_pass():
+    """Eight sequences in ONE pass at the 8B width (one layer): the matrix-core projections with two
+    sets of four sequences, input rows staged in two groups, the down projection cut into four
+    segments along K, sequences of different lengths."""
+    _run_teacher_forced(synth.LLAMA_8B.replace(n_layers=1), 0x250522766, synth.WDTYPE_BF16, batch=8, T0=96, steps=2, gpu_generated=True)
 
 
 def test_two_models_interleaved_on_a_side_stream():
