@@ -23,7 +23,8 @@ constexpr int kMaxBatchApi = 16;    // sequences one decode step accepts (run as
 constexpr int kMaxSplits = 64;           // max KV splits per (sequence, kv head)
 constexpr int kMinSplitLen = 64;         // do not split the cache finer than this many rows
 constexpr int kLdsActBytes = 128 * 1024; // LDS region holding the staged activation vector(s)
-constexpr int kLdsAuxBytes = 24 * 1024;  // partial sums, reduction scratch
+constexpr int kLdsAuxBytes = 24 * 1024;  // partial sums of earlier K segments (per wave), then kLdsXsumBytes of per-unit input sums
+constexpr int kLdsXsumBytes = 4 * 1024;  // tail of the aux region: sum of every staged 32-element unit (int4 matrix-core path)
 constexpr int kSpinLimit = 1 << 16;
 
 

@@ -170,7 +170,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     const u32 sl = steps_done * (u32)M.L;
 
     const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = ncta * kFusedWaves;
-    float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
+    float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * kAccFloatsPerWave;
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64;   // behind the RoPE rows
     WgVote vote{(u32*)(red + 16), 0u};   // behind the reduction scratch and the positions
     // One iteration = one K segment of one projection; only (phase, segment) are carried from one
@@ -237,7 +237,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (wave == 0) dbg_event(M, ph, EV_SYNCED, lane);
         u64* wv = D.kind < 4 ? dbg_wave_slots(M, n_phases, D.layer, wave) : nullptr;
         if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
-        if constexpr (kQuad) gemv_run_quad<B>(S, ring, xs, myacc, batch, lane, epi);
+        if constexpr (kQuad) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         else gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         asm volatile("" ::"s"(warm));   // keeps the touch alive
         if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
@@ -279,7 +279,7 @@ template <int WD, int HD, int G>
 inline hipError_t launch_fused_family(const FusedLaunch& a, const char** what) {
     if (a.batch == 1) return launch_fused_instance<WD, 1, HD, G>(a, what);
     if (a.batch == 2) return launch_fused_instance<WD, 2, HD, G>(a, what);
-    if constexpr (kQuadOf<WD, kMaxBatchFused>) {
+    if constexpr (WD == W_BF16) {   // eight sequences per pass: bf16 only (fused_pass_rows on the host decides)
         if (a.batch > kMaxBatch) return launch_fused_instance<WD, kMaxBatchFused, HD, G>(a, what);
     }
     return launch_fused_instance<WD, 4, HD, G>(a, what);

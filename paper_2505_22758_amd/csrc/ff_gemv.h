@@ -27,8 +27,12 @@ template <int WD> constexpr int kDepthOf = WD == W_INT4 ? 2 * FF_DEPTH : FF_DEPT
 template <int WD> constexpr int kChunkUnitsOf = 64 * kUnrOf<WD>;   // units of one row covered by one stage of one wave
 // With two or more sequences per pass the bf16 projections run on the matrix cores in groups of
 // four rows (gemv_run_quad below) instead of row pairs on the vector ALUs.
-template <int WD, int B> constexpr bool kQuadOf = WD == W_BF16 && B > 1;
-constexpr int kQuadChunkUnits = 128;   // units of one row covered by one stage of one wave in that mode
+template <int WD, int B> constexpr bool kQuadOf = (WD == W_BF16 || WD == W_INT4) && B > 1;
+template <int WD> constexpr int kQuadLoadsOf = WD == W_INT4 ? 4 : 8;       // 16-byte loads per lane and stage in that mode ...
+template <int WD> constexpr int kQuadChunkUnitsOf = 16 * kQuadLoadsOf<WD>; // ... = units of one row covered by one stage of one wave
+constexpr int kAccFloatsPerWave = (kLdsAuxBytes - kLdsXsumBytes) / 4 / kWaves;   // partial sums a wave can carry between K segments
+// Per-unit input sums of the int4 matrix-core path live at the end of the aux region (xs = start of LDS).
+__device__ __forceinline__ float* xsum_of(const float4* xs) { return (float*)((uint8_t*)xs + kLdsActBytes + kLdsAuxBytes - kLdsXsumBytes); }
 
 // ---------------------------------------------------------------- reductions
 // Sum over the 64 lanes with DPP row operations; the result is wave-uniform.
@@ -229,7 +233,7 @@ struct Stream {
     static constexpr int seg_units = (kLdsActBytes / (B * EPU * 4)) / kChunkUnits * kChunkUnits;
 
     // quad: rows are dealt out in groups of four (p0, my_pairs count groups) and a stage covers
-    // kQuadChunkUnits units of each of the four rows instead of kChunkUnits units of two rows.
+    // kQuadChunkUnitsOf units of each of the four rows instead of kChunkUnits units of two rows.
     __device__ __forceinline__ static Stream make(const PMat& M, int seg, int gwave, int n_gwaves, bool quad = false) {
         Stream S;
         S.w = M.w; S.s = M.s; S.z = M.z; S.N = M.n; S.K = M.k; S.ng = M.k / 128;
@@ -240,7 +244,7 @@ struct Stream {
         S.j0 = seg * seg_units;
         S.nunits = min(seg_units, total_units - S.j0);
         S.nup = (S.nunits + kChunkUnits - 1) / kChunkUnits * kChunkUnits;
-        S.cpr = S.nup / (quad ? kQuadChunkUnits : kChunkUnits);
+        S.cpr = S.nup / (quad ? kQuadChunkUnitsOf<WD> : kChunkUnits);
         // row pairs [p0, p0 + my_pairs) of this wave; the products fit 32 bits (rows * waves < 2^32)
         const u32 npairs = quad ? (u32)(M.n + 3) / 4 : (u32)(M.n + 1) / 2;
         S.p0 = (int)(npairs * (u32)gwave / (u32)n_gwaves);
@@ -279,15 +283,21 @@ __device__ __forceinline__ void load_stage(const Stream<WD, B>& S, int pair, int
 }
 
 // The same for a group of four rows: lane (blk = lane / 4, r = lane % 4) loads unit blk of row r of
-// each of the stage's eight 16-unit slices, i.e. a wave load covers 256 contiguous bytes of four rows.
-template <int B>
-__device__ __forceinline__ void load_stage_quad(const Stream<W_BF16, B>& S, int grp, int chunk, Stage<W_BF16>& st, int lane) {
+// each of the stage's 16-unit slices, i.e. a wave load covers 256 contiguous bytes of four rows.
+template <int WD, int B>
+__device__ __forceinline__ void load_stage_quad(const Stream<WD, B>& S, int grp, int chunk, Stage<WD>& st, int lane) {
+    constexpr int NL = kQuadLoadsOf<WD>, kUnr = kUnrOf<WD>;
     const int row = min(4 * grp + (lane & 3), S.N - 1);
     const uint8_t* rp = S.w + (size_t)row * S.rowb + (size_t)S.j0 * 16;
 #pragma unroll
-    for (int u = 0; u < 8; u++) {
-        const int j = min((chunk * 8 + u) * 16 + (lane >> 2), S.nunits - 1);
-        st.w[u >> 2][u & 3] = ldg_stream(rp + (size_t)j * 16);
+    for (int u = 0; u < NL; u++) {
+        const int j = min((chunk * NL + u) * 16 + (lane >> 2), S.nunits - 1);
+        st.w[u / kUnr][u % kUnr] = ldg_stream(rp + (size_t)j * 16);
+        if constexpr (WD == W_INT4) {
+            const size_t gi = (size_t)row * S.ng + (S.j0 + j) / 4;
+            st.s[u / kUnr][u % kUnr] = as_global(S.s)[gi];
+            st.z[u / kUnr][u % kUnr] = as_global(S.z)[gi];
+        }
     }
 }
 
@@ -439,21 +449,32 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
 // are multiplied.  Unit j of sequence b sits at index (j ^ ((b & 3) << 2)) of its plane, which spreads
 // the four lanes of a block over different LDS banks.  More than four sequences take one
 // accumulator pair per set of four (the weights in registers are reused).
+// Value of lane I of every aligned group of four lanes (DPP quad permute).
+template <int I>
+__device__ __forceinline__ float quad_bcast(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), I * 0x55, 0xF, 0xF, true));
+}
 typedef short mfma_s4 __attribute__((ext_vector_type(4)));
 typedef float mfma_f4 __attribute__((ext_vector_type(4)));
 
-template <int B, class Epi>
-__device__ __forceinline__ void gemv_run_quad(const Stream<W_BF16, B>& S, Stage<W_BF16> (&ring)[kDepthOf<W_BF16>], const float4* xs,
+template <int WD, int B, class Epi>
+__device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs,
                                               float* myacc, int batch, int lane, Epi& epi) {
-    constexpr int kDepth = kDepthOf<W_BF16>;
+    static_assert(WD == W_BF16 || (WD == W_INT4 && B <= 4), "matrix-core path: bf16, or int4 with one set of sequences");
+    constexpr int kDepth = kDepthOf<WD>;
+    constexpr int NL = kQuadLoadsOf<WD>, kUnr = kUnrOf<WD>;
     constexpr int NC = (B + 3) / 4;   // sets of four sequences (one accumulator pair each)
     const int nup = S.nup;
+    const int r4 = lane & 3;
     const u32x4* xh[NC];
 #pragma unroll
     for (int c = 0; c < NC; c++) {
-        const int bl = min(4 * c + (lane & 3), B - 1);   // sequence whose inputs this lane feeds (columns >= B are never read back)
-        xh[c] = (const u32x4*)xs + (size_t)(2 * bl) * nup + ((lane >> 2) ^ ((bl & 3) << 2));
+        const int bl = min(4 * c + r4, B - 1);   // sequence whose inputs this lane feeds (columns >= B are never read back)
+        if constexpr (WD == W_BF16) xh[c] = (const u32x4*)xs + (size_t)(2 * bl) * nup + ((lane >> 2) ^ ((bl & 3) << 2));
+        else xh[c] = (const u32x4*)xs + ((size_t)(2 * bl) * nup + (lane >> 2)) * 4;
     }
+    const int bl0 = min(r4, B - 1);
+    const float* xsum = xsum_of(xs) + (size_t)bl0 * nup + (lane >> 2);   // int4 only
     mfma_f4 acc0[NC], acc1[NC];
 #pragma unroll
     for (int c = 0; c < NC; c++) { acc0[c] = mfma_f4{0.f, 0.f, 0.f, 0.f}; acc1[c] = mfma_f4{0.f, 0.f, 0.f, 0.f}; }
@@ -462,18 +483,50 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<W_BF16, B>& S, Stage<
     for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
 
     auto half = [](u32 a, u32 b) { u32x2 v{a, b}; return __builtin_bit_cast(mfma_s4, v); };
-    auto compute = [&](const Stage<W_BF16>& st) {
+    auto compute = [&](const Stage<WD>& st) {
 #pragma unroll
-        for (int u = 0; u < 8; u++) {
-            const int off = (cc * 8 + u) * 16;
-            const u32x4 w = st.w[u >> 2][u & 3];
+        for (int u = 0; u < NL; u++) {
+            const int off = (cc * NL + u) * 16;
+            const u32x4 w = st.w[u / kUnr][u % kUnr];
+            if constexpr (WD == W_BF16) {
 #pragma unroll
-            for (int c = 0; c < NC; c++) {
-                const u32x4 h = xh[c][off], l = xh[c][off + nup];
-                acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(h.x, h.y), acc0[c], 0, 0, 0);
-                acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(l.x, l.y), acc1[c], 0, 0, 0);
-                acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(h.z, h.w), acc0[c], 0, 0, 0);
-                acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(l.z, l.w), acc1[c], 0, 0, 0);
+                for (int c = 0; c < NC; c++) {
+                    const u32x4 h = xh[c][off], l = xh[c][off + nup];
+                    acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(h.x, h.y), acc0[c], 0, 0, 0);
+                    acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(l.x, l.y), acc1[c], 0, 0, 0);
+                    acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(h.z, h.w), acc0[c], 0, 0, 0);
+                    acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(l.z, l.w), acc1[c], 0, 0, 0);
+                }
+            } else {
+                // int4 group-128: the unit's 32 codes n become the bf16 numbers 128 + n by bit
+                // operations alone (0x4300 | n: exponent 2^7, n in the mantissa), so the blocks
+                // deliver d = sum (128 + n) x, and with X = sum of the unit's x (staged beside it)
+                //   sum s (n - z) x  =  s (d - (128 + z) X).
+                // Scale s and zero z belong to the ROW, which the lanes of a block hold one each:
+                // they are passed round the four lanes with quad permutes.
+                const u32 ww[4] = {w.x, w.y, w.z, w.w};
+                mfma_f4 dh = {0.f, 0.f, 0.f, 0.f}, dl = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < 4; q++) {   // 8 codes = one 16-byte chunk of heads and one of remainders
+                    const u32x4 h = xh[0][(size_t)off * 4 + (q ^ r4)], l = xh[0][((size_t)nup + off) * 4 + (q ^ r4)];
+                    const u32 e = ww[q] & 0x0F0F0F0Fu, o = (ww[q] >> 4) & 0x0F0F0F0Fu;   // codes 0,2,4,6 / 1,3,5,7 as bytes
+                    const u32 a0 = __builtin_amdgcn_perm(o, e, 0x0c040c00u) | 0x43004300u;   // codes 0, 1
+                    const u32 a1 = __builtin_amdgcn_perm(o, e, 0x0c050c01u) | 0x43004300u;   // codes 2, 3
+                    const u32 a2 = __builtin_amdgcn_perm(o, e, 0x0c060c02u) | 0x43004300u;   // codes 4, 5
+                    const u32 a3 = __builtin_amdgcn_perm(o, e, 0x0c070c03u) | 0x43004300u;   // codes 6, 7
+                    dh = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a0, a1), half(h.x, h.y), dh, 0, 0, 0);
+                    dl = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a0, a1), half(l.x, l.y), dl, 0, 0, 0);
+                    dh = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a2, a3), half(h.z, h.w), dh, 0, 0, 0);
+                    dl = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a2, a3), half(l.z, l.w), dl, 0, 0, 0);
+                }
+                const float X = xsum[off];
+                const float sc = f16_to_f((f16_t)st.s[u / kUnr][u % kUnr]);
+                const float zp = 128.f + f16_to_f((f16_t)st.z[u / kUnr][u % kUnr]);
+                // row i of the block: scale and zero held by lane i of the quad
+                acc0[0][0] = fmaf(quad_bcast<0>(sc), fmaf(-quad_bcast<0>(zp), X, dh[0] + dl[0]), acc0[0][0]);
+                acc0[0][1] = fmaf(quad_bcast<1>(sc), fmaf(-quad_bcast<1>(zp), X, dh[1] + dl[1]), acc0[0][1]);
+                acc0[0][2] = fmaf(quad_bcast<2>(sc), fmaf(-quad_bcast<2>(zp), X, dh[2] + dl[2]), acc0[0][2]);
+                acc0[0][3] = fmaf(quad_bcast<3>(sc), fmaf(-quad_bcast<3>(zp), X, dh[3] + dl[3]), acc0[0][3]);
             }
         }
         if (cc == S.cpr - 1) {   // group finished (for this K segment): add up the sixteen blocks
@@ -510,7 +563,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<W_BF16, B>& S, Stage<
         }
         if (++cc == S.cpr) { cc = 0; ++pc; }
     };
-    auto load = [&](Stage<W_BF16>& st) {
+    auto load = [&](Stage<WD>& st) {
         load_stage_quad(S, pl, cl, st, lane);
         if (++cl == S.cpr) { cl = 0; ++pl; }
     };

@@ -66,7 +66,7 @@ __device__ __forceinline__ void op_gemv_body(const PMat& W, const ActSrc& src, i
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int gwave = blockIdx.x * kWaves + wave, n_gwaves = gridDim.x * kWaves;
-    float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * (kLdsAuxBytes / 4 / kWaves);
+    float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * kAccFloatsPerWave;
     Stage<WD> ring[kDepthOf<WD>];
     Stream<WD, B> S = Stream<WD, B>::make(W, 0, gwave, n_gwaves);
     const int nseg = S.nseg;

@@ -144,15 +144,19 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 // Writes quad qi (elements 4*qi .. 4*qi+3) of sequence b into the staged vector.  Plain form: the
 // quad-planar fp32 layout of stage_act.  SPLIT form (input of gemv_run_quad): every value v is
 // stored as bf16 head h = v truncated and bf16 remainder of v - h (the pair carries 16 mantissa
-// bits), heads in plane 2b and remainders in plane 2b+1 of nup 16-byte units each, element order as
-// in a weight unit, unit j at index j ^ ((b & 3) << 2).
+// bits), heads in plane 2b and remainders in plane 2b+1, element order as in a weight unit.
+//   bf16 weights (8 elements = 16 bytes per unit and plane): unit j at index j ^ ((b & 3) << 2);
+//   int4 weights (32 elements = four 16-byte chunks per unit and plane): chunk q of unit j at
+//   index 4 j + (q ^ (b & 3)), and the sum of the unit's 32 values in xsum_of(xs)[b * nup + j].
+// Either way the four lanes of a matrix-core block (same j, sequences 0..3) hit different banks.
+// All lanes of a unit must call together (int4: eight consecutive quads = eight consecutive lanes).
 template <int EPU, bool SPLIT>
 __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, const float4& t) {
     constexpr int NQ = EPU / 4;
     if constexpr (!SPLIT) {
         xs[((size_t)b * NQ + qi % NQ) * nup + qi / NQ] = t;
     } else {
-        static_assert(EPU == 8, "bf16 weights only");
+        static_assert(EPU == 8 || EPU == 32, "bf16 or int4 weights");
         const float v[4] = {t.x, t.y, t.z, t.w};
         u32 h[4], l[4];
 #pragma unroll
@@ -160,9 +164,22 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
             h[e] = __float_as_uint(v[e]) & 0xFFFF0000u;
             l[e] = __float_as_uint(v[e] - __uint_as_float(h[e]));
         }
-        const int j = (qi >> 1) ^ ((b & 3) << 2);
-        u32x2* ph = (u32x2*)(xs + (size_t)(2 * b) * nup + j) + (qi & 1);
-        u32x2* pl = (u32x2*)(xs + (size_t)(2 * b + 1) * nup + j) + (qi & 1);
+        u32x2 *ph, *pl;
+        if constexpr (EPU == 8) {
+            const int j = (qi >> 1) ^ ((b & 3) << 2);
+            ph = (u32x2*)(xs + (size_t)(2 * b) * nup + j) + (qi & 1);
+            pl = (u32x2*)(xs + (size_t)(2 * b + 1) * nup + j) + (qi & 1);
+        } else {
+            const int j = qi >> 3, q = ((qi >> 1) & 3) ^ (b & 3);
+            ph = (u32x2*)(xs + ((size_t)(2 * b) * nup + j) * 4 + q) + (qi & 1);
+            pl = (u32x2*)(xs + ((size_t)(2 * b + 1) * nup + j) * 4 + q) + (qi & 1);
+            // the sum of the values as the matrix cores will see them (head + stored remainder)
+            float hv[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) hv[e] = __uint_as_float(h[e]) + __uint_as_float(l[e] & 0xFFFF0000u);
+            const float us = group_sum<8>((hv[0] + hv[1]) + (hv[2] + hv[3]));
+            if ((qi & 7) == 0) xsum_of(xs)[(size_t)b * nup + j] = us;
+        }
         *ph = u32x2{(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
         *pl = u32x2{(l[0] >> 16) | (l[1] & 0xFFFF0000u), (l[2] >> 16) | (l[3] & 0xFFFF0000u)};
     }

@@ -157,6 +157,8 @@ def test_tiny_shaped_int8_and_int4_steps():
     for wd in (synth.WDTYPE_INT8, synth.WDTYPE_INT4):
         _run_teacher_forced(S, 40 + wd, wd, batch=1, T0=70, steps=4)
         _run_teacher_forced(S, 50 + wd, wd, batch=4, T0=33, steps=2)
+        _run_teacher_forced(S, 60 + wd, wd, batch=2, T0=21, steps=2)
+        _run_teacher_forced(S, 70 + wd, wd, batch=3, T0=45, steps=2)
 
 
 def test_out_of_range_position_is_reported_and_skipped():
