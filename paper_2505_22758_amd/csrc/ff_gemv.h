@@ -25,9 +25,9 @@ template <int WD> constexpr int kUnrOf = WD == W_INT4 ? 2 : 4;
 #endif
 template <int WD> constexpr int kDepthOf = WD == W_INT4 ? 2 * FF_DEPTH : FF_DEPTH;
 template <int WD> constexpr int kChunkUnitsOf = 64 * kUnrOf<WD>;   // units of one row covered by one stage of one wave
-// With two or more sequences per pass the bf16 projections run on the matrix cores in groups of
-// four rows (gemv_run_quad below) instead of row pairs on the vector ALUs.
-template <int WD, int B> constexpr bool kQuadOf = (WD == W_BF16 || WD == W_INT4) && B > 1;
+// With two or more sequences per pass the projections run on the matrix cores in groups of four
+// rows (gemv_run_quad below) instead of row pairs on the vector ALUs.
+template <int WD, int B> constexpr bool kQuadOf = B > 1;
 template <int WD> constexpr int kQuadLoadsOf = WD == W_INT4 ? 4 : 8;       // 16-byte loads per lane and stage in that mode ...
 template <int WD> constexpr int kQuadChunkUnitsOf = 16 * kQuadLoadsOf<WD>; // ... = units of one row covered by one stage of one wave
 constexpr int kAccFloatsPerWave = (kLdsAuxBytes - kLdsXsumBytes) / 4 / kWaves;   // partial sums a wave can carry between K segments
@@ -299,6 +299,9 @@ __device__ __forceinline__ void load_stage_quad(const Stream<WD, B>& S, int grp,
             st.z[u / kUnr][u % kUnr] = as_global(S.z)[gi];
         }
     }
+    if constexpr (WD == W_INT8) {
+        if (chunk == S.cpr - 1) st.rs[0] = as_global(S.s)[row];   // this lane's row
+    }
 }
 
 // Issue the first min(kDepth, n_it) iterations of a stream into the ring; returns how many.
@@ -460,7 +463,7 @@ typedef float mfma_f4 __attribute__((ext_vector_type(4)));
 template <int WD, int B, class Epi>
 __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs,
                                               float* myacc, int batch, int lane, Epi& epi) {
-    static_assert(WD == W_BF16 || (WD == W_INT4 && B <= 4), "matrix-core path: bf16, or int4 with one set of sequences");
+    static_assert(WD == W_BF16 || B <= 4, "more than one set of four sequences: bf16 only");
     constexpr int kDepth = kDepthOf<WD>;
     constexpr int NL = kQuadLoadsOf<WD>, kUnr = kUnrOf<WD>;
     constexpr int NC = (B + 3) / 4;   // sets of four sequences (one accumulator pair each)
@@ -471,6 +474,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
     for (int c = 0; c < NC; c++) {
         const int bl = min(4 * c + r4, B - 1);   // sequence whose inputs this lane feeds (columns >= B are never read back)
         if constexpr (WD == W_BF16) xh[c] = (const u32x4*)xs + (size_t)(2 * bl) * nup + ((lane >> 2) ^ ((bl & 3) << 2));
+        else if constexpr (WD == W_INT8) xh[c] = (const u32x4*)xs + ((size_t)(2 * bl) * nup + ((lane >> 2) ^ ((bl & 2) << 1))) * 2;
         else xh[c] = (const u32x4*)xs + ((size_t)(2 * bl) * nup + (lane >> 2)) * 4;
     }
     const int bl0 = min(r4, B - 1);
@@ -496,6 +500,27 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
                     acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(l.x, l.y), acc1[c], 0, 0, 0);
                     acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(h.z, h.w), acc0[c], 0, 0, 0);
                     acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(l.z, l.w), acc1[c], 0, 0, 0);
+                }
+            } else if constexpr (WD == W_INT8) {
+                // int8 per-channel: a signed byte is exact in bf16 (8 significant bits), so the
+                // unit's 16 codes are converted (sign-extending byte conversion, then the upper
+                // halves of two floats packed into one register) and multiplied like bf16
+                // weights; the row scale is applied to the finished sums.
+                const u32 ww[4] = {w.x, w.y, w.z, w.w};
+                auto pack = [](float lo, float hi) { return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u); };
+#pragma unroll
+                for (int q = 0; q < 2; q++) {   // 8 codes = one 16-byte chunk of heads and one of remainders
+                    const int qq = q ^ (bl0 & 1);
+                    const u32x4 h = xh[0][(size_t)off * 2 + qq], l = xh[0][((size_t)nup + off) * 2 + qq];
+                    const u32 wa = ww[2 * q], wb = ww[2 * q + 1];
+                    const u32 a0 = pack((float)(int)(int8_t)wa, (float)(int)(int8_t)(wa >> 8));
+                    const u32 a1 = pack((float)(int)(int8_t)(wa >> 16), (float)((int)wa >> 24));
+                    const u32 a2 = pack((float)(int)(int8_t)wb, (float)(int)(int8_t)(wb >> 8));
+                    const u32 a3 = pack((float)(int)(int8_t)(wb >> 16), (float)((int)wb >> 24));
+                    acc0[0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a0, a1), half(h.x, h.y), acc0[0], 0, 0, 0);
+                    acc1[0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a0, a1), half(l.x, l.y), acc1[0], 0, 0, 0);
+                    acc0[0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a2, a3), half(h.z, h.w), acc0[0], 0, 0, 0);
+                    acc1[0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a2, a3), half(l.z, l.w), acc1[0], 0, 0, 0);
                 }
             } else {
                 // int4 group-128: the unit's 32 codes n become the bf16 numbers 128 + n by bit
@@ -541,6 +566,10 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
                     v += __shfl_xor(v, 16);
                     v += __shfl_xor(v, 32);
                     t[i] = v;   // row 4*group + i, sequence 4*c + lane % 4
+                }
+                if constexpr (WD == W_INT8) {   // row scales: lane r of a quad holds that of row r
+                    const float rs = f16_to_f((f16_t)st.rs[0]);
+                    t[0] *= quad_bcast<0>(rs); t[1] *= quad_bcast<1>(rs); t[2] *= quad_bcast<2>(rs); t[3] *= quad_bcast<3>(rs);
                 }
                 acc0[c] = mfma_f4{0.f, 0.f, 0.f, 0.f};
                 acc1[c] = mfma_f4{0.f, 0.f, 0.f, 0.f};

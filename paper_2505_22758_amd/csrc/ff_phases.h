@@ -146,6 +146,8 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 // stored as bf16 head h = v truncated and bf16 remainder of v - h (the pair carries 16 mantissa
 // bits), heads in plane 2b and remainders in plane 2b+1, element order as in a weight unit.
 //   bf16 weights (8 elements = 16 bytes per unit and plane): unit j at index j ^ ((b & 3) << 2);
+//   int8 weights (16 elements = two 16-byte chunks): chunk q of unit j at index
+//   2 (j ^ ((b & 2) << 1)) + (q ^ (b & 1));
 //   int4 weights (32 elements = four 16-byte chunks per unit and plane): chunk q of unit j at
 //   index 4 j + (q ^ (b & 3)), and the sum of the unit's 32 values in xsum_of(xs)[b * nup + j].
 // Either way the four lanes of a matrix-core block (same j, sequences 0..3) hit different banks.
@@ -156,7 +158,7 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
     if constexpr (!SPLIT) {
         xs[((size_t)b * NQ + qi % NQ) * nup + qi / NQ] = t;
     } else {
-        static_assert(EPU == 8 || EPU == 32, "bf16 or int4 weights");
+        static_assert(EPU == 8 || EPU == 16 || EPU == 32, "bf16, int8 or int4 weights");
         const float v[4] = {t.x, t.y, t.z, t.w};
         u32 h[4], l[4];
 #pragma unroll
@@ -169,6 +171,10 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
             const int j = (qi >> 1) ^ ((b & 3) << 2);
             ph = (u32x2*)(xs + (size_t)(2 * b) * nup + j) + (qi & 1);
             pl = (u32x2*)(xs + (size_t)(2 * b + 1) * nup + j) + (qi & 1);
+        } else if constexpr (EPU == 16) {
+            const int j = (qi >> 2) ^ ((b & 2) << 1), q = ((qi >> 1) & 1) ^ (b & 1);
+            ph = (u32x2*)(xs + ((size_t)(2 * b) * nup + j) * 2 + q) + (qi & 1);
+            pl = (u32x2*)(xs + ((size_t)(2 * b + 1) * nup + j) * 2 + q) + (qi & 1);
         } else {
             const int j = qi >> 3, q = ((qi >> 1) & 3) ^ (b & 3);
             ph = (u32x2*)(xs + ((size_t)(2 * b) * nup + j) * 4 + q) + (qi & 1);

@@ -76,10 +76,10 @@ int check_config(const ff_config* c) {
     // the row partition among waves is computed in 32 bits: (rows / 2) * (waves in the grid) < 2^32
     if (c->vocab > (1 << 21) || c->d_ffn > (1 << 20) || c->d_model > (1 << 20) || qd > (1 << 20))
         return fail(FF_ERR_UNSUPPORTED, "matrix with more than 2^21 rows");
-    // with two or more sequences per pass the bf16 and int4 kernels (matrix-core projections)
-    // normalise a row in a single staging pass (8 quads per thread)
-    if (c->wdtype != W_INT8 && c->max_batch > 1 && c->d_model > 8192)
-        return fail(FF_ERR_UNSUPPORTED, "d_model %d > 8192 with max_batch > 1 is not supported for bf16 and int4 weights", c->d_model);
+    // with two or more sequences per pass (matrix-core projections) a row is normalised in a
+    // single staging pass (8 quads per thread)
+    if (c->max_batch > 1 && c->d_model > 8192)
+        return fail(FF_ERR_UNSUPPORTED, "d_model %d > 8192 with max_batch > 1 is not supported", c->d_model);
     if ((size_t)c->d_model * 4 * std::min(c->max_batch, kMaxBatch) > (size_t)kLdsActBytes)
         return fail(FF_ERR_UNSUPPORTED, "d_model %d x max_batch %d does not fit the on-chip input buffer (RMSNorm needs the whole row)", c->d_model, c->max_batch);
     return FF_OK;
