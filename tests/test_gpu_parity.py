@@ -212,6 +212,16 @@ def test_llama8b_shaped_one_layer_batch8_single_pass():
     _run_teacher_forced(synth.LLAMA_8B.replace(n_layers=1), 0x250522766, synth.WDTYPE_BF16, batch=8, T0=96, steps=2, gpu_generated=True)
 
 
+def test_llama8b_shaped_one_layer_quantised_batches():
+    """The matrix-core projections for int8 and int4 weights at the 8B width (one layer): the down
+    projection's 14336-column input staged in one long pass (batch 2) and in two K segments
+    (batch 4), several chunks per row group."""
+    S = synth.LLAMA_8B.replace(n_layers=1)
+    _run_teacher_forced(S, 0x250522767, synth.WDTYPE_INT8, batch=2, T0=80, steps=1, gpu_generated=True)
+    _run_teacher_forced(S, 0x250522768, synth.WDTYPE_INT8, batch=4, T0=70, steps=1, gpu_generated=True)
+    _run_teacher_forced(S, 0x250522769, synth.WDTYPE_INT4, batch=2, T0=90, steps=1, gpu_generated=True)
+
+
 def test_two_models_interleaved_on_a_side_stream():
     """Two models of different geometry (head_dim 64 vs 128, bf16 vs int8) alive at once and stepped
     alternately on a non-default stream: no state is shared between models, and a model's result does
