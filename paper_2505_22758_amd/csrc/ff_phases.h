@@ -143,8 +143,8 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 
 // Writes quad qi (elements 4*qi .. 4*qi+3) of sequence b into the staged vector.  Plain form: the
 // quad-planar fp32 layout of stage_act.  SPLIT form (input of gemv_run_quad): every value v is
-// stored as bf16 head h = v truncated and bf16 remainder of v - h (the pair carries 16 mantissa
-// bits), heads in plane 2b and remainders in plane 2b+1, element order as in a weight unit.
+// stored as bf16 head h = v rounded to nearest and bf16 remainder = v - h truncated (the pair carries
+// 16 mantissa bits), heads in plane 2b and remainders in plane 2b+1, element order as in a weight unit.
 //   bf16 weights (8 elements = 16 bytes per unit and plane): unit j at index j ^ ((b & 3) << 2);
 //   int8 weights (16 elements = two 16-byte chunks): chunk q of unit j at index
 //   2 (j ^ ((b & 2) << 1)) + (q ^ (b & 1));
@@ -163,8 +163,8 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
         u32 h[4], l[4];
 #pragma unroll
         for (int e = 0; e < 4; e++) {
-            h[e] = __float_as_uint(v[e]) & 0xFFFF0000u;
-            l[e] = __float_as_uint(v[e] - __uint_as_float(h[e]));
+            h[e] = (__float_as_uint(v[e]) + 0x8000u) & 0xFFFF0000u;   // nearest (ties away): the remainder's sign is random,
+            l[e] = __float_as_uint(v[e] - __uint_as_float(h[e]));     // so truncating it below leaves no bias
         }
         u32x2 *ph, *pl;
         if constexpr (EPU == 8) {
