@@ -25,6 +25,10 @@ constexpr int kMinSplitLen = 64;         // do not split the cache finer than th
 constexpr int kLdsActBytes = 128 * 1024; // LDS region holding the staged activation vector(s)
 constexpr int kLdsAuxBytes = 24 * 1024;  // partial sums of earlier K segments (per wave), then kLdsXsumBytes of per-unit input sums
 constexpr int kLdsXsumBytes = 4 * 1024;  // tail of the aux region: sum of every staged 32-element unit (int4 matrix-core path)
+constexpr int kLdsRopeBytes = 8 * 64 * 8;   // behind the aux region: (cos, sin) rows of up to 8 sequences
+constexpr int kLdsMiscBytes = 256;          // then: reduction scratch, positions, vote slots
+constexpr int kLdsPairBytes = 1024;         // then: mailboxes of wave pairs that share a row group (gemv_run_quad)
+constexpr int kLdsFusedBytes = kLdsActBytes + kLdsAuxBytes + kLdsRopeBytes + kLdsMiscBytes + kLdsPairBytes;
 constexpr int kSpinLimit = 1 << 16;
 
 

@@ -33,6 +33,13 @@ template <int WD> constexpr int kQuadChunkUnitsOf = 16 * kQuadLoadsOf<WD>; // ..
 constexpr int kAccFloatsPerWave = (kLdsAuxBytes - kLdsXsumBytes) / 4 / kWaves;   // partial sums a wave can carry between K segments
 // Per-unit input sums of the int4 matrix-core path live at the end of the aux region (xs = start of LDS).
 __device__ __forceinline__ float* xsum_of(const float4* xs) { return (float*)((uint8_t*)xs + kLdsActBytes + kLdsAuxBytes - kLdsXsumBytes); }
+// Mailboxes of the wave pairs (0,1) and (2,3) of a workgroup: [pair][side][16 x 8 floats], then one flag word per pair.
+typedef __attribute__((address_space(3))) float lds_float;
+typedef __attribute__((address_space(3))) u32 lds_u32;
+__device__ __forceinline__ lds_float* pairbox_of(const float4* xs) {
+    return (lds_float*)((uint8_t*)xs + kLdsActBytes + kLdsAuxBytes + kLdsRopeBytes + kLdsMiscBytes);
+}
+constexpr int kPairBoxFloats = 32;   // per (pair, side): 4 rows x 8 sequences
 
 // ---------------------------------------------------------------- reductions
 // Sum over the 64 lanes with DPP row operations; the result is wave-uniform.
@@ -226,7 +233,7 @@ struct Stream {
     size_t rowb;
     int N, K, ng;
     int nseg, seg, j0, nunits, cpr, nup;
-    int p0, my_pairs, n_it;
+    int p0, c0, n_it;   // first row pair (or group) and first chunk of it, iterations
 
     static constexpr int EPU = WTraits<WD>::EPU;
     static constexpr int kChunkUnits = kChunkUnitsOf<WD>;
@@ -245,11 +252,22 @@ struct Stream {
         S.nunits = min(seg_units, total_units - S.j0);
         S.nup = (S.nunits + kChunkUnits - 1) / kChunkUnits * kChunkUnits;
         S.cpr = S.nup / (quad ? kQuadChunkUnitsOf<WD> : kChunkUnits);
-        // row pairs [p0, p0 + my_pairs) of this wave; the products fit 32 bits (rows * waves < 2^32)
+        // row pairs (groups) [p0, p1) of this wave; the products fit 32 bits (rows * waves < 2^32)
         const u32 npairs = quad ? (u32)(M.n + 3) / 4 : (u32)(M.n + 1) / 2;
         S.p0 = (int)(npairs * (u32)gwave / (u32)n_gwaves);
-        S.my_pairs = (int)(npairs * (u32)(gwave + 1) / (u32)n_gwaves) - S.p0;
-        S.n_it = S.my_pairs * S.cpr;
+        S.c0 = 0;
+        S.n_it = ((int)(npairs * (u32)(gwave + 1) / (u32)n_gwaves) - S.p0) * S.cpr;
+        // Groups of four rows that come out as an odd number of HALF groups per wave (the 8B QKV
+        // projection: 1.5) are dealt out in halves along K instead: the wave's work is the flat
+        // range [gwave * h, (gwave + 1) * h) of (group, chunk) iterations, h = chunks per wave, so
+        // an odd wave starts in the middle of the group its even neighbour (same workgroup)
+        // began; the two exchange their partial sums through LDS (gemv_run_quad).
+        if (quad && S.nseg == 1 && (S.cpr & 1) == 0 && (2 * npairs) % (u32)n_gwaves == 0 && ((2 * npairs / (u32)n_gwaves) & 1)) {
+            const int h = (int)(2 * npairs / (u32)n_gwaves) * (S.cpr / 2);
+            S.p0 = gwave * h / S.cpr;
+            S.c0 = gwave * h % S.cpr;
+            S.n_it = h;
+        }
         return S;
     }
 };
@@ -300,7 +318,7 @@ __device__ __forceinline__ void load_stage_quad(const Stream<WD, B>& S, int grp,
         }
     }
     if constexpr (WD == W_INT8) {
-        if (chunk == S.cpr - 1) st.rs[0] = as_global(S.s)[row];   // this lane's row
+        st.rs[0] = as_global(S.s)[row];   // this lane's row (every stage: a wave may end in the middle of a group)
     }
 }
 
@@ -308,7 +326,7 @@ __device__ __forceinline__ void load_stage_quad(const Stream<WD, B>& S, int grp,
 template <bool QUAD, int WD, int B>
 __device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], int lane) {
     constexpr int kDepth = kDepthOf<WD>;
-    int pair = S.p0, chunk = 0, n = 0;
+    int pair = S.p0, chunk = S.c0, n = 0;
 #pragma unroll
     for (int s = 0; s < kDepth; s++) {
         if (s < S.n_it) {
@@ -482,12 +500,12 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
     mfma_f4 acc0[NC], acc1[NC];
 #pragma unroll
     for (int c = 0; c < NC; c++) { acc0[c] = mfma_f4{0.f, 0.f, 0.f, 0.f}; acc1[c] = mfma_f4{0.f, 0.f, 0.f, 0.f}; }
-    int pc = S.p0, cc = 0;          // (group, chunk) of the next compute
-    int pl = S.p0, cl = 0;          // (group, chunk) of the next load = iteration kDepth
+    int pc = S.p0, cc = S.c0;       // (group, chunk) of the next compute
+    int pl = S.p0, cl = S.c0;       // (group, chunk) of the next load = iteration kDepth
     for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
 
     auto half = [](u32 a, u32 b) { u32x2 v{a, b}; return __builtin_bit_cast(mfma_s4, v); };
-    auto compute = [&](const Stage<WD>& st) {
+    auto compute = [&](const Stage<WD>& st, bool last) {
 #pragma unroll
         for (int u = 0; u < NL; u++) {
             const int off = (cc * NL + u) * 16;
@@ -554,10 +572,10 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
                 acc0[0][3] = fmaf(quad_bcast<3>(sc), fmaf(-quad_bcast<3>(zp), X, dh[3] + dl[3]), acc0[0][3]);
             }
         }
-        if (cc == S.cpr - 1) {   // group finished (for this K segment): add up the sixteen blocks
+        if (cc == S.cpr - 1 || last) {   // group finished (for this K segment, or this wave's part of it): add up the sixteen blocks
+            float t[NC][4];
 #pragma unroll
             for (int c = 0; c < NC; c++) {
-                float t[4];
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
                     float v = acc0[c][i] + acc1[c][i];
@@ -565,27 +583,65 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
                     v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xF, 0xF, true));   // row_ror:4
                     v += __shfl_xor(v, 16);
                     v += __shfl_xor(v, 32);
-                    t[i] = v;   // row 4*group + i, sequence 4*c + lane % 4
+                    t[c][i] = v;   // row 4*group + i, sequence 4*c + lane % 4
                 }
                 if constexpr (WD == W_INT8) {   // row scales: lane r of a quad holds that of row r
                     const float rs = f16_to_f((f16_t)st.rs[0]);
-                    t[0] *= quad_bcast<0>(rs); t[1] *= quad_bcast<1>(rs); t[2] *= quad_bcast<2>(rs); t[3] *= quad_bcast<3>(rs);
+                    t[c][0] *= quad_bcast<0>(rs); t[c][1] *= quad_bcast<1>(rs); t[c][2] *= quad_bcast<2>(rs); t[c][3] *= quad_bcast<3>(rs);
                 }
                 acc0[c] = mfma_f4{0.f, 0.f, 0.f, 0.f};
                 acc1[c] = mfma_f4{0.f, 0.f, 0.f, 0.f};
+            }
+            // A group shared with the neighbouring wave (see Stream::make): each of the two drops
+            // its sums into its side of the pair's mailbox and then bumps the pair's flag; the
+            // one that finds the flag already bumped adds the other's sums and finishes the rows.
+            // LDS executes a wave's operations in order, so the sums are in place before the flag
+            // moves; nobody waits for anybody.
+            const bool ended_early = cc != S.cpr - 1, started_late = pc == S.p0 && S.c0 != 0;
+            bool finish = true;
+            if (ended_early || started_late) {
+                const int pair = (int)(threadIdx.x >> 7), side = ended_early ? 0 : 1;
+                lds_float* box = pairbox_of(xs);
+                lds_u32* flag = (lds_u32*)(box + 4 * kPairBoxFloats) + pair;
+                lds_float* mine = box + (pair * 2 + side) * kPairBoxFloats;
+                lds_float* other = box + (pair * 2 + (1 - side)) * kPairBoxFloats;
+                if (lane < 4) {
+#pragma unroll
+                    for (int c = 0; c < NC; c++)
+#pragma unroll
+                        for (int i = 0; i < 4; i++) mine[(c * 4 + lane) * 4 + i] = t[c][i];
+                }
+                asm volatile("" ::: "memory");
+                u32 seen = 0;
+                if (lane == 0) seen = __hip_atomic_fetch_add(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                seen = (u32)__builtin_amdgcn_readfirstlane((int)seen);
+                asm volatile("" ::: "memory");
+                finish = seen != 0;
+                if (finish) {
+                    if (lane < 4) {
+#pragma unroll
+                        for (int c = 0; c < NC; c++)
+#pragma unroll
+                            for (int i = 0; i < 4; i++) t[c][i] += other[(c * 4 + lane) * 4 + i];
+                    }
+                    if (lane == 0) *flag = 0u;   // next use: a later projection, behind workgroup barriers
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < NC; c++) {
                 const int b = 4 * c + lane;
-                if (lane < 4 && b < batch) {   // lanes 0..3 finish one sequence each
+                if (finish && lane < 4 && b < batch) {   // lanes 0..3 finish one sequence each
                     if (S.nseg > 1) {
                         float* a = myacc + ((size_t)(pc - S.p0) * B + b) * 4;
 #pragma unroll
                         for (int i = 0; i < 4; i++) {
-                            if (S.seg > 0) t[i] += a[i];
-                            if (S.seg < S.nseg - 1) a[i] = t[i];
+                            if (S.seg > 0) t[c][i] += a[i];
+                            if (S.seg < S.nseg - 1) a[i] = t[c][i];
                         }
                     }
                     if (S.seg == S.nseg - 1) {
-                        epi(2 * pc, b, t[0], t[1]);
-                        if (4 * pc + 2 < S.N) epi(2 * pc + 1, b, t[2], t[3]);
+                        epi(2 * pc, b, t[c][0], t[c][1]);
+                        if (4 * pc + 2 < S.N) epi(2 * pc + 1, b, t[c][2], t[c][3]);
                     }
                 }
             }
@@ -600,7 +656,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
     for (; it + 2 * kDepth <= S.n_it; it += kDepth) {
 #pragma unroll
         for (int s = 0; s < kDepth; s++) {
-            compute(ring[s]);
+            compute(ring[s], false);
             __builtin_amdgcn_sched_barrier(0);
             load(ring[s]);
             __builtin_amdgcn_sched_barrier(0);
@@ -610,7 +666,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
 #pragma unroll
         for (int s = 0; s < kDepth; s++) {
             if (it + s < S.n_it) {
-                compute(ring[s]);
+                compute(ring[s], it + s == S.n_it - 1);
                 __builtin_amdgcn_sched_barrier(0);
                 if (it + s + kDepth < S.n_it) load(ring[s]);
                 __builtin_amdgcn_sched_barrier(0);

@@ -283,7 +283,7 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     m->head_loaded = false;
     m->bar_gen = 0;
     m->n_cta = prop.multiProcessorCount;
-    m->lds_bytes = kLdsActBytes + kLdsAuxBytes + kMaxBatchFused * 64 * sizeof(float2) + 256;
+    m->lds_bytes = kLdsFusedBytes;
     if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
 
     DevModel& D = m->dev;
