@@ -367,16 +367,31 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
             }
             float ss[RB];   // only meaningful if the vote passes
             bool mine = true;
+            // With a single row in flight the lane first ORs the counter mismatches of all its
+            // words together (one operation per word) and looks at single quads only if something
+            // is stale; with several rows that form needs more registers than there are beside
+            // the weight tiles (it spills), so they test quad by quad.
+            u32 dirty = 0;
+            if constexpr (RB == 1) {
+#pragma unroll
+                for (int u = 0; u < QB; u++) {
+                    dirty |= (v[0][u].x ^ S.tag) | (v[0][u].y ^ S.tag) | (v[0][u].z ^ S.tag) | (v[0][u].w ^ S.tag);
+                    if constexpr (HAS_ADD) dirty |= (a[0][u].x ^ S.add_tag) | (a[0][u].y ^ S.add_tag) | (a[0][u].z ^ S.add_tag) | (a[0][u].w ^ S.add_tag);
+                }
+                dirty &= 15u;
+            }
 #pragma unroll
             for (int r = 0; r < RB; r++) {
                 stale[r] = 0;
                 ss[r] = 0.f;
 #pragma unroll
                 for (int u = 0; u < QB; u++) {
-                    bool ok = cfresh(v[r][u].x, S.tag) && cfresh(v[r][u].y, S.tag) && cfresh(v[r][u].z, S.tag) && cfresh(v[r][u].w, S.tag);
-                    if constexpr (HAS_ADD)
-                        ok = ok && cfresh(a[r][u].x, S.add_tag) && cfresh(a[r][u].y, S.add_tag) && cfresh(a[r][u].z, S.add_tag) && cfresh(a[r][u].w, S.add_tag);
-                    if (!ok) stale[r] |= 1u << u;
+                    if (RB > 1 || dirty) {
+                        bool ok = cfresh(v[r][u].x, S.tag) && cfresh(v[r][u].y, S.tag) && cfresh(v[r][u].z, S.tag) && cfresh(v[r][u].w, S.tag);
+                        if constexpr (HAS_ADD)
+                            ok = ok && cfresh(a[r][u].x, S.add_tag) && cfresh(a[r][u].y, S.add_tag) && cfresh(a[r][u].z, S.add_tag) && cfresh(a[r][u].w, S.add_tag);
+                        if (!ok) stale[r] |= 1u << u;
+                    }
                     if constexpr (HAS_GAIN) {
                         float4 t = make_float4(cvalue(v[r][u].x), cvalue(v[r][u].y), cvalue(v[r][u].z), cvalue(v[r][u].w));
                         if constexpr (HAS_ADD) { t.x += cvalue(a[r][u].x); t.y += cvalue(a[r][u].y); t.z += cvalue(a[r][u].z); t.w += cvalue(a[r][u].w); }
