@@ -87,7 +87,10 @@ int ff_model_bytes(const ff_config *cfg, size_t *packed_bytes, size_t *scratch_b
 /* Creates a model over caller-owned device buffers (contents of packed_dev undefined until the
  * load calls below have run; scratch_dev is cleared here on `stream`).  FF_ERR_NOMEM if a buffer
  * is smaller than ff_model_bytes reports, FF_ERR_UNSUPPORTED for dimensions without a kernel
- * instance (head_dim must be 64 or 128, n_q_heads/n_kv_heads in {1,2,4,8}, d_model % 8 == 0 ...). */
+ * instance: (head_dim, n_q_heads / n_kv_heads) must be (64, 4), (128, 4) or (128, 8); d_model,
+ * n_q_heads * head_dim and d_ffn multiples of 8 (bf16), 16 (int8) or 128 (int4);
+ * d_model * 4 bytes * min(max_batch, 4) <= 128 KiB (a normalised input row is held on chip whole);
+ * d_model <= 8192 when max_batch > 1. */
 int ff_model_create(const ff_config *cfg, void *packed_dev, size_t packed_bytes, void *scratch_dev,
                     size_t scratch_bytes, void *stream, ff_model **out);
 
