@@ -506,10 +506,28 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
 
     auto half = [](u32 a, u32 b) { u32x2 v{a, b}; return __builtin_bit_cast(mfma_s4, v); };
     auto compute = [&](const Stage<WD>& st, bool last) {
+        // int4: the staged inputs of unit u+1 are requested from LDS before unit u is multiplied
+        // (with one wave per SIMD nothing else hides the LDS latency, and a unit needs nine reads)
+        u32x4 hx[2][4], lx[2][4];
+        float Xs[2];
+        auto fetch = [&](int u, int slot) {
+            const size_t off = (size_t)(cc * NL + u) * 16;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                hx[slot][q] = xh[0][off * 4 + (q ^ r4)];
+                lx[slot][q] = xh[0][((size_t)nup + off) * 4 + (q ^ r4)];
+            }
+            Xs[slot] = xsum[off];
+        };
+        if constexpr (WD == W_INT4) fetch(0, 0);
 #pragma unroll
         for (int u = 0; u < NL; u++) {
             const int off = (cc * NL + u) * 16;
             const u32x4 w = st.w[u / kUnr][u % kUnr];
+            if constexpr (WD == W_INT4) {
+                if (u + 1 < NL) fetch(u + 1, (u + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if constexpr (WD == W_BF16) {
 #pragma unroll
                 for (int c = 0; c < NC; c++) {
@@ -551,7 +569,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
                 mfma_f4 dh = {0.f, 0.f, 0.f, 0.f}, dl = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int q = 0; q < 4; q++) {   // 8 codes = one 16-byte chunk of heads and one of remainders
-                    const u32x4 h = xh[0][(size_t)off * 4 + (q ^ r4)], l = xh[0][((size_t)nup + off) * 4 + (q ^ r4)];
+                    const u32x4 h = hx[u & 1][q], l = lx[u & 1][q];
                     const u32 e = ww[q] & 0x0F0F0F0Fu, o = (ww[q] >> 4) & 0x0F0F0F0Fu;   // codes 0,2,4,6 / 1,3,5,7 as bytes
                     const u32 a0 = __builtin_amdgcn_perm(o, e, 0x0c040c00u) | 0x43004300u;   // codes 0, 1
                     const u32 a1 = __builtin_amdgcn_perm(o, e, 0x0c050c01u) | 0x43004300u;   // codes 2, 3
@@ -562,7 +580,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
                     dh = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a2, a3), half(h.z, h.w), dh, 0, 0, 0);
                     dl = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(a2, a3), half(l.z, l.w), dl, 0, 0, 0);
                 }
-                const float X = xsum[off];
+                const float X = Xs[u & 1];
                 const float sc = f16_to_f((f16_t)st.s[u / kUnr][u % kUnr]);
                 const float zp = 128.f + f16_to_f((f16_t)st.z[u / kUnr][u % kUnr]);
                 // row i of the block: scale and zero held by lane i of the quad
