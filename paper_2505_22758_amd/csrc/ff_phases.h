@@ -2,6 +2,7 @@
 // device functions used by the fused kernel (ordered by tagged dataflow) and, with launch
 // boundaries as the ordering, by the per-operation baseline kernels.
 #pragma once
+#include <type_traits>
 #include "ff_gemv.h"
 
 namespace ff {
@@ -418,30 +419,41 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
         }
         if (!all_ok) return false;
         if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
+        // Usually every (lane, u) holds a real quad (the vector is a whole number of NT*QB quads,
+        // no padding): that case runs without the per-lane range tests, each of which is a
+        // divergent branch -- expensive for a wave that has its SIMD to itself.
+        const bool exact = nquads == padquads && padquads == QB * NT;
+        auto write_quad = [&](auto EX, int r, int u, int b, float rs) {
+            constexpr bool kExact = decltype(EX)::value;
+            const int qi = tid + u * NT;
+            if (kExact || qi < padquads) {
+                float4 t = make_float4(cvalue(v[r][u].x), cvalue(v[r][u].y), cvalue(v[r][u].z), cvalue(v[r][u].w));
+                if constexpr (HAS_ADD) { t.x += cvalue(a[r][u].x); t.y += cvalue(a[r][u].y); t.z += cvalue(a[r][u].z); t.w += cvalue(a[r][u].w); }
+                if (!kExact && qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
+                else {
+                    if (S.wb && (u32)qi >= wb_lo && (u32)qi < wb_hi) {   // this workgroup's slice of the published sum
+                        cword_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
+                        cst2(w, t.x, t.y, S.wb_tag);
+                        cst2(w + 2, t.z, t.w, S.wb_tag);
+                    }
+                    if constexpr (HAS_GAIN) {
+                        t.x *= bf_lo(g[u].x) * rs; t.y *= bf_hi(g[u].x) * rs; t.z *= bf_lo(g[u].y) * rs; t.w *= bf_hi(g[u].y) * rs;
+                    }
+                }
+                stage_store<EPU, SPLIT>(xs, nup, b, qi, t);
+            }
+        };
 #pragma unroll
         for (int r = 0; r < RB; r++) {
             const int b = b0 + r;
             if (b < batch) {
                 const float rs = HAS_GAIN ? rsqrtf(tot[r] / (float)K + S.eps) : 1.f;
+                if (exact) {
 #pragma unroll
-                for (int u = 0; u < QB; u++) {
-                    const int qi = tid + u * NT;
-                    if (qi < padquads) {
-                        float4 t = make_float4(cvalue(v[r][u].x), cvalue(v[r][u].y), cvalue(v[r][u].z), cvalue(v[r][u].w));
-                        if constexpr (HAS_ADD) { t.x += cvalue(a[r][u].x); t.y += cvalue(a[r][u].y); t.z += cvalue(a[r][u].z); t.w += cvalue(a[r][u].w); }
-                        if (qi >= nquads) t = make_float4(0.f, 0.f, 0.f, 0.f);
-                        else {
-                            if (S.wb && (u32)qi >= wb_lo && (u32)qi < wb_hi) {   // this workgroup's slice of the published sum
-                                cword_t* w = S.wb + (size_t)b * S.wb_stride + k0 + qi * 4;
-                                cst2(w, t.x, t.y, S.wb_tag);
-                                cst2(w + 2, t.z, t.w, S.wb_tag);
-                            }
-                            if constexpr (HAS_GAIN) {
-                                t.x *= bf_lo(g[u].x) * rs; t.y *= bf_hi(g[u].x) * rs; t.z *= bf_lo(g[u].y) * rs; t.w *= bf_hi(g[u].y) * rs;
-                            }
-                        }
-                        stage_store<EPU, SPLIT>(xs, nup, b, qi, t);
-                    }
+                    for (int u = 0; u < QB; u++) write_quad(std::true_type{}, r, u, b, rs);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < QB; u++) write_quad(std::false_type{}, r, u, b, rs);
                 }
             }
         }
