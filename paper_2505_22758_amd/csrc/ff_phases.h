@@ -341,15 +341,17 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
         u32 stale[RB];   // quads (bit u) of row r this lane still has to (re)load
 #pragma unroll
         for (int r = 0; r < RB; r++) { stale[r] = (1u << QB) - 1; tot[r] = 0.f; }
-        for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
-            // first round: every quad of every lane; later rounds: only what came back stale, so a
-            // vector that was mostly complete is not fetched twice
+        // first every quad of every lane, unconditionally (no per-lane branches on the way to the
+        // first request); after a failed vote only what came back stale, so a vector that was
+        // mostly complete is not fetched twice
+        auto load_quads = [&](auto ALL) {
+            constexpr bool kAll = decltype(ALL)::value;
 #pragma unroll
             for (int r = 0; r < RB; r++) {
 #pragma unroll
                 for (int u = 0; u < QB; u++) {
                     const int k = k0 + min(tid + u * NT, nquads - 1) * 4;   // clamped: every load is issued
-                    if (spins == 0 || ((stale[r] >> u) & 1)) {
+                    if (kAll || ((stale[r] >> u) & 1)) {
                         if (erow[r]) {   // bf16 values are exact in the compact format: mark them fresh
                             u32x2 w = *as_global((const u32x2*)(erow[r] + k));
                             const u32 t = S.tag & 15u;
@@ -363,9 +365,12 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                             a[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
                         }
                     }
-                    if constexpr (HAS_GAIN) { if (spins == 0 && r == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
+                    if constexpr (HAS_GAIN && kAll) { if (r == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
                 }
             }
+        };
+        load_quads(std::true_type{});
+        for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
             float ss[RB];   // only meaningful if the vote passes
             bool mine = true;
             // With a single row in flight the lane first ORs the counter mismatches of all its
@@ -416,6 +421,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                 if (!vote.all<NT>(lw)) return false;
                 if (ev && tid == 0) { as_global(ev)[2] = wall_clock64(); as_global(ev)[5] += 1; }
             }
+            if (!all_ok) load_quads(std::false_type{});
         }
         if (!all_ok) return false;
         if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
