@@ -57,7 +57,7 @@ template <int NW, int HD, int G>
 __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
                                                        uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, int ncta, WgVote& vote, u64* ev = nullptr) {
     constexpr int NT = NW * 64;
-    const int share = max(1, ncta / (batch * M.Hkv));
+    const int share = max(1, (int)((u32)ncta / (u32)(batch * M.Hkv)));
     int base = 0;
     bool ok = true;
     TaggedAttnIO xio{in_tag, out_tag, &vote};
@@ -65,16 +65,17 @@ __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const 
         const int T = pos[b];
         const int ns = attn_nsplit(T, share);
         const int nitems = M.Hkv * ns;
-        int first = ((int)blockIdx.x - base) % ncta;
-        if (first < 0) first += ncta;
+        // (32-bit unsigned arithmetic throughout: this runs between the end of the QKV projection
+        // and the first cache loads, and 64-bit or signed divisions are long instruction sequences)
+        const int first = (int)(((u32)blockIdx.x + (u32)ncta - (u32)base) % (u32)ncta);   // base < ncta
         for (int it = first; it < nitems; it += ncta) {
-            int j = it / ns, s = it % ns;
-            int t0 = (int)((long)T * s / ns), t1 = (int)((long)T * (s + 1) / ns);
+            const int j = (int)((u32)it / (u32)ns), s = it - j * ns;
+            const int t0 = (int)((u32)T * (u32)s / (u32)ns), t1 = (int)((u32)T * (u32)(s + 1) / (u32)ns);   // T * 64 < 2^32
             bool cur = s == ns - 1;
             ok = attn_item<HD, G, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds, ev) && ok;
             if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, out_cnt, (float*)lds, vote, ev) && ok;
         }
-        base = (base + nitems) % ncta;
+        base = (int)(((u32)base + (u32)nitems) % (u32)ncta);
     }
     return ok;
 }

@@ -378,6 +378,7 @@ int ff_kv_bytes(const ff_model* m, int32_t batch, int32_t max_ctx, size_t* bytes
     if (!m || !bytes) return fail(FF_ERR_ARG, "null argument");
     if (batch < 1 || batch > m->cfg.max_batch) return fail(FF_ERR_ARG, "batch %d outside [1,%d]", batch, m->cfg.max_batch);
     if (max_ctx < 1) return fail(FF_ERR_ARG, "max_ctx must be positive");
+    if (max_ctx > (1 << 24)) return fail(FF_ERR_UNSUPPORTED, "max_ctx above 2^24 rows (the split arithmetic of the attention phase is 32-bit)");
     const ff_config& c = m->cfg;
     size_t cache = align256((size_t)c.n_layers * batch * c.n_kv_heads * 2 * (size_t)max_ctx * c.head_dim * 2);
     size_t rope = align256((size_t)max_ctx * (c.head_dim / 2) * sizeof(float2));
