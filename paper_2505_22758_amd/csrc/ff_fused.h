@@ -171,7 +171,8 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     const u32 steps_done = (u32)__builtin_amdgcn_readfirstlane(xld_u32(M.stepctr));
     const u32 sl = steps_done * (u32)M.L;
 
-    const int gwave = blockIdx.x * kFusedWaves + wave, n_gwaves = ncta * kFusedWaves;
+    const int gwave = blockIdx.x * kFusedWaves + wave;
+    const UDiv n_gwaves = UDiv::of((u32)ncta * kFusedWaves), n_ctas = UDiv::of((u32)ncta);
     float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * kAccFloatsPerWave;
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64;   // behind the RoPE rows
     WgVote vote{(u32*)(red + 16), 0u};   // behind the reduction scratch and the positions
@@ -201,7 +202,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         // gemv_run only: keeping it out of the loop-carried state lets it stay in the registers
         // the loads were issued to (a copy would have to wait for the data).
         TSrc src = D.src;
-        src.ncta = ncta;
+        src.ncta = n_ctas;
         if (seg > 0) src.wb = nullptr;
         const bool att_first = D.kind == PH_O && seg == 0;
         Stage<WD> ring[kDepthOf<WD>];
@@ -221,7 +222,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             u64* aev = dbg_stage_slots(M, n_phases, ncta, D.layer, 4);
             if (aev && threadIdx.x == 0) { as_global(aev)[0] = wall_clock64(); as_global(aev)[4] = 0; as_global(aev)[5] = 0; }
             const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
-                                                                tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, ncta, vote, aev);
+                                                                tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, n_ctas, vote, aev);
             if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
             if (wave == 0) dbg_event(M, ph, EV_ATT_END, lane);
             if (!ok) return;

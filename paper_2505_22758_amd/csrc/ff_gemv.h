@@ -223,6 +223,16 @@ __device__ __forceinline__ float dot_i4x8_codes(u32 w, const float4& x0, const f
 }
 __device__ __forceinline__ float sum4(const float4& v) { return (v.x + v.y) + (v.z + v.w); }
 
+// Division by a launch constant (waves or workgroups in the grid) that is a power of two on the
+// usual 256-workgroup launch: a shift there, a division otherwise.  It sits on the path between two
+// projections, where a 32-bit division is a thirty-instruction sequence.
+struct UDiv {
+    u32 n; int sh;   // sh >= 0: n == 1 << sh
+    __device__ __forceinline__ static UDiv of(u32 n) { return UDiv{n, (n & (n - 1)) == 0 ? (int)__builtin_ctz(n) : -1}; }
+    __device__ __forceinline__ u32 div(u32 x) const { return sh >= 0 ? x >> sh : x / n; }
+    __device__ __forceinline__ u32 mod(u32 x) const { return sh >= 0 ? x & (n - 1) : x % n; }
+};
+
 // ---------------------------------------------------------------- per-wave view of one GEMV
 // A projection is cut along K into segments whose staged input fits the LDS activation region
 // (one segment except for the widest inputs at batch 4); along N every wave of the grid owns a
@@ -241,7 +251,7 @@ struct Stream {
 
     // quad: rows are dealt out in groups of four (p0, my_pairs count groups) and a stage covers
     // kQuadChunkUnitsOf units of each of the four rows instead of kChunkUnits units of two rows.
-    __device__ __forceinline__ static Stream make(const PMat& M, int seg, int gwave, int n_gwaves, bool quad = false) {
+    __device__ __forceinline__ static Stream make(const PMat& M, int seg, int gwave, const UDiv& n_gwaves, bool quad = false) {
         Stream S;
         S.w = M.w; S.s = M.s; S.z = M.z; S.N = M.n; S.K = M.k; S.ng = M.k / 128;
         S.rowb = WD == W_BF16 ? (size_t)M.k * 2 : WD == W_INT8 ? (size_t)M.k : (size_t)M.k / 2;
@@ -254,16 +264,16 @@ struct Stream {
         S.cpr = S.nup / (quad ? kQuadChunkUnitsOf<WD> : kChunkUnits);
         // row pairs (groups) [p0, p1) of this wave; the products fit 32 bits (rows * waves < 2^32)
         const u32 npairs = quad ? (u32)(M.n + 3) / 4 : (u32)(M.n + 1) / 2;
-        S.p0 = (int)(npairs * (u32)gwave / (u32)n_gwaves);
+        S.p0 = (int)n_gwaves.div(npairs * (u32)gwave);
         S.c0 = 0;
-        S.n_it = ((int)(npairs * (u32)(gwave + 1) / (u32)n_gwaves) - S.p0) * S.cpr;
+        S.n_it = ((int)n_gwaves.div(npairs * (u32)(gwave + 1)) - S.p0) * S.cpr;
         // Groups of four rows that come out as an odd number of HALF groups per wave (the 8B QKV
         // projection: 1.5) are dealt out in halves along K instead: the wave's work is the flat
         // range [gwave * h, (gwave + 1) * h) of (group, chunk) iterations, h = chunks per wave, so
         // an odd wave starts in the middle of the group its even neighbour (same workgroup)
         // began; the two exchange their partial sums through LDS (gemv_run_quad).
-        if (quad && S.nseg == 1 && (S.cpr & 1) == 0 && (2 * npairs) % (u32)n_gwaves == 0 && ((2 * npairs / (u32)n_gwaves) & 1)) {
-            const int h = (int)(2 * npairs / (u32)n_gwaves) * (S.cpr / 2);
+        if (quad && S.nseg == 1 && (S.cpr & 1) == 0 && n_gwaves.mod(2 * npairs) == 0 && (n_gwaves.div(2 * npairs) & 1)) {
+            const int h = (int)n_gwaves.div(2 * npairs) * (S.cpr / 2);
             S.p0 = gwave * h / S.cpr;
             S.c0 = gwave * h % S.cpr;
             S.n_it = h;

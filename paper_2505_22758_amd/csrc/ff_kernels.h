@@ -55,8 +55,9 @@ __device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const 
 // the wave wait for every load it has in flight, weight tiles included.
 template <int NW, int HD, int G>
 __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
-                                                       uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, int ncta, WgVote& vote, u64* ev = nullptr) {
+                                                       uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, const UDiv& nc, WgVote& vote, u64* ev = nullptr) {
     constexpr int NT = NW * 64;
+    const int ncta = (int)nc.n;
     const int share = max(1, (int)((u32)ncta / (u32)(batch * M.Hkv)));
     int base = 0;
     bool ok = true;
@@ -67,7 +68,7 @@ __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const 
         const int nitems = M.Hkv * ns;
         // (32-bit unsigned arithmetic throughout: this runs between the end of the QKV projection
         // and the first cache loads, and 64-bit or signed divisions are long instruction sequences)
-        const int first = (int)(((u32)blockIdx.x + (u32)ncta - (u32)base) % (u32)ncta);   // base < ncta
+        const int first = (int)nc.mod((u32)blockIdx.x + (u32)ncta - (u32)base);   // base < ncta
         for (int it = first; it < nitems; it += ncta) {
             const int j = (int)((u32)it / (u32)ns), s = it - j * ns;
             const int t0 = (int)((u32)T * (u32)s / (u32)ns), t1 = (int)((u32)T * (u32)(s + 1) / (u32)ns);   // T * 64 < 2^32
@@ -75,7 +76,7 @@ __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const 
             ok = attn_item<HD, G, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds, ev) && ok;
             if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, out_cnt, (float*)lds, vote, ev) && ok;
         }
-        base = (int)(((u32)base + (u32)nitems) % (u32)ncta);
+        base = (int)nc.mod((u32)base + (u32)nitems);
     }
     return ok;
 }

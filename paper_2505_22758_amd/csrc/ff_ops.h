@@ -65,7 +65,8 @@ __device__ __forceinline__ void op_gemv_body(const PMat& W, const ActSrc& src, i
     float4* xs = (float4*)lds;
     float* red = (float*)(lds + kLdsActBytes + kLdsAuxBytes);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int gwave = blockIdx.x * kWaves + wave, n_gwaves = gridDim.x * kWaves;
+    const int gwave = blockIdx.x * kWaves + wave;
+    const UDiv n_gwaves = UDiv::of(gridDim.x * kWaves);
     float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * kAccFloatsPerWave;
     Stage<WD> ring[kDepthOf<WD>];
     Stream<WD, B> S = Stream<WD, B>::make(W, 0, gwave, n_gwaves);

@@ -118,7 +118,7 @@ struct TSrc {
     const cword_t* add = nullptr; size_t add_stride = 0; u32 add_tag = 0;  // optional: + sublayer output
     cword_t* wb = nullptr; size_t wb_stride = 0; u32 wb_tag = 0;           // optional: publish the sum (residual stream)
     const bf16_t* gain = nullptr; float eps = 0.f;                         // optional: RMSNorm
-    int ncta = 1;                                                          // workgroups in the grid (each publishes 1/ncta of wb)
+    UDiv ncta = {1, 0};                                                    // workgroups in the grid (each publishes 1/ncta of wb)
     bool eager = false;   // re-read the whole vector while waiting instead of polling samples (see stage_tagged_onepass)
 };
 
@@ -209,7 +209,7 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
     const int lane = tid & 63;
     const int nquads = nunits * NQ;
     const int padquads = nup * NQ;
-    const u32 wb_lo = (u32)nquads * blockIdx.x / (u32)S.ncta, wb_hi = (u32)nquads * (blockIdx.x + 1) / (u32)S.ncta;
+    const u32 wb_lo = S.ncta.div((u32)nquads * blockIdx.x), wb_hi = S.ncta.div((u32)nquads * (blockIdx.x + 1));
     for (int b = 0; b < batch; b++) {
         float4* xb = xs + (size_t)b * NQ * nup;
         const cword_t* src = S.base + (size_t)b * S.stride;
@@ -320,7 +320,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
     const int lane = tid & 63;
     const int nquads = nunits * NQ;
     const int padquads = nup * NQ;
-    const u32 wb_lo = (u32)nquads * blockIdx.x / (u32)S.ncta, wb_hi = (u32)nquads * (blockIdx.x + 1) / (u32)S.ncta;
+    const u32 wb_lo = S.ncta.div((u32)nquads * blockIdx.x), wb_hi = S.ncta.div((u32)nquads * (blockIdx.x + 1));
     for (int b0 = 0; b0 < batch; b0 += RB) {
         // rows b0 .. b0+RB-1; a row past the batch repeats the last one (loaded and checked, never written)
         const cword_t* src[RB];
