@@ -161,7 +161,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // the grid size is a kernel argument and the positions are staged in LDS once.
     static_assert(kLdsRopeBytes == kMaxBatchFused * 64 * sizeof(float2) && kLdsMiscBytes >= (16 + 2 * (1 + WgVote::kMaxSums) * kFusedWaves) * 4, "LDS layout");
     int* pos_lds = (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64 + 8);
-    if (threadIdx.x < batch) pos_lds[threadIdx.x] = pos[threadIdx.x];
+    if ((int)threadIdx.x < batch) pos_lds[threadIdx.x] = pos[threadIdx.x];
     if (threadIdx.x < 2) ((lds_u32*)(pairbox_of(xs) + 4 * kPairBoxFloats))[threadIdx.x] = 0u;
     __syncthreads();
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its

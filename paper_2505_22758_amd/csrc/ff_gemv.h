@@ -404,9 +404,6 @@ template <int WD, int B, class Epi>
 __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs, float* myacc,
                                          int batch, int lane, Epi& epi) {
     constexpr int kDepth = kDepthOf<WD>;
-    constexpr int kUnr = kUnrOf<WD>;
-    constexpr int EPU = WTraits<WD>::EPU;
-    constexpr int NQ = EPU / 4;
     const int nup = S.nup;
     float acc[2][B];
 #pragma unroll
