@@ -495,6 +495,13 @@ __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, in
     }
 }
 
+// 2^x straight from the hardware unit (v_exp_f32, about 1 ulp): the library routine wraps it in a
+// rescaling sequence so that results below the normal range come out as denormals; here the
+// arguments are differences to a running maximum (<= 0) and the results softmax weights, for which
+// a flush to zero at 2^-126 is immaterial, and the sequence would be executed dozens of times on
+// the attention's critical path.
+__device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // ---------------------------------------------------------------- split-KV attention
 // One work item = (sequence b, kv head j, rows [t0, t1) of its cache [+ this step's own k,v]).
 // All G query heads that share kv head j are processed together, so each cached K and V element
@@ -605,7 +612,7 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
             s = group_sum<LPR>(s) * sc;
             if (valid) {
                 float mn = fmaxf(m[g], s);
-                float corr = exp2f(m[g] - mn), p = exp2f(s - mn);
+                float corr = exp2_hw(m[g] - mn), p = exp2_hw(s - mn);
                 l[g] = l[g] * corr + p;
 #pragma unroll
                 for (int e = 0; e < 8; e++) o[g][e] = fmaf(p, vf[e], o[g][e] * corr);
@@ -678,7 +685,7 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
         for (int s = 0; s < NS; s++) mx = fmaxf(mx, sm[s * G + g]);
         float lt = 0.f, ot = 0.f;
         for (int s = 0; s < NS; s++) {
-            float w = exp2f(sm[s * G + g] - mx);   // empty states have m = -inf -> weight 0
+            float w = exp2_hw(sm[s * G + g] - mx);   // empty states have m = -inf -> weight 0
             lt = fmaf(sl[s * G + g], w, lt);
             ot = fmaf(so[((size_t)s * G + g) * HD + dim], w, ot);
         }
@@ -711,7 +718,7 @@ __device__ void attn_merge(const DevModel& M, int b, int j, int nsplit, float* l
         for (int s = 0; s < nsplit; s++) mx = fmaxf(mx, ms[g * kMaxSplits + s]);
         float lt = 0.f;
         for (int s = 0; s < nsplit; s++) {
-            float w = exp2f(ms[g * kMaxSplits + s] - mx);
+            float w = exp2_hw(ms[g * kMaxSplits + s] - mx);
             ms[g * kMaxSplits + s] = w;
             lt = fmaf(ls[g * kMaxSplits + s], w, lt);
         }
@@ -793,7 +800,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
 #pragma unroll
             for (int u = 0; u < kSB; u++) {
                 const int s = min(s0 + u, nsplit - 1);
-                const float w = exp2f(ms[g * kMaxSplits + s] - mx);
+                const float w = exp2_hw(ms[g * kMaxSplits + s] - mx);
                 lt = fmaf(ls[g * kMaxSplits + s], s0 + u < nsplit ? w : 0.f, lt);
             }
         }
@@ -812,7 +819,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
 #pragma unroll
             for (int u = 0; u < kSB; u++) {
                 const float mu = ms[g * kMaxSplits + min(s0 + u, nsplit - 1)];
-                const float w = s0 + u < nsplit ? exp2f(mu - mx) * inv : 0.f;
+                const float w = s0 + u < nsplit ? exp2_hw(mu - mx) * inv : 0.f;
                 a0 = fmaf(__uint_as_float(r[u].x), w, a0);
                 a1 = fmaf(__uint_as_float(r[u].z), w, a1);
             }
