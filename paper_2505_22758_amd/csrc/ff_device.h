@@ -21,7 +21,10 @@ constexpr int kMaxBatch = 4;        // sequences one kernel pass works on
 constexpr int kMaxBatchFused = 8;   // ... of the fused kernel with bf16 weights, if the input rows of 8 sequences fit in LDS
 constexpr int kMaxBatchApi = 16;    // sequences one decode step accepts (run as passes of kMaxBatch)
 constexpr int kMaxSplits = 64;           // max KV splits per (sequence, kv head)
-constexpr int kMinSplitLen = 64;         // do not split the cache finer than this many rows
+#ifndef FF_MIN_SPLIT
+#define FF_MIN_SPLIT 64   // can be overridden at build time for sweeps (32 and 128 both measured 2 % slower at ctx 1024)
+#endif
+constexpr int kMinSplitLen = FF_MIN_SPLIT;   // do not split the cache finer than this many rows
 constexpr int kLdsActBytes = 128 * 1024; // LDS region holding the staged activation vector(s)
 constexpr int kLdsAuxBytes = 24 * 1024;  // partial sums of earlier K segments (per wave), then kLdsXsumBytes of per-unit input sums
 constexpr int kLdsXsumBytes = 4 * 1024;  // tail of the aux region: sum of every staged 32-element unit (int4 matrix-core path)
