@@ -49,6 +49,12 @@ def test_argument_validation_needs_no_device():
     with pytest.raises(binding.FFError) as e:
         binding.ff_model_bytes(bad)
     assert e.value.code == binding.FF_ERR_UNSUPPORTED
+    # a normalised input row wider than one staging pass is only supported one sequence at a time
+    wide = synth.LLAMA_70B.replace(d_model=16384, n_q_heads=128, n_kv_heads=16)
+    binding.ff_model_bytes(binding.make_config(wide, max_batch=1))
+    with pytest.raises(binding.FFError) as e:
+        binding.ff_model_bytes(binding.make_config(wide, max_batch=2))
+    assert e.value.code == binding.FF_ERR_UNSUPPORTED
     # null handles are rejected, not dereferenced
     assert binding._lib.ff_decode_step(None, None, None, None, None, 1, None) == binding.FF_ERR_ARG
     assert binding._lib.ff_kv_bytes(None, 1, 16, None) == binding.FF_ERR_ARG
