@@ -222,6 +222,14 @@ def test_llama8b_shaped_one_layer_quantised_batches():
     _run_teacher_forced(S, 0x250522769, synth.WDTYPE_INT4, batch=2, T0=90, steps=1, gpu_generated=True)
 
 
+def test_wide_model_staged_in_several_passes():
+    """d_model 16384 (one layer, batch 1): the normalised input rows no longer fit one staging pass
+    of eight quads per thread, so the embedding, the residual sum and the final norm go through
+    the several-pass staging with its separate rescaling step."""
+    S = synth.TINY.replace(name="wide", n_layers=1, d_model=16384, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ffn=2048, vocab=1000)
+    _run_teacher_forced(S, 0x25052276a, synth.WDTYPE_BF16, batch=1, T0=40, steps=2, gpu_generated=True)
+
+
 def test_two_models_interleaved_on_a_side_stream():
     """Two models of different geometry (head_dim 64 vs 128, bf16 vs int8) alive at once and stepped
     alternately on a non-default stream: no state is shared between models, and a model's result does
