@@ -230,6 +230,17 @@ def test_wide_model_staged_in_several_passes():
     _run_teacher_forced(S, 0x25052276a, synth.WDTYPE_BF16, batch=1, T0=40, steps=2, gpu_generated=True)
 
 
+def test_eight_query_heads_per_kv_head_small_model_all_formats():
+    """The (head_dim 128, 8 query heads per kv head) kernel family on a small model, in the batch
+    classes the 70B-shaped tests do not reach: eight sequences in one pass (bf16), and the int8 and
+    int4 matrix-core projections at batch 4 and 3."""
+    S = synth.TINY.replace(name="g8", n_layers=2, d_model=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, d_ffn=1536, vocab=1500)
+    _run_teacher_forced(S, 0x25052276b, synth.WDTYPE_BF16, batch=8, T0=70, steps=2)
+    _run_teacher_forced(S, 0x25052276c, synth.WDTYPE_INT8, batch=4, T0=33, steps=2)
+    _run_teacher_forced(S, 0x25052276d, synth.WDTYPE_INT4, batch=3, T0=90, steps=2)
+    _run_teacher_forced(S, 0x25052276e, synth.WDTYPE_INT4, batch=1, T0=130, steps=2)
+
+
 def test_two_models_interleaved_on_a_side_stream():
     """Two models of different geometry (head_dim 64 vs 128, bf16 vs int8) alive at once and stepped
     alternately on a non-default stream: no state is shared between models, and a model's result does
