@@ -241,6 +241,15 @@ def test_eight_query_heads_per_kv_head_small_model_all_formats():
     _run_teacher_forced(S, 0x25052276e, synth.WDTYPE_INT4, batch=1, T0=130, steps=2)
 
 
+def test_half_a_row_group_per_wave():
+    """d_model 2048 at batch 2: the output and down projections have 512 four-row groups for the
+    1024 waves of the grid, so every wave multiplies half of a group (split along K) and every
+    group is finished through the wave pair's mailbox; bf16 and int4."""
+    S = synth.TINY.replace(name="half", n_layers=2, d_model=2048, n_q_heads=16, n_kv_heads=4, head_dim=128, d_ffn=2048, vocab=3000)
+    _run_teacher_forced(S, 0x25052276f, synth.WDTYPE_BF16, batch=2, T0=50, steps=2)
+    _run_teacher_forced(S, 0x250522770, synth.WDTYPE_INT4, batch=4, T0=20, steps=2)
+
+
 def test_two_models_interleaved_on_a_side_stream():
     """Two models of different geometry (head_dim 64 vs 128, bf16 vs int8) alive at once and stepped
     alternately on a non-default stream: no state is shared between models, and a model's result does
