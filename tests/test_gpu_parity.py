@@ -209,7 +209,8 @@ def test_llama8b_shaped_one_layer_batch8_single_pass():
     """Eight sequences in ONE pass at the 8B width (one layer): the matrix-core projections with two
     sets of four sequences, input rows staged in two groups, the down projection cut into four
     segments along K, sequences of different lengths."""
-    _run_teacher_forced(synth.LLAMA_8B.replace(n_layers=1), 0x250522766, synth.WDTYPE_BF16, batch=8, T0=96, steps=2, gpu_generated=True)
+    _run_teacher_forced(synth.LLAMA_8B.replace(n_layers=1), 0x250522766, synth.WDTYPE_BF16, batch=8, T0=[96, 1, 300, 64, 63, 65, 0, 200], steps=2,
+                        gpu_generated=True)
 
 
 def test_llama8b_shaped_one_layer_quantised_batches():
