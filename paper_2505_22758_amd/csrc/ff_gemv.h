@@ -249,7 +249,7 @@ struct Stream {
     static constexpr int kChunkUnits = kChunkUnitsOf<WD>;
     static constexpr int seg_units = (kLdsActBytes / (B * EPU * 4)) / kChunkUnits * kChunkUnits;
 
-    // quad: rows are dealt out in groups of four (p0, my_pairs count groups) and a stage covers
+    // quad: rows are dealt out in groups of four (p0 counts groups) and a stage covers
     // kQuadChunkUnitsOf units of each of the four rows instead of kChunkUnits units of two rows.
     __device__ __forceinline__ static Stream make(const PMat& M, int seg, int gwave, const UDiv& n_gwaves, bool quad = false) {
         Stream S;

@@ -192,6 +192,7 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
     }
 }
 
+// Several-pass form (vectors longer than one pass of stage_tagged_onepass; one row at a time).
 // The workgroup stages elements [k0, k0 + nunits*EPU) of every batch row into LDS in the
 // quad-planar layout of stage_act, re-reading the tagged sources until their producers have
 // written them.  Every thread issues all loads of its share of a batch at once and speculatively
