@@ -40,6 +40,9 @@ WORKLOADS = {
     "llama3-8b-int8-b1-ctx4096": ("llama3-8b", 1, 1, 4096),
     "llama3-8b-int4-b1-ctx2048": ("llama3-8b", 2, 1, 2048),
     "llama3-8b-int4-b4-ctx2048": ("llama3-8b", 2, 4, 2048),
+    # the full 80-layer model: 139 GB of packed weights, generated and packed layer by layer on the GPU
+    "llama3-70b-bf16-b1-ctx2048": ("llama3-70b", 0, 1, 2048),
+    "llama3-70b-bf16-b16-ctx2048": ("llama3-70b", 0, 16, 2048),
 }
 
 
@@ -119,6 +122,8 @@ def main():
         dec.load_layer(l, lw)
         torch.cuda.synchronize()
         del lw
+        if shape.n_layers > 40 and (l + 1) % 8 == 0:   # a long set-up says that it is alive
+            print(f"bench.py: layer {l + 1}/{shape.n_layers} generated and packed", file=sys.stderr, flush=True)
     hw = synth.make_head(shape, seed, wdtype, dev)
     dec.load_head(hw)
     torch.cuda.synchronize()
