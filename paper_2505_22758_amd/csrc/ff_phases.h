@@ -835,6 +835,9 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
 // available per (sequence, kv head).
 __device__ __forceinline__ int attn_nsplit(int ncache, int share) {
     int ns = ncache / kMinSplitLen;
+    // more than 16 slices cost the merge a second, serial round of partial loads (it gathers 16
+    // at a time): go beyond 16 only once the slices are 128 rows long
+    if (ns > 16) ns = max(16, ncache / (2 * kMinSplitLen));
     ns = min(ns, min(share, kMaxSplits));
     return max(ns, 1);
 }
