@@ -10,16 +10,16 @@ from tests import helpers
 pytestmark = pytest.mark.gpu
 
 
-def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, gpu_generated=False):
+def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, gpu_generated=False, quant_lm_head=True):
     from paper_2505_22758_amd import binding
     from oracle import oracle
     T0s = helpers.prefill_lengths(T0, batch)   # one prefill length for all sequences, or one each
     max_ctx = max(T0s) + steps + 3
     if gpu_generated:
-        M, okv, dec, caches = helpers.both_sides_gpu_generated(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2)
+        M, okv, dec, caches = helpers.both_sides_gpu_generated(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2, quant_lm_head=quant_lm_head)
     else:
-        M, okv = helpers.oracle_side(shape, seed, wdtype, batch, T0, max_ctx)
-        dec, caches = helpers.hip_side(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2)
+        M, okv = helpers.oracle_side(shape, seed, wdtype, batch, T0, max_ctx, quant_lm_head=quant_lm_head)
+        dec, caches = helpers.hip_side(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2, quant_lm_head=quant_lm_head)
     toks = synth.make_tokens(shape, seed, steps, batch)
     logits_f = torch.zeros(batch, shape.vocab, dtype=torch.float32, device="cuda:0")
     logits_p = torch.zeros_like(logits_f)
@@ -159,6 +159,15 @@ def test_tiny_shaped_int8_and_int4_steps():
         _run_teacher_forced(S, 50 + wd, wd, batch=4, T0=33, steps=2)
         _run_teacher_forced(S, 60 + wd, wd, batch=2, T0=21, steps=2)
         _run_teacher_forced(S, 70 + wd, wd, batch=3, T0=45, steps=2)
+
+
+def test_quantised_layers_with_a_bf16_lm_head():
+    """quant_lm_head = 0: the LM head keeps bf16 weights while the layers are int8 / int4, so it
+    runs as separate launches behind the fused kernel (final residual sum, norm, projection)."""
+    S = synth.TINY.replace(d_ffn=1408)
+    _run_teacher_forced(S, 81, synth.WDTYPE_INT8, batch=1, T0=40, steps=3, quant_lm_head=False)
+    _run_teacher_forced(S, 82, synth.WDTYPE_INT4, batch=3, T0=25, steps=2, quant_lm_head=False)
+    _run_teacher_forced(S, 83, synth.WDTYPE_INT8, batch=6, T0=10, steps=2, quant_lm_head=False)
 
 
 def test_out_of_range_position_is_reported_and_skipped():
