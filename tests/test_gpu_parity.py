@@ -170,6 +170,40 @@ def test_quantised_layers_with_a_bf16_lm_head():
     _run_teacher_forced(S, 83, synth.WDTYPE_INT8, batch=6, T0=10, steps=2, quant_lm_head=False)
 
 
+def test_timeline_buffer_of_the_documented_size():
+    """ff_debug_timeline with a buffer of exactly the size the header states: stamps arrive in order
+    (input staged before the projection is done, phase after phase) and nothing is written behind
+    the buffer; ff_fused_schedule reports the launch shape the layout depends on."""
+    from paper_2505_22758_amd import binding
+    S = synth.TINY
+    dec, caches = helpers.hip_side(S, 5, synth.WDTYPE_BF16, 2, 30, max_ctx=40)
+    barriers, W, threads = binding.ff_fused_schedule(dec.model)
+    assert barriers == 0 and W > 0 and threads == 256
+    P = 4 * S.n_layers + 1
+    n = 12 * P + 72 * W
+    guard = 64
+    buf = torch.full((n + guard,), -1, dtype=torch.int64, device="cuda:0")
+    buf[:n] = 0
+    tok = torch.tensor([3, 4], dtype=torch.int32, device="cuda:0")
+    pos = torch.tensor([30, 30], dtype=torch.int32, device="cuda:0")
+    lg = torch.zeros(2, S.vocab, device="cuda:0")
+    binding.ff_debug_timeline(dec.model, buf)
+    binding.ff_decode_step(dec.model, tok, pos, caches[0][0], lg, 2)
+    torch.cuda.synchronize()
+    binding.ff_debug_timeline(dec.model, None)
+    binding.ff_status(dec.model)
+    h = buf.cpu().numpy()
+    assert (h[n:] == -1).all()
+    t = h[:12 * P].reshape(P, 12)
+    staged, done = t[:, 0], t[:, 1]
+    assert (staged > 0).all() and (done > staged).all() and (staged[1:] > done[:-1]).all()
+    # stamps off: a further step leaves the buffer alone
+    before = buf.clone()
+    binding.ff_decode_step(dec.model, tok, pos + 1, caches[0][0], lg, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(before, buf)
+
+
 def test_out_of_range_position_is_reported_and_skipped():
     from paper_2505_22758_amd import binding
     S = synth.TINY
