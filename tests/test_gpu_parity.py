@@ -170,6 +170,40 @@ def test_quantised_layers_with_a_bf16_lm_head():
     _run_teacher_forced(S, 83, synth.WDTYPE_INT8, batch=6, T0=10, steps=2, quant_lm_head=False)
 
 
+def test_model_load_in_one_call_and_partial_cache_fills():
+    """ff_model_load (create + every layer + head in one call) gives the same model as the
+    layer-by-layer calls; a cache filled in two pieces (rows [0, 17) and [17, 30)) equals one
+    filled at once: logits bit-identical."""
+    from paper_2505_22758_amd import binding
+    S, seed, T0 = synth.TINY, 9, 30
+    dec, caches = helpers.hip_side(S, seed, synth.WDTYPE_INT8, 1, T0, max_ctx=40)
+    cfg = binding.make_config(S, synth.WDTYPE_INT8, 1)
+    pb, sb = binding.ff_model_bytes(cfg)
+    packed = torch.empty(pb, dtype=torch.uint8, device="cuda:0")
+    scratch = torch.empty(sb, dtype=torch.uint8, device="cuda:0")
+    layers = [synth.make_layer(S, seed, l, synth.WDTYPE_INT8, "cuda:0") for l in range(S.n_layers)]
+    head = synth.make_head(S, seed, synth.WDTYPE_INT8, "cuda:0")
+    model = binding.ff_model_load(cfg, layers, head, packed, scratch)
+    kvbuf = torch.zeros(binding.ff_kv_bytes(model, 1, 40), dtype=torch.uint8, device="cuda:0")
+    kv = binding.ff_kv_alloc(model, 1, 40, kvbuf)
+    for l in range(S.n_layers):
+        k, v = synth.make_kv_prefill(S, seed, l, 0, T0, "cuda:0")
+        binding.ff_kv_fill(kv, l, 0, 0, k[:17].contiguous(), v[:17].contiguous())
+        binding.ff_kv_fill(kv, l, 0, 17, k[17:].contiguous(), v[17:].contiguous())
+    tok = torch.tensor([7], dtype=torch.int32, device="cuda:0")
+    pos = torch.tensor([T0], dtype=torch.int32, device="cuda:0")
+    a = torch.zeros(1, S.vocab, device="cuda:0")
+    b = torch.zeros(1, S.vocab, device="cuda:0")
+    binding.ff_decode_step(dec.model, tok, pos, caches[0][0], a, 1)
+    binding.ff_decode_step(model, tok, pos, kv, b, 1)
+    torch.cuda.synchronize()
+    binding.ff_status(dec.model)
+    binding.ff_status(model)
+    assert torch.equal(a, b)
+    binding.ff_kv_free(kv)
+    binding.ff_model_free(model)
+
+
 def test_timeline_buffer_of_the_documented_size():
     """ff_debug_timeline with a buffer of exactly the size the header states: stamps arrive in order
     (input staged before the projection is done, phase after phase) and nothing is written behind
