@@ -3,10 +3,10 @@
  *
  * One call to ff_decode_step runs one forward step of a Llama-style decoder (paper Section 2.1:
  * pre-RMSNorm, grouped-query attention with RoPE, SwiGLU FFN) for a batch of independent sequences
- * in ONE persistent kernel launch covering all layers (paper abstract and Section 3: a single
+ * in ONE persistent kernel launch covering all layers (paper abstract and Section 4: a single
  * kernel invocation per generated token), followed inside the same launch by the final norm and the
  * LM head.  ff_decode_step_perop runs the same step as one launch per operation on the same
- * buffers (the paper's "Baseline": separate kernel launches, Section 3 / latency tables).
+ * buffers (the paper's "Baseline": separate kernel launches, as in the latency tables of Sections 3 and 5.3).
  *
  * Conventions
  *   - Every pointer named *_dev is DEVICE memory on the current HIP device; it is allocated and
@@ -106,7 +106,7 @@ int ff_model_load(const ff_config *cfg, const ff_layer_weights *layers, const ff
                   void *stream, ff_model **out);
 int ff_model_free(ff_model *m);
 
-/* KV cache for `batch` independent sequences of at most max_ctx positions (paper Section 4.2:
+/* KV cache for `batch` independent sequences of at most max_ctx positions (paper Section 5.2:
  * caches are distinct per sequence).  bf16; keys are stored rotated.  Also holds the RoPE
  * cos/sin table for positions [0, max_ctx), built here on `stream`. */
 int ff_kv_bytes(const ff_model *m, int32_t batch, int32_t max_ctx, size_t *bytes);
@@ -119,21 +119,26 @@ int ff_kv_read(ff_kv *kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, v
                void *stream);
 int ff_kv_free(ff_kv *kv);
 
-/* One decode step (paper Section 3.2, attention and GLU schedules; final norm and LM head added).
+/* One decode step (paper Section 4.2, attention and GLU schedules; final norm and LM head added).
  *   tokens_dev    int32 [batch]   token ids, each in [0, vocab)
  *   positions_dev int32 [batch]   number of rows already cached for each sequence (= the position
  *                                 of this token); this step appends K,V at that row and attends to
  *                                 rows 0..position inclusive.  The caller advances positions.
  *   logits_dev    fp32  [batch][vocab]   valid once `stream` has synchronised.
- * Asynchronous; an out-of-range position or token makes the kernel skip the step and record
- * FF_ERR_RANGE in the model's status word (see ff_status).  Steps on one model must not overlap.
- * One kernel pass serves up to 4 sequences (paper Section 4.2: batches 2-4 replicate the inputs and
+ * Asynchronous; an out-of-range position or token anywhere in the batch makes every kernel of the
+ * step skip its work (all passes: nothing is appended, and logits_dev is not written unless the LM
+ * head has a weight type of its own and runs as separate launches) and record FF_ERR_RANGE in the
+ * model's status word (see ff_status).  Steps on one model must not overlap.
+ * A step's launches carry no host-side per-step state (exchange tags and write counters derive
+ * from a counter in the model's scratch), so a step may be recorded into a HIP graph and replayed.
+ * One kernel pass serves up to 4 sequences (paper Section 5.2: batches 2-4 replicate the inputs and
  * read every weight once), or up to 8 with bf16 weights when d_model <= 4096 and max_batch > 4;
  * a larger batch runs as consecutive passes on the stream, each streaming the weights again. */
 int ff_decode_step(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
                    float *logits_dev, int32_t batch, void *stream);
 
-/* Same step as separate per-operation launches (baseline of the paper's latency tables). */
+/* Same step as separate per-operation launches (baseline of the paper's latency tables).  After a
+ * range error the cache is unchanged and logits_dev holds undefined values. */
 int ff_decode_step_perop(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
                          float *logits_dev, int32_t batch, void *stream);
 
@@ -144,8 +149,22 @@ int ff_decode_step_perop(ff_model *m, const int32_t *tokens_dev, const int32_t *
 int ff_status(ff_model *m, void *stream);
 
 /* Writes matrix `which` (FF_MAT_*) of `layer` (ignored for FF_MAT_LMHEAD) as fp32, canonical
- * [N][K] order, dequantised from the PACKED copy exactly as the decode kernels dequantise it. */
+ * [N][K] order, dequantised element by element from the PACKED copy by the defining formula
+ * (q * s, (code - z) * s).  This checks the packing; the decode kernels never form single weights
+ * (they scale finished sums), so their arithmetic is exported by ff_debug_gemv below. */
 int ff_debug_dequant(const ff_model *m, int32_t layer, int32_t which, float *out_dev, void *stream);
+
+/* Runs the decode kernels' own projection code on caller input: out_dev[b][n] = sum_k W[n][k] *
+ * in_dev[b][k] for matrix `which` of `layer`, fp32 in_dev [batch][K], fp32 out_dev [batch][N] with
+ * rows in canonical order.  path 0: the vector-ALU streaming GEMV (batch 1..4) used at batch 1 and
+ * by the per-operation baseline; path 1: the matrix-core GEMV of batches >= 2 (batch 2..4, input
+ * staged as bf16 head + remainder; K * 4 bytes * batch must fit the 128 KiB input buffer).  Fed with
+ * unit vectors it returns the columns of W exactly as the hot path dequantises them (the int8 row
+ * scale and the int4 group scale / zero are applied to sums there, which for a unit vector is the
+ * single product of the defining formula).  Uses the model's scratch: must not overlap a decode
+ * step.  FF_ERR_ARG for a batch the path does not serve (or above the model's max_batch). */
+int ff_debug_gemv(ff_model *m, int32_t layer, int32_t which, const float *in_dev, float *out_dev,
+                  int32_t batch, int32_t path, void *stream);
 
 /* Profiling aid: when buf_dev is non-NULL, every following fused step writes 100 MHz wall-clock
  * stamps into it; NULL switches it off.  With P = 4*n_layers+1 projection phases and W workgroups
@@ -158,6 +177,13 @@ int ff_debug_dequant(const ff_model *m, int32_t layer, int32_t which, float *out
  *                     then 8 about its attention work (start, queries seen, rows done, partial
  *                     stored, split maxima seen and merged output stored if it merges, end) */
 int ff_debug_timeline(ff_model *m, void *buf_dev);
+
+/* Test hook for the FF_ERR_TIMEOUT path: while `workgroup` is >= 0, that workgroup of every
+ * following fused step leaves at once without publishing anything, so each workgroup that needs its
+ * output gives up after its own bounded wait (a fraction of a second), all kernels end normally and
+ * ff_status reports FF_ERR_TIMEOUT; -1 switches the hook off.  The model must then be created
+ * again (see ff_status). */
+int ff_debug_mute_workgroup(ff_model *m, int32_t workgroup);
 
 /* Number of device-wide barriers one fused step executes (0: phases are ordered by tagged dataflow;
  * kept for tests of the schedule), and the number of

@@ -5,7 +5,7 @@
  * operations per layer of the paper's sublayer table (Section 2.1: QKV projection, QK^T, PV,
  * attention output projection, GLU in/gate projection, GLU output projection) with pre-RMSNorm,
  * RoPE, grouped-query attention and SwiGLU, followed by the final norm and LM head.  The fused
- * kernel re-associates these sums (split-KV attention with an online-softmax merge, Section 3.2)
+ * kernel re-associates these sums (split-KV attention with an online-softmax merge, Section 4.2)
  * but reaches exactly this result up to rounding order, so nothing here is blocked, fused or
  * split: every sum is a plain loop.
  *

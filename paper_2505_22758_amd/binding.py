@@ -25,7 +25,7 @@ FF_MAT = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 
 
 EXPORTS = ["ff_last_error", "ff_model_bytes", "ff_model_create", "ff_model_load_layer", "ff_model_load_head",
            "ff_model_load", "ff_model_free", "ff_kv_bytes", "ff_kv_alloc", "ff_kv_fill", "ff_kv_read", "ff_kv_free",
-           "ff_decode_step", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_timeline",
+           "ff_decode_step", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_mute_workgroup",
            "ff_fused_schedule"]
 
 
@@ -66,7 +66,9 @@ _lib.ff_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.ff_decode_step_perop.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.ff_status.argtypes = [_vp, _vp]
 _lib.ff_debug_dequant.argtypes = [_vp, _i32, _i32, _vp, _vp]
+_lib.ff_debug_gemv.argtypes = [_vp, _i32, _i32, _vp, _vp, _i32, _i32, _vp]
 _lib.ff_debug_timeline.argtypes = [_vp, _vp]
+_lib.ff_debug_mute_workgroup.argtypes = [_vp, _i32]
 _lib.ff_fused_schedule.argtypes = [_vp, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32)]
 
 
@@ -196,8 +198,17 @@ def ff_debug_dequant(model: int, layer: int, which: str, out: torch.Tensor, stre
     _check(_lib.ff_debug_dequant(model, layer, FF_MAT[which], _ptr(out), _stream(stream)), "ff_debug_dequant")
 
 
+def ff_debug_gemv(model: int, layer: int, which: str, x: torch.Tensor, out: torch.Tensor, path: int, stream=None) -> None:
+    assert x.dtype == torch.float32 and out.dtype == torch.float32 and x.dim() == 2 and out.shape[0] == x.shape[0]
+    _check(_lib.ff_debug_gemv(model, layer, FF_MAT[which], _ptr(x), _ptr(out), x.shape[0], path, _stream(stream)), "ff_debug_gemv")
+
+
 def ff_debug_timeline(model: int, buf) -> None:
     _check(_lib.ff_debug_timeline(model, _ptr(buf) if buf is not None else None), "ff_debug_timeline")
+
+
+def ff_debug_mute_workgroup(model: int, workgroup: int) -> None:
+    _check(_lib.ff_debug_mute_workgroup(model, workgroup), "ff_debug_mute_workgroup")
 
 
 def ff_fused_schedule(model: int):

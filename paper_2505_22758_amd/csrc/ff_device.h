@@ -83,7 +83,7 @@ struct DevModel {
     // counter in its lowest mantissa bits): residual stream (two buffers), sublayer output, merged
     // attention output, SwiGLU output
     u32* cx;  u32* cx2;  u32* cdelta;  u32* cattn_o;  u32* ch;
-    u32* stepctr;    // number of fused steps executed so far on these buffers (skipped steps do not count)
+    u32* stepctr;    // [0] fused launches executed so far on these buffers (skipped steps do not count); [1] sequences the last one served
     u32x2* tpart_m;  u32x2* tpart_l;  u32x2* tpart_o;
     int* status;
     u64* dbg;        // optional timeline buffer (null unless enabled through the debug entry point)
@@ -94,6 +94,7 @@ struct DevKV {
     const float2* rope;  // [max_ctx][hd/2] (cos, sin)
     int max_ctx, batch;
     int seq0;            // first sequence of the current pass (kernels number their sequences from 0)
+    int step_batch;      // sequences of the whole decode step (all passes)
     __device__ bf16_t* plane(const DevModel& M, int l, int b, int j, int kv) const {
         return base + ((((size_t)l * batch + (seq0 + b)) * M.Hkv + j) * 2 + kv) * (size_t)max_ctx * M.hd;
     }

@@ -1,5 +1,6 @@
 // The fused whole-model decode kernel (one persistent launch per decode step).
 #pragma once
+#include <mutex>
 #include "ff_kernels.h"
 
 namespace ff {
@@ -12,7 +13,7 @@ constexpr int kFusedThreads = kFusedWaves * 64;
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
 
 // ---------------------------------------------------------------- the fused whole-model kernel
-// One launch = one decode step for all layers (paper abstract, Section 3).  Phases per layer:
+// One launch = one decode step for all layers (paper abstract, Section 4).  Phases per layer:
 // [RMSNorm + QKV projection + RoPE + cache append] [split-KV attention + merge] [output projection]
 // [residual + RMSNorm + gate/up projection + SwiGLU] [down projection]; then residual + final norm
 // + LM head.  The residual additions are folded into the staging of the next normalised
@@ -20,12 +21,12 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 //
 // Synchronisation between phases is by dataflow on tagged values (see tagged_t): a phase starts in
 // a workgroup as soon as the vector it consumes carries the producing phase's tag.  The paper's
-// kernel separates the same phases with an atomic device-wide barrier plus fences (Section 3.1);
+// kernel separates the same phases with an atomic device-wide barrier plus fences (Section 4.1);
 // on this chip a barrier round trip, the wait for store acknowledgements before it and the input
 // load after it are three dependent trips through a memory pipeline that is full of weight
 // traffic, so the dependency is carried by the data instead.
 //
-// Memory pipeline (the paper's cross-layer overlap, Section 3.1, re-designed for CDNA4): each of
+// Memory pipeline (the paper's cross-layer overlap, Section 4.1, re-designed for CDNA4): each of
 // wave owns a ring of kDepth register stages of 16-byte non-temporal weight loads.  When a phase
 // ends, the first kDepth stages of the NEXT weight matrix are issued at once and the loads of the
 // next input vector right behind them, speculatively: by the time they return (results come back
@@ -141,12 +142,15 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
 template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
-                                                                     int batch, u32 tag_base, int lm_in_kernel, int ncta) {
+                                                                     int batch, int lm_in_kernel, int ncta, int mute_wg) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    if (!inputs_ok(M, KV, tokens, pos, batch)) {
+    if (!inputs_ok(M, KV, tokens, pos)) {
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(M.status, kStatusRange);
         return;
     }
+    // Test hook for the time-out path: the muted workgroup publishes nothing, so every workgroup
+    // that needs its output runs into its own bounded wait, records the time-out and leaves.
+    if ((int)blockIdx.x == mute_wg) return;
     constexpr int EPU = WTraits<WD>::EPU;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -170,6 +174,12 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // steps executed so far on the compact buffers (kept on the device: a skipped step does not count)
     const u32 steps_done = (u32)__builtin_amdgcn_readfirstlane(xld_u32(M.stepctr));
     const u32 sl = steps_done * (u32)M.L;
+    // The 32-bit tags of this step's queries, keys, values and attention partials: a fresh range
+    // per executed step, derived from the same device-side counter, so that a launch carries no
+    // host-side step state (a launch recorded into a HIP graph replays correctly).  Tags wrap after
+    // 2^32 / (5 L + 1) steps; a slot could only be mistaken for fresh if it had not been rewritten
+    // for exactly that many steps, and every slot a step reads is rewritten by that step first.
+    const u32 tag_base = steps_done * (u32)(kTagsPerLayer * M.L + 1);
 
     const int gwave = blockIdx.x * kFusedWaves + wave;
     const UDiv n_gwaves = UDiv::of((u32)ncta * kFusedWaves), n_ctas = UDiv::of((u32)ncta);
@@ -252,29 +262,37 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     }
     // this step has been executed: the next one uses the next write counters (workgroup 0 can only
     // get here after every workgroup has taken part in every phase, i.e. has read the counter)
-    if (blockIdx.x == 0 && threadIdx.x == 0) xst_u32(M.stepctr, steps_done + 1u);
+    // Word 1 of the counter block: sequences whose compact exchange rows this launch has written
+    // (k_scrub_rows re-initialises further rows before a larger batch runs).
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        xst_u32(M.stepctr + 1, (u32)batch);
+        xst_u32(M.stepctr, steps_done + 1u);
+    }
 }
 
 // Host-side launcher of one weight-type family; defined once per weight type in its own
 // translation unit so that the instances compile in parallel.
 struct FusedLaunch {
     DevModel M; DevKV KV; const int* tokens; const int* pos; float* logits;
-    int batch; u32 tag_base; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream;
+    int batch; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream; int mute_wg;
 };
 template <int WD, int B, int HD, int G>
 inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what) {
     auto kern = fused_decode_kernel<WD, B, HD, G>;
-    static bool ready = false;
-    if (!ready) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
-        if (e != hipSuccess) { *what = "hipFuncSetAttribute"; return e; }
+    // one-time set-up per instance (thread-safe; a failure is remembered and reported by every call)
+    static std::once_flag once;
+    static hipError_t setup_err = hipSuccess;
+    static const char* setup_what = "";
+    std::call_once(once, [&] {
+        setup_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
+        if (setup_err != hipSuccess) { setup_what = "hipFuncSetAttribute"; return; }
         int occ = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, kFusedThreads, a.lds_bytes);
-        if (e != hipSuccess) { *what = "hipOccupancyMaxActiveBlocksPerMultiprocessor"; return e; }
-        if (occ < 1) { *what = "fused kernel does not fit on a compute unit"; return hipErrorLaunchOutOfResources; }
-        ready = true;
-    }
-    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.tag_base, a.lm_in_kernel, a.n_cta);
+        setup_err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, kFusedThreads, a.lds_bytes);
+        if (setup_err != hipSuccess) { setup_what = "hipOccupancyMaxActiveBlocksPerMultiprocessor"; return; }
+        if (occ < 1) { setup_what = "fused kernel does not fit on a compute unit"; setup_err = hipErrorLaunchOutOfResources; }
+    });
+    if (setup_err != hipSuccess) { *what = setup_what; return setup_err; }
+    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.lm_in_kernel, a.n_cta, a.mute_wg);
     *what = "fused kernel launch";
     return hipGetLastError();
 }

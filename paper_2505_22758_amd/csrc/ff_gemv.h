@@ -392,9 +392,9 @@ __device__ __forceinline__ void stage_fma(const Stage<WD>& st, const float4* xs,
     }
 }
 
-// Weight-streaming GEMV over one stream for up to B batch rows (paper Section 3.2: batch-one
+// Weight-streaming GEMV over one stream for up to B batch rows (paper Section 4.2: batch-one
 // projections are matrix-vector products with the input cached on chip and each workgroup owning
-// some rows of W; Section 4.2: at batch 2-4 the weights are still read exactly once and the inputs
+// some rows of W; Section 5.2: at batch 2-4 the weights are still read exactly once and the inputs
 // replicated).  On entry ring[s] holds iteration s (s < min(kDepth, n_it)); iteration i+kDepth is
 // issued into the slot iteration i has just freed, so 2*kDepth*kUnr 16-byte non-temporal loads
 // per lane stay in flight across row boundaries.  epi(pair, b, v0, v1) runs on lane 0 with the two
@@ -471,7 +471,7 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
 // i).  Here A = the four weight rows over four consecutive k (half of the lane's 16-byte unit) and
 // B = the staged inputs of sequences 0..3 over the same k, so one instruction does the 64
 // multiply-adds that cost 16 vector FMAs plus conversions in gemv_run, and the cost no longer
-// grows with the batch (paper Section 4.2 keeps the weights read once at batch 2-4; this keeps the
+// grows with the batch (paper Section 5.2 keeps the weights read once at batch 2-4; this keeps the
 // arithmetic from becoming the limit there).  The inputs stay fp32-accurate: staging splits every
 // value into a bf16 head and a bf16 remainder (two planes per sequence, see stage_store), and both
 // are multiplied.  Unit j of sequence b sits at index (j ^ ((b & 3) << 2)) of its plane, which spreads

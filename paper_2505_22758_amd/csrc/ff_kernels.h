@@ -10,9 +10,11 @@ constexpr int kTagsPerLayer = 5;   // phase instances (= exchange tags) per laye
 constexpr int kStatusRange = -3;
 constexpr int kStatusTimeout = -5;
 
-__device__ __forceinline__ bool inputs_ok(const DevModel& M, const DevKV& KV, const int* tokens, const int* pos, int batch) {
+// tokens / pos point to the first sequence of the current pass; the check covers every sequence of
+// the whole decode step (all passes), so that a bad token or position anywhere skips every pass.
+__device__ __forceinline__ bool inputs_ok(const DevModel& M, const DevKV& KV, const int* tokens, const int* pos) {
     bool ok = true;
-    for (int b = 0; b < batch; b++) {
+    for (int b = -KV.seq0; b < KV.step_batch - KV.seq0; b++) {
         int p = pos[b], t = tokens[b];
         ok = ok && p >= 0 && p < KV.max_ctx && t >= 0 && t < M.V;
     }
@@ -47,7 +49,7 @@ __device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const 
 }
 
 // Fused kernel: queries / current k,v are awaited through their tags; the workgroup that owns the
-// last split of (b, j) also merges all splits of that head group (paper Section 3.2: the reduction
+// last split of (b, j) also merges all splits of that head group (paper Section 4.2: the reduction
 // is fused into the attention pass instead of a separate kernel).  The head geometry is a template
 // parameter here (one kernel instance per geometry) to keep the register footprint of the fused
 // kernel down to what the model at hand needs.  `pos` points to the positions staged in LDS and

@@ -6,7 +6,7 @@ namespace ff {
 
 // ---------------------------------------------------------------- per-operation baseline kernels
 __global__ void __launch_bounds__(kThreads) op_embed(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch) {
-    if (!inputs_ok(M, KV, tokens, pos, batch)) {
+    if (!inputs_ok(M, KV, tokens, pos)) {
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(M.status, kStatusRange);
         return;
     }
@@ -35,7 +35,11 @@ __global__ void __launch_bounds__(kThreads) op_rmsnorm(const float* x, const bf1
 // Re-initialises rows [row0, row1) of the compact exchange vectors so that their counter bits are
 // the ones just BEFORE each vector's first write of the next step: rows a smaller batch has left
 // untouched for a while could otherwise carry, by chance, the bits a later reader waits for.
-__global__ void __launch_bounds__(kThreads) k_scrub_rows(DevModel M, int row0, int row1) {
+// The decision is taken on the device (rows [stepctr[1], batch) are scrubbed, usually none), so the
+// launch itself carries no host-side state and may be recorded into a HIP graph.
+__global__ void __launch_bounds__(kThreads) k_scrub_rows(DevModel M, int batch) {
+    const int row0 = (int)as_global(M.stepctr)[1], row1 = batch;
+    if (row0 >= row1) return;
     const u32 sl = as_global(M.stepctr)[0] * (u32)M.L;
     const int qd = M.Hq * M.hd;
     const size_t per_row = (size_t)3 * M.d + qd + M.F;
@@ -92,9 +96,48 @@ __global__ void __launch_bounds__(kThreads) op_gemv(PMat W, const float* in, int
         op_gemv_body<WD, B>(W, src, batch, lds, epi);
     }
 }
+// Debug: the matrix-core GEMV of the fused kernel (gemv_run_quad on the split-bf16 staged input) as
+// a kernel of its own on plain fp32 input rows; out[b][row] in packed row order.  The projection
+// must fit one K segment.
+template <int WD, int B>
+__global__ void __launch_bounds__(kThreads) k_debug_gemv_quad(PMat W, const float* in, int in_stride, float* out, int batch) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int EPU = WTraits<WD>::EPU;
+    float4* xs = (float4*)lds;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gwave = blockIdx.x * kWaves + wave;
+    const UDiv n_gwaves = UDiv::of(gridDim.x * kWaves);
+    float* myacc = (float*)(lds + kLdsActBytes) + (size_t)wave * kAccFloatsPerWave;
+    if (threadIdx.x < 2) ((lds_u32*)(pairbox_of(xs) + 4 * kPairBoxFloats))[threadIdx.x] = 0u;
+    const Stream<WD, B> S = Stream<WD, B>::make(W, 0, gwave, n_gwaves, true);
+    Stage<WD> ring[kDepthOf<WD>];
+    prefetch_stream<true>(S, ring, lane);
+    const int padquads = S.nup * (EPU / 4), nquads = S.nunits * (EPU / 4);
+    for (int b = 0; b < batch; b++)
+        for (int q0 = 0; q0 < padquads; q0 += kThreads) {   // whole waves call together (see stage_store)
+            const int qi = q0 + (int)threadIdx.x;
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (qi < nquads) t = PlainIO::ld4(in + (size_t)b * in_stride, qi * 4);
+            if (qi < padquads) stage_store<EPU, true>(xs, S.nup, b, qi, t);
+        }
+    __syncthreads();
+    EpiStore epi{out, W.n};
+    gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
+}
+// Debug: rows of a raw projection output y[b][packed rows] in canonical order (same maps as k_dequant).
+__global__ void k_unmap_rows(const float* y, int y_stride, float* out, int n_can, int map, int parity, int row_off, int hd, int batch) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_can * batch; i += gridDim.x * blockDim.x) {
+        const int b = i / n_can, r = i % n_can;
+        int pr;
+        if (map == 1) { int head = r / hd, within = r % hd, half = hd / 2; pr = head * hd + 2 * (within % half) + within / half; }
+        else if (map == 2) pr = 2 * r + parity;
+        else pr = r;
+        out[(size_t)b * n_can + r] = y[(size_t)b * y_stride + pr + row_off];
+    }
+}
 // y holds raw QKV outputs in packed row order [B][rows]
 __global__ void __launch_bounds__(kThreads) op_rope_append(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch, int layer) {
-    if (!inputs_ok(M, KV, tokens, pos, batch)) return;
+    if (!inputs_ok(M, KV, tokens, pos)) return;
     __shared__ float2 rope_s[kMaxBatch * 64];
     for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kThreads) {
         int b = i / (M.hd / 2), f = i % (M.hd / 2);
@@ -111,12 +154,12 @@ __global__ void __launch_bounds__(kThreads) op_rope_append(DevModel M, DevKV KV,
 }
 __global__ void __launch_bounds__(kThreads) op_attn_partial(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch, int layer) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    if (!inputs_ok(M, KV, tokens, pos, batch)) return;
+    if (!inputs_ok(M, KV, tokens, pos)) return;
     attention_phase_plain<kWaves>(M, KV, pos, batch, layer, lds);
 }
 // grid = batch * Hkv; must be launched with the same share (= partial grid / (batch*Hkv)) in `share`
 __global__ void __launch_bounds__(kThreads) op_attn_merge(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch, int share) {
-    if (!inputs_ok(M, KV, tokens, pos, batch)) return;
+    if (!inputs_ok(M, KV, tokens, pos)) return;
     int b = blockIdx.x / M.Hkv, j = blockIdx.x % M.Hkv;
     int ns = attn_nsplit(pos[b], share);
     const int G = M.Hq / M.Hkv;

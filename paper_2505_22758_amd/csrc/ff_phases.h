@@ -15,7 +15,7 @@ namespace ff {
 // tell from the data itself whether its producer has run: it simply re-reads until every tag it
 // needs matches.  Dependencies are thereby resolved by dataflow -- no device-wide barrier, no
 // waiting for store acknowledgements -- and a vector is on the critical path for one store->load
-// hop only (paper Section 3.1 needs a fence + global barrier on its hardware for the same RAW hazard).
+// hop only (paper Section 4.1 needs a fence + global barrier on its hardware for the same RAW hazard).
 #ifndef FF_TLD_AUX
 #define FF_TLD_AUX 17   /* sc0 | sc1 */
 #endif
@@ -73,10 +73,30 @@ __device__ __forceinline__ u32x2 cld2(const cword_t* base, int i) {   // element
 // cannot overwrite a slot another wave has yet to read (the vote after that lies behind the next
 // vote's barrier, which that other wave only reaches after its read).  All threads must take part
 // in every vote, in the same order.
+//
+// The voters are normally all waves of the workgroup (synchronised with the hardware barrier).  With
+// `bar` set they are a GROUP of NT / 64 consecutive waves starting at wave `wave0`, while the
+// workgroup's other waves do unrelated work and never reach a barrier: the group then synchronises
+// through a monotonic arrival counter in LDS (each wave completes its own LDS operations, bumps the
+// counter and re-reads it until the whole group has arrived).
 struct WgVote {
     static constexpr int kMaxSums = 4;
-    u32* slots;   // LDS, 2 * (1 + kMaxSums) * (waves per workgroup) words
+    u32* slots;   // LDS, 2 * (1 + kMaxSums) * (voting waves) words
     u32 par;
+    lds_u32* bar = nullptr;   // arrival counter of a wave group (null: the whole workgroup votes)
+    u32 bar_gen = 0;          // arrivals expected so far
+    int wave0 = 0;            // first wave of the group
+    int nwaves = 0;           // waves in the group (with `bar` only)
+    __device__ __forceinline__ int tid() const { return (int)threadIdx.x - 64 * wave0; }
+    // Barrier among the voters.  Orders LDS accesses only (which is all the groups share).
+    __device__ __forceinline__ void sync() {
+        if (bar == nullptr) { __syncthreads(); return; }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        bar_gen += (u32)nwaves;
+        if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        while ((int)(__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - bar_gen) < 0) __builtin_amdgcn_s_sleep(1);
+        asm volatile("" ::: "memory");
+    }
     template <int NT>
     __device__ __forceinline__ bool all(bool ok) {
         const float none[1] = {0.f};
@@ -92,11 +112,12 @@ struct WgVote {
         u32* f = slots + par * (1 + kMaxSums) * NW;
         par ^= 1u;
         if ((threadIdx.x & 63) == 0) {
-            f[threadIdx.x >> 6] = w;
+            const int wv = (int)(threadIdx.x >> 6) - wave0;
+            f[wv] = w;
 #pragma unroll
-            for (int n = 0; n < N; n++) f[(1 + n) * NW + (threadIdx.x >> 6)] = __float_as_uint(part[n]);
+            for (int n = 0; n < N; n++) f[(1 + n) * NW + wv] = __float_as_uint(part[n]);
         }
-        __syncthreads();
+        sync();
         u32 r = 1u;
 #pragma unroll
         for (int i = 0; i < NW; i++) r &= f[i];
@@ -290,7 +311,7 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
             static_assert(!SPLIT, "the rescaling pass below works on the fp32 layout");
             ss = wave_sum_uniform(ss);
             if (lane == 0) red[tid >> 6] = ss;
-            __syncthreads();
+            vote.sync();
             float tot = 0.f;
 #pragma unroll
             for (int w = 0; w < NT / 64; w++) tot += red[w];
@@ -301,10 +322,10 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
                 v4.x *= r; v4.y *= r; v4.z *= r; v4.w *= r;
                 xb[(size_t)qd * nup + j] = v4;
             }
-            if (b + 1 < batch) __syncthreads();   // `red` is rewritten for the next row
+            if (b + 1 < batch) vote.sync();   // `red` is rewritten for the next row
         }
     }
-    __syncthreads();
+    vote.sync();
     return true;
 }
 
@@ -465,7 +486,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
             }
         }
     }
-    __syncthreads();
+    vote.sync();
     return true;
 }
 
@@ -506,7 +527,7 @@ __device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2
 // ---------------------------------------------------------------- split-KV attention
 // One work item = (sequence b, kv head j, rows [t0, t1) of its cache [+ this step's own k,v]).
 // All G query heads that share kv head j are processed together, so each cached K and V element
-// is read exactly once (paper Section 3.2, core attention: workgroups are split among KV heads and
+// is read exactly once (paper Section 4.2, core attention: workgroups are split among KV heads and
 // hold the queries of that head; the current token's k,v are taken from the exchange buffer, not
 // from the cache).  Result: per query head the partial (max score, denominator, unnormalised
 // output) of a FlashDecoding-style split, in base-2 exponent units.
@@ -517,6 +538,8 @@ __device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2
 // the workgroup, all of which take part).  XIO supplies the exchange accesses (plain buffers for
 // the per-operation kernels, tagged buffers for the fused kernel); returns false on a time-out.
 struct PlainAttnIO {
+    __device__ __forceinline__ int tid() const { return (int)threadIdx.x; }   // the whole workgroup takes part
+    __device__ __forceinline__ void sync() const { __syncthreads(); }
     // Workgroup-collective: the G query rows of kv head j, then (with_cur) this step's own key and
     // value row, as floats into dst[G*HD + 2*HD] (LDS); ends with a workgroup barrier.
     template <int HD, int G, int NT>
@@ -540,7 +563,9 @@ struct PlainAttnIO {
 struct TaggedAttnIO {
     u32 in_tag;    // tag of q / kvcur (this layer's QKV projection)
     u32 out_tag;   // tag of the partials and of attn_o (this layer's attention)
-    WgVote* vote;
+    WgVote* vote;  // the waves that work on the item together (the workgroup, or a group of its waves)
+    __device__ __forceinline__ int tid() const { return vote->tid(); }
+    __device__ __forceinline__ void sync() const { vote->sync(); }
     // Workgroup-collective, same contract as PlainAttnIO::stage_inputs.  The whole input of an
     // item is a few kilobytes (one or two 16-byte pairs per thread), so the workgroup simply
     // re-reads it until the QKV projection's tag is on every element; returns false on a time-out.
@@ -558,7 +583,7 @@ struct TaggedAttnIO {
             bool ok = true;
 #pragma unroll
             for (int u = 0; u < PP; u++) {
-                const int p = min((int)threadIdx.x + u * NT, np - 1);   // clamped: every load is issued
+                const int p = min(tid() + u * NT, np - 1);   // clamped: every load is issued
                 const tagged_t* src = p < NQ2 ? qb + 2 * p : p < NQ2 + NK2 ? kb + 2 * (p - NQ2) : vb + 2 * (p - NQ2 - NK2);
                 r[u] = tld2(src, 0);
             }
@@ -570,10 +595,10 @@ struct TaggedAttnIO {
         if (!done) { atomicCAS(M.status, 0, -51); return false; }
 #pragma unroll
         for (int u = 0; u < PP; u++) {
-            const int p = (int)threadIdx.x + u * NT;
+            const int p = tid() + u * NT;
             if (p < np) { dst[2 * p] = __uint_as_float(r[u].x); dst[2 * p + 1] = __uint_as_float(r[u].z); }
         }
-        __syncthreads();
+        sync();
         return true;
     }
     template <int HD>
@@ -590,7 +615,8 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     constexpr int RPW = 64 / LPR;      // rows per wave load
     constexpr int NS = NW * RPW;       // partial states per workgroup
     constexpr int NT = NW * 64;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = xio.tid();   // 0 .. NT-1 among the NW waves that work on the item
+    const int lane = tid & 63, wave = tid >> 6;
     const int grp = lane / LPR, sub = lane % LPR;
     const float sc = 1.4426950408889634f / sqrtf((float)HD);   // alpha * log2(e)
 
@@ -640,7 +666,7 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     // merge area, then read by every lane from LDS
     float* xin = (float*)lds + 2 * NS * G + (size_t)NS * G * HD;
     const bool ok = xio.template stage_inputs<HD, G, NT>(M, b, j, with_cur, xin);
-    if (ev && threadIdx.x == 0) as_global(ev)[1] = wall_clock64();
+    if (ev && tid == 0) as_global(ev)[1] = wall_clock64();
     if (!ok) return false;   // uniform
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -671,16 +697,16 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     float* sl = sm + NS * G;              // [NS][G]
     float* so = sl + NS * G;              // [NS][G][HD]
     const int si = wave * RPW + grp;
-    if (ev && threadIdx.x == 0) as_global(ev)[2] = wall_clock64();
-    __syncthreads();
+    if (ev && tid == 0) as_global(ev)[2] = wall_clock64();
+    xio.sync();
 #pragma unroll
     for (int g = 0; g < G; g++) {
         if (sub == 0) { sm[si * G + g] = m[g]; sl[si * G + g] = l[g]; }
 #pragma unroll
         for (int e = 0; e < 8; e++) so[((size_t)si * G + g) * HD + sub * 8 + e] = o[g][e];
     }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < G * HD; idx += NT) {
+    xio.sync();
+    for (int idx = tid; idx < G * HD; idx += NT) {
         int g = idx / HD, dim = idx % HD;
         float mx = -INFINITY;
         for (int s = 0; s < NS; s++) mx = fmaxf(mx, sm[s * G + g]);
@@ -693,11 +719,11 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
         size_t hs = ((size_t)b * M.Hq + (j * G + g)) * kMaxSplits + split;
         xio.template store_partial<HD>(M, hs, dim, ot, mx, lt);
     }
-    if (ev && threadIdx.x == 0) as_global(ev)[3] = wall_clock64();
+    if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
     return ok;
 }
 
-// Final merge for (b, kv head j) over nsplit partials (paper Section 3.2: combine per-block maximum
+// Final merge for (b, kv head j) over nsplit partials (paper Section 4.2: combine per-block maximum
 // and denominator, rescale by own/global denominator ratio, sum): writes attn_o[b][h][:].
 // Workgroup-collective; uses 2*G*kMaxSplits floats of LDS.
 template <int HD, int G, int NT>
@@ -748,6 +774,7 @@ template <int HD, int G, int NT>
 __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, u32 out_cnt, float* lds, WgVote& vote, u64* ev = nullptr) {
     float* ms = lds;
     float* ls = lds + G * kMaxSplits;
+    const int tid = vote.tid();   // 0 .. NT-1 among the voting waves
     constexpr int kSB = 16;   // splits gathered per batch of loads
     constexpr u32 kAll = (1u << kSB) - 1;
     // (re)loads the partial outputs of splits s0.. (bit u of mask = split s0+u) for output pair d2
@@ -766,13 +793,13 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
     // waited for: all partials of a head group arrive in one round trip, and whatever is still
     // stale (the last split's rows, typically) is re-read selectively.
     u32x4 r[kSB];
-    const bool pre = (int)threadIdx.x < G * HD / 2;
-    if (pre) issue(r, (b * M.Hq + (j * G + (int)threadIdx.x / (HD / 2))) * kMaxSplits, ((int)threadIdx.x % (HD / 2)) * 2, 0, kAll);
-    __syncthreads();
+    const bool pre = tid < G * HD / 2;
+    if (pre) issue(r, (b * M.Hq + (j * G + tid / (HD / 2))) * kMaxSplits, (tid % (HD / 2)) * 2, 0, kAll);
+    vote.sync();
     bool done = false;
     for (int spins = 0; spins < kSpinLimit && !done; spins++) {
         bool ok = true;
-        for (int idx = threadIdx.x; idx < G * nsplit; idx += NT) {
+        for (int idx = tid; idx < G * nsplit; idx += NT) {
             int g = idx / nsplit, s = idx % nsplit;
             int hs = (b * M.Hq + (j * G + g)) * kMaxSplits + s;
             u32x2 pm = tld1(M.tpart_m, hs), pl = tld1(M.tpart_l, hs);
@@ -784,9 +811,9 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
         if (!done) __builtin_amdgcn_s_sleep(2);
     }
     if (!done) { atomicCAS(M.status, 0, -53); return false; }
-    if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
+    if (ev && tid == 0) as_global(ev)[4] = wall_clock64();
     bool all_ok = true;
-    for (int idx = threadIdx.x; idx < G * HD / 2; idx += NT) {
+    for (int idx = tid; idx < G * HD / 2; idx += NT) {
         int g = idx / (HD / 2), d2 = (idx % (HD / 2)) * 2;
         int hs = (b * M.Hq + (j * G + g)) * kMaxSplits;
         // every thread reduces the maxima and denominators of its head itself (independent LDS
@@ -808,7 +835,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
         const float inv = 1.0f / lt;
         float a0 = 0.f, a1 = 0.f;
         for (int s0 = 0; s0 < nsplit; s0 += kSB) {
-            u32 need = (idx == (int)threadIdx.x && s0 == 0) ? 0u : kAll;   // the first batch is already in flight
+            u32 need = (idx == tid && s0 == 0) ? 0u : kAll;   // the first batch is already in flight
             bool ok = false;
             for (int spins = 0; spins < kSpinLimit && !ok; spins++) {
                 issue(r, hs, d2, s0, need);
@@ -827,7 +854,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
         }
         cst2(M.cattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, out_cnt);
     }
-    if (ev && threadIdx.x == 0) as_global(ev)[5] = wall_clock64();
+    if (ev && tid == 0) as_global(ev)[5] = wall_clock64();
     return vote.all<NT>(all_ok);
 }
 
@@ -939,7 +966,7 @@ struct EpiQKVTagged {   // pos: positions of this step, staged in LDS
     }
 };
 struct EpiDeltaTagged {   // projections feeding the residual stream: publish the output, the next
-    cword_t* delta; int d; u32 tag;    // normalised staging adds it (paper Section 3.2: added to the residual)
+    cword_t* delta; int d; u32 tag;    // normalised staging adds it (paper Section 4.2: added to the residual)
     __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const { cst2(delta + (size_t)b * d + 2 * pair, v0, v1, tag); }
 };
 struct EpiSwiGLUTagged {   // packed rows (2i, 2i+1) = (gate_i, up_i):  h_i = silu(gate_i) * up_i

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -153,10 +154,9 @@ struct ff_model {
     std::vector<PLayer> host_layers;
     std::vector<char> layer_loaded;
     bool head_loaded;
-    uint32_t bar_gen;
-    int rows_clean = 0;   // sequences whose compact exchange rows the last fused launch wrote (or that were re-initialised since)
     int n_cta;
     size_t lds_bytes;
+    int mute_wg = -1;   // test hook (ff_debug_mute_workgroup)
 };
 struct ff_kv {
     ff_model* model;
@@ -218,12 +218,10 @@ int check_step_args(ff_model* m, const int32_t* tokens, const int32_t* pos, ff_k
 template <int WD, int B>
 int launch_gemv(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st) {
     auto kern = op_gemv<WD, B>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        int rc = set_lds(kern, m->lds_bytes);
-        if (rc) return rc;
-        attr_set = true;
-    }
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)m->lds_bytes); });
+    if (attr_err != hipSuccess) return fail(FF_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(attr_err));
     kern<<<m->n_cta, kThreads, m->lds_bytes, st>>>(W, in, in_stride, out, batch, epi);
     return FF_OK;
 }
@@ -281,7 +279,6 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     m->scratch = (uint8_t*)scratch_dev;
     m->layer_loaded.assign(cfg->n_layers, 0);
     m->head_loaded = false;
-    m->bar_gen = 0;
     m->n_cta = prop.multiProcessorCount;
     m->lds_bytes = kLdsFusedBytes;
     if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
@@ -315,6 +312,9 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     hipError_t e = hipMemcpyAsync(m->packed + P.layers_tab, m->host_layers.data(), sizeof(PLayer) * cfg->n_layers, hipMemcpyHostToDevice, st);
     if (e == hipSuccess) {
         k_fill_u32<<<256, 256, 0, st>>>((u32*)m->scratch, P.scratch_bytes / 4, 0u);
+        // a model for single sequences never sees its batch grow: its one row is initialised here
+        // and ff_decode_step launches no k_scrub_rows
+        if (cfg->max_batch == 1) k_scrub_rows<<<64, kThreads, 0, st>>>(m->dev, 1);
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(st);   // host_layers is pageable: finish the copy before returning
@@ -400,7 +400,7 @@ int ff_kv_alloc(ff_model* m, int32_t batch, int32_t max_ctx, void* kv_dev, size_
     size_t cache = align256((size_t)c.n_layers * batch * c.n_kv_heads * 2 * (size_t)max_ctx * c.head_dim * 2);
     kv->dev.base = (bf16_t*)kv_dev;
     kv->dev.rope = (const float2*)((uint8_t*)kv_dev + cache);
-    kv->dev.max_ctx = max_ctx; kv->dev.batch = batch; kv->dev.seq0 = 0;
+    kv->dev.max_ctx = max_ctx; kv->dev.batch = batch; kv->dev.seq0 = 0; kv->dev.step_batch = batch;
     int n = max_ctx * (c.head_dim / 2);
     k_rope_table<<<(n + 255) / 256, 256, 0, (hipStream_t)stream>>>((float2*)kv->dev.rope, max_ctx, c.head_dim, (double)c.rope_theta);
     hipError_t e = hipGetLastError();
@@ -436,18 +436,21 @@ int ff_kv_free(ff_kv* kv) {
 }
 
 namespace {
-// One pass of the fused kernel over sequences [seq0, seq0 + batch), batch <= fused_pass_rows.
-int fused_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch, int seq0,
-               hipStream_t st) {
-    const int lm_in_kernel = m->dev.lm.wd == m->cfg.wdtype;
+// One pass of the fused kernel over sequences [seq0, seq0 + batch) of a step of step_batch
+// sequences, batch <= fused_pass_rows.  Nothing here depends on host-side state that changes from
+// step to step (exchange tags, write counters and the rows to re-initialise all derive from
+// counters kept on the device), so the launches of a step may be recorded into a HIP graph.
+int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch, int seq0,
+               int step_batch, hipStream_t st) {
+    const int lm_in_kernel = D.lm.wd == m->cfg.wdtype;
     DevKV kvd = kv->dev;
     kvd.seq0 = seq0;
-    if (batch > m->rows_clean) {   // rows a smaller batch left behind: see k_scrub_rows
-        k_scrub_rows<<<64, kThreads, 0, st>>>(m->dev, m->rows_clean, batch);
+    kvd.step_batch = step_batch;
+    if (m->cfg.max_batch > 1) {   // rows a smaller batch left behind: see k_scrub_rows (decides on the device)
+        k_scrub_rows<<<64, kThreads, 0, st>>>(D, batch);
         HIPCHK(hipGetLastError());
     }
-    m->rows_clean = batch;
-    FusedLaunch a{m->dev, kvd, tokens_dev, positions_dev, logits_dev, batch, m->bar_gen, lm_in_kernel, m->n_cta, m->lds_bytes, st};
+    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg};
     const char* what = "";
     const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     hipError_t e = hipErrorInvalidValue;
@@ -457,13 +460,11 @@ int fused_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_
     FF_FUSED_FAMILIES(FF_TRY_FAMILY)
 #undef FF_TRY_FAMILY
     if (e != hipSuccess) return fail(e == hipErrorLaunchOutOfResources ? FF_ERR_UNSUPPORTED : FF_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
-    // exchange tags only grow: every step uses a fresh range, so values of earlier steps never match
-    m->bar_gen += (uint32_t)(kTagsPerLayer * m->cfg.n_layers + 1);
     if (!lm_in_kernel) {   // LM head of a different weight type than the layers: separate launches
         const ff_config& c = m->cfg;
-        op_final_x<<<16, kThreads, 0, st>>>(m->dev.x, m->dev.cx, m->dev.cdelta, batch * c.d_model);
-        op_rmsnorm<<<batch, kThreads, 0, st>>>(m->dev.x, m->dev.gf, m->dev.xn, c.d_model, c.rms_eps);
-        int rc = gemv_op(m, m->dev.lm, m->dev.xn, c.d_model, logits_dev, batch, EPI_STORE, st);
+        op_final_x<<<16, kThreads, 0, st>>>(D.x, D.cx, D.cdelta, batch * c.d_model);
+        op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, D.gf, D.xn, c.d_model, c.rms_eps);
+        int rc = gemv_op(m, D.lm, D.xn, c.d_model, logits_dev, batch, EPI_STORE, st);
         if (rc) return rc;
         HIPCHK(hipGetLastError());
     }
@@ -479,8 +480,8 @@ int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positi
     if (rc) return rc;
     const int rows = fused_pass_rows(m->cfg);
     for (int s0 = 0; s0 < batch; s0 += rows) {
-        rc = fused_pass(m, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(rows, batch - s0), s0,
-                        (hipStream_t)stream);
+        rc = fused_pass(m, m->dev, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(rows, batch - s0),
+                        s0, batch, (hipStream_t)stream);
         if (rc) return rc;
     }
     return FF_OK;
@@ -488,17 +489,17 @@ int ff_decode_step(ff_model* m, const int32_t* tokens_dev, const int32_t* positi
 
 namespace {
 int perop_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch, int seq0,
-               hipStream_t st) {
+               int step_batch, hipStream_t st) {
     int rc = 0;
     DevKV kvd = kv->dev;
     kvd.seq0 = seq0;
+    kvd.step_batch = step_batch;
     const DevModel& D = m->dev;
     const ff_config& c = m->cfg;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if ((rc = set_lds(op_attn_partial, m->lds_bytes))) return rc;
-        attr_set = true;
-    }
+    static std::once_flag once;
+    static int attr_rc = 0;
+    std::call_once(once, [&] { attr_rc = set_lds(op_attn_partial, m->lds_bytes); });
+    if (attr_rc) return fail(FF_ERR_HIP, "hipFuncSetAttribute failed for the attention kernel");
     const int qd = c.n_q_heads * c.head_dim, qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     const int share = std::max(1, m->n_cta / (batch * c.n_kv_heads));
     const int ew_grid = 64;
@@ -530,7 +531,7 @@ int ff_decode_step_perop(ff_model* m, const int32_t* tokens_dev, const int32_t* 
     if (rc) return rc;
     for (int s0 = 0; s0 < batch; s0 += kMaxBatch) {
         rc = perop_pass(m, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(kMaxBatch, batch - s0), s0,
-                        (hipStream_t)stream);
+                        batch, (hipStream_t)stream);
         if (rc) return rc;
     }
     return FF_OK;
@@ -552,26 +553,84 @@ int ff_status(ff_model* m, void* stream) {
     return FF_OK;
 }
 
-int ff_debug_dequant(const ff_model* m, int32_t layer, int32_t which, float* out_dev, void* stream) {
-    if (!m || !out_dev) return fail(FF_ERR_ARG, "null argument");
+}  // extern "C"
+
+namespace {
+// Which packed matrix holds canonical matrix `which`, and how canonical rows map to packed rows.
+struct MatSel { PMat W; int n_can, map, parity, row_off; };
+int select_matrix(const ff_model* m, int32_t layer, int32_t which, MatSel* out) {
     const ff_config& c = m->cfg;
     if (which != FF_MAT_LMHEAD && (layer < 0 || layer >= c.n_layers)) return fail(FF_ERR_ARG, "layer %d out of range", layer);
-    int qr = c.n_q_heads * c.head_dim, kr = c.n_kv_heads * c.head_dim;
-    PMat W;
-    int n_can, map = 0, parity = 0, row_off = 0;
+    const int qr = c.n_q_heads * c.head_dim, kr = c.n_kv_heads * c.head_dim;
     const PLayer* L = which == FF_MAT_LMHEAD ? nullptr : &m->host_layers[layer];
+    MatSel s{};
     switch (which) {
-        case FF_MAT_WQ: W = L->qkv; n_can = qr; map = 1; break;
-        case FF_MAT_WK: W = L->qkv; n_can = kr; map = 1; row_off = qr; break;
-        case FF_MAT_WV: W = L->qkv; n_can = kr; row_off = qr + kr; break;
-        case FF_MAT_WO: W = L->o; n_can = c.d_model; break;
-        case FF_MAT_WGATE: W = L->gu; n_can = c.d_ffn; map = 2; parity = 0; break;
-        case FF_MAT_WUP: W = L->gu; n_can = c.d_ffn; map = 2; parity = 1; break;
-        case FF_MAT_WDOWN: W = L->down; n_can = c.d_model; break;
-        case FF_MAT_LMHEAD: W = m->dev.lm; n_can = c.vocab; break;
+        case FF_MAT_WQ: s.W = L->qkv; s.n_can = qr; s.map = 1; break;
+        case FF_MAT_WK: s.W = L->qkv; s.n_can = kr; s.map = 1; s.row_off = qr; break;
+        case FF_MAT_WV: s.W = L->qkv; s.n_can = kr; s.row_off = qr + kr; break;
+        case FF_MAT_WO: s.W = L->o; s.n_can = c.d_model; break;
+        case FF_MAT_WGATE: s.W = L->gu; s.n_can = c.d_ffn; s.map = 2; s.parity = 0; break;
+        case FF_MAT_WUP: s.W = L->gu; s.n_can = c.d_ffn; s.map = 2; s.parity = 1; break;
+        case FF_MAT_WDOWN: s.W = L->down; s.n_can = c.d_model; break;
+        case FF_MAT_LMHEAD: s.W = m->dev.lm; s.n_can = c.vocab; break;
         default: return fail(FF_ERR_ARG, "unknown matrix id %d", which);
     }
-    k_dequant<<<2048, 256, 0, (hipStream_t)stream>>>(W, out_dev, n_can, map, parity, row_off, c.head_dim);
+    *out = s;
+    return FF_OK;
+}
+template <int WD, int B>
+int launch_debug_quad(ff_model* m, const PMat& W, const float* in, float* out, int batch, hipStream_t st) {
+    auto kern = k_debug_gemv_quad<WD, B>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)m->lds_bytes); });
+    if (attr_err != hipSuccess) return fail(FF_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(attr_err));
+    kern<<<m->n_cta, kThreads, m->lds_bytes, st>>>(W, in, W.k, out, batch);
+    return FF_OK;
+}
+template <int WD>
+int debug_quad_any(ff_model* m, const PMat& W, const float* in, float* out, int batch, hipStream_t st) {
+    if (batch == 2) return launch_debug_quad<WD, 2>(m, W, in, out, batch, st);
+    return launch_debug_quad<WD, 4>(m, W, in, out, batch, st);
+}
+}  // namespace
+
+extern "C" {
+
+int ff_debug_gemv(ff_model* m, int32_t layer, int32_t which, const float* in_dev, float* out_dev, int32_t batch, int32_t path, void* stream) {
+    if (!m || !in_dev || !out_dev) return fail(FF_ERR_ARG, "null argument");
+    if (path != 0 && path != 1) return fail(FF_ERR_ARG, "path must be 0 (vector ALU) or 1 (matrix cores)");
+    const int max_rows = std::min(m->cfg.max_batch, kMaxBatch);
+    if (batch < 1 || batch > max_rows || (path == 1 && batch < 2)) return fail(FF_ERR_ARG, "batch %d not served by this path (model max_batch %d)", batch, m->cfg.max_batch);
+    MatSel s;
+    int rc = select_matrix(m, layer, which, &s);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const PMat& W = s.W;
+    const int epu = W.wd == W_BF16 ? 8 : W.wd == W_INT8 ? 16 : 32;
+    if (path == 1 && (size_t)W.k * 4 * (size_t)(batch <= 2 ? 2 : 4) > (size_t)kLdsActBytes)
+        return fail(FF_ERR_UNSUPPORTED, "matrix-core debug GEMV needs the input rows in one K segment (K = %d)", W.k);
+    (void)epu;
+    // raw output in packed row order: straight into out_dev when rows need no mapping and the matrix
+    // is not shared (LM head, output and down projections), else through the per-op row buffer
+    const bool direct = s.map == 0 && s.row_off == 0 && W.n == s.n_can;
+    float* raw = direct ? out_dev : m->dev.y;
+    if (path == 0) rc = gemv_op(m, W, in_dev, W.k, raw, batch, EPI_STORE, st);
+    else if (W.wd == W_BF16) rc = debug_quad_any<W_BF16>(m, W, in_dev, raw, batch, st);
+    else if (W.wd == W_INT8) rc = debug_quad_any<W_INT8>(m, W, in_dev, raw, batch, st);
+    else rc = debug_quad_any<W_INT4>(m, W, in_dev, raw, batch, st);
+    if (rc) return rc;
+    if (!direct) k_unmap_rows<<<256, 256, 0, st>>>(raw, W.n, out_dev, s.n_can, s.map, s.parity, s.row_off, m->cfg.head_dim, batch);
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+
+int ff_debug_dequant(const ff_model* m, int32_t layer, int32_t which, float* out_dev, void* stream) {
+    if (!m || !out_dev) return fail(FF_ERR_ARG, "null argument");
+    MatSel s;
+    int rc = select_matrix(m, layer, which, &s);
+    if (rc) return rc;
+    k_dequant<<<2048, 256, 0, (hipStream_t)stream>>>(s.W, out_dev, s.n_can, s.map, s.parity, s.row_off, m->cfg.head_dim);
     HIPCHK(hipGetLastError());
     return FF_OK;
 }
@@ -579,6 +638,13 @@ int ff_debug_dequant(const ff_model* m, int32_t layer, int32_t which, float* out
 int ff_debug_timeline(ff_model* m, void* buf_dev) {
     if (!m) return fail(FF_ERR_ARG, "null argument");
     m->dev.dbg = (u64*)buf_dev;
+    return FF_OK;
+}
+
+int ff_debug_mute_workgroup(ff_model* m, int32_t workgroup) {
+    if (!m) return fail(FF_ERR_ARG, "null argument");
+    if (workgroup < -1 || workgroup >= m->n_cta) return fail(FF_ERR_ARG, "workgroup %d outside [-1, %d)", workgroup, m->n_cta);
+    m->mute_wg = workgroup;
     return FF_OK;
 }
 
