@@ -137,6 +137,20 @@ int ff_kv_free(ff_kv *kv);
 int ff_decode_step(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
                    float *logits_dev, int32_t batch, void *stream);
 
+/* For callers that cannot allocate device memory or bring a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation): the same step as ff_decode_step, with the
+ * activation-exchange scratch taken from an array of FF_STATIC_SCRATCH_BYTES that is built into the
+ * library's device code (one copy per GPU, held until the process ends) instead of the model's
+ * scratch_dev; only the model's status word is still used.  Calls no allocating routine.  The
+ * array is shared by every model and call on the GPU and is re-initialised on `stream` at the
+ * start of each call (two small extra launches), so calls need not follow each other on the same
+ * model -- but two calls that overlap in time on one GPU race on it and give undefined results.
+ * FF_ERR_NOMEM if the configuration's scratch (ff_model_bytes) exceeds the array: it holds the tiny
+ * shape at any batch, the 8B shape up to max_batch 2 and the 70B shape at max_batch 1. */
+#define FF_STATIC_SCRATCH_BYTES (8u << 20)
+int ff_decode_step_static(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
+                          float *logits_dev, int32_t batch, void *stream);
+
 /* Same step as separate per-operation launches (baseline of the paper's latency tables).  After a
  * range error the cache is unchanged and logits_dev holds undefined values. */
 int ff_decode_step_perop(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,

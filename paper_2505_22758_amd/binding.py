@@ -25,7 +25,7 @@ FF_MAT = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 
 
 EXPORTS = ["ff_last_error", "ff_model_bytes", "ff_model_create", "ff_model_load_layer", "ff_model_load_head",
            "ff_model_load", "ff_model_free", "ff_kv_bytes", "ff_kv_alloc", "ff_kv_fill", "ff_kv_read", "ff_kv_free",
-           "ff_decode_step", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_mute_workgroup",
+           "ff_decode_step", "ff_decode_step_static", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_mute_workgroup",
            "ff_fused_schedule"]
 
 
@@ -64,6 +64,7 @@ _lib.ff_kv_read.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.ff_kv_free.argtypes = [_vp]
 _lib.ff_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.ff_decode_step_perop.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
+_lib.ff_decode_step_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.ff_status.argtypes = [_vp, _vp]
 _lib.ff_debug_dequant.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.ff_debug_gemv.argtypes = [_vp, _i32, _i32, _vp, _vp, _i32, _i32, _vp]
@@ -180,6 +181,13 @@ def ff_decode_step(model: int, tokens: torch.Tensor, positions: torch.Tensor, kv
                    stream=None) -> None:
     assert tokens.dtype == torch.int32 and positions.dtype == torch.int32 and logits.dtype == torch.float32
     _check(_lib.ff_decode_step(model, _ptr(tokens), _ptr(positions), kv, _ptr(logits), batch, _stream(stream)), "ff_decode_step")
+
+
+def ff_decode_step_static(model: int, tokens: torch.Tensor, positions: torch.Tensor, kv: int, logits: torch.Tensor, batch: int,
+                          stream=None) -> None:
+    assert tokens.dtype == torch.int32 and positions.dtype == torch.int32 and logits.dtype == torch.float32
+    _check(_lib.ff_decode_step_static(model, _ptr(tokens), _ptr(positions), kv, _ptr(logits), batch, _stream(stream)),
+           "ff_decode_step_static")
 
 
 def ff_decode_step_perop(model: int, tokens: torch.Tensor, positions: torch.Tensor, kv: int, logits: torch.Tensor,

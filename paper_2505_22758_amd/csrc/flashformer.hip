@@ -14,6 +14,12 @@
 
 using namespace ff;
 
+// Exchange scratch of ff_decode_step_static: one copy per GPU the library runs on, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels receive
+// the device address obtained from it (static_scratch_ptr below).
+constexpr size_t kStaticScratchBytes = FF_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local std::string g_err;
@@ -532,6 +538,68 @@ int ff_decode_step_perop(ff_model* m, const int32_t* tokens_dev, const int32_t* 
     for (int s0 = 0; s0 < batch; s0 += kMaxBatch) {
         rc = perop_pass(m, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(kMaxBatch, batch - s0), s0,
                         batch, (hipStream_t)stream);
+        if (rc) return rc;
+    }
+    return FF_OK;
+}
+
+}  // extern "C"
+
+namespace {
+// Device address of this GPU's copy of the static scratch array (looked up once per device).
+int static_scratch_ptr(uint8_t** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static uint8_t* ptrs[kMaxDevices] = {};
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(FF_ERR_UNSUPPORTED, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255)) return fail(FF_ERR_HIP, "static scratch array has no usable device address");
+        ptrs[dev] = (uint8_t*)p;
+    }
+    *out = ptrs[dev];
+    return FF_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int ff_decode_step_static(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch,
+                          void* stream) {
+    int rc = check_step_args(m, tokens_dev, positions_dev, kv, logits_dev, batch);
+    if (rc) return rc;
+    const Plan& P = m->plan;
+    if (P.scratch_bytes > kStaticScratchBytes)
+        return fail(FF_ERR_NOMEM, "this configuration needs %zu bytes of exchange scratch, the static array holds %zu", P.scratch_bytes,
+                    kStaticScratchBytes);
+    uint8_t* s = nullptr;
+    if ((rc = static_scratch_ptr(&s))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    // the model's exchange pointers moved onto the static array (same layout); the status word and
+    // the optional timeline stay with the model, where ff_status looks for them
+    DevModel D = m->dev;
+    D.x = (float*)(s + P.x); D.xn = (float*)(s + P.xn); D.q = (float*)(s + P.q); D.kvcur = (float*)(s + P.kvcur);
+    D.attn_o = (float*)(s + P.attn_o); D.h = (float*)(s + P.h); D.y = (float*)(s + P.y);
+    D.part_m = (float*)(s + P.part_m); D.part_l = (float*)(s + P.part_l); D.part_o = (float*)(s + P.part_o);
+    D.cx = (u32*)(s + P.cx); D.cx2 = (u32*)(s + P.cx2); D.cdelta = (u32*)(s + P.cdelta); D.tq = (u32x2*)(s + P.tq);
+    D.tkvcur = (u32x2*)(s + P.tkvcur); D.cattn_o = (u32*)(s + P.cattn_o); D.ch = (u32*)(s + P.ch);
+    D.stepctr = (u32*)(s + P.stepctr);
+    D.tpart_m = (u32x2*)(s + P.tpart_m); D.tpart_l = (u32x2*)(s + P.tpart_l); D.tpart_o = (u32x2*)(s + P.tpart_o);
+    // The array keeps whatever the last call (of any model) left: everything this step's kernels
+    // test before they write it is cleared first -- tags and step counter to zero (a fill kernel,
+    // not a memset node, so the call may be recorded into a HIP graph), then the write-counter
+    // bits of the compact rows (k_scrub_rows sees "0 rows clean").
+    k_fill_u32<<<256, 256, 0, st>>>((u32*)s, P.scratch_bytes / 4, 0u);
+    k_scrub_rows<<<64, kThreads, 0, st>>>(D, std::min(batch, fused_pass_rows(m->cfg)));
+    HIPCHK(hipGetLastError());
+    const int rows = fused_pass_rows(m->cfg);
+    for (int s0 = 0; s0 < batch; s0 += rows) {
+        rc = fused_pass(m, D, tokens_dev + s0, positions_dev + s0, kv, logits_dev + (size_t)s0 * m->cfg.vocab, std::min(rows, batch - s0), s0,
+                        batch, st);
         if (rc) return rc;
     }
     return FF_OK;
