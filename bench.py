@@ -21,11 +21,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per fused launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # a plain copy of known size); the summary under profiles/ gives the commands and the raw figures.
-TRAFFIC_FILES = {"llama3-8b-bf16-b1-ctx1024": "profiles/fused_decode_kernel_llama3-8b-bf16-b1-ctx1024.md"}
-
-
 def measured_traffic(workload):
-    path = os.path.join(ROOT, TRAFFIC_FILES.get(workload, ""))
+    """traffic_bytes_per_launch of the workload's committed rocprofv3 summary, if it has one."""
+    path = os.path.join(ROOT, "profiles", f"fused_decode_kernel_{workload}.md")
     if not os.path.isfile(path):
         return None
     for line in open(path):
@@ -95,6 +93,7 @@ def main():
     ap.add_argument("--ctx", type=int, default=0, help="override the workload's KV context (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-perop", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the streaming-read ceiling measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-traffic kernel to scale rocprofv3 --pmc counters by)")
     args = ap.parse_args()
@@ -116,27 +115,14 @@ def main():
     total_steps = args.warmup + args.steps
     max_ctx = ctx + total_steps + 1
 
-    dec = binding.Decoder(shape, wdtype, max_batch=batch, device=dev)
-    for l in range(shape.n_layers):
-        lw = synth.make_layer(shape, seed, l, wdtype, dev)
-        dec.load_layer(l, lw)
-        torch.cuda.synchronize()
-        del lw
-        if shape.n_layers > 40 and (l + 1) % 8 == 0:   # a long set-up says that it is alive
-            print(f"bench.py: layer {l + 1}/{shape.n_layers} generated and packed", file=sys.stderr, flush=True)
-    hw = synth.make_head(shape, seed, wdtype, dev)
-    dec.load_head(hw)
+    # weights and cache prefill: the library's device-side generator (same bits as synth.py, tested)
+    dec = binding.Decoder.synthetic(shape, seed, wdtype, max_batch=batch, device=dev)
     torch.cuda.synchronize()
-    del hw
-    torch.cuda.empty_cache()
 
     def new_cache():
         buf = torch.zeros(binding.ff_kv_bytes(dec.model, batch, max_ctx), dtype=torch.uint8, device=dev)
         kv = binding.ff_kv_alloc(dec.model, batch, max_ctx, buf)
-        for l in range(shape.n_layers):
-            for b in range(batch):
-                k, v = synth.make_kv_prefill(shape, seed, l, b, ctx, dev)
-                binding.ff_kv_fill(kv, l, b, 0, k, v)
+        binding.ff_kv_fill_synthetic(kv, seed, ctx)
         torch.cuda.synchronize()
         return kv, buf
 
@@ -166,6 +152,23 @@ def main():
         del a, b
         torch.cuda.empty_cache()
 
+    # streaming-read ceiling of this machine (what a kernel that only streams 4 GiB achieves)
+    ceiling_gbs = None
+    if not args.no_ceiling:
+        probe = torch.empty(1 << 30, dtype=torch.float32, device=dev)   # 4 GiB
+        probe.fill_(1.0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(2):
+            binding.ff_debug_stream_read(probe)
+        e0.record()
+        for _ in range(5):
+            binding.ff_debug_stream_read(probe)
+        e1.record()
+        torch.cuda.synchronize()
+        ceiling_gbs = 5 * probe.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del probe
+        torch.cuda.empty_cache()
+
     kv, kv_buf = new_cache()
     run(binding.ff_decode_step, kv, 0, args.warmup)
     wall_ms, per_step_ms = run(binding.ff_decode_step, kv, args.warmup, args.steps)
@@ -182,7 +185,8 @@ def main():
         "metric": "per-token decode latency", "value": ms_per_step * 1e3, "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": {0: "bf16", 1: "int8", 2: "int4"}[wdtype] + " weights, f32 activations/accumulate",
+        "dtype": {0: "bf16", 1: "int8", 2: "int4"}[wdtype] + " weights, f32 accumulate; activations exchanged between phases as f32 rounded to 22 mantissa bits"
+                 + ("" if batch == 1 else ", staged projection inputs as bf16 head + bf16 remainder (17 bits)"),
         "data": "synthetic",
         "config": {"workload": args.workload if not (args.batch or args.ctx) else f"{args.workload} with batch {batch}, ctx {ctx}",
                    "batch": batch, "kv_context": ctx,
@@ -191,7 +195,8 @@ def main():
         "latency_us_p10_p50_p90": [float(np.percentile(per_step_ms, q)) * 1e3 for q in (10, 50, 90)],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.batch or args.ctx) else measured_traffic(args.workload),
-                     "kernel": "fused_decode_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": alg_bytes},
+                     "kernel": "fused_decode_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": alg_bytes,
+                     "ceiling_gbs": ceiling_gbs, "frac_of_ceiling": None if ceiling_gbs is None else achieved / ceiling_gbs},
     }
 
     if not args.no_perop:

@@ -104,6 +104,15 @@ int ff_model_load_head(ff_model *m, const ff_head_weights *w, void *stream);
 int ff_model_load(const ff_config *cfg, const ff_layer_weights *layers, const ff_head_weights *head,
                   void *packed_dev, size_t packed_bytes, void *scratch_dev, size_t scratch_bytes,
                   void *stream, ff_model **out);
+
+/* Creates a model (as ff_model_create) and fills it on the device with the seeded synthetic weights
+ * of this package's input generators (paper_2505_22758_amd/synth.py is the definition: a counter
+ * hash of (seed, tensor name, element index); bf16 tensors ~N(0, 0.02), gains 1 + N(0, 0.02), int8
+ * codes uniform in [-127, 127] with fp16 row scales, int4 codes and zeros uniform in [0, 15] with
+ * fp16 group scales).  Bit-identical to generating the canonical tensors with synth.py and loading
+ * them with ff_model_load (tested); several hundred times faster for the 139 GB 70B shape. */
+int ff_model_load_synthetic(const ff_config *cfg, uint64_t seed, void *packed_dev, size_t packed_bytes,
+                            void *scratch_dev, size_t scratch_bytes, void *stream, ff_model **out);
 int ff_model_free(ff_model *m);
 
 /* KV cache for `batch` independent sequences of at most max_ctx positions (paper Section 5.2:
@@ -117,6 +126,9 @@ int ff_kv_fill(ff_kv *kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, c
                const void *v_dev, void *stream);
 int ff_kv_read(ff_kv *kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, void *k_dev, void *v_dev,
                void *stream);
+/* Fills rows [0, n_ctx) of every (layer, sequence) with the seeded synthetic prefill of synth.py
+ * (~N(0, 1) in bf16, taken as already rotated keys); same bits as ff_kv_fill of make_kv_prefill. */
+int ff_kv_fill_synthetic(ff_kv *kv, uint64_t seed, int32_t n_ctx, void *stream);
 int ff_kv_free(ff_kv *kv);
 
 /* One decode step (paper Section 4.2, attention and GLU schedules; final norm and LM head added).
@@ -191,6 +203,12 @@ int ff_debug_gemv(ff_model *m, int32_t layer, int32_t which, const float *in_dev
  *                     then 8 about its attention work (start, queries seen, rows done, partial
  *                     stored, split maxima seen and merged output stored if it merges, end) */
 int ff_debug_timeline(ff_model *m, void *buf_dev);
+
+/* Measurement aid: one launch that reads `bytes` of buf_dev once with the access pattern of the
+ * decode kernels' weight stream (n_workgroups workgroups of 256 threads, one contiguous slab each,
+ * eight 16-byte non-temporal loads in flight per lane).  Timed by the benchmark to report the
+ * streaming-read ceiling of the machine beside the nominal HBM peak. */
+int ff_debug_stream_read(const void *buf_dev, size_t bytes, int32_t n_workgroups, void *stream);
 
 /* Test hook for the FF_ERR_TIMEOUT path: while `workgroup` is >= 0, that workgroup of every
  * following fused step leaves at once without publishing anything, so each workgroup that needs its

@@ -24,8 +24,8 @@ FF_W_BF16, FF_W_INT8_PC, FF_W_INT4_G128 = 0, 1, 2
 FF_MAT = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 6, "lm_head": 7}
 
 EXPORTS = ["ff_last_error", "ff_model_bytes", "ff_model_create", "ff_model_load_layer", "ff_model_load_head",
-           "ff_model_load", "ff_model_free", "ff_kv_bytes", "ff_kv_alloc", "ff_kv_fill", "ff_kv_read", "ff_kv_free",
-           "ff_decode_step", "ff_decode_step_static", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_mute_workgroup",
+           "ff_model_load", "ff_model_load_synthetic", "ff_model_free", "ff_kv_bytes", "ff_kv_alloc", "ff_kv_fill", "ff_kv_read", "ff_kv_fill_synthetic", "ff_kv_free",
+           "ff_decode_step", "ff_decode_step_static", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_stream_read", "ff_debug_mute_workgroup",
            "ff_fused_schedule"]
 
 
@@ -56,11 +56,14 @@ _lib.ff_model_load_layer.argtypes = [_vp, _i32, C.POINTER(ff_layer_weights), _vp
 _lib.ff_model_load_head.argtypes = [_vp, C.POINTER(ff_head_weights), _vp]
 _lib.ff_model_load.argtypes = [C.POINTER(ff_config), C.POINTER(ff_layer_weights), C.POINTER(ff_head_weights), _vp, _sz, _vp,
                                _sz, _vp, C.POINTER(_vp)]
+_lib.ff_model_load_synthetic.argtypes = [C.POINTER(ff_config), C.c_uint64, _vp, _sz, _vp, _sz, _vp, C.POINTER(_vp)]
 _lib.ff_model_free.argtypes = [_vp]
 _lib.ff_kv_bytes.argtypes = [_vp, _i32, _i32, C.POINTER(_sz)]
 _lib.ff_kv_alloc.argtypes = [_vp, _i32, _i32, _vp, _sz, _vp, C.POINTER(_vp)]
 _lib.ff_kv_fill.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.ff_kv_read.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
+_lib.ff_kv_fill_synthetic.argtypes = [_vp, C.c_uint64, _i32, _vp]
+_lib.ff_debug_stream_read.argtypes = [_vp, _sz, _i32, _vp]
 _lib.ff_kv_free.argtypes = [_vp]
 _lib.ff_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.ff_decode_step_perop.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
@@ -148,6 +151,14 @@ def ff_model_load(cfg: ff_config, layers: list, head: dict, packed: torch.Tensor
     return h.value
 
 
+def ff_model_load_synthetic(cfg: ff_config, seed: int, packed: torch.Tensor, scratch: torch.Tensor, stream=None) -> int:
+    h = _vp()
+    _check(_lib.ff_model_load_synthetic(C.byref(cfg), seed & 0xFFFFFFFFFFFFFFFF, _ptr(packed), packed.numel() * packed.element_size(),
+                                        _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream), C.byref(h)),
+           "ff_model_load_synthetic")
+    return h.value
+
+
 def ff_model_free(model: int) -> None:
     _check(_lib.ff_model_free(model), "ff_model_free")
 
@@ -171,6 +182,14 @@ def ff_kv_fill(kv: int, layer: int, seq: int, pos0: int, k: torch.Tensor, v: tor
 
 def ff_kv_read(kv: int, layer: int, seq: int, pos0: int, k_out: torch.Tensor, v_out: torch.Tensor, stream=None) -> None:
     _check(_lib.ff_kv_read(kv, layer, seq, pos0, k_out.shape[0], _ptr(k_out), _ptr(v_out), _stream(stream)), "ff_kv_read")
+
+
+def ff_kv_fill_synthetic(kv: int, seed: int, n_ctx: int, stream=None) -> None:
+    _check(_lib.ff_kv_fill_synthetic(kv, seed & 0xFFFFFFFFFFFFFFFF, n_ctx, _stream(stream)), "ff_kv_fill_synthetic")
+
+
+def ff_debug_stream_read(buf: torch.Tensor, n_workgroups: int = 256, stream=None) -> None:
+    _check(_lib.ff_debug_stream_read(_ptr(buf), buf.numel() * buf.element_size(), n_workgroups, _stream(stream)), "ff_debug_stream_read")
 
 
 def ff_kv_free(kv: int) -> None:
@@ -238,6 +257,20 @@ class Decoder:
         self.model = ff_model_create(self.cfg, self.packed, self.scratch)
         self.kv = None
         self.kv_buf = None
+
+    @classmethod
+    def synthetic(cls, shape, seed: int, wdtype=FF_W_BF16, max_batch=1, quant_lm_head=True, device="cuda:0"):
+        """A decoder filled on the device with the seeded synthetic weights (ff_model_load_synthetic)."""
+        self = cls.__new__(cls)
+        self.shape, self.device = shape, torch.device(device)
+        self.cfg = make_config(shape, wdtype, max_batch, quant_lm_head)
+        pb, sb = ff_model_bytes(self.cfg)
+        self.packed = torch.empty(pb, dtype=torch.uint8, device=self.device)
+        self.scratch = torch.empty(sb, dtype=torch.uint8, device=self.device)
+        self.model = ff_model_load_synthetic(self.cfg, seed, self.packed, self.scratch)
+        self.kv = None
+        self.kv_buf = None
+        return self
 
     def load_layer(self, layer: int, lw: dict):
         ff_model_load_layer(self.model, layer, lw)

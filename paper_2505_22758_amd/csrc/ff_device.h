@@ -79,7 +79,7 @@ struct DevModel {
     float* part_o;   //                            [B][Hq][kMaxSplits][hd]
     // tagged exchange buffers of the fused kernel: (fp32 bits, tag) pairs, same shapes as above
     u32x2* tq;  u32x2* tkvcur;
-    // the vectors every workgroup reads whole, in the compact 4-byte format (value with a 4-bit write
+    // the vectors every workgroup reads whole, in the compact 4-byte format (value with a 2-bit write
     // counter in its lowest mantissa bits): residual stream (two buffers), sublayer output, merged
     // attention output, SwiGLU output
     u32* cx;  u32* cx2;  u32* cdelta;  u32* cattn_o;  u32* ch;

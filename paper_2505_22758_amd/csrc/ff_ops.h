@@ -46,23 +46,24 @@ __global__ void __launch_bounds__(kThreads) k_scrub_rows(DevModel M, int batch) 
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < per_row * (size_t)(row1 - row0); i += (size_t)gridDim.x * kThreads) {
         const int r = row0 + (int)(i / per_row);
         size_t e = i % per_row;
-        if (e < (size_t)M.d) { as_global(M.cx)[(size_t)r * M.d + e] = (sl - 1u) & 15u; continue; }
+        if (e < (size_t)M.d) { as_global(M.cx)[(size_t)r * M.d + e] = (sl - 1u) & kCntMask; continue; }
         e -= M.d;
-        if (e < (size_t)M.d) { as_global(M.cx2)[(size_t)r * M.d + e] = (sl - 1u) & 15u; continue; }
+        if (e < (size_t)M.d) { as_global(M.cx2)[(size_t)r * M.d + e] = (sl - 1u) & kCntMask; continue; }
         e -= M.d;
-        if (e < (size_t)M.d) { as_global(M.cdelta)[(size_t)r * M.d + e] = (2u * sl - 1u) & 15u; continue; }
+        if (e < (size_t)M.d) { as_global(M.cdelta)[(size_t)r * M.d + e] = (2u * sl - 1u) & kCntMask; continue; }
         e -= M.d;
-        if (e < (size_t)qd) { as_global(M.cattn_o)[(size_t)r * qd + e] = (sl - 1u) & 15u; continue; }
+        if (e < (size_t)qd) { as_global(M.cattn_o)[(size_t)r * qd + e] = (sl - 1u) & kCntMask; continue; }
         e -= qd;
-        as_global(M.ch)[(size_t)r * M.F + e] = (sl - 1u) & 15u;
+        as_global(M.ch)[(size_t)r * M.F + e] = (sl - 1u) & kCntMask;
     }
 }
 
 __global__ void __launch_bounds__(kThreads) op_final_x(float* x, const u32* tx, const u32* tdelta, int n) {
     for (int i = blockIdx.x * kThreads + threadIdx.x; i < n; i += gridDim.x * kThreads)
-        x[i] = __uint_as_float(tx[i] & ~15u) + __uint_as_float(tdelta[i] & ~15u);
+        x[i] = __uint_as_float(tx[i] & ~kCntMask) + __uint_as_float(tdelta[i] & ~kCntMask);
 }
 enum { EPI_STORE = 0, EPI_RESIDUAL = 1 };
+enum { REPACK_COPY = 0, REPACK_ROPE = 1, REPACK_INTERLEAVE = 2 };
 template <int WD, int B, class Epi>
 __device__ __forceinline__ void op_gemv_body(const PMat& W, const ActSrc& src, int batch, uint8_t* lds, Epi& epi) {
     constexpr int EPU = WTraits<WD>::EPU;
@@ -179,7 +180,6 @@ __global__ void __launch_bounds__(kThreads) op_swiglu(DevModel M, int batch) {
 }
 
 // ---------------------------------------------------------------- loaders and utilities
-enum { REPACK_COPY = 0, REPACK_ROPE = 1, REPACK_INTERLEAVE = 2 };
 // dst row r  <-  source row per mode.  row_bytes is a multiple of 2.
 __global__ void __launch_bounds__(kThreads) k_repack_rows(uint8_t* dst, const uint8_t* src_a, const uint8_t* src_b, int n_rows,
                                                          size_t row_bytes, int mode, int hd) {
@@ -245,6 +245,119 @@ __global__ void k_dequant(PMat W, float* out, int n_can, int map, int parity, in
         }
         out[i] = v;
     }
+}
+// ---------------------------------------------------------------- seeded synthetic tensors
+// Device-side twin of the seeded input generators (the Python module synth.py of this package): a
+// value is a function of (tensor key, element index) only, through a counter-based 32-bit hash, so
+// both sides produce identical bits.  Integer operations, one int -> fp32 conversion, single fp32
+// multiplies / adds (no contraction) and round-to-nearest-even narrowing only.
+__device__ __forceinline__ u32 synth_mix(u32 x) {
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ u32 synth_hash(u32 key, u32 stream, u64 idx) {
+    const u32 k = key ^ (stream * 0x85EBCA6Bu);
+    return synth_mix(synth_mix((u32)idx ^ k) + (u32)(idx >> 32) * 0x27D4EB2Fu + 0x165667B1u);
+}
+// approx N(mean, std): sum of four 16-bit uniforms, centred, scaled (scale = std / 37837.22 in fp32)
+__device__ __forceinline__ bf16_t synth_normal_bf16(u32 key, u64 idx, float scale, float mean) {
+    const u32 h1 = synth_hash(key, 0u, idx), h2 = synth_hash(key, 1u, idx);
+    const int s = (int)((h1 & 0xFFFFu) + (h1 >> 16) + (h2 & 0xFFFFu) + (h2 >> 16)) - 131070;
+    float v = (float)s * scale;
+    asm volatile("" : "+v"(v));   // the product is rounded before the mean is added (no fused multiply-add)
+    if (mean != 0.f) v = v + mean;
+    return f_to_bf(v);
+}
+__device__ __forceinline__ int synth_uniform_int(u32 key, u64 idx, int lo, int hi) {
+    const u64 span = (u64)(hi - lo + 1);
+    return (int)(((u64)synth_hash(key, 2u, idx) * span) >> 32) + lo;
+}
+// fp16 bits of c * (1 + u / 4), u in [0, 1) with 16 bits of resolution
+__device__ __forceinline__ f16_t synth_scale_f16(u32 key, u64 idx, float c) {
+    const float u = (float)(synth_hash(key, 3u, idx) >> 16) * (1.0f / 65536.0f);
+    const _Float16 h = (_Float16)(c * (1.0f + 0.25f * u));   // 1 + u / 4 is exact in fp32 either way; one rounded product
+    f16_t bits;
+    __builtin_memcpy(&bits, &h, 2);
+    return bits;
+}
+struct SynthMat {   // one canonical matrix [n][k] of the seeded recipe
+    u32 key_w, key_s, key_z;
+    int k;
+    float c_scale;   // int8: 0.02 / 73.6, int4: 0.02 / 6.5 (fp32)
+};
+// Fills packed rows [0, n_rows) of a matrix part: packed row r holds canonical row src(r) of A (or,
+// interleaved mode, of A / B alternately), same row maps as k_repack_rows.  dst_w rows of row_bytes;
+// dst_s / dst_z rows of one fp16 (int8) or k/128 fp16 (int4).
+__global__ void __launch_bounds__(kThreads) k_synth_rows(uint8_t* dst_w, f16_t* dst_s, f16_t* dst_z, int n_rows, int wd, SynthMat A, SynthMat B,
+                                                        int mode, int hd, float w_scale) {
+    for (int r = blockIdx.x; r < n_rows; r += gridDim.x) {
+        int sr;
+        const SynthMat* Mt = &A;
+        if (mode == REPACK_ROPE) {
+            int head = r / hd, within = r % hd;
+            sr = head * hd + within / 2 + (within & 1) * (hd / 2);
+        } else if (mode == REPACK_INTERLEAVE) {
+            sr = r / 2;
+            if (r & 1) Mt = &B;
+        } else {
+            sr = r;
+        }
+        const int k = Mt->k;
+        const u64 e0 = (u64)sr * (u64)k;
+        if (wd == W_BF16) {
+            bf16_t* d = (bf16_t*)(dst_w + (size_t)r * k * 2);
+            for (int c = threadIdx.x; c < k; c += kThreads) d[c] = synth_normal_bf16(Mt->key_w, e0 + c, w_scale, 0.f);
+        } else if (wd == W_INT8) {
+            int8_t* d = (int8_t*)(dst_w + (size_t)r * k);
+            for (int c = threadIdx.x; c < k; c += kThreads) d[c] = (int8_t)synth_uniform_int(Mt->key_w, e0 + c, -127, 127);
+            if (threadIdx.x == 0) dst_s[r] = synth_scale_f16(Mt->key_s, (u64)sr, Mt->c_scale);
+        } else {
+            uint8_t* d = dst_w + (size_t)r * (k / 2);
+            for (int c = threadIdx.x; c < k / 2; c += kThreads) {
+                const int lo = synth_uniform_int(Mt->key_w, e0 + 2 * c, 0, 15), hi = synth_uniform_int(Mt->key_w, e0 + 2 * c + 1, 0, 15);
+                d[c] = (uint8_t)(lo | (hi << 4));
+            }
+            const int ng = k / 128;
+            for (int g = threadIdx.x; g < ng; g += kThreads) {
+                dst_s[(size_t)r * ng + g] = synth_scale_f16(Mt->key_s, (u64)sr * ng + g, Mt->c_scale);
+                const _Float16 z = (_Float16)(float)synth_uniform_int(Mt->key_z, (u64)sr * ng + g, 0, 15);
+                f16_t zb;
+                __builtin_memcpy(&zb, &z, 2);
+                dst_z[(size_t)r * ng + g] = zb;
+            }
+        }
+    }
+}
+// bf16 vector / table of n elements ~ N(mean, std)
+__global__ void k_synth_normal(bf16_t* dst, size_t n, u32 key, float scale, float mean) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = synth_normal_bf16(key, i, scale, mean);
+}
+// Cache rows [0, n_ctx) of one (layer, sequence): canonical element (t, j, e) -> plane (j, K|V) row t
+__global__ void k_synth_kv(bf16_t* plane0, size_t plane_elems, int Hkv, int hd, int n_ctx, u32 key_k, u32 key_v, float scale) {
+    const size_t tot = (size_t)n_ctx * Hkv * hd;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < tot; i += (size_t)gridDim.x * blockDim.x) {
+        const int e = i % hd, j = (i / hd) % Hkv;
+        const size_t t = i / ((size_t)hd * Hkv);
+        bf16_t* kp = plane0 + (size_t)j * 2 * plane_elems + t * hd + e;
+        kp[0] = synth_normal_bf16(key_k, i, scale, 0.f);
+        kp[plane_elems] = synth_normal_bf16(key_v, i, scale, 0.f);
+    }
+}
+// Streams `bytes` once (16-byte non-temporal loads, 8 in flight per lane, one contiguous slab per
+// workgroup): the read ceiling the decode kernels are measured against.
+__global__ void __launch_bounds__(kThreads) k_stream_read(const u32x4* __restrict__ p, size_t n16, u32* sink) {
+    const size_t per = n16 / gridDim.x;
+    const FF_GLOBAL u32x4* q = as_global(p) + per * blockIdx.x;
+    u32 acc = 0;
+    size_t i = threadIdx.x;
+    for (; i + 7 * kThreads < per; i += 8 * kThreads) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = __builtin_nontemporal_load(q + i + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < 8; u++) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x12345678u) sink[0] = acc;   // keeps the loads alive
 }
 __global__ void k_fill_u32(u32* p, size_t n, u32 v) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;

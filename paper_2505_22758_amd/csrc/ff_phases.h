@@ -41,22 +41,24 @@ __device__ __forceinline__ u32x4 tld2(const tagged_t* base, int i) {
 
 // ---------------------------------------------------------------- compact exchange format
 // The vectors that every workgroup reads whole (residual stream, sublayer outputs, merged attention
-// output, SwiGLU output) travel as 4-byte words: the fp32 value rounded to 20 mantissa bits, with
-// the low 4 bits of a per-buffer WRITE COUNTER in the freed bits.  Every element of such a buffer
+// output, SwiGLU output) travel as 4-byte words: the fp32 value rounded to 22 mantissa bits, with
+// the low 2 bits of a per-buffer WRITE COUNTER in the freed bits.  Every element of such a buffer
 // (for the sequences of the step) is rewritten each time the buffer is written, and the counter
 // grows by exactly one per write, so whatever a reader can find in a slot is either the value it
-// waits for or the previous write, whose 4 bits differ.  The counter is derived from the number of
+// waits for or the previous write, whose counter bits differ (one bit would tell the two apart; two
+// leave a margin and cost a quarter of an fp32 ulp).  The counter is derived from the number of
 // steps EXECUTED on the buffers (kept on the device: a skipped step changes nothing), the layer and
 // the phase.  Rows of sequences beyond the previous step's batch are re-initialised by the host
 // side (a small fill) before a larger batch runs.  Two elements move per 8-byte coherent access.
 typedef u32 cword_t;
+constexpr u32 kCntMask = 3u;   // counter bits of a compact word
 __device__ __forceinline__ u32 cpack(float v, u32 cnt) {
     const u32 b = __float_as_uint(v);
-    const u32 r = (b & 0x7F800000u) == 0x7F800000u ? b : b + 8u;   // round to nearest; infinities and NaNs keep their class
-    return (r & ~15u) | (cnt & 15u);
+    const u32 r = (b & 0x7F800000u) == 0x7F800000u ? b : b + (kCntMask + 1u) / 2u;   // round to nearest; infinities and NaNs keep their class
+    return (r & ~kCntMask) | (cnt & kCntMask);
 }
-__device__ __forceinline__ float cvalue(u32 w) { return __uint_as_float(w & ~15u); }
-__device__ __forceinline__ bool cfresh(u32 w, u32 cnt) { return ((w ^ cnt) & 15u) == 0; }
+__device__ __forceinline__ float cvalue(u32 w) { return __uint_as_float(w & ~kCntMask); }
+__device__ __forceinline__ bool cfresh(u32 w, u32 cnt) { return ((w ^ cnt) & kCntMask) == 0; }
 __device__ __forceinline__ void cst1(cword_t* p, float v, u32 cnt) { xst_u32(p, cpack(v, cnt)); }
 __device__ __forceinline__ void cst2(cword_t* p, float v0, float v1, u32 cnt) {   // p 8-byte aligned
     xst2((float*)p, __uint_as_float(cpack(v0, cnt)), __uint_as_float(cpack(v1, cnt)));
@@ -73,30 +75,10 @@ __device__ __forceinline__ u32x2 cld2(const cword_t* base, int i) {   // element
 // cannot overwrite a slot another wave has yet to read (the vote after that lies behind the next
 // vote's barrier, which that other wave only reaches after its read).  All threads must take part
 // in every vote, in the same order.
-//
-// The voters are normally all waves of the workgroup (synchronised with the hardware barrier).  With
-// `bar` set they are a GROUP of NT / 64 consecutive waves starting at wave `wave0`, while the
-// workgroup's other waves do unrelated work and never reach a barrier: the group then synchronises
-// through a monotonic arrival counter in LDS (each wave completes its own LDS operations, bumps the
-// counter and re-reads it until the whole group has arrived).
 struct WgVote {
     static constexpr int kMaxSums = 4;
-    u32* slots;   // LDS, 2 * (1 + kMaxSums) * (voting waves) words
+    u32* slots;   // LDS, 2 * (1 + kMaxSums) * (waves per workgroup) words
     u32 par;
-    lds_u32* bar = nullptr;   // arrival counter of a wave group (null: the whole workgroup votes)
-    u32 bar_gen = 0;          // arrivals expected so far
-    int wave0 = 0;            // first wave of the group
-    int nwaves = 0;           // waves in the group (with `bar` only)
-    __device__ __forceinline__ int tid() const { return (int)threadIdx.x - 64 * wave0; }
-    // Barrier among the voters.  Orders LDS accesses only (which is all the groups share).
-    __device__ __forceinline__ void sync() {
-        if (bar == nullptr) { __syncthreads(); return; }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        bar_gen += (u32)nwaves;
-        if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        while ((int)(__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - bar_gen) < 0) __builtin_amdgcn_s_sleep(1);
-        asm volatile("" ::: "memory");
-    }
     template <int NT>
     __device__ __forceinline__ bool all(bool ok) {
         const float none[1] = {0.f};
@@ -112,12 +94,11 @@ struct WgVote {
         u32* f = slots + par * (1 + kMaxSums) * NW;
         par ^= 1u;
         if ((threadIdx.x & 63) == 0) {
-            const int wv = (int)(threadIdx.x >> 6) - wave0;
-            f[wv] = w;
+            f[threadIdx.x >> 6] = w;
 #pragma unroll
-            for (int n = 0; n < N; n++) f[(1 + n) * NW + wv] = __float_as_uint(part[n]);
+            for (int n = 0; n < N; n++) f[(1 + n) * NW + (threadIdx.x >> 6)] = __float_as_uint(part[n]);
         }
-        sync();
+        __syncthreads();
         u32 r = 1u;
 #pragma unroll
         for (int i = 0; i < NW; i++) r &= f[i];
@@ -165,8 +146,8 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 
 // Writes quad qi (elements 4*qi .. 4*qi+3) of sequence b into the staged vector.  Plain form: the
 // quad-planar fp32 layout of stage_act.  SPLIT form (input of gemv_run_quad): every value v is
-// stored as bf16 head h = v rounded to nearest and bf16 remainder = v - h truncated (the pair carries
-// 16 mantissa bits), heads in plane 2b and remainders in plane 2b+1, element order as in a weight unit.
+// stored as bf16 head h = v rounded to nearest and bf16 remainder = v - h rounded to nearest (the
+// pair carries 17 significant bits), heads in plane 2b and remainders in plane 2b+1, element order as in a weight unit.
 //   bf16 weights (8 elements = 16 bytes per unit and plane): unit j at index j ^ ((b & 3) << 2);
 //   int8 weights (16 elements = two 16-byte chunks): chunk q of unit j at index
 //   2 (j ^ ((b & 2) << 1)) + (q ^ (b & 1));
@@ -185,8 +166,8 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
         u32 h[4], l[4];
 #pragma unroll
         for (int e = 0; e < 4; e++) {
-            h[e] = (__float_as_uint(v[e]) + 0x8000u) & 0xFFFF0000u;   // nearest (ties away): the remainder's sign is random,
-            l[e] = __float_as_uint(v[e] - __uint_as_float(h[e]));     // so truncating it below leaves no bias
+            h[e] = (__float_as_uint(v[e]) + 0x8000u) & 0xFFFF0000u;                                 // nearest (ties away)
+            l[e] = (__float_as_uint(v[e] - __uint_as_float(h[e])) + 0x8000u) & 0xFFFF0000u;           // the remainder too: |error| <= 2^-18 |v|
         }
         u32x2 *ph, *pl;
         if constexpr (EPU == 8) {
@@ -204,12 +185,12 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
             // the sum of the values as the matrix cores will see them (head + stored remainder)
             float hv[4];
 #pragma unroll
-            for (int e = 0; e < 4; e++) hv[e] = __uint_as_float(h[e]) + __uint_as_float(l[e] & 0xFFFF0000u);
+            for (int e = 0; e < 4; e++) hv[e] = __uint_as_float(h[e]) + __uint_as_float(l[e]);
             const float us = group_sum<8>((hv[0] + hv[1]) + (hv[2] + hv[3]));
             if ((qi & 7) == 0) xsum_of(xs)[(size_t)b * nup + j] = us;
         }
         *ph = u32x2{(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
-        *pl = u32x2{(l[0] >> 16) | (l[1] & 0xFFFF0000u), (l[2] >> 16) | (l[3] & 0xFFFF0000u)};
+        *pl = u32x2{(l[0] >> 16) | l[1], (l[2] >> 16) | l[3]};
     }
 }
 
@@ -253,7 +234,7 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
                     if (spins == 0 || ((stale >> u) & 1)) {
                         if (erow) {   // bf16 values are exact in the compact format: mark them fresh
                             u32x2 w = *as_global((const u32x2*)(erow + k));
-                            const u32 t = S.tag & 15u;
+                            const u32 t = S.tag & kCntMask;
                             v[u] = u32x4{(w.x << 16) | t, (w.x & 0xFFFF0000u) | t, (w.y << 16) | t, (w.y & 0xFFFF0000u) | t};
                         } else {
                             const u32x2 lo = cld2(src, k), hi = cld2(src, k + 2);
@@ -311,7 +292,7 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
             static_assert(!SPLIT, "the rescaling pass below works on the fp32 layout");
             ss = wave_sum_uniform(ss);
             if (lane == 0) red[tid >> 6] = ss;
-            vote.sync();
+            __syncthreads();
             float tot = 0.f;
 #pragma unroll
             for (int w = 0; w < NT / 64; w++) tot += red[w];
@@ -322,10 +303,10 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
                 v4.x *= r; v4.y *= r; v4.z *= r; v4.w *= r;
                 xb[(size_t)qd * nup + j] = v4;
             }
-            if (b + 1 < batch) vote.sync();   // `red` is rewritten for the next row
+            if (b + 1 < batch) __syncthreads();   // `red` is rewritten for the next row
         }
     }
-    vote.sync();
+    __syncthreads();
     return true;
 }
 
@@ -376,7 +357,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                     if (kAll || ((stale[r] >> u) & 1)) {
                         if (erow[r]) {   // bf16 values are exact in the compact format: mark them fresh
                             u32x2 w = *as_global((const u32x2*)(erow[r] + k));
-                            const u32 t = S.tag & 15u;
+                            const u32 t = S.tag & kCntMask;
                             v[r][u] = u32x4{(w.x << 16) | t, (w.x & 0xFFFF0000u) | t, (w.y << 16) | t, (w.y & 0xFFFF0000u) | t};
                         } else {
                             const u32x2 lo = cld2(src[r], k), hi = cld2(src[r], k + 2);
@@ -406,7 +387,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                     dirty |= (v[0][u].x ^ S.tag) | (v[0][u].y ^ S.tag) | (v[0][u].z ^ S.tag) | (v[0][u].w ^ S.tag);
                     if constexpr (HAS_ADD) dirty |= (a[0][u].x ^ S.add_tag) | (a[0][u].y ^ S.add_tag) | (a[0][u].z ^ S.add_tag) | (a[0][u].w ^ S.add_tag);
                 }
-                dirty &= 15u;
+                dirty &= kCntMask;
             }
 #pragma unroll
             for (int r = 0; r < RB; r++) {
@@ -486,7 +467,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
             }
         }
     }
-    vote.sync();
+    __syncthreads();
     return true;
 }
 
@@ -538,8 +519,6 @@ __device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2
 // the workgroup, all of which take part).  XIO supplies the exchange accesses (plain buffers for
 // the per-operation kernels, tagged buffers for the fused kernel); returns false on a time-out.
 struct PlainAttnIO {
-    __device__ __forceinline__ int tid() const { return (int)threadIdx.x; }   // the whole workgroup takes part
-    __device__ __forceinline__ void sync() const { __syncthreads(); }
     // Workgroup-collective: the G query rows of kv head j, then (with_cur) this step's own key and
     // value row, as floats into dst[G*HD + 2*HD] (LDS); ends with a workgroup barrier.
     template <int HD, int G, int NT>
@@ -563,9 +542,7 @@ struct PlainAttnIO {
 struct TaggedAttnIO {
     u32 in_tag;    // tag of q / kvcur (this layer's QKV projection)
     u32 out_tag;   // tag of the partials and of attn_o (this layer's attention)
-    WgVote* vote;  // the waves that work on the item together (the workgroup, or a group of its waves)
-    __device__ __forceinline__ int tid() const { return vote->tid(); }
-    __device__ __forceinline__ void sync() const { vote->sync(); }
+    WgVote* vote;
     // Workgroup-collective, same contract as PlainAttnIO::stage_inputs.  The whole input of an
     // item is a few kilobytes (one or two 16-byte pairs per thread), so the workgroup simply
     // re-reads it until the QKV projection's tag is on every element; returns false on a time-out.
@@ -583,7 +560,7 @@ struct TaggedAttnIO {
             bool ok = true;
 #pragma unroll
             for (int u = 0; u < PP; u++) {
-                const int p = min(tid() + u * NT, np - 1);   // clamped: every load is issued
+                const int p = min((int)threadIdx.x + u * NT, np - 1);   // clamped: every load is issued
                 const tagged_t* src = p < NQ2 ? qb + 2 * p : p < NQ2 + NK2 ? kb + 2 * (p - NQ2) : vb + 2 * (p - NQ2 - NK2);
                 r[u] = tld2(src, 0);
             }
@@ -595,10 +572,10 @@ struct TaggedAttnIO {
         if (!done) { atomicCAS(M.status, 0, -51); return false; }
 #pragma unroll
         for (int u = 0; u < PP; u++) {
-            const int p = tid() + u * NT;
+            const int p = (int)threadIdx.x + u * NT;
             if (p < np) { dst[2 * p] = __uint_as_float(r[u].x); dst[2 * p + 1] = __uint_as_float(r[u].z); }
         }
-        sync();
+        __syncthreads();
         return true;
     }
     template <int HD>
@@ -615,8 +592,7 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     constexpr int RPW = 64 / LPR;      // rows per wave load
     constexpr int NS = NW * RPW;       // partial states per workgroup
     constexpr int NT = NW * 64;
-    const int tid = xio.tid();   // 0 .. NT-1 among the NW waves that work on the item
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, sub = lane % LPR;
     const float sc = 1.4426950408889634f / sqrtf((float)HD);   // alpha * log2(e)
 
@@ -666,7 +642,7 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     // merge area, then read by every lane from LDS
     float* xin = (float*)lds + 2 * NS * G + (size_t)NS * G * HD;
     const bool ok = xio.template stage_inputs<HD, G, NT>(M, b, j, with_cur, xin);
-    if (ev && tid == 0) as_global(ev)[1] = wall_clock64();
+    if (ev && threadIdx.x == 0) as_global(ev)[1] = wall_clock64();
     if (!ok) return false;   // uniform
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -697,16 +673,16 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     float* sl = sm + NS * G;              // [NS][G]
     float* so = sl + NS * G;              // [NS][G][HD]
     const int si = wave * RPW + grp;
-    if (ev && tid == 0) as_global(ev)[2] = wall_clock64();
-    xio.sync();
+    if (ev && threadIdx.x == 0) as_global(ev)[2] = wall_clock64();
+    __syncthreads();
 #pragma unroll
     for (int g = 0; g < G; g++) {
         if (sub == 0) { sm[si * G + g] = m[g]; sl[si * G + g] = l[g]; }
 #pragma unroll
         for (int e = 0; e < 8; e++) so[((size_t)si * G + g) * HD + sub * 8 + e] = o[g][e];
     }
-    xio.sync();
-    for (int idx = tid; idx < G * HD; idx += NT) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * HD; idx += NT) {
         int g = idx / HD, dim = idx % HD;
         float mx = -INFINITY;
         for (int s = 0; s < NS; s++) mx = fmaxf(mx, sm[s * G + g]);
@@ -719,7 +695,7 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
         size_t hs = ((size_t)b * M.Hq + (j * G + g)) * kMaxSplits + split;
         xio.template store_partial<HD>(M, hs, dim, ot, mx, lt);
     }
-    if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
+    if (ev && threadIdx.x == 0) as_global(ev)[3] = wall_clock64();
     return ok;
 }
 
@@ -774,7 +750,6 @@ template <int HD, int G, int NT>
 __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, u32 out_cnt, float* lds, WgVote& vote, u64* ev = nullptr) {
     float* ms = lds;
     float* ls = lds + G * kMaxSplits;
-    const int tid = vote.tid();   // 0 .. NT-1 among the voting waves
     constexpr int kSB = 16;   // splits gathered per batch of loads
     constexpr u32 kAll = (1u << kSB) - 1;
     // (re)loads the partial outputs of splits s0.. (bit u of mask = split s0+u) for output pair d2
@@ -793,13 +768,13 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
     // waited for: all partials of a head group arrive in one round trip, and whatever is still
     // stale (the last split's rows, typically) is re-read selectively.
     u32x4 r[kSB];
-    const bool pre = tid < G * HD / 2;
-    if (pre) issue(r, (b * M.Hq + (j * G + tid / (HD / 2))) * kMaxSplits, (tid % (HD / 2)) * 2, 0, kAll);
-    vote.sync();
+    const bool pre = (int)threadIdx.x < G * HD / 2;
+    if (pre) issue(r, (b * M.Hq + (j * G + (int)threadIdx.x / (HD / 2))) * kMaxSplits, ((int)threadIdx.x % (HD / 2)) * 2, 0, kAll);
+    __syncthreads();
     bool done = false;
     for (int spins = 0; spins < kSpinLimit && !done; spins++) {
         bool ok = true;
-        for (int idx = tid; idx < G * nsplit; idx += NT) {
+        for (int idx = threadIdx.x; idx < G * nsplit; idx += NT) {
             int g = idx / nsplit, s = idx % nsplit;
             int hs = (b * M.Hq + (j * G + g)) * kMaxSplits + s;
             u32x2 pm = tld1(M.tpart_m, hs), pl = tld1(M.tpart_l, hs);
@@ -811,9 +786,9 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
         if (!done) __builtin_amdgcn_s_sleep(2);
     }
     if (!done) { atomicCAS(M.status, 0, -53); return false; }
-    if (ev && tid == 0) as_global(ev)[4] = wall_clock64();
+    if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
     bool all_ok = true;
-    for (int idx = tid; idx < G * HD / 2; idx += NT) {
+    for (int idx = threadIdx.x; idx < G * HD / 2; idx += NT) {
         int g = idx / (HD / 2), d2 = (idx % (HD / 2)) * 2;
         int hs = (b * M.Hq + (j * G + g)) * kMaxSplits;
         // every thread reduces the maxima and denominators of its head itself (independent LDS
@@ -835,7 +810,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
         const float inv = 1.0f / lt;
         float a0 = 0.f, a1 = 0.f;
         for (int s0 = 0; s0 < nsplit; s0 += kSB) {
-            u32 need = (idx == tid && s0 == 0) ? 0u : kAll;   // the first batch is already in flight
+            u32 need = (idx == (int)threadIdx.x && s0 == 0) ? 0u : kAll;   // the first batch is already in flight
             bool ok = false;
             for (int spins = 0; spins < kSpinLimit && !ok; spins++) {
                 issue(r, hs, d2, s0, need);
@@ -854,7 +829,7 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
         }
         cst2(M.cattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, out_cnt);
     }
-    if (ev && tid == 0) as_global(ev)[5] = wall_clock64();
+    if (ev && threadIdx.x == 0) as_global(ev)[5] = wall_clock64();
     return vote.all<NT>(all_ok);
 }
 

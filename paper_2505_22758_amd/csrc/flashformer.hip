@@ -19,6 +19,7 @@ using namespace ff;
 // the device address obtained from it (static_scratch_ptr below).
 constexpr size_t kStaticScratchBytes = FF_STATIC_SCRATCH_BYTES;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static __device__ unsigned int sink_word;   // never-written target that keeps k_stream_read's loads alive
 
 namespace {
 
@@ -375,6 +376,92 @@ int ff_model_load(const ff_config* cfg, const ff_layer_weights* layers, const ff
     return FF_OK;
 }
 
+}  // extern "C"
+
+namespace {
+// ---- the seeded recipe of the package's input generators, host part: tensor keys ----
+uint32_t crc32_ieee(const char* s) {   // the common reflected CRC-32 (polynomial 0xEDB88320)
+    uint32_t c = 0xFFFFFFFFu;
+    for (; *s; ++s) {
+        c ^= (uint8_t)*s;
+        for (int b = 0; b < 8; b++) c = (c >> 1) ^ (0xEDB88320u & (0u - (c & 1u)));
+    }
+    return ~c;
+}
+uint32_t tensor_key(uint64_t seed, const char* fmt, ...) {
+    char name[96];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(name, sizeof name, fmt, ap);
+    va_end(ap);
+    return (uint32_t)seed * 0x9E3779B1u + crc32_ieee(name);
+}
+constexpr double kIh4Std = 37837.22;   // std of the sum of four uniform 16-bit integers
+SynthMat synth_mat(uint64_t seed, int layer, const char* which, int k, int wd) {
+    SynthMat s;
+    if (layer >= 0) {
+        s.key_w = tensor_key(seed, "l%d.%s", layer, which);
+        s.key_s = tensor_key(seed, "l%d.%s.s", layer, which);
+        s.key_z = tensor_key(seed, "l%d.%s.z", layer, which);
+    } else {
+        s.key_w = tensor_key(seed, "%s", which);
+        s.key_s = tensor_key(seed, "%s.s", which);
+        s.key_z = tensor_key(seed, "%s.z", which);
+    }
+    s.k = k;
+    s.c_scale = wd == W_INT8 ? (float)(0.02 / 73.6) : (float)(0.02 / 6.5);
+    return s;
+}
+int synth_part(const MatPlan& dst, uint8_t* packed, int dst_row, int n_rows, const SynthMat& a, const SynthMat& b, int mode, int hd, hipStream_t st) {
+    const size_t rb = dst.wd == W_BF16 ? (size_t)dst.k * 2 : dst.wd == W_INT8 ? (size_t)dst.k : (size_t)dst.k / 2;
+    const size_t sb = dst.wd == W_INT8 ? 2 : (size_t)(dst.k / 128) * 2;
+    k_synth_rows<<<std::min(n_rows, 8192), kThreads, 0, st>>>(packed + dst.w + (size_t)dst_row * rb, (f16_t*)(packed + dst.s + (size_t)dst_row * sb),
+                                                             (f16_t*)(packed + dst.z + (size_t)dst_row * sb), n_rows, dst.wd, a, b, mode, hd,
+                                                             (float)(0.02 / kIh4Std));
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int ff_model_load_synthetic(const ff_config* cfg, uint64_t seed, void* packed_dev, size_t packed_bytes, void* scratch_dev, size_t scratch_bytes,
+                            void* stream, ff_model** out) {
+    ff_model* m = nullptr;
+    int rc = ff_model_create(cfg, packed_dev, packed_bytes, scratch_dev, scratch_bytes, stream, &m);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const ff_config& c = m->cfg;
+    const int qr = c.n_q_heads * c.head_dim, kr = c.n_kv_heads * c.head_dim, wd = c.wdtype;
+    const float gscale = (float)(0.02 / kIh4Std);
+    for (int l = 0; l < c.n_layers && !rc; l++) {
+        const LayerPlan& L = m->plan.layers[l];
+        k_synth_normal<<<16, 256, 0, st>>>((bf16_t*)(m->packed + L.g1), (size_t)c.d_model, tensor_key(seed, "l%d.attn_norm", l), gscale, 1.0f);
+        k_synth_normal<<<16, 256, 0, st>>>((bf16_t*)(m->packed + L.g2), (size_t)c.d_model, tensor_key(seed, "l%d.ffn_norm", l), gscale, 1.0f);
+        const SynthMat wq = synth_mat(seed, l, "wq", c.d_model, wd), wk = synth_mat(seed, l, "wk", c.d_model, wd), wv = synth_mat(seed, l, "wv", c.d_model, wd),
+                       wo = synth_mat(seed, l, "wo", qr, wd), wg = synth_mat(seed, l, "w_gate", c.d_model, wd), wu = synth_mat(seed, l, "w_up", c.d_model, wd),
+                       wdn = synth_mat(seed, l, "w_down", c.d_ffn, wd);
+        if (!rc) rc = synth_part(L.qkv, m->packed, 0, qr, wq, wq, REPACK_ROPE, c.head_dim, st);
+        if (!rc) rc = synth_part(L.qkv, m->packed, qr, kr, wk, wk, REPACK_ROPE, c.head_dim, st);
+        if (!rc) rc = synth_part(L.qkv, m->packed, qr + kr, kr, wv, wv, REPACK_COPY, c.head_dim, st);
+        if (!rc) rc = synth_part(L.o, m->packed, 0, c.d_model, wo, wo, REPACK_COPY, c.head_dim, st);
+        if (!rc) rc = synth_part(L.gu, m->packed, 0, 2 * c.d_ffn, wg, wu, REPACK_INTERLEAVE, c.head_dim, st);
+        if (!rc) rc = synth_part(L.down, m->packed, 0, c.d_model, wdn, wdn, REPACK_COPY, c.head_dim, st);
+        m->layer_loaded[l] = 1;
+    }
+    if (!rc) {
+        k_synth_normal<<<2048, 256, 0, st>>>((bf16_t*)(m->packed + m->plan.embed), (size_t)c.vocab * c.d_model, tensor_key(seed, "embed"), gscale, 0.f);
+        k_synth_normal<<<16, 256, 0, st>>>((bf16_t*)(m->packed + m->plan.gf), (size_t)c.d_model, tensor_key(seed, "final_norm"), gscale, 1.0f);
+        const SynthMat lm = synth_mat(seed, -1, "lm_head", c.d_model, m->plan.lm.wd);
+        rc = synth_part(m->plan.lm, m->packed, 0, c.vocab, lm, lm, REPACK_COPY, c.head_dim, st);
+        m->head_loaded = true;
+    }
+    if (!rc && hipGetLastError() != hipSuccess) rc = fail(FF_ERR_HIP, "synthetic fill launch failed");
+    if (rc) { delete m; return rc; }
+    *out = m;
+    return FF_OK;
+}
+
 int ff_model_free(ff_model* m) {
     delete m;
     return FF_OK;
@@ -436,6 +523,34 @@ int ff_kv_fill(ff_kv* kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, c
 int ff_kv_read(ff_kv* kv, int32_t layer, int32_t seq, int32_t pos0, int32_t n, void* k_dev, void* v_dev, void* stream) {
     return kv_copy(kv, layer, seq, pos0, n, k_dev, v_dev, stream, 1);
 }
+int ff_kv_fill_synthetic(ff_kv* kv, uint64_t seed, int32_t n_ctx, void* stream) {
+    if (!kv) return fail(FF_ERR_ARG, "null argument");
+    if (n_ctx < 0 || n_ctx > kv->max_ctx) return fail(FF_ERR_RANGE, "n_ctx %d outside [0, max_ctx %d]", n_ctx, kv->max_ctx);
+    if (n_ctx == 0) return FF_OK;
+    const ff_config& c = kv->model->cfg;
+    const size_t plane = (size_t)kv->max_ctx * c.head_dim;
+    const size_t tot = (size_t)n_ctx * c.n_kv_heads * c.head_dim;
+    const int grid = (int)std::min<size_t>((tot + 255) / 256, 1024);
+    for (int l = 0; l < c.n_layers; l++)
+        for (int b = 0; b < kv->batch; b++) {
+            bf16_t* base = kv->dev.base + (((size_t)l * kv->batch + b) * c.n_kv_heads) * 2 * plane;
+            k_synth_kv<<<grid, 256, 0, (hipStream_t)stream>>>(base, plane, c.n_kv_heads, c.head_dim, n_ctx, tensor_key(seed, "kv.l%d.s%d.k", l, b),
+                                                             tensor_key(seed, "kv.l%d.s%d.v", l, b), (float)(1.0 / kIh4Std));
+        }
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+
+int ff_debug_stream_read(const void* buf_dev, size_t bytes, int32_t n_workgroups, void* stream) {
+    if (!buf_dev || bytes < (size_t)1 << 20 || n_workgroups < 1 || n_workgroups > 65536) return fail(FF_ERR_ARG, "bad argument");
+    if ((uintptr_t)buf_dev & 15) return fail(FF_ERR_ARG, "buffer must be 16-byte aligned");
+    void* sink = nullptr;
+    HIPCHK(hipGetSymbolAddress(&sink, HIP_SYMBOL(sink_word)));
+    k_stream_read<<<n_workgroups, kThreads, 0, (hipStream_t)stream>>>((const u32x4*)buf_dev, bytes / 16, (u32*)sink);
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+
 int ff_kv_free(ff_kv* kv) {
     delete kv;
     return FF_OK;

@@ -187,7 +187,7 @@ def test_llama8b_bf16_batch1_ctx1024_full_size(capsys):
     """The benchmark workload at full size (32 layers, d 4096, vocab 128256, ctx 1024), in the
     launch configuration bench.py times; every logit of the configured 64 teacher-forced steps is
     compared (the per-operation path on the first four), and the arg-max rate is a rate over 64
-    decisions.  The 4-bit write counters of the exchange vectors come round 128 times."""
+    decisions.  The 2-bit write counters of the exchange vectors come round 512 times."""
     _run_teacher_forced(synth.LLAMA_8B, 0x250522758, synth.WDTYPE_BF16, batch=1, T0=1024, steps=64, gpu_generated=True, perop_steps=4,
                         capsys=capsys)
 
@@ -434,8 +434,9 @@ def test_two_models_interleaved_on_a_side_stream():
 
 def test_batch_size_changing_from_step_to_step():
     """Steps of different batch sizes on one model and one cache: a sequence that sits out some steps
-    (among them exactly as many as make the exchange vectors' 4-bit write counters come round again:
-    with 4 layers, 4 steps) must not be served values its exchange rows kept from its last step."""
+    (the exchange vectors' 2-bit write counters come round every step of this 4-layer model, so any
+    number of skipped steps leaves the counter bits a reader would accept) must not be served values
+    its exchange rows kept from its last step."""
     from paper_2505_22758_amd import binding
     from oracle import oracle
     shape, seed, T0 = synth.TINY, 0x77, 20
@@ -639,4 +640,60 @@ def test_a_silent_workgroup_ends_in_a_timeout_not_a_hang():
         binding.ff_status(dec.model)
         assert float((lg - want).abs().max()) < 1e-3
         binding.ff_kv_free(kv)
+        dec.close()
+
+
+def test_synthetic_loaders_match_the_python_generators_bit_for_bit():
+    """ff_model_load_synthetic / ff_kv_fill_synthetic (device-side generator) against the canonical
+    tensors of synth.py loaded through ff_model_load / ff_kv_fill: every dequantised matrix, the cache
+    buffers and the logits of a decode step (embedding, gains) must be identical.  The seed has more
+    than 32 bits (the key uses its low word on both sides)."""
+    from paper_2505_22758_amd import binding
+    S, seed, T0, B = synth.TINY.replace(n_layers=2, d_ffn=1408), 0x250522758, 33, 2
+    for wd, qlm in ((synth.WDTYPE_BF16, True), (synth.WDTYPE_INT8, True), (synth.WDTYPE_INT8, False), (synth.WDTYPE_INT4, True)):
+        cfg = binding.make_config(S, wd, B, qlm)
+        pb, sb = binding.ff_model_bytes(cfg)
+        packed = torch.zeros(pb, dtype=torch.uint8, device="cuda:0")
+        scratch = torch.zeros(sb, dtype=torch.uint8, device="cuda:0")
+        layers = [synth.make_layer(S, seed, l, wd, "cuda:0") for l in range(S.n_layers)]
+        head = synth.make_head(S, seed, wd, "cuda:0", qlm)
+        ma = binding.ff_model_load(cfg, layers, head, packed, scratch)
+        dec = binding.Decoder.synthetic(S, seed, wd, B, qlm)
+        mb = dec.model
+        for l in range(S.n_layers):
+            for which in synth.LAYER_MATS:
+                n, k = synth.mat_shape(S, which)
+                a = torch.empty(n, k, dtype=torch.float32, device="cuda:0")
+                b = torch.empty_like(a)
+                binding.ff_debug_dequant(ma, l, which, a)
+                binding.ff_debug_dequant(mb, l, which, b)
+                assert torch.equal(a, b), (wd, l, which)
+        a = torch.empty(S.vocab, S.d_model, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        binding.ff_debug_dequant(ma, 0, "lm_head", a)
+        binding.ff_debug_dequant(mb, 0, "lm_head", b)
+        assert torch.equal(a, b), (wd, "lm_head")
+        bufs, kvs = [], []
+        for m in (ma, mb):
+            buf = torch.zeros(binding.ff_kv_bytes(m, B, T0 + 4), dtype=torch.uint8, device="cuda:0")
+            bufs.append(buf)
+            kvs.append(binding.ff_kv_alloc(m, B, T0 + 4, buf))
+        for l in range(S.n_layers):
+            for sq in range(B):
+                k, v = synth.make_kv_prefill(S, seed, l, sq, T0, "cuda:0")
+                binding.ff_kv_fill(kvs[0], l, sq, 0, k, v)
+        binding.ff_kv_fill_synthetic(kvs[1], seed, T0)
+        torch.cuda.synchronize()
+        assert torch.equal(bufs[0], bufs[1]), (wd, "kv prefill")
+        tok = torch.tensor([5, 4000], dtype=torch.int32, device="cuda:0")
+        pos = torch.full((B,), T0, dtype=torch.int32, device="cuda:0")
+        la, lb = torch.zeros(B, S.vocab, device="cuda:0"), torch.zeros(B, S.vocab, device="cuda:0")
+        binding.ff_decode_step(ma, tok, pos, kvs[0], la, B)
+        binding.ff_decode_step(mb, tok, pos, kvs[1], lb, B)
+        binding.ff_status(ma)
+        binding.ff_status(mb)
+        assert torch.equal(la, lb) and bool(torch.isfinite(la).all()), (wd, "logits")
+        for kv in kvs:
+            binding.ff_kv_free(kv)
+        binding.ff_model_free(ma)
         dec.close()
