@@ -35,6 +35,8 @@ WORKLOADS = {
     # name: (shape, wdtype, batch, context)
     "tiny-bf16-b1-ctx128": ("tiny", 0, 1, 128),
     "llama3-8b-bf16-b1-ctx1024": ("llama3-8b", 0, 1, 1024),
+    "llama3-8b-bf16-b8-ctx1024": ("llama3-8b", 0, 8, 1024),     # one pass of eight sequences
+    "llama3-8b-bf16-b16-ctx1024": ("llama3-8b", 0, 16, 1024),   # two passes of eight
     "llama3-8b-int8-b1-ctx4096": ("llama3-8b", 1, 1, 4096),
     "llama3-8b-int4-b1-ctx2048": ("llama3-8b", 2, 1, 2048),
     "llama3-8b-int4-b4-ctx2048": ("llama3-8b", 2, 4, 2048),
@@ -83,6 +85,85 @@ def cpu_baseline(shape, wdtype, ctx, seed, n_layers_sample=16, steps=16, gen_dev
                       f"ctx {ctx}; per-layer time x {shape.n_layers} + head time"}
 
 
+def stack_ablation(args):
+    """The paper's component studies on this machine (Section 3: stacked square linear layers;
+    Section 5.3: stacked attention and GLU blocks): Baseline (one launch per operation) / Fused (one
+    persistent kernel, tiles requested after the input has arrived) / + Overlap (tiles requested before
+    the input is waited for).  Prints one JSON line per cell."""
+    import numpy as np
+    import torch
+    from paper_2505_22758_amd import binding, synth
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    reps = args.steps
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3   # us
+
+    def graphed(fn):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return timed(g.replay)
+
+    layers_list = [int(v) for v in args.layers.split(",")]
+    if args.stack == "linear":
+        for d in [int(v) for v in args.dim.split(",")]:
+            for L in layers_list:
+                w = synth.normal_bf16(7, f"stack{d}", (L, d, d), 0.02, dev)
+                x = synth.normal_bf16(7, "stack.x", (d,), 1.0, dev).float()
+                y = torch.empty_like(x)
+                scratch = torch.zeros(2 * ((4 * d + 255) // 256 * 256) + 256, dtype=torch.uint8, device=dev)
+                cell = {"stack": "linear", "dim": d, "layers": L, "weight_bytes": 2 * L * d * d}
+                for mode, name in ((0, "baseline"), (1, "fused"), (2, "fused+overlap")):
+                    us = timed(lambda: binding.ff_debug_stack_linear(w, x, y, mode, scratch))
+                    cell[name + "_us"] = us
+                    cell[name + "_gbs"] = cell["weight_bytes"] / us / 1e3
+                cell["baseline_graph_us"] = graphed(lambda: binding.ff_debug_stack_linear(w, x, y, 0, scratch))
+                assert int(scratch[-256:].view(torch.int32)[0]) == 0, "a stacked-linear launch recorded a time-out"
+                print(json.dumps(cell), flush=True)
+                del w
+                torch.cuda.empty_cache()
+        return
+    base = synth.SHAPES["llama3-8b"]
+    if args.stack == "attn":     # attention sublayer with a vestigial FFN (d_ffn 128: 0.4 % of the layer's bytes)
+        shape, ctx = base.replace(name="stack-attn", d_ffn=128, vocab=256), 1024
+    else:                        # GLU sublayer with a vestigial attention (4 query / 1 kv head of 128, one cached row: 3 % of the bytes)
+        shape, ctx = base.replace(name="stack-glu", n_q_heads=4, n_kv_heads=1, vocab=256), 1
+    for L in layers_list:
+        S = shape.replace(n_layers=L)
+        dec = binding.Decoder.synthetic(S, 11, synth.WDTYPE_BF16, 1, device=dev)
+        dec.alloc_kv(1, ctx + 4)
+        binding.ff_kv_fill_synthetic(dec.kv, 11, ctx)
+        tok = torch.tensor([5], dtype=torch.int32, device=dev)
+        pos = torch.tensor([ctx], dtype=torch.int32, device=dev)
+        lg = torch.zeros(1, S.vocab, device=dev)
+        wbytes = synth.weight_bytes_per_step(S, synth.WDTYPE_BF16) + synth.kv_bytes_per_step(S, 1, ctx)
+        cell = {"stack": args.stack, "layers": L, "bytes_per_step": wbytes}
+        cell["baseline_us"] = timed(lambda: dec.step(tok, pos, lg, perop=True))
+        cell["baseline_graph_us"] = graphed(lambda: dec.step(tok, pos, lg, perop=True))
+        binding.ff_debug_set_overlap(dec.model, False)
+        cell["fused_us"] = timed(lambda: dec.step(tok, pos, lg))
+        binding.ff_debug_set_overlap(dec.model, True)
+        cell["fused+overlap_us"] = timed(lambda: dec.step(tok, pos, lg))
+        binding.ff_status(dec.model)
+        for k in ("baseline", "fused", "fused+overlap"):
+            cell[k + "_gbs"] = wbytes / cell[k + "_us"] / 1e3
+        print(json.dumps(cell), flush=True)
+        dec.close()
+        del dec
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +175,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-perop", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the streaming-read ceiling measurement")
+    ap.add_argument("--stack", choices=["linear", "attn", "glu"], help="component ablation instead of the decode benchmark")
+    ap.add_argument("--dim", default="2048,4096,8192", help="--stack linear: widths")
+    ap.add_argument("--layers", default="1,4,32", help="--stack: depths")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-traffic kernel to scale rocprofv3 --pmc counters by)")
     args = ap.parse_args()
@@ -101,6 +185,9 @@ def main():
         print("bench.py: this build runs on exactly one GPU (the paper's kernel is single-GPU); --gpus must be 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.stack:
+        return stack_ablation(args)
 
     import numpy as np
     import torch

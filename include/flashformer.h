@@ -210,6 +210,22 @@ int ff_debug_timeline(ff_model *m, void *buf_dev);
  * streaming-read ceiling of the machine beside the nominal HBM peak. */
 int ff_debug_stream_read(const void *buf_dev, size_t bytes, int32_t n_workgroups, void *stream);
 
+/* Ablation of the paper's preliminary study (Section 3, stacked square linear layers on one input
+ * vector): y = W[n_layers-1] ... W[1] W[0] x with W bf16 [n_layers][d][d] (row-major [out][in]), x and y
+ * fp32 [d] device vectors.  mode 0: one streaming-GEMV launch per layer ("Baseline"); mode 1: one
+ * persistent kernel with a tagged hand-over between layers ("Fused"); mode 2: the same with each
+ * layer's first weight tiles requested before its input is waited for ("+ Overlap").  d must be a
+ * multiple of 2048 in [2048, 32768]; scratch_dev: 2 * align256(4 d) + 256 bytes, 256-byte aligned.
+ * The word at scratch offset 2 * align256(4 d) is a status word (0 = ok) that the caller clears. */
+int ff_debug_stack_linear(const void *w_dev, int32_t d, int32_t n_layers, const float *x_dev, float *y_dev,
+                          int32_t mode, void *scratch_dev, size_t scratch_bytes, void *stream);
+
+/* Ablation switch (the "Fused" vs "+ Overlap" columns of the paper's latency tables, Sections 3 and
+ * 5.3): overlap = 0 makes the fused kernel request a projection's first weight tiles only after its
+ * input has arrived (no cross-layer memory overlap); nonzero restores the default.  bf16 models with
+ * max_batch 1 only (FF_ERR_UNSUPPORTED otherwise).  Results are identical either way. */
+int ff_debug_set_overlap(ff_model *m, int32_t overlap);
+
 /* Test hook for the FF_ERR_TIMEOUT path: while `workgroup` is >= 0, that workgroup of every
  * following fused step leaves at once without publishing anything, so each workgroup that needs its
  * output gives up after its own bounded wait (a fraction of a second), all kernels end normally and

@@ -25,7 +25,7 @@ FF_MAT = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 
 
 EXPORTS = ["ff_last_error", "ff_model_bytes", "ff_model_create", "ff_model_load_layer", "ff_model_load_head",
            "ff_model_load", "ff_model_load_synthetic", "ff_model_free", "ff_kv_bytes", "ff_kv_alloc", "ff_kv_fill", "ff_kv_read", "ff_kv_fill_synthetic", "ff_kv_free",
-           "ff_decode_step", "ff_decode_step_static", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_stream_read", "ff_debug_mute_workgroup",
+           "ff_decode_step", "ff_decode_step_static", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_stream_read", "ff_debug_stack_linear", "ff_debug_set_overlap", "ff_debug_mute_workgroup",
            "ff_fused_schedule"]
 
 
@@ -64,6 +64,7 @@ _lib.ff_kv_fill.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.ff_kv_read.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.ff_kv_fill_synthetic.argtypes = [_vp, C.c_uint64, _i32, _vp]
 _lib.ff_debug_stream_read.argtypes = [_vp, _sz, _i32, _vp]
+_lib.ff_debug_stack_linear.argtypes = [_vp, _i32, _i32, _vp, _vp, _i32, _vp, _sz, _vp]
 _lib.ff_kv_free.argtypes = [_vp]
 _lib.ff_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.ff_decode_step_perop.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
@@ -73,6 +74,7 @@ _lib.ff_debug_dequant.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.ff_debug_gemv.argtypes = [_vp, _i32, _i32, _vp, _vp, _i32, _i32, _vp]
 _lib.ff_debug_timeline.argtypes = [_vp, _vp]
 _lib.ff_debug_mute_workgroup.argtypes = [_vp, _i32]
+_lib.ff_debug_set_overlap.argtypes = [_vp, _i32]
 _lib.ff_fused_schedule.argtypes = [_vp, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32)]
 
 
@@ -192,6 +194,12 @@ def ff_debug_stream_read(buf: torch.Tensor, n_workgroups: int = 256, stream=None
     _check(_lib.ff_debug_stream_read(_ptr(buf), buf.numel() * buf.element_size(), n_workgroups, _stream(stream)), "ff_debug_stream_read")
 
 
+def ff_debug_stack_linear(w: torch.Tensor, x: torch.Tensor, y: torch.Tensor, mode: int, scratch: torch.Tensor, stream=None) -> None:
+    assert w.dtype == torch.bfloat16 and w.dim() == 3 and w.shape[1] == w.shape[2] and x.dtype == torch.float32 and y.dtype == torch.float32
+    _check(_lib.ff_debug_stack_linear(_ptr(w), w.shape[1], w.shape[0], _ptr(x), _ptr(y), mode, _ptr(scratch),
+                                      scratch.numel() * scratch.element_size(), _stream(stream)), "ff_debug_stack_linear")
+
+
 def ff_kv_free(kv: int) -> None:
     _check(_lib.ff_kv_free(kv), "ff_kv_free")
 
@@ -232,6 +240,10 @@ def ff_debug_gemv(model: int, layer: int, which: str, x: torch.Tensor, out: torc
 
 def ff_debug_timeline(model: int, buf) -> None:
     _check(_lib.ff_debug_timeline(model, _ptr(buf) if buf is not None else None), "ff_debug_timeline")
+
+
+def ff_debug_set_overlap(model: int, overlap: bool) -> None:
+    _check(_lib.ff_debug_set_overlap(model, int(overlap)), "ff_debug_set_overlap")
 
 
 def ff_debug_mute_workgroup(model: int, workgroup: int) -> None:

@@ -142,7 +142,7 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
 template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
-                                                                     int batch, int lm_in_kernel, int ncta, int mute_wg) {
+                                                                     int batch, int lm_in_kernel, int ncta, int mute_wg, int no_overlap) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     if (!inputs_ok(M, KV, tokens, pos)) {
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(M.status, kStatusRange);
@@ -216,7 +216,10 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (seg > 0) src.wb = nullptr;
         const bool att_first = D.kind == PH_O && seg == 0;
         Stage<WD> ring[kDepthOf<WD>];
-        prefetch_stream<kQuad>(S, ring, lane);
+        // (ablation switch, single-sequence bf16 instances only: with no_overlap the tiles are requested
+        // after the input has arrived, as in a fused kernel without cross-layer memory overlap)
+        constexpr bool kHasSwitch = B == 1 && WD == W_BF16;
+        if (!kHasSwitch || !no_overlap) prefetch_stream<kQuad>(S, ring, lane);
         if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);
         // Touch the descriptor the NEXT phase will fetch, so that it sits in the scalar cache by
         // then instead of costing a trip to memory at the head of that phase.
@@ -248,6 +251,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             return;
         }
         if (wave == 0) dbg_event(M, ph, EV_SYNCED, lane);
+        if (kHasSwitch && no_overlap) prefetch_stream<kQuad>(S, ring, lane);
         u64* wv = D.kind < 4 ? dbg_wave_slots(M, n_phases, D.layer, wave) : nullptr;
         if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
         if constexpr (kQuad) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
@@ -274,7 +278,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
 // translation unit so that the instances compile in parallel.
 struct FusedLaunch {
     DevModel M; DevKV KV; const int* tokens; const int* pos; float* logits;
-    int batch; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream; int mute_wg;
+    int batch; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream; int mute_wg; int no_overlap;
 };
 template <int WD, int B, int HD, int G>
 inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what) {
@@ -292,7 +296,7 @@ inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what)
         if (occ < 1) { setup_what = "fused kernel does not fit on a compute unit"; setup_err = hipErrorLaunchOutOfResources; }
     });
     if (setup_err != hipSuccess) { *what = setup_what; return setup_err; }
-    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.lm_in_kernel, a.n_cta, a.mute_wg);
+    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.lm_in_kernel, a.n_cta, a.mute_wg, a.no_overlap);
     *what = "fused kernel launch";
     return hipGetLastError();
 }

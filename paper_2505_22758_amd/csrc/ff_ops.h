@@ -275,7 +275,9 @@ __device__ __forceinline__ int synth_uniform_int(u32 key, u64 idx, int lo, int h
 // fp16 bits of c * (1 + u / 4), u in [0, 1) with 16 bits of resolution
 __device__ __forceinline__ f16_t synth_scale_f16(u32 key, u64 idx, float c) {
     const float u = (float)(synth_hash(key, 3u, idx) >> 16) * (1.0f / 65536.0f);
-    const _Float16 h = (_Float16)(c * (1.0f + 0.25f * u));   // 1 + u / 4 is exact in fp32 either way; one rounded product
+    float p = c * (1.0f + 0.25f * u);   // 1 + u / 4 is exact in fp32 either way; one rounded fp32 product ...
+    asm volatile("" : "+v"(p));         // ... which is then narrowed (kept apart: a fused multiply-narrow would round once)
+    const _Float16 h = (_Float16)p;
     f16_t bits;
     __builtin_memcpy(&bits, &h, 2);
     return bits;

@@ -2,6 +2,7 @@
 #include "../../include/flashformer.h"
 #include "ff_fused.h"
 #include "ff_ops.h"
+#include "ff_stack.h"
 
 #include <algorithm>
 #include <cstdarg>
@@ -164,6 +165,7 @@ struct ff_model {
     int n_cta;
     size_t lds_bytes;
     int mute_wg = -1;   // test hook (ff_debug_mute_workgroup)
+    int no_overlap = 0; // ablation switch (ff_debug_set_overlap)
 };
 struct ff_kv {
     ff_model* model;
@@ -571,7 +573,7 @@ int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const 
         k_scrub_rows<<<64, kThreads, 0, st>>>(D, batch);
         HIPCHK(hipGetLastError());
     }
-    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg};
+    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg, m->no_overlap};
     const char* what = "";
     const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     hipError_t e = hipErrorInvalidValue;
@@ -821,6 +823,81 @@ int ff_debug_dequant(const ff_model* m, int32_t layer, int32_t which, float* out
 int ff_debug_timeline(ff_model* m, void* buf_dev) {
     if (!m) return fail(FF_ERR_ARG, "null argument");
     m->dev.dbg = (u64*)buf_dev;
+    return FF_OK;
+}
+
+}  // extern "C"
+
+namespace {
+template <bool OVERLAP>
+int launch_stack(const StackArgs& a, int n_cta, hipStream_t st) {
+    auto kern = stack_linear_kernel<OVERLAP>;
+    static std::once_flag once;
+    static hipError_t setup_err = hipSuccess;
+    std::call_once(once, [&] {
+        setup_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsFusedBytes);
+        int occ = 0;
+        if (setup_err == hipSuccess) setup_err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, kFusedThreads, kLdsFusedBytes);
+        if (setup_err == hipSuccess && occ < 1) setup_err = hipErrorLaunchOutOfResources;
+    });
+    if (setup_err != hipSuccess) return fail(FF_ERR_HIP, "stacked-linear kernel set-up failed: %s", hipGetErrorString(setup_err));
+    kern<<<n_cta, kFusedThreads, kLdsFusedBytes, st>>>(a, n_cta);
+    return FF_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int ff_debug_stack_linear(const void* w_dev, int32_t d, int32_t n_layers, const float* x_dev, float* y_dev, int32_t mode, void* scratch_dev,
+                          size_t scratch_bytes, void* stream) {
+    if (!w_dev || !x_dev || !y_dev || !scratch_dev) return fail(FF_ERR_ARG, "null argument");
+    if (mode < 0 || mode > 2) return fail(FF_ERR_ARG, "mode must be 0 (one launch per layer), 1 (fused) or 2 (fused + overlap)");
+    // every wave of the grid must own rows of every layer (d / 2 row pairs over 1024 waves) and the staged
+    // vector must be a whole number of tile chunks
+    if (d < 2048 || d % 2048 || (size_t)d * 4 > (size_t)kLdsActBytes || n_layers < 1 || n_layers > 4096)
+        return fail(FF_ERR_UNSUPPORTED, "d must be a multiple of 2048 in [2048, 32768], n_layers in [1, 4096]");
+    const size_t need = 2 * align256((size_t)d * 4) + 256;
+    if (scratch_bytes < need || ((uintptr_t)scratch_dev & 255)) return fail(FF_ERR_NOMEM, "scratch needs %zu bytes, 256-byte aligned", need);
+    hipStream_t st = (hipStream_t)stream;
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    int n_cta = 0;
+    HIPCHK(hipDeviceGetAttribute(&n_cta, hipDeviceAttributeMultiprocessorCount, dev));
+    uint8_t* s = (uint8_t*)scratch_dev;
+    if (mode == 0) {
+        // plain fp32 vectors ping-pong in the scratch; one streaming-GEMV launch per layer
+        float* b0 = (float*)s;
+        float* b1 = (float*)(s + align256((size_t)d * 4));
+        HIPCHK(hipMemcpyAsync(b0, x_dev, (size_t)d * 4, hipMemcpyDeviceToDevice, st));
+        ff_model shim;   // launch_gemv only needs the launch shape
+        shim.n_cta = n_cta; shim.lds_bytes = kLdsFusedBytes;
+        for (int l = 0; l < n_layers; l++) {
+            PMat W;
+            W.w = (const uint8_t*)w_dev + (size_t)l * d * d * 2; W.s = nullptr; W.z = nullptr; W.n = d; W.k = d; W.wd = W_BF16;
+            int rc = launch_gemv<W_BF16, 1>(&shim, W, (l & 1) ? b1 : b0, d, (l & 1) ? b0 : b1, 1, EPI_STORE, st);
+            if (rc) return rc;
+        }
+        HIPCHK(hipMemcpyAsync(y_dev, (n_layers & 1) ? b1 : b0, (size_t)d * 4, hipMemcpyDeviceToDevice, st));
+        HIPCHK(hipGetLastError());
+        return FF_OK;
+    }
+    StackArgs a;
+    a.w = (const uint8_t*)w_dev; a.d = d; a.n_layers = n_layers;
+    a.buf[0] = (cword_t*)s; a.buf[1] = (cword_t*)(s + align256((size_t)d * 4));
+    a.status = (int*)(s + 2 * align256((size_t)d * 4));
+    k_stack_pack<<<16, 256, 0, st>>>(a, x_dev);
+    int rc = mode == 2 ? launch_stack<true>(a, n_cta, st) : launch_stack<false>(a, n_cta, st);
+    if (rc) return rc;
+    k_stack_unpack<<<16, 256, 0, st>>>(a, y_dev);
+    HIPCHK(hipGetLastError());
+    return FF_OK;
+}
+
+int ff_debug_set_overlap(ff_model* m, int32_t overlap) {
+    if (!m) return fail(FF_ERR_ARG, "null argument");
+    if (!overlap && (m->cfg.wdtype != W_BF16 || m->cfg.max_batch != 1))
+        return fail(FF_ERR_UNSUPPORTED, "the no-overlap variant exists for bf16 models with max_batch 1 only");
+    m->no_overlap = overlap ? 0 : 1;
     return FF_OK;
 }
 

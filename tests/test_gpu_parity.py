@@ -697,3 +697,44 @@ def test_synthetic_loaders_match_the_python_generators_bit_for_bit():
             binding.ff_kv_free(kv)
         binding.ff_model_free(ma)
         dec.close()
+
+
+def test_stacked_linear_layers_all_modes_against_the_oracle():
+    """ff_debug_stack_linear (the ablation kernel of the paper's stacked-linear study) against the
+    oracle's matrix-vector product applied layer after layer: one launch per layer, fused, and fused
+    with cross-layer overlap give the same vector within the exchange format's rounding."""
+    from paper_2505_22758_amd import binding
+    from oracle import oracle
+    for d, L in ((2048, 3), (4096, 2), (6144, 5)):
+        w = synth.normal_bf16(5, f"stack{d}", (L, d, d), 0.02, "cuda:0")
+        x = synth.normal_bf16(5, "stack.x", (d,), 1.0, "cuda:0").float()
+        ref = x.cpu().numpy().astype(np.float64)
+        for l in range(L):
+            ref = oracle.matvec({"w": w[l].cpu()}, ref)
+        scratch = torch.zeros(2 * ((4 * d + 255) // 256 * 256) + 256, dtype=torch.uint8, device="cuda:0")
+        for mode in (0, 1, 2):
+            y = torch.full((d,), 7.0, device="cuda:0")
+            for _ in range(2):   # twice: the second call starts from the first one's exchange words
+                binding.ff_debug_stack_linear(w, x, y, mode, scratch)
+            torch.cuda.synchronize()
+            assert int(scratch[-256:].view(torch.int32)[0]) == 0
+            err = np.max(np.abs(y.cpu().numpy().astype(np.float64) - ref)) / np.max(np.abs(ref))
+            print(f"stacked linear d={d} L={L} mode {mode}: max error / max |y| = {err:.2e}")
+            assert err < 2e-6 * L, (d, L, mode, err)
+
+
+def test_overlap_switch_changes_timing_not_results():
+    """ff_debug_set_overlap(False) (tiles requested after the input has arrived) gives bit-identical logits."""
+    from paper_2505_22758_amd import binding
+    S, seed, T0 = synth.TINY, 101, 40
+    dec, caches = helpers.hip_side(S, seed, synth.WDTYPE_BF16, 1, T0, max_ctx=T0 + 4, n_caches=2)
+    tok = torch.tensor([9], dtype=torch.int32, device="cuda:0")
+    pos = torch.tensor([T0], dtype=torch.int32, device="cuda:0")
+    a, b = torch.zeros(1, S.vocab, device="cuda:0"), torch.zeros(1, S.vocab, device="cuda:0")
+    binding.ff_decode_step(dec.model, tok, pos, caches[0][0], a, 1)
+    binding.ff_debug_set_overlap(dec.model, False)
+    binding.ff_decode_step(dec.model, tok, pos, caches[1][0], b, 1)
+    binding.ff_debug_set_overlap(dec.model, True)
+    binding.ff_status(dec.model)
+    assert torch.equal(a, b)
+    dec.close()
