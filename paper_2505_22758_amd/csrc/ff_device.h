@@ -57,9 +57,21 @@ struct PLayer {
     PMat down;
 };
 
+// Order of the gate/up row pairs in the packed copy.  Identity (nw == 0): packed pair q = FFN unit q.
+// Interleaved (nw = waves in the grid, P = F / nw pairs per wave): the wave that owns packed pairs
+// [w P, (w + 1) P) holds FFN units w, w + nw, w + 2 nw, ... so that the i-th pair of EVERY wave
+// together cover the contiguous units [i nw, (i + 1) nw): a K chunk of the down projection's input is
+// complete as soon as every wave has finished a fixed, small number of its pairs (see glu_run).
+struct GuPerm {
+    int P, nw;
+    __host__ __device__ int unit_of_pair(int q) const { return nw ? (q % P) * nw + q / P : q; }
+    __host__ __device__ int pair_of_unit(int f) const { return nw ? (f % nw) * P + f / nw : f; }
+};
+
 // Everything the kernels need about the model and its exchange buffers.
 struct DevModel {
     int L, d, Hq, Hkv, hd, F, V;
+    GuPerm gu;               // gate/up pair order of the packed copy
     float eps;
     const PLayer* layers;    // device array [L]
     const bf16_t* embed;

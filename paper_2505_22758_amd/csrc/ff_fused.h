@@ -66,7 +66,7 @@ struct EpiFused {
     __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         switch (kind) {
             case PH_QKV: EpiQKVTagged{M, KV, pos, layer, rope, tag}(pair, b, v0, v1); break;
-            case PH_GU: EpiSwiGLUTagged{M.ch, M.F, cnt}(pair, b, v0, v1); break;
+            case PH_GU: EpiSwiGLUTagged{M.ch, M.F, cnt, M.gu}(pair, b, v0, v1); break;
             case PH_LM: EpiStore{logits, M.V}(pair, b, v0, v1); break;
             default: EpiDeltaTagged{M.cdelta, M.d, cnt}(pair, b, v0, v1); break;
         }
@@ -142,7 +142,7 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
 template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
-                                                                     int batch, int lm_in_kernel, int ncta, int mute_wg, int no_overlap) {
+                                                                     int batch, int lm_in_kernel, int ncta, int mute_wg, int no_overlap, int glu_off) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     if (!inputs_ok(M, KV, tokens, pos)) {
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(M.status, kStatusRange);
@@ -167,6 +167,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     int* pos_lds = (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64 + 8);
     if ((int)threadIdx.x < batch) pos_lds[threadIdx.x] = pos[threadIdx.x];
     if (threadIdx.x < 2) ((lds_u32*)(pairbox_of(xs) + 4 * kPairBoxFloats))[threadIdx.x] = 0u;
+    if (B == 1 && threadIdx.x < kGluMaxChunks) ((lds_u32*)pairbox_of(xs))[threadIdx.x] = 0u;   // arrival counters of the staged h chunks (glu_run)
     __syncthreads();
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
     // weight type differs from the layers' (then the host launches it separately).
@@ -254,12 +255,36 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (kHasSwitch && no_overlap) prefetch_stream<kQuad>(S, ring, lane);
         u64* wv = D.kind < 4 ? dbg_wave_slots(M, n_phases, D.layer, wave) : nullptr;
         if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
-        if constexpr (kQuad) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
+        bool glu_done = false;
+        if constexpr (B == 1) {
+            if (glu_off >= 0 && D.kind == PH_GU) {
+                // gate/up, SwiGLU and down projection as one stream, the down projection's input
+                // staged chunk by chunk on the way (glu_run); the DOWN phase below is skipped
+                const PhaseDesc Dd = phase_desc(M, tokens, tag_base, sl, ph + 1, lm_in_kernel, phase_state(M, ph + 1), false);
+                const Stream<WD, B> Sd = Stream<WD, B>::make(Dd.W, 0, gwave, n_gwaves, false);
+                const int pd = (int)n_gwaves.div((u32)(M.d / 2) + n_gwaves.n - 1u);   // most down-projection row pairs a wave owns
+                float* lacc = (float*)(lds + kLdsActBytes + kLdsAuxBytes) - (size_t)(kFusedWaves - wave) * pd * 128;
+                GluStager<WD> stg{M.ch, sl + (u32)D.layer, M.F, Sd.nup, Sd.cpr, (float4*)(lds + glu_off), (lds_u32*)pairbox_of(xs)};
+                EpiSwiGLUTagged epig{M.ch, M.F, D.out_cnt, M.gu};
+                EpiDeltaTagged epid{M.cdelta, M.d, Dd.out_cnt};
+                const bool okg = glu_run<WD>(S, Sd, ring, xs, stg, lacc, (u32)kFusedWaves * (u32)(D.layer + 1),
+                                             kChunkUnitsOf<WD> * WTraits<WD>::EPU / M.gu.nw, lane, epig, epid);
+                if (!okg) {
+                    if (lane == 0) atomicCAS(M.status, 0, -57 - 10 * ph);
+                    return;
+                }
+                if (wv && lane == 0) as_global(wv)[PH_DOWN] = wall_clock64();
+                glu_done = true;
+            }
+        }
+        if (glu_done) { /* both projections are finished */ }
+        else if constexpr (kQuad) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         else gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         asm volatile("" ::"s"(warm));   // keeps the touch alive
         if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
         if (wv && lane == 0) as_global(wv)[D.kind] = wall_clock64();
         // next iteration: further K segment of the same projection, or the next projection
+        if (glu_done) ++ph;   // the down projection ran inside glu_run
         if (seg + 1 < S.nseg) ++seg;
         else if (ph + 1 < n_phases) { ++ph; seg = 0; }
         else break;
@@ -279,6 +304,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
 struct FusedLaunch {
     DevModel M; DevKV KV; const int* tokens; const int* pos; float* logits;
     int batch; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream; int mute_wg; int no_overlap;
+    int glu_off;   // >= 0: single-sequence passes run gate/up + down as one stream (glu_run), staged h at this LDS offset
 };
 template <int WD, int B, int HD, int G>
 inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what) {
@@ -296,7 +322,7 @@ inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what)
         if (occ < 1) { setup_what = "fused kernel does not fit on a compute unit"; setup_err = hipErrorLaunchOutOfResources; }
     });
     if (setup_err != hipSuccess) { *what = setup_what; return setup_err; }
-    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.lm_in_kernel, a.n_cta, a.mute_wg, a.no_overlap);
+    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.lm_in_kernel, a.n_cta, a.mute_wg, a.no_overlap, a.glu_off);
     *what = "fused kernel launch";
     return hipGetLastError();
 }

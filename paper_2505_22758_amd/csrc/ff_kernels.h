@@ -1,6 +1,7 @@
 // Kernels: the fused whole-model decode step, the per-operation baseline, and the loaders.
 #pragma once
 #include "ff_phases.h"
+#include "ff_glu.h"
 
 namespace ff {
 

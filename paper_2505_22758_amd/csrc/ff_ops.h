@@ -126,12 +126,12 @@ __global__ void __launch_bounds__(kThreads) k_debug_gemv_quad(PMat W, const floa
     gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
 }
 // Debug: rows of a raw projection output y[b][packed rows] in canonical order (same maps as k_dequant).
-__global__ void k_unmap_rows(const float* y, int y_stride, float* out, int n_can, int map, int parity, int row_off, int hd, int batch) {
+__global__ void k_unmap_rows(const float* y, int y_stride, float* out, int n_can, int map, int parity, int row_off, int hd, int batch, GuPerm perm) {
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_can * batch; i += gridDim.x * blockDim.x) {
         const int b = i / n_can, r = i % n_can;
         int pr;
         if (map == 1) { int head = r / hd, within = r % hd, half = hd / 2; pr = head * hd + 2 * (within % half) + within / half; }
-        else if (map == 2) pr = 2 * r + parity;
+        else if (map == 2) pr = 2 * perm.pair_of_unit(r) + parity;
         else pr = r;
         out[(size_t)b * n_can + r] = y[(size_t)b * y_stride + pr + row_off];
     }
@@ -171,7 +171,7 @@ __global__ void __launch_bounds__(kThreads) op_attn_merge(DevModel M, DevKV KV, 
 }
 // y holds raw gate/up outputs, rows interleaved [B][2F]
 __global__ void __launch_bounds__(kThreads) op_swiglu(DevModel M, int batch) {
-    EpiSwiGLU<PlainIO> epi{M.h, M.F};
+    EpiSwiGLU<PlainIO> epi{M.h, M.F, M.gu};
     for (int i = blockIdx.x * kThreads + threadIdx.x; i < M.F * batch; i += gridDim.x * kThreads) {
         int b = i / M.F, p = i % M.F;
         const float* y = M.y + (size_t)b * 2 * M.F + 2 * p;
@@ -182,14 +182,14 @@ __global__ void __launch_bounds__(kThreads) op_swiglu(DevModel M, int batch) {
 // ---------------------------------------------------------------- loaders and utilities
 // dst row r  <-  source row per mode.  row_bytes is a multiple of 2.
 __global__ void __launch_bounds__(kThreads) k_repack_rows(uint8_t* dst, const uint8_t* src_a, const uint8_t* src_b, int n_rows,
-                                                         size_t row_bytes, int mode, int hd) {
+                                                         size_t row_bytes, int mode, int hd, GuPerm perm) {
     for (int r = blockIdx.x; r < n_rows; r += gridDim.x) {
         const uint8_t* src;
         if (mode == REPACK_ROPE) {
             int head = r / hd, within = r % hd;
             src = src_a + (size_t)(head * hd + within / 2 + (within & 1) * (hd / 2)) * row_bytes;
         } else if (mode == REPACK_INTERLEAVE) {
-            src = ((r & 1) ? src_b : src_a) + (size_t)(r / 2) * row_bytes;
+            src = ((r & 1) ? src_b : src_a) + (size_t)perm.unit_of_pair(r / 2) * row_bytes;
         } else {
             src = src_a + (size_t)r * row_bytes;
         }
@@ -224,13 +224,13 @@ __global__ void k_kv_copy(DevKV KV, int L_unused, int Hkv, int hd, bf16_t* plane
 }
 // Dequantise packed matrix element-wise into canonical [N][K] fp32.  map: 0 identity, 1 RoPE-pair
 // block, 2 interleave (even rows: parity 0, odd rows: parity 1); row_off = first packed row.
-__global__ void k_dequant(PMat W, float* out, int n_can, int map, int parity, int row_off, int hd) {
+__global__ void k_dequant(PMat W, float* out, int n_can, int map, int parity, int row_off, int hd, GuPerm perm) {
     size_t tot = (size_t)n_can * W.k;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < tot; i += (size_t)gridDim.x * blockDim.x) {
         int r = i / W.k, c = i % W.k;
         int pr;
         if (map == 1) { int head = r / hd, within = r % hd, half = hd / 2; pr = head * hd + 2 * (within % half) + within / half; }
-        else if (map == 2) pr = 2 * r + parity;
+        else if (map == 2) pr = 2 * perm.pair_of_unit(r) + parity;
         else pr = r;
         pr += row_off;
         const uint8_t* row = W.w + (size_t)pr * W.row_bytes();
@@ -291,7 +291,7 @@ struct SynthMat {   // one canonical matrix [n][k] of the seeded recipe
 // interleaved mode, of A / B alternately), same row maps as k_repack_rows.  dst_w rows of row_bytes;
 // dst_s / dst_z rows of one fp16 (int8) or k/128 fp16 (int4).
 __global__ void __launch_bounds__(kThreads) k_synth_rows(uint8_t* dst_w, f16_t* dst_s, f16_t* dst_z, int n_rows, int wd, SynthMat A, SynthMat B,
-                                                        int mode, int hd, float w_scale) {
+                                                        int mode, int hd, float w_scale, GuPerm perm) {
     for (int r = blockIdx.x; r < n_rows; r += gridDim.x) {
         int sr;
         const SynthMat* Mt = &A;
@@ -299,7 +299,7 @@ __global__ void __launch_bounds__(kThreads) k_synth_rows(uint8_t* dst_w, f16_t* 
             int head = r / hd, within = r % hd;
             sr = head * hd + within / 2 + (within & 1) * (hd / 2);
         } else if (mode == REPACK_INTERLEAVE) {
-            sr = r / 2;
+            sr = perm.unit_of_pair(r / 2);
             if (r & 1) Mt = &B;
         } else {
             sr = r;

@@ -899,10 +899,10 @@ struct EpiResidual {
 // packed rows (2i, 2i+1) = (gate_i, up_i):  h_i = silu(gate_i) * up_i
 template <class IO>
 struct EpiSwiGLU {
-    float* h; int F;
+    float* h; int F; GuPerm perm;
     __device__ __forceinline__ void operator()(int pair, int b, float g, float u) const {
         float s = g / (1.0f + expf(-g));
-        IO::st(h + (size_t)b * F + pair, s * u);
+        IO::st(h + (size_t)b * F + perm.unit_of_pair(pair), s * u);
     }
 };
 // ---- fused-kernel epilogues: outputs go to the tagged exchange buffers ----
@@ -945,10 +945,10 @@ struct EpiDeltaTagged {   // projections feeding the residual stream: publish th
     __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const { cst2(delta + (size_t)b * d + 2 * pair, v0, v1, tag); }
 };
 struct EpiSwiGLUTagged {   // packed rows (2i, 2i+1) = (gate_i, up_i):  h_i = silu(gate_i) * up_i
-    cword_t* h; int F; u32 tag;
+    cword_t* h; int F; u32 tag; GuPerm perm;
     __device__ __forceinline__ void operator()(int pair, int b, float g, float u) const {
         float s = g / (1.0f + expf(-g));
-        cst1(h + (size_t)b * F + pair, s * u, tag);
+        cst1(h + (size_t)b * F + perm.unit_of_pair(pair), s * u, tag);
     }
 };
 struct EpiStore {   // plain output rows (logits; per-op raw projections)

@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -166,6 +167,7 @@ struct ff_model {
     size_t lds_bytes;
     int mute_wg = -1;   // test hook (ff_debug_mute_workgroup)
     int no_overlap = 0; // ablation switch (ff_debug_set_overlap)
+    int glu_off = -1;   // >= 0: LDS offset of the staged SwiGLU output when gate/up + down run as one stream (glu_run)
 };
 struct ff_kv {
     ff_model* model;
@@ -186,21 +188,21 @@ PMat to_pmat(const MatPlan& p, uint8_t* base) {
 
 // copy canonical rows [n_rows] of `src` into packed rows starting at dst_row, with row mapping
 int repack(const MatPlan& dst, uint8_t* packed, int dst_row, int n_rows, const ff_matrix& a, const ff_matrix* b, int mode, int hd,
-           hipStream_t st) {
+           const GuPerm& perm, hipStream_t st) {
     if (!a.w || (b && !b->w)) return fail(FF_ERR_ARG, "matrix pointer is null");
     size_t rb = dst.wd == W_BF16 ? (size_t)dst.k * 2 : dst.wd == W_INT8 ? (size_t)dst.k : (size_t)dst.k / 2;
     int grid = std::min(n_rows, 4096);
     k_repack_rows<<<grid, kThreads, 0, st>>>(packed + dst.w + (size_t)dst_row * rb, (const uint8_t*)a.w, b ? (const uint8_t*)b->w : nullptr,
-                                             n_rows, rb, mode, hd);
+                                             n_rows, rb, mode, hd, perm);
     if (dst.wd != W_BF16) {
         if (!a.s || (b && !b->s)) return fail(FF_ERR_ARG, "scale pointer is null for a quantised matrix");
         size_t sb = dst.wd == W_INT8 ? 2 : (size_t)(dst.k / 128) * 2;
         k_repack_rows<<<grid, kThreads, 0, st>>>(packed + dst.s + (size_t)dst_row * sb, (const uint8_t*)a.s, b ? (const uint8_t*)b->s : nullptr,
-                                                 n_rows, sb, mode, hd);
+                                                 n_rows, sb, mode, hd, perm);
         if (dst.wd == W_INT4) {
             if (!a.z || (b && !b->z)) return fail(FF_ERR_ARG, "zero-point pointer is null for an int4 matrix");
             k_repack_rows<<<grid, kThreads, 0, st>>>(packed + dst.z + (size_t)dst_row * sb, (const uint8_t*)a.z,
-                                                     b ? (const uint8_t*)b->z : nullptr, n_rows, sb, mode, hd);
+                                                     b ? (const uint8_t*)b->z : nullptr, n_rows, sb, mode, hd, perm);
         }
     }
     HIPCHK(hipGetLastError());
@@ -295,6 +297,25 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     DevModel& D = m->dev;
     D.L = cfg->n_layers; D.d = cfg->d_model; D.Hq = cfg->n_q_heads; D.Hkv = cfg->n_kv_heads; D.hd = cfg->head_dim;
     D.F = cfg->d_ffn; D.V = cfg->vocab; D.eps = cfg->rms_eps;
+    {   // gate/up pairs interleaved over the grid's waves when every wave owns the same whole number of
+        // pairs and a staged K chunk of the down projection is a whole number of "one pair per wave" rounds
+        const int nw = m->n_cta * kFusedWaves;
+        const int chunk_elems = cfg->wdtype == W_BF16 ? kChunkUnitsOf<W_BF16> * 8 : cfg->wdtype == W_INT8 ? kChunkUnitsOf<W_INT8> * 16 : kChunkUnitsOf<W_INT4> * 32;
+        const char* off = getenv("FF_NO_GLU_PIPE");
+        const bool ok = cfg->d_ffn % nw == 0 && chunk_elems % nw == 0 && !(off && off[0] == '1');
+        D.gu = ok ? GuPerm{cfg->d_ffn / nw, nw} : GuPerm{0, 0};
+        // glu_run (single-sequence passes) needs the staged h beside the staged projection input, the
+        // per-lane partial sums of a wave's down-projection rows at the end of the aux region, at most
+        // kGluMaxChunks chunks and at least a ring's worth of gate/up stages per wave
+        const int qd = cfg->n_q_heads * cfg->head_dim;
+        const int in_off = (std::max(cfg->d_model, qd) + chunk_elems - 1) / chunk_elems * chunk_elems * 4;
+        const int f_pad = (cfg->d_ffn + chunk_elems - 1) / chunk_elems * chunk_elems;
+        const int pd = (cfg->d_model / 2 + nw - 1) / nw;                       // most down-projection row pairs a wave owns
+        const int cpr_g = (cfg->d_model + chunk_elems - 1) / chunk_elems;      // stages per gate/up pair
+        const bool fits = (size_t)in_off + (size_t)f_pad * 4 + (size_t)kFusedWaves * pd * 512 <= (size_t)kLdsActBytes + kLdsAuxBytes &&
+                          f_pad / chunk_elems <= kGluMaxChunks && (cfg->d_ffn / nw) * cpr_g >= 4;
+        m->glu_off = ok && fits ? in_off : -1;
+    }
     D.layers = (const PLayer*)(m->packed + P.layers_tab);
     D.embed = (const bf16_t*)(m->packed + P.embed);
     D.gf = (const bf16_t*)(m->packed + P.gf);
@@ -342,12 +363,12 @@ int ff_model_load_layer(ff_model* m, int32_t layer, const ff_layer_weights* w, v
     HIPCHK(hipMemcpyAsync(m->packed + L.g1, w->attn_norm, (size_t)c.d_model * 2, hipMemcpyDeviceToDevice, st));
     HIPCHK(hipMemcpyAsync(m->packed + L.g2, w->ffn_norm, (size_t)c.d_model * 2, hipMemcpyDeviceToDevice, st));
     int qr = c.n_q_heads * c.head_dim, kr = c.n_kv_heads * c.head_dim, rc;
-    if ((rc = repack(L.qkv, m->packed, 0, qr, w->wq, nullptr, REPACK_ROPE, c.head_dim, st))) return rc;
-    if ((rc = repack(L.qkv, m->packed, qr, kr, w->wk, nullptr, REPACK_ROPE, c.head_dim, st))) return rc;
-    if ((rc = repack(L.qkv, m->packed, qr + kr, kr, w->wv, nullptr, REPACK_COPY, c.head_dim, st))) return rc;
-    if ((rc = repack(L.o, m->packed, 0, c.d_model, w->wo, nullptr, REPACK_COPY, c.head_dim, st))) return rc;
-    if ((rc = repack(L.gu, m->packed, 0, 2 * c.d_ffn, w->w_gate, &w->w_up, REPACK_INTERLEAVE, c.head_dim, st))) return rc;
-    if ((rc = repack(L.down, m->packed, 0, c.d_model, w->w_down, nullptr, REPACK_COPY, c.head_dim, st))) return rc;
+    if ((rc = repack(L.qkv, m->packed, 0, qr, w->wq, nullptr, REPACK_ROPE, c.head_dim, m->dev.gu, st))) return rc;
+    if ((rc = repack(L.qkv, m->packed, qr, kr, w->wk, nullptr, REPACK_ROPE, c.head_dim, m->dev.gu, st))) return rc;
+    if ((rc = repack(L.qkv, m->packed, qr + kr, kr, w->wv, nullptr, REPACK_COPY, c.head_dim, m->dev.gu, st))) return rc;
+    if ((rc = repack(L.o, m->packed, 0, c.d_model, w->wo, nullptr, REPACK_COPY, c.head_dim, m->dev.gu, st))) return rc;
+    if ((rc = repack(L.gu, m->packed, 0, 2 * c.d_ffn, w->w_gate, &w->w_up, REPACK_INTERLEAVE, c.head_dim, m->dev.gu, st))) return rc;
+    if ((rc = repack(L.down, m->packed, 0, c.d_model, w->w_down, nullptr, REPACK_COPY, c.head_dim, m->dev.gu, st))) return rc;
     m->layer_loaded[layer] = 1;
     return FF_OK;
 }
@@ -359,7 +380,7 @@ int ff_model_load_head(ff_model* m, const ff_head_weights* w, void* stream) {
     const ff_config& c = m->cfg;
     HIPCHK(hipMemcpyAsync(m->packed + m->plan.embed, w->embed, (size_t)c.vocab * c.d_model * 2, hipMemcpyDeviceToDevice, st));
     HIPCHK(hipMemcpyAsync(m->packed + m->plan.gf, w->final_norm, (size_t)c.d_model * 2, hipMemcpyDeviceToDevice, st));
-    int rc = repack(m->plan.lm, m->packed, 0, c.vocab, w->lm_head, nullptr, REPACK_COPY, c.head_dim, st);
+    int rc = repack(m->plan.lm, m->packed, 0, c.vocab, w->lm_head, nullptr, REPACK_COPY, c.head_dim, m->dev.gu, st);
     if (rc) return rc;
     m->head_loaded = true;
     return FF_OK;
@@ -414,12 +435,13 @@ SynthMat synth_mat(uint64_t seed, int layer, const char* which, int k, int wd) {
     s.c_scale = wd == W_INT8 ? (float)(0.02 / 73.6) : (float)(0.02 / 6.5);
     return s;
 }
-int synth_part(const MatPlan& dst, uint8_t* packed, int dst_row, int n_rows, const SynthMat& a, const SynthMat& b, int mode, int hd, hipStream_t st) {
+int synth_part(const MatPlan& dst, uint8_t* packed, int dst_row, int n_rows, const SynthMat& a, const SynthMat& b, int mode, int hd,
+               const GuPerm& perm, hipStream_t st) {
     const size_t rb = dst.wd == W_BF16 ? (size_t)dst.k * 2 : dst.wd == W_INT8 ? (size_t)dst.k : (size_t)dst.k / 2;
     const size_t sb = dst.wd == W_INT8 ? 2 : (size_t)(dst.k / 128) * 2;
     k_synth_rows<<<std::min(n_rows, 8192), kThreads, 0, st>>>(packed + dst.w + (size_t)dst_row * rb, (f16_t*)(packed + dst.s + (size_t)dst_row * sb),
                                                              (f16_t*)(packed + dst.z + (size_t)dst_row * sb), n_rows, dst.wd, a, b, mode, hd,
-                                                             (float)(0.02 / kIh4Std));
+                                                             (float)(0.02 / kIh4Std), perm);
     HIPCHK(hipGetLastError());
     return FF_OK;
 }
@@ -443,19 +465,19 @@ int ff_model_load_synthetic(const ff_config* cfg, uint64_t seed, void* packed_de
         const SynthMat wq = synth_mat(seed, l, "wq", c.d_model, wd), wk = synth_mat(seed, l, "wk", c.d_model, wd), wv = synth_mat(seed, l, "wv", c.d_model, wd),
                        wo = synth_mat(seed, l, "wo", qr, wd), wg = synth_mat(seed, l, "w_gate", c.d_model, wd), wu = synth_mat(seed, l, "w_up", c.d_model, wd),
                        wdn = synth_mat(seed, l, "w_down", c.d_ffn, wd);
-        if (!rc) rc = synth_part(L.qkv, m->packed, 0, qr, wq, wq, REPACK_ROPE, c.head_dim, st);
-        if (!rc) rc = synth_part(L.qkv, m->packed, qr, kr, wk, wk, REPACK_ROPE, c.head_dim, st);
-        if (!rc) rc = synth_part(L.qkv, m->packed, qr + kr, kr, wv, wv, REPACK_COPY, c.head_dim, st);
-        if (!rc) rc = synth_part(L.o, m->packed, 0, c.d_model, wo, wo, REPACK_COPY, c.head_dim, st);
-        if (!rc) rc = synth_part(L.gu, m->packed, 0, 2 * c.d_ffn, wg, wu, REPACK_INTERLEAVE, c.head_dim, st);
-        if (!rc) rc = synth_part(L.down, m->packed, 0, c.d_model, wdn, wdn, REPACK_COPY, c.head_dim, st);
+        if (!rc) rc = synth_part(L.qkv, m->packed, 0, qr, wq, wq, REPACK_ROPE, c.head_dim, m->dev.gu, st);
+        if (!rc) rc = synth_part(L.qkv, m->packed, qr, kr, wk, wk, REPACK_ROPE, c.head_dim, m->dev.gu, st);
+        if (!rc) rc = synth_part(L.qkv, m->packed, qr + kr, kr, wv, wv, REPACK_COPY, c.head_dim, m->dev.gu, st);
+        if (!rc) rc = synth_part(L.o, m->packed, 0, c.d_model, wo, wo, REPACK_COPY, c.head_dim, m->dev.gu, st);
+        if (!rc) rc = synth_part(L.gu, m->packed, 0, 2 * c.d_ffn, wg, wu, REPACK_INTERLEAVE, c.head_dim, m->dev.gu, st);
+        if (!rc) rc = synth_part(L.down, m->packed, 0, c.d_model, wdn, wdn, REPACK_COPY, c.head_dim, m->dev.gu, st);
         m->layer_loaded[l] = 1;
     }
     if (!rc) {
         k_synth_normal<<<2048, 256, 0, st>>>((bf16_t*)(m->packed + m->plan.embed), (size_t)c.vocab * c.d_model, tensor_key(seed, "embed"), gscale, 0.f);
         k_synth_normal<<<16, 256, 0, st>>>((bf16_t*)(m->packed + m->plan.gf), (size_t)c.d_model, tensor_key(seed, "final_norm"), gscale, 1.0f);
         const SynthMat lm = synth_mat(seed, -1, "lm_head", c.d_model, m->plan.lm.wd);
-        rc = synth_part(m->plan.lm, m->packed, 0, c.vocab, lm, lm, REPACK_COPY, c.head_dim, st);
+        rc = synth_part(m->plan.lm, m->packed, 0, c.vocab, lm, lm, REPACK_COPY, c.head_dim, m->dev.gu, st);
         m->head_loaded = true;
     }
     if (!rc && hipGetLastError() != hipSuccess) rc = fail(FF_ERR_HIP, "synthetic fill launch failed");
@@ -573,7 +595,7 @@ int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const 
         k_scrub_rows<<<64, kThreads, 0, st>>>(D, batch);
         HIPCHK(hipGetLastError());
     }
-    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg, m->no_overlap};
+    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg, m->no_overlap, m->glu_off};
     const char* what = "";
     const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     hipError_t e = hipErrorInvalidValue;
@@ -805,7 +827,7 @@ int ff_debug_gemv(ff_model* m, int32_t layer, int32_t which, const float* in_dev
     else if (W.wd == W_INT8) rc = debug_quad_any<W_INT8>(m, W, in_dev, raw, batch, st);
     else rc = debug_quad_any<W_INT4>(m, W, in_dev, raw, batch, st);
     if (rc) return rc;
-    if (!direct) k_unmap_rows<<<256, 256, 0, st>>>(raw, W.n, out_dev, s.n_can, s.map, s.parity, s.row_off, m->cfg.head_dim, batch);
+    if (!direct) k_unmap_rows<<<256, 256, 0, st>>>(raw, W.n, out_dev, s.n_can, s.map, s.parity, s.row_off, m->cfg.head_dim, batch, m->dev.gu);
     HIPCHK(hipGetLastError());
     return FF_OK;
 }
@@ -815,7 +837,7 @@ int ff_debug_dequant(const ff_model* m, int32_t layer, int32_t which, float* out
     MatSel s;
     int rc = select_matrix(m, layer, which, &s);
     if (rc) return rc;
-    k_dequant<<<2048, 256, 0, (hipStream_t)stream>>>(s.W, out_dev, s.n_can, s.map, s.parity, s.row_off, m->cfg.head_dim);
+    k_dequant<<<2048, 256, 0, (hipStream_t)stream>>>(s.W, out_dev, s.n_can, s.map, s.parity, s.row_off, m->cfg.head_dim, m->dev.gu);
     HIPCHK(hipGetLastError());
     return FF_OK;
 }
