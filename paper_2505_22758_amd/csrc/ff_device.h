@@ -19,6 +19,7 @@ constexpr int kThreads = 256;            // threads per workgroup (4 waves, one 
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxBatch = 4;        // sequences one kernel pass works on
 constexpr int kMaxBatchFused = 8;   // ... of the fused kernel with bf16 weights, if the input rows of 8 sequences fit in LDS
+constexpr int kMaxBatchWide = 16;   // ... of its wide instance (bf16 weights): inputs staged one K segment at a time, RMSNorm scale applied to the outputs
 constexpr int kMaxBatchApi = 16;    // sequences one decode step accepts (run as passes of kMaxBatch)
 constexpr int kMaxSplits = 64;           // max KV splits per (sequence, kv head)
 #ifndef FF_MIN_SPLIT

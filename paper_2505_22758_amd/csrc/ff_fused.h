@@ -155,7 +155,14 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float4* xs = (float4*)lds;
-    float2* rope_lds = (float2*)(lds + kLdsActBytes + kLdsAuxBytes);   // [batch][hd/2]
+    // A wide pass (more than kMaxBatchFused sequences, bf16 weights) keeps its RoPE rows in the tail of
+    // the aux region that only int4 weights use plus the regular RoPE region behind it, and its
+    // positions and per-wave sums of squares (deferred RMSNorm, see PostScale) in the mailbox region
+    // (wave pairs never share a row group there).
+    constexpr bool kWide = B > kMaxBatchFused;
+    static_assert(!kWide || (WD == W_BF16 && kLdsXsumBytes + kLdsRopeBytes >= B * 64 * (int)sizeof(float2) && kLdsPairBytes >= (B + kFusedWaves * kMaxBatchWide) * 4 &&
+                             B <= kMaxBatchWide), "LDS layout of the wide pass");
+    float2* rope_lds = (float2*)(lds + kLdsActBytes + kLdsAuxBytes - (kWide ? kLdsXsumBytes : 0));   // [batch][hd/2]
     for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kFusedThreads) {
         int b = i / (M.hd / 2), f = i % (M.hd / 2);
         rope_lds[i] = KV.rope[(size_t)pos[b] * (M.hd / 2) + f];
@@ -164,9 +171,11 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // make the wave wait for everything it has in flight (its prefetched weight tiles included), so
     // the grid size is a kernel argument and the positions are staged in LDS once.
     static_assert(kLdsRopeBytes == kMaxBatchFused * 64 * sizeof(float2) && kLdsMiscBytes >= (16 + 2 * (1 + WgVote::kMaxSums) * kFusedWaves) * 4, "LDS layout");
-    int* pos_lds = (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64 + 8);
+    int* pos_lds = kWide ? (int*)(lds + kLdsActBytes + kLdsAuxBytes + kLdsRopeBytes + kLdsMiscBytes)
+                         : (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64 + 8);
+    float* rowss = (float*)(lds + kLdsActBytes + kLdsAuxBytes + kLdsRopeBytes + kLdsMiscBytes) + kMaxBatchWide;   // wide pass only: [wave][sequence]
     if ((int)threadIdx.x < batch) pos_lds[threadIdx.x] = pos[threadIdx.x];
-    if (threadIdx.x < 2) ((lds_u32*)(pairbox_of(xs) + 4 * kPairBoxFloats))[threadIdx.x] = 0u;
+    if (!kWide && threadIdx.x < 2) ((lds_u32*)(pairbox_of(xs) + 4 * kPairBoxFloats))[threadIdx.x] = 0u;
     if (B == 1 && threadIdx.x < kGluMaxChunks) ((lds_u32*)pairbox_of(xs))[threadIdx.x] = 0u;   // arrival counters of the staged h chunks (glu_run)
     __syncthreads();
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
@@ -214,7 +223,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         // the loads were issued to (a copy would have to wait for the data).
         TSrc src = D.src;
         src.ncta = n_ctas;
-        if (seg > 0) src.wb = nullptr;
+        if (!kWide && seg > 0) src.wb = nullptr;   // (a wide pass publishes the residual stream segment by segment)
         const bool att_first = D.kind == PH_O && seg == 0;
         Stage<WD> ring[kDepthOf<WD>];
         // (ablation switch, single-sequence bf16 instances only: with no_overlap the tiles are requested
@@ -244,8 +253,8 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (wave == 0) dbg_event(M, ph, EV_H_START, lane);
         bool ok;
         u64* ev = dbg_stage_slots(M, n_phases, ncta, D.layer, D.kind);
-        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
-        else ok = stage_tagged<EPU, false, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
+        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev, rowss);
+        else ok = stage_tagged<EPU, false, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev, rowss);
         if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
         if (!ok) {
             if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);
@@ -278,6 +287,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             }
         }
         if (glu_done) { /* both projections are finished */ }
+        else if constexpr (kWide) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi, PostScale{src.gain ? rowss : nullptr, 1.f / (float)S.K, M.eps});
         else if constexpr (kQuad) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         else gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         asm volatile("" ::"s"(warm));   // keeps the touch alive
@@ -305,6 +315,7 @@ struct FusedLaunch {
     DevModel M; DevKV KV; const int* tokens; const int* pos; float* logits;
     int batch; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream; int mute_wg; int no_overlap;
     int glu_off;   // >= 0: single-sequence passes run gate/up + down as one stream (glu_run), staged h at this LDS offset
+    int wide;      // the pass runs on the wide instance (K-segmented inputs, LM head outside the kernel)
 };
 template <int WD, int B, int HD, int G>
 inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what) {
@@ -330,7 +341,8 @@ template <int WD, int HD, int G>
 inline hipError_t launch_fused_family(const FusedLaunch& a, const char** what) {
     if (a.batch == 1) return launch_fused_instance<WD, 1, HD, G>(a, what);
     if (a.batch == 2) return launch_fused_instance<WD, 2, HD, G>(a, what);
-    if constexpr (WD == W_BF16) {   // eight sequences per pass: bf16 only (fused_pass_rows on the host decides)
+    if constexpr (WD == W_BF16) {   // more than four sequences per pass: bf16 only (fused_pass_rows on the host decides)
+        if (a.wide) return launch_fused_instance<WD, kMaxBatchWide, HD, G>(a, what);
         if (a.batch > kMaxBatch) return launch_fused_instance<WD, kMaxBatchFused, HD, G>(a, what);
     }
     return launch_fused_instance<WD, 4, HD, G>(a, what);

@@ -316,8 +316,13 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
 // a single workgroup barrier and the staged vectors are written once, already scaled.  The loads
 // of all RB rows are in flight together: behind a wave's weight prefetch a round trip takes
 // microseconds, and one per row would make the hand-over grow with the batch.
-template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT, int RB>
-__device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, int tid, WgVote& vote, u64* ev) {
+// DEFER (wide passes, where [k0, k0 + nunits*EPU) is one K segment of a longer row): the staged
+// values keep the gain but not the 1/rms factor; every wave adds its share of the segment's sums of
+// squares to rowss[wave * kMaxBatchWide + b] (set, not added, by the first segment), and the
+// projection scales its finished sums instead (PostScale).
+template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT, int RB, bool DEFER = false>
+__device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, int tid, WgVote& vote, u64* ev,
+                                                     float* rowss = nullptr) {
     constexpr int NQ = EPU / 4;
     if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
     const int lane = tid & 63;
@@ -373,8 +378,8 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
             }
         };
         load_quads(std::true_type{});
+        float ss[RB];   // only meaningful if the vote passes
         for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
-            float ss[RB];   // only meaningful if the vote passes
             bool mine = true;
             // With a single row in flight the lane first ORs the counter mismatches of all its
             // words together (one operation per word) and looks at single quads only if something
@@ -410,7 +415,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                 mine = mine && stale[r] == 0;
                 if constexpr (HAS_GAIN) ss[r] = wave_sum_uniform(ss[r]);
             }
-            if constexpr (HAS_GAIN) all_ok = vote.all_sum<NT, RB>(mine, ss, tot);
+            if constexpr (HAS_GAIN && !DEFER) all_ok = vote.all_sum<NT, RB>(mine, ss, tot);
             else all_ok = vote.all<NT>(mine);
             if (ev && tid == 0 && spins == 0 && b0 == 0) as_global(ev)[1] = wall_clock64();
             if (!all_ok && !S.eager) {
@@ -428,6 +433,17 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
         }
         if (!all_ok) return false;
         if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
+        if constexpr (HAS_GAIN && DEFER) {
+            if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < RB; r++) {
+                    if (b0 + r < batch) {
+                        float* p = rowss + (tid >> 6) * kMaxBatchWide + b0 + r;
+                        *p = (k0 == 0 ? 0.f : *p) + ss[r];
+                    }
+                }
+            }
+        }
         // Usually every (lane, u) holds a real quad (the vector is a whole number of NT*QB quads,
         // no padding): that case runs without the per-lane range tests, each of which is a
         // divergent branch -- expensive for a wave that has its SIMD to itself.
@@ -456,7 +472,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
         for (int r = 0; r < RB; r++) {
             const int b = b0 + r;
             if (b < batch) {
-                const float rs = HAS_GAIN ? rsqrtf(tot[r] / (float)K + S.eps) : 1.f;
+                const float rs = HAS_GAIN && !DEFER ? rsqrtf(tot[r] / (float)K + S.eps) : 1.f;
                 if (exact) {
 #pragma unroll
                     for (int u = 0; u < QB; u++) write_quad(std::true_type{}, r, u, b, rs);
@@ -478,10 +494,17 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
 // no SPLIT form (the host rejects such configurations).
 template <int EPU, bool HAS_ADD, int NT, bool SPLIT, int RBMAX>
 __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
-                                             WgVote& vote, u64* ev = nullptr) {
+                                             WgVote& vote, u64* ev = nullptr, float* rowss = nullptr) {
     constexpr int RB4 = RBMAX < 4 ? RBMAX : 4, RB2 = RBMAX < 2 ? RBMAX : 2;
     const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
-    if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
+    if constexpr (RBMAX > kMaxBatchFused) {
+        // wide pass: K segments of two quads per thread, eight rows in flight together, deferred
+        // normalisation (a segment never holds a whole normalised row's worth of squares)
+        static_assert(SPLIT && (kLdsActBytes / (RBMAX * 4)) / 4 <= 2 * NT, "a wide pass's segment is two quads per thread");
+        if constexpr (HAS_ADD) return stage_tagged_onepass<EPU, true, true, NT, 2, true, 8, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev, rowss);
+        else if (S.gain) return stage_tagged_onepass<EPU, false, true, NT, 2, true, 8, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev, rowss);
+        else return stage_tagged_onepass<EPU, false, false, NT, 2, true, 8, false>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+    } else if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
         if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         if constexpr (SPLIT) return false;

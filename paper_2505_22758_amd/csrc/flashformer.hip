@@ -95,10 +95,31 @@ int check_config(const ff_config* c) {
     return FF_OK;
 }
 
-// Sequences one pass of the fused kernel serves: 8 with bf16 weights when their input rows fit the
-// on-chip buffer together (and the model is created for that many), else up to 4.
+// Does a pass of `batch` sequences run on the wide instance of the fused kernel (bf16 weights, up to
+// kMaxBatchWide sequences, inputs staged one K segment at a time)?  Five to eight sequences whose whole
+// input rows fit the on-chip buffer together take the eight-sequence instance instead.
+bool pass_is_wide(const ff_config& c, int batch) {
+    if (c.wdtype != W_BF16 || batch <= kMaxBatch) return false;
+    return batch > kMaxBatchFused || (size_t)c.d_model * 4 * kMaxBatchFused > (size_t)kLdsActBytes;
+}
+// The wide instance carries a wave's partial sums from one K segment to the next in LDS: the row
+// groups a wave owns (of the widest projection, on a grid of `nwaves` waves) times 16 sequences must fit.
+bool wide_fits(const ff_config& c, int nwaves) {
+    const int qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const int rows = std::max(std::max(qkv_rows, c.d_model), 2 * c.d_ffn);
+    const int groups = ((rows + 3) / 4 + nwaves - 1) / nwaves;
+    return groups * 4 * kMaxBatchWide <= kAccFloatsPerWave;
+}
+constexpr int kGridWaves = 256 * kFusedWaves;   // waves of the fused kernel's grid on the chip the kernels are built for
+
+// Sequences one pass of the fused kernel serves: with bf16 weights and a model created for more than
+// four, 8 (input rows fit the on-chip buffer together) or 16 (wide instance); else up to 4.
 int fused_pass_rows(const ff_config& c) {
-    if (c.wdtype == W_BF16 && c.max_batch > kMaxBatch && (size_t)c.d_model * 4 * kMaxBatchFused <= (size_t)kLdsActBytes) return kMaxBatchFused;
+    if (c.wdtype == W_BF16 && c.max_batch > kMaxBatch) {
+        if (c.max_batch <= kMaxBatchFused && !pass_is_wide(c, c.max_batch)) return kMaxBatchFused;
+        if (wide_fits(c, kGridWaves)) return kMaxBatchWide;
+        if (!pass_is_wide(c, kMaxBatchFused)) return kMaxBatchFused;
+    }
     return std::min(c.max_batch, kMaxBatch);
 }
 
@@ -293,6 +314,10 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     m->n_cta = prop.multiProcessorCount;
     m->lds_bytes = kLdsFusedBytes;
     if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
+    if (fused_pass_rows(*cfg) > kMaxBatchFused && !wide_fits(*cfg, m->n_cta * kFusedWaves)) {
+        delete m;
+        return fail(FF_ERR_UNSUPPORTED, "max_batch %d needs the wide pass, whose partial sums do not fit a grid of %d workgroups", cfg->max_batch, prop.multiProcessorCount);
+    }
 
     DevModel& D = m->dev;
     D.L = cfg->n_layers; D.d = cfg->d_model; D.Hq = cfg->n_q_heads; D.Hkv = cfg->n_kv_heads; D.hd = cfg->head_dim;
@@ -587,7 +612,8 @@ namespace {
 // counters kept on the device), so the launches of a step may be recorded into a HIP graph.
 int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch, int seq0,
                int step_batch, hipStream_t st) {
-    const int lm_in_kernel = D.lm.wd == m->cfg.wdtype;
+    const bool wide = pass_is_wide(m->cfg, batch);   // (batch <= fused_pass_rows: a wide pass only where the wide instance fits)
+    const int lm_in_kernel = D.lm.wd == m->cfg.wdtype && !wide;
     DevKV kvd = kv->dev;
     kvd.seq0 = seq0;
     kvd.step_batch = step_batch;
@@ -595,7 +621,8 @@ int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const 
         k_scrub_rows<<<64, kThreads, 0, st>>>(D, batch);
         HIPCHK(hipGetLastError());
     }
-    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg, m->no_overlap, m->glu_off};
+    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg, m->no_overlap, m->glu_off,
+                  wide ? 1 : 0};
     const char* what = "";
     const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     hipError_t e = hipErrorInvalidValue;
@@ -605,12 +632,14 @@ int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const 
     FF_FUSED_FAMILIES(FF_TRY_FAMILY)
 #undef FF_TRY_FAMILY
     if (e != hipSuccess) return fail(e == hipErrorLaunchOutOfResources ? FF_ERR_UNSUPPORTED : FF_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
-    if (!lm_in_kernel) {   // LM head of a different weight type than the layers: separate launches
+    if (!lm_in_kernel) {   // LM head of a different weight type than the layers, or a wide pass: separate launches
         const ff_config& c = m->cfg;
         op_final_x<<<16, kThreads, 0, st>>>(D.x, D.cx, D.cdelta, batch * c.d_model);
         op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, D.gf, D.xn, c.d_model, c.rms_eps);
-        int rc = gemv_op(m, D.lm, D.xn, c.d_model, logits_dev, batch, EPI_STORE, st);
-        if (rc) return rc;
+        for (int b0 = 0; b0 < batch; b0 += kMaxBatch) {
+            int rc = gemv_op(m, D.lm, D.xn + (size_t)b0 * c.d_model, c.d_model, logits_dev + (size_t)b0 * c.vocab, std::min(kMaxBatch, batch - b0), EPI_STORE, st);
+            if (rc) return rc;
+        }
         HIPCHK(hipGetLastError());
     }
     return FF_OK;

@@ -750,3 +750,14 @@ def test_glu_as_one_stream_small_model_all_formats():
         _run_teacher_forced(S, 0x250522780 + wd, wd, batch=1, T0=37, steps=3)
     _run_teacher_forced(S, 0x250522784, synth.WDTYPE_BF16, batch=2, T0=20, steps=2)
     _run_teacher_forced(S, 0x250522785, synth.WDTYPE_INT4, batch=3, T0=20, steps=2)
+
+
+def test_wide_pass_of_up_to_16_sequences_small_model():
+    """More than eight sequences (bf16 weights) run as ONE pass whose inputs are staged one K segment
+    of 2048 elements at a time (d_model 4096 = 2 segments, d_ffn 6144 = 3), with the RMSNorm scale
+    applied to the projection outputs and the LM head in launches of its own: a full pass of 16 and a
+    ragged one of 11, sequences of different lengths, two layers so that the second one stages
+    residual stream + sublayer output segment by segment."""
+    S = synth.TINY.replace(name="wide", n_layers=2, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ffn=6144, vocab=3000)
+    _run_teacher_forced(S, 0x250522790, synth.WDTYPE_BF16, batch=16, T0=[40, 0, 1, 130, 64, 63, 65, 9, 300, 17, 128, 5, 77, 256, 2, 33], steps=2)
+    _run_teacher_forced(S, 0x250522791, synth.WDTYPE_BF16, batch=11, T0=[7, 70, 0, 129, 31, 64, 200, 1, 90, 12, 55], steps=2)
