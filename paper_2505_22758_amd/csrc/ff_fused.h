@@ -207,6 +207,10 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // the previous projection), so batch 1 keeps the unpinned form.
     constexpr bool kScalarState = B > 1;
     constexpr bool kQuad = kQuadOf<WD, B>;   // matrix-core GEMV on groups of four rows, split-bf16 staged input
+    // wide pass: register ring and tile accumulators of the dense projections, alive over the K
+    // segments of a projection (see dense_run)
+    Stage<W_BF16> wring[2];
+    mfma_f4 dah[kDenseMaxTiles], dal[kDenseMaxTiles];
     int ph = 0, seg = 0;
     for (;;) {
         if constexpr (kScalarState) {
@@ -229,7 +233,11 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         // (ablation switch, single-sequence bf16 instances only: with no_overlap the tiles are requested
         // after the input has arrived, as in a fused kernel without cross-layer memory overlap)
         constexpr bool kHasSwitch = B == 1 && WD == W_BF16;
-        if (!kHasSwitch || !no_overlap) prefetch_stream<kQuad>(S, ring, lane);
+        DenseStream DS;
+        if constexpr (kWide) {
+            DS = DenseStream::make(D.W, seg, n_ctas);
+            if (seg == 0) dense_prefetch(DS, wring, wave, lane);   // (later segments: requested at the end of the previous one)
+        } else if (!kHasSwitch || !no_overlap) prefetch_stream<kQuad>(S, ring, lane);
         if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);
         // Touch the descriptor the NEXT phase will fetch, so that it sits in the scalar cache by
         // then instead of costing a trip to memory at the head of that phase.
@@ -287,7 +295,13 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             }
         }
         if (glu_done) { /* both projections are finished */ }
-        else if constexpr (kWide) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi, PostScale{src.gain ? rowss : nullptr, 1.f / (float)S.K, M.eps});
+        else if constexpr (kWide) {
+            if (seg == 0) {
+#pragma unroll
+                for (int t = 0; t < kDenseMaxTiles; t++) { dah[t] = mfma_f4{0.f, 0.f, 0.f, 0.f}; dal[t] = mfma_f4{0.f, 0.f, 0.f, 0.f}; }
+            }
+            dense_run(DS, wring, xs, dah, dal, batch, wave, lane, epi, PostScale{src.gain ? rowss : nullptr, 1.f / (float)S.K, M.eps});
+        }
         else if constexpr (kQuad) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         else gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         asm volatile("" ::"s"(warm));   // keeps the touch alive

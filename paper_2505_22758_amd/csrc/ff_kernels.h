@@ -2,6 +2,7 @@
 #pragma once
 #include "ff_phases.h"
 #include "ff_glu.h"
+#include "ff_dense.h"
 
 namespace ff {
 

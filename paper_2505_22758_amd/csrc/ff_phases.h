@@ -144,6 +144,23 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
     return false;
 }
 
+// The same over all batch rows: lane i samples row (i / 4) % batch at one of four positions (shifted
+// per workgroup), one coherent 4-byte load per lane and round.
+template <bool HAS_ADD>
+__device__ __forceinline__ bool light_wait_rows(const TSrc& S, int batch, int k0, int nel, int lane) {
+    const int sample = min(k0 + (int)(((long)(lane & 3) * nel) / 4) + (int)(blockIdx.x % 64) * 2 + (lane >> 6), k0 + nel - 1);
+    const int row = (lane >> 2) % batch;
+    const cword_t* sb = S.base + (size_t)row * S.stride;
+    const cword_t* sa = HAS_ADD ? S.add + (size_t)row * S.add_stride : nullptr;
+    for (int spins = 0; spins < kSpinLimit; spins++) {
+        bool ok = cfresh(cld1(sb, sample), S.tag);
+        if constexpr (HAS_ADD) ok = ok && cfresh(cld1(sa, sample), S.add_tag);
+        if (__all(ok)) return true;
+        __builtin_amdgcn_s_sleep(4);
+    }
+    return false;
+}
+
 // Writes quad qi (elements 4*qi .. 4*qi+3) of sequence b into the staged vector.  Plain form: the
 // quad-planar fp32 layout of stage_act.  SPLIT form (input of gemv_run_quad): every value v is
 // stored as bf16 head h = v rounded to nearest and bf16 remainder = v - h rounded to nearest (the
@@ -155,7 +172,8 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
 //   index 4 j + (q ^ (b & 3)), and the sum of the unit's 32 values in xsum_of(xs)[b * nup + j].
 // Either way the four lanes of a matrix-core block (same j, sequences 0..3) hit different banks.
 // All lanes of a unit must call together (int4: eight consecutive quads = eight consecutive lanes).
-template <int EPU, bool SPLIT>
+// XSW (bf16 weights, wide pass): unit j of sequence b at index j ^ b instead (the layout dense_run reads).
+template <int EPU, bool SPLIT, bool XSW = false>
 __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, const float4& t) {
     constexpr int NQ = EPU / 4;
     if constexpr (!SPLIT) {
@@ -171,7 +189,7 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
         }
         u32x2 *ph, *pl;
         if constexpr (EPU == 8) {
-            const int j = (qi >> 1) ^ ((b & 3) << 2);
+            const int j = XSW ? (qi >> 1) ^ (b & 15) : (qi >> 1) ^ ((b & 3) << 2);
             ph = (u32x2*)(xs + (size_t)(2 * b) * nup + j) + (qi & 1);
             pl = (u32x2*)(xs + (size_t)(2 * b + 1) * nup + j) + (qi & 1);
         } else if constexpr (EPU == 16) {
@@ -320,7 +338,17 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
 // values keep the gain but not the 1/rms factor; every wave adds its share of the segment's sums of
 // squares to rowss[wave * kMaxBatchWide + b] (set, not added, by the first segment), and the
 // projection scales its finished sums instead (PostScale).
-template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT, int RB, bool DEFER = false>
+//
+// CACHED (passes of eight or more sequences): a workgroup then reads hundreds of kilobytes per
+// projection, every workgroup of the chip the same ones, and the 8-byte coherent loads (which each
+// fetch from the memory side) are what the hand-over costs.  Here wave 0 first waits on a sample of
+// coherent loads for the producers to finish, drops the cached copies of earlier contents (an
+// agent-scope acquire fence = one invalidate of the vector caches; at the first segment of an
+// input and after any stale read), and the rows are then read with plain 16-byte loads that the
+// workgroups of an XCD serve each other out of their L2.  The counter in every word still decides:
+// a word that comes back stale (read before its producer wrote it, and thereby cached again) sends
+// the workgroup round the loop -- sample wait, invalidate, re-read of the stale quads.
+template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT, int RB, bool DEFER = false, bool CACHED = false>
 __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, int tid, WgVote& vote, u64* ev,
                                                      float* rowss = nullptr) {
     constexpr int NQ = EPU / 4;
@@ -364,19 +392,39 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                             u32x2 w = *as_global((const u32x2*)(erow[r] + k));
                             const u32 t = S.tag & kCntMask;
                             v[r][u] = u32x4{(w.x << 16) | t, (w.x & 0xFFFF0000u) | t, (w.y << 16) | t, (w.y & 0xFFFF0000u) | t};
+                        } else if constexpr (CACHED) {
+                            v[r][u] = *as_global((const u32x4*)(src[r] + k));
                         } else {
                             const u32x2 lo = cld2(src[r], k), hi = cld2(src[r], k + 2);
                             v[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
                         }
                         if constexpr (HAS_ADD) {
-                            const u32x2 lo = cld2(add[r], k), hi = cld2(add[r], k + 2);
-                            a[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                            if constexpr (CACHED) a[r][u] = *as_global((const u32x4*)(add[r] + k));
+                            else {
+                                const u32x2 lo = cld2(add[r], k), hi = cld2(add[r], k + 2);
+                                a[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                            }
                         }
                     }
                     if constexpr (HAS_GAIN && kAll) { if (r == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
                 }
             }
         };
+        // CACHED: sample wait by wave 0, optionally followed by the invalidate; false on a time-out
+        auto sync_in = [&](bool invalidate) {
+            bool lw = true;
+            if (tid < 64 && !S.tokens) {
+                lw = light_wait_rows<HAS_ADD>(S, batch, k0, nunits * EPU, lane);
+                if (invalidate) {
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                }
+            }
+            return vote.all<NT>(lw);
+        };
+        if constexpr (CACHED) {
+            if (b0 == 0 && !sync_in(k0 == 0)) return false;
+        }
         load_quads(std::true_type{});
         float ss[RB];   // only meaningful if the vote passes
         for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
@@ -418,7 +466,13 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
             if constexpr (HAS_GAIN && !DEFER) all_ok = vote.all_sum<NT, RB>(mine, ss, tot);
             else all_ok = vote.all<NT>(mine);
             if (ev && tid == 0 && spins == 0 && b0 == 0) as_global(ev)[1] = wall_clock64();
-            if (!all_ok && !S.eager) {
+            if constexpr (CACHED) {
+                if (!all_ok) {
+                    __builtin_amdgcn_s_sleep(8);
+                    if (!sync_in(true)) return false;
+                    if (ev && tid == 0) { as_global(ev)[2] = wall_clock64(); as_global(ev)[5] += 1; }
+                }
+            } else if (!all_ok && !S.eager) {
                 // A producer that is still streaming weights should not have to compete with 256
                 // workgroups re-reading its output: wait on a few samples.  An eager source is
                 // written by a handful of workgroups while the rest of the chip idles (the merged
@@ -465,7 +519,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                         t.x *= bf_lo(g[u].x) * rs; t.y *= bf_hi(g[u].x) * rs; t.z *= bf_lo(g[u].y) * rs; t.w *= bf_hi(g[u].y) * rs;
                     }
                 }
-                stage_store<EPU, SPLIT>(xs, nup, b, qi, t);
+                stage_store<EPU, SPLIT, DEFER>(xs, nup, b, qi, t);   // (DEFER = wide pass = the dense layout)
             }
         };
 #pragma unroll
@@ -496,27 +550,28 @@ template <int EPU, bool HAS_ADD, int NT, bool SPLIT, int RBMAX>
 __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
                                              WgVote& vote, u64* ev = nullptr, float* rowss = nullptr) {
     constexpr int RB4 = RBMAX < 4 ? RBMAX : 4, RB2 = RBMAX < 2 ? RBMAX : 2;
+    constexpr bool C = RBMAX >= kMaxBatchFused;   // cached reads behind an invalidate (see stage_tagged_onepass)
     const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
     if constexpr (RBMAX > kMaxBatchFused) {
         // wide pass: K segments of two quads per thread, eight rows in flight together, deferred
         // normalisation (a segment never holds a whole normalised row's worth of squares)
         static_assert(SPLIT && (kLdsActBytes / (RBMAX * 4)) / 4 <= 2 * NT, "a wide pass's segment is two quads per thread");
-        if constexpr (HAS_ADD) return stage_tagged_onepass<EPU, true, true, NT, 2, true, 8, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev, rowss);
-        else if (S.gain) return stage_tagged_onepass<EPU, false, true, NT, 2, true, 8, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev, rowss);
-        else return stage_tagged_onepass<EPU, false, false, NT, 2, true, 8, false>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if constexpr (HAS_ADD) return stage_tagged_onepass<EPU, true, true, NT, 2, true, 8, true, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev, rowss);
+        else if (S.gain) return stage_tagged_onepass<EPU, false, true, NT, 2, true, 8, true, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev, rowss);
+        else return stage_tagged_onepass<EPU, false, false, NT, 2, true, 8, true, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
     } else if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
-        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4, SPLIT, RB4, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8, SPLIT, RB2, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         if constexpr (SPLIT) return false;
         else return stage_tagged_multipass<EPU, true, true, NT, 8, false>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else if (S.gain) {       // embedding rows
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8, SPLIT, RB2, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         if constexpr (SPLIT) return false;
         else return stage_tagged_multipass<EPU, false, true, NT, 8, false>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else {
-        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4, SPLIT, RB4, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8, SPLIT, RB4, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14, SPLIT, RB2, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         return stage_tagged_multipass<EPU, false, false, NT, 14, SPLIT>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     }
 }

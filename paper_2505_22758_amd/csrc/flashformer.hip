@@ -102,22 +102,23 @@ bool pass_is_wide(const ff_config& c, int batch) {
     if (c.wdtype != W_BF16 || batch <= kMaxBatch) return false;
     return batch > kMaxBatchFused || (size_t)c.d_model * 4 * kMaxBatchFused > (size_t)kLdsActBytes;
 }
-// The wide instance carries a wave's partial sums from one K segment to the next in LDS: the row
-// groups a wave owns (of the widest projection, on a grid of `nwaves` waves) times 16 sequences must fit.
-bool wide_fits(const ff_config& c, int nwaves) {
+// The wide instance gives every workgroup a contiguous range of rows of each projection, in tiles
+// of 16 whose accumulators stay in registers: at most kDenseMaxTiles tiles per workgroup (on a grid
+// of n_cta workgroups), and whole row pairs.
+bool wide_fits(const ff_config& c, int n_cta) {
     const int qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     const int rows = std::max(std::max(qkv_rows, c.d_model), 2 * c.d_ffn);
-    const int groups = ((rows + 3) / 4 + nwaves - 1) / nwaves;
-    return groups * 4 * kMaxBatchWide <= kAccFloatsPerWave;
+    const int groups = ((rows + 3) / 4 + n_cta - 1) / n_cta;
+    return (4 * groups + 15) / 16 <= kDenseMaxTiles && c.d_model % 2 == 0;
 }
-constexpr int kGridWaves = 256 * kFusedWaves;   // waves of the fused kernel's grid on the chip the kernels are built for
+constexpr int kGridCtas = 256;   // workgroups of the fused kernel's grid on the chip the kernels are built for
 
 // Sequences one pass of the fused kernel serves: with bf16 weights and a model created for more than
 // four, 8 (input rows fit the on-chip buffer together) or 16 (wide instance); else up to 4.
 int fused_pass_rows(const ff_config& c) {
     if (c.wdtype == W_BF16 && c.max_batch > kMaxBatch) {
         if (c.max_batch <= kMaxBatchFused && !pass_is_wide(c, c.max_batch)) return kMaxBatchFused;
-        if (wide_fits(c, kGridWaves)) return kMaxBatchWide;
+        if (wide_fits(c, kGridCtas)) return kMaxBatchWide;
         if (!pass_is_wide(c, kMaxBatchFused)) return kMaxBatchFused;
     }
     return std::min(c.max_batch, kMaxBatch);
@@ -314,9 +315,9 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     m->n_cta = prop.multiProcessorCount;
     m->lds_bytes = kLdsFusedBytes;
     if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
-    if (fused_pass_rows(*cfg) > kMaxBatchFused && !wide_fits(*cfg, m->n_cta * kFusedWaves)) {
+    if (fused_pass_rows(*cfg) > kMaxBatchFused && !wide_fits(*cfg, m->n_cta)) {
         delete m;
-        return fail(FF_ERR_UNSUPPORTED, "max_batch %d needs the wide pass, whose partial sums do not fit a grid of %d workgroups", cfg->max_batch, prop.multiProcessorCount);
+        return fail(FF_ERR_UNSUPPORTED, "max_batch %d needs the wide pass, whose row tiles do not fit a grid of %d workgroups", cfg->max_batch, prop.multiProcessorCount);
     }
 
     DevModel& D = m->dev;
