@@ -86,13 +86,27 @@ __device__ __forceinline__ void dense_run(const DenseStream& D, Stage<W_BF16> (&
     const int n = lane & 15, g = lane >> 4;
     const u32x4* xh = (const u32x4*)xs + (size_t)(2 * n) * D.nup;
     const u32x4* xl = xh + D.nup;
+    // The eight k steps of a stage in two groups of four: the group's eight LDS reads are issued
+    // together, then its eight matrix-core instructions (a read waited for one at a time would add
+    // its latency sixteen times per stage).
     auto compute = [&](const Stage<W_BF16>& st, int h, mfma_f4& ch, mfma_f4& cl) {
 #pragma unroll
-        for (int u = 0; u < 8; u++) {
-            const int j = (64 * wave + 32 * h + 4 * u + g) ^ n;
-            const mfma_bf8 a = __builtin_bit_cast(mfma_bf8, st.w[u >> 2][u & 3]);
-            ch = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(mfma_bf8, xh[j]), ch, 0, 0, 0);
-            cl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(mfma_bf8, xl[j]), cl, 0, 0, 0);
+        for (int u0 = 0; u0 < 8; u0 += 4) {
+            u32x4 bh[4], bl[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int j = (64 * wave + 32 * h + 4 * (u0 + u) + g) ^ n;
+                bh[u] = xh[j];
+                bl[u] = xl[j];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const mfma_bf8 a = __builtin_bit_cast(mfma_bf8, st.w[(u0 + u) >> 2][(u0 + u) & 3]);
+                ch = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(mfma_bf8, bh[u]), ch, 0, 0, 0);
+                cl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(mfma_bf8, bl[u]), cl, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     const int j0n = D.j0 + kDenseSegUnits, nunitsn = min(kDenseSegUnits, D.total_units - j0n);   // the next segment (if D.more)

@@ -161,6 +161,13 @@ __device__ __forceinline__ bool light_wait_rows(const TSrc& S, int batch, int k0
     return false;
 }
 
+// (a, b) rounded to bf16 (nearest even) and packed, a in the low half: v_cvt_pk_bf16_f32.
+typedef float pk_f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 pk_bf2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32 pack_bf16(float a, float b) {
+    return __builtin_bit_cast(u32, __builtin_convertvector(pk_f2{a, b}, pk_bf2));
+}
+
 // Writes quad qi (elements 4*qi .. 4*qi+3) of sequence b into the staged vector.  Plain form: the
 // quad-planar fp32 layout of stage_act.  SPLIT form (input of gemv_run_quad): every value v is
 // stored as bf16 head h = v rounded to nearest and bf16 remainder = v - h rounded to nearest (the
@@ -180,13 +187,12 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
         xs[((size_t)b * NQ + qi % NQ) * nup + qi / NQ] = t;
     } else {
         static_assert(EPU == 8 || EPU == 16 || EPU == 32, "bf16, int8 or int4 weights");
-        const float v[4] = {t.x, t.y, t.z, t.w};
-        u32 h[4], l[4];
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            h[e] = (__float_as_uint(v[e]) + 0x8000u) & 0xFFFF0000u;                                 // nearest (ties away)
-            l[e] = (__float_as_uint(v[e] - __uint_as_float(h[e])) + 0x8000u) & 0xFFFF0000u;           // the remainder too: |error| <= 2^-18 |v|
-        }
+        // heads and remainders with the packed conversion (two values per instruction, round to
+        // nearest even): |error| <= 2^-18 |v|
+        const u32 h01 = pack_bf16(t.x, t.y), h23 = pack_bf16(t.z, t.w);
+        u32 h[4] = {h01 << 16, h01 & 0xFFFF0000u, h23 << 16, h23 & 0xFFFF0000u};
+        const u32 l01 = pack_bf16(t.x - __uint_as_float(h[0]), t.y - __uint_as_float(h[1])), l23 = pack_bf16(t.z - __uint_as_float(h[2]), t.w - __uint_as_float(h[3]));
+        u32 l[4] = {l01 << 16, l01 & 0xFFFF0000u, l23 << 16, l23 & 0xFFFF0000u};   // (only the int4 unit sums below look at these)
         u32x2 *ph, *pl;
         if constexpr (EPU == 8) {
             const int j = XSW ? (qi >> 1) ^ (b & 15) : (qi >> 1) ^ ((b & 3) << 2);
@@ -207,8 +213,8 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
             const float us = group_sum<8>((hv[0] + hv[1]) + (hv[2] + hv[3]));
             if ((qi & 7) == 0) xsum_of(xs)[(size_t)b * nup + j] = us;
         }
-        *ph = u32x2{(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
-        *pl = u32x2{(l[0] >> 16) | l[1], (l[2] >> 16) | l[3]};
+        *ph = u32x2{h01, h23};
+        *pl = u32x2{l01, l23};
     }
 }
 
@@ -423,7 +429,9 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
             return vote.all<NT>(lw);
         };
         if constexpr (CACHED) {
-            if (b0 == 0 && !sync_in(k0 == 0)) return false;
+            // first segment of an input: wait + invalidate; later segments are read on the strength
+            // of the first one's wait (a stale word still sends the workgroup round the loop below)
+            if (b0 == 0 && k0 == 0 && !sync_in(true)) return false;
         }
         load_quads(std::true_type{});
         float ss[RB];   // only meaningful if the vote passes
@@ -502,6 +510,11 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
         // no padding): that case runs without the per-lane range tests, each of which is a
         // divergent branch -- expensive for a wave that has its SIMD to itself.
         const bool exact = nquads == padquads && padquads == QB * NT;
+        float gf[HAS_GAIN && DEFER ? QB : 1][4];   // the gains as floats, converted once for all rows
+        if constexpr (HAS_GAIN && DEFER) {
+#pragma unroll
+            for (int u = 0; u < QB; u++) { gf[u][0] = bf_lo(g[u].x); gf[u][1] = bf_hi(g[u].x); gf[u][2] = bf_lo(g[u].y); gf[u][3] = bf_hi(g[u].y); }
+        }
         auto write_quad = [&](auto EX, int r, int u, int b, float rs) {
             constexpr bool kExact = decltype(EX)::value;
             const int qi = tid + u * NT;
@@ -516,7 +529,8 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                         cst2(w + 2, t.z, t.w, S.wb_tag);
                     }
                     if constexpr (HAS_GAIN) {
-                        t.x *= bf_lo(g[u].x) * rs; t.y *= bf_hi(g[u].x) * rs; t.z *= bf_lo(g[u].y) * rs; t.w *= bf_hi(g[u].y) * rs;
+                        if constexpr (DEFER) { t.x *= gf[u][0]; t.y *= gf[u][1]; t.z *= gf[u][2]; t.w *= gf[u][3]; }
+                        else { t.x *= bf_lo(g[u].x) * rs; t.y *= bf_hi(g[u].x) * rs; t.z *= bf_lo(g[u].y) * rs; t.w *= bf_hi(g[u].y) * rs; }
                     }
                 }
                 stage_store<EPU, SPLIT, DEFER>(xs, nup, b, qi, t);   // (DEFER = wide pass = the dense layout)
