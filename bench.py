@@ -36,7 +36,7 @@ WORKLOADS = {
     "tiny-bf16-b1-ctx128": ("tiny", 0, 1, 128),
     "llama3-8b-bf16-b1-ctx1024": ("llama3-8b", 0, 1, 1024),
     "llama3-8b-bf16-b8-ctx1024": ("llama3-8b", 0, 8, 1024),     # one pass of eight sequences
-    "llama3-8b-bf16-b16-ctx1024": ("llama3-8b", 0, 16, 1024),   # two passes of eight
+    "llama3-8b-bf16-b16-ctx1024": ("llama3-8b", 0, 16, 1024),   # one wide pass
     "llama3-8b-int8-b1-ctx4096": ("llama3-8b", 1, 1, 4096),
     "llama3-8b-int4-b1-ctx2048": ("llama3-8b", 2, 1, 2048),
     "llama3-8b-int4-b4-ctx2048": ("llama3-8b", 2, 4, 2048),

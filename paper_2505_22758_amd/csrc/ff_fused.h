@@ -63,11 +63,12 @@ __device__ __forceinline__ u64* dbg_stage_slots(const DevModel& M, int n_phases,
 struct EpiFused {
     int kind; u32 tag; u32 cnt;   // tag: 32-bit tag of q / k,v; cnt: write counter of the compact output vector
     const DevModel& M; const DevKV& KV; const int* pos; int layer; const float2* rope; float* logits;
+    int pair0 = 0;   // LM head in row blocks (wide pass): first row pair of the block
     __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         switch (kind) {
             case PH_QKV: EpiQKVTagged{M, KV, pos, layer, rope, tag}(pair, b, v0, v1); break;
             case PH_GU: EpiSwiGLUTagged{M.ch, M.F, cnt, M.gu}(pair, b, v0, v1); break;
-            case PH_LM: EpiStore{logits, M.V}(pair, b, v0, v1); break;
+            case PH_LM: EpiStore{logits, M.V}(pair + pair0, b, v0, v1); break;
             default: EpiDeltaTagged{M.cdelta, M.d, cnt}(pair, b, v0, v1); break;
         }
     }
@@ -180,7 +181,9 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     __syncthreads();
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
     // weight type differs from the layers' (then the host launches it separately).
-    const int n_phases = 4 * M.L + (lm_in_kernel ? 1 : 0);
+    // (lm_in_kernel: number of LM-head phases; 1, or with a wide pass the number of row blocks)
+    const int n_phases = 4 * M.L + lm_in_kernel;
+    const int dbg_phases = 4 * M.L + (lm_in_kernel ? 1 : 0);   // phases the optional timeline buffer has slots for (further LM blocks share the last)
     // steps executed so far on the compact buffers (kept on the device: a skipped step does not count)
     const u32 steps_done = (u32)__builtin_amdgcn_readfirstlane(xld_u32(M.stepctr));
     const u32 sl = steps_done * (u32)M.L;
@@ -217,9 +220,20 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             ph = __builtin_amdgcn_readfirstlane(ph);
             seg = __builtin_amdgcn_readfirstlane(seg);
         }
-        const PhaseDesc D = phase_desc(M, tokens, tag_base, sl, ph, lm_in_kernel, phase_state(M, ph), kScalarState);
-        const Stream<WD, B> S = Stream<WD, B>::make(D.W, seg, gwave, n_gwaves, kQuad);
+        // (wide pass: the LM head runs in row blocks of at most kDenseMaxTiles tiles per workgroup,
+        // one phase per block, all described like the first)
+        const int lm_block = kWide ? max(ph - 4 * M.L, 0) : 0;
+        PhaseDesc D = phase_desc(M, tokens, tag_base, sl, ph - lm_block, lm_in_kernel, phase_state(M, ph - lm_block), kScalarState);
         EpiFused epi{D.kind, D.out_tag, D.out_cnt, M, KV, pos_lds, D.layer, rope_lds, logits};
+        if constexpr (kWide) {
+            if (D.kind == PH_LM) {
+                const int block_rows = kDenseMaxTiles * 16 * ncta, row0 = lm_block * block_rows;
+                D.W.w += (size_t)row0 * D.W.row_bytes();
+                D.W.n = min(block_rows, D.W.n - row0);
+                epi.pair0 = row0 >> 1;
+            }
+        }
+        const Stream<WD, B> S = Stream<WD, B>::make(D.W, seg, gwave, n_gwaves, kQuad);
         // The wave's first tiles of this projection are requested before anything it has to wait
         // for (its input vector; for the output projection the whole attention), so the memory
         // pipe has work while the dependency resolves.  The ring lives from here to the end of
@@ -238,7 +252,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             DS = DenseStream::make(D.W, seg, n_ctas);
             if (seg == 0) dense_prefetch(DS, wring, wave, lane);   // (later segments: requested at the end of the previous one)
         } else if (!kHasSwitch || !no_overlap) prefetch_stream<kQuad>(S, ring, lane);
-        if (wave == 0) dbg_event(M, ph, EV_PF_ISSUED, lane);
+        if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_PF_ISSUED, lane);
         // Touch the descriptor the NEXT phase will fetch, so that it sits in the scalar cache by
         // then instead of costing a trip to memory at the head of that phase.
         u32 warm = 0;
@@ -249,18 +263,18 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (att_first) {
             // split-KV attention + merge of this layer (the ring holds the output projection's tiles)
             __syncthreads();   // every wave has finished reading the staged input: LDS is free
-            if (wave == 0) dbg_event(M, ph, EV_ATT_START, lane);
-            u64* aev = dbg_stage_slots(M, n_phases, ncta, D.layer, 4);
+            if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_ATT_START, lane);
+            u64* aev = dbg_stage_slots(M, dbg_phases, ncta, D.layer, 4);
             if (aev && threadIdx.x == 0) { as_global(aev)[0] = wall_clock64(); as_global(aev)[4] = 0; as_global(aev)[5] = 0; }
             const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
                                                                 tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, n_ctas, vote, aev);
             if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
-            if (wave == 0) dbg_event(M, ph, EV_ATT_END, lane);
+            if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_ATT_END, lane);
             if (!ok) return;
         }
-        if (wave == 0) dbg_event(M, ph, EV_H_START, lane);
+        if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_H_START, lane);
         bool ok;
-        u64* ev = dbg_stage_slots(M, n_phases, ncta, D.layer, D.kind);
+        u64* ev = dbg_stage_slots(M, dbg_phases, ncta, D.layer, D.kind);
         if (src.add) ok = stage_tagged<EPU, true, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev, rowss);
         else ok = stage_tagged<EPU, false, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev, rowss);
         if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
@@ -268,9 +282,9 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);
             return;
         }
-        if (wave == 0) dbg_event(M, ph, EV_SYNCED, lane);
+        if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_SYNCED, lane);
         if (kHasSwitch && no_overlap) prefetch_stream<kQuad>(S, ring, lane);
-        u64* wv = D.kind < 4 ? dbg_wave_slots(M, n_phases, D.layer, wave) : nullptr;
+        u64* wv = D.kind < 4 ? dbg_wave_slots(M, dbg_phases, D.layer, wave) : nullptr;
         if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
         bool glu_done = false;
         if constexpr (B == 1) {
@@ -305,7 +319,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         else if constexpr (kQuad) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         else gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         asm volatile("" ::"s"(warm));   // keeps the touch alive
-        if (wave == 0) dbg_event(M, ph, EV_RUN_DONE, lane);
+        if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_RUN_DONE, lane);
         if (wv && lane == 0) as_global(wv)[D.kind] = wall_clock64();
         // next iteration: further K segment of the same projection, or the next projection
         if (glu_done) ++ph;   // the down projection ran inside glu_run

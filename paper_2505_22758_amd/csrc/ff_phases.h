@@ -677,6 +677,9 @@ struct TaggedAttnIO {
     }
 };
 
+#ifndef FF_ATTN_BATCH
+#define FF_ATTN_BATCH 4   // wave loads of K and of V in flight per wave (can be overridden at build time for sweeps)
+#endif
 template <int HD, int G, int NW, class XIO>
 __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, int layer, int b, int j, int t0, int t1, bool with_cur,
                           int split, uint8_t* lds, u64* ev = nullptr) {
@@ -717,7 +720,7 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     };
     // Cached rows do not depend on this step: the first kAttnBatch wave-loads are issued BEFORE the
     // queries are waited for, so the wait for the QKV projection overlaps them.
-    constexpr int kAttnBatch = 4;
+    constexpr int kAttnBatch = FF_ATTN_BATCH;
     constexpr int kStride = NW * RPW * kAttnBatch;
     u32x4 kw[kAttnBatch], vw[kAttnBatch];
     auto issue = [&](int tb0) {

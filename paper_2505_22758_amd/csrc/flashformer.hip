@@ -614,7 +614,10 @@ namespace {
 int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const int32_t* positions_dev, ff_kv* kv, float* logits_dev, int32_t batch, int seq0,
                int step_batch, hipStream_t st) {
     const bool wide = pass_is_wide(m->cfg, batch);   // (batch <= fused_pass_rows: a wide pass only where the wide instance fits)
-    const int lm_in_kernel = D.lm.wd == m->cfg.wdtype && !wide;
+    // LM head inside the fused kernel when its weights have the layers' type: one phase, or with a
+    // wide pass one phase per block of kDenseMaxTiles tiles per workgroup
+    const int lm_block_rows = kDenseMaxTiles * 16 * m->n_cta;
+    const int lm_in_kernel = D.lm.wd != m->cfg.wdtype ? 0 : wide ? (m->cfg.vocab + lm_block_rows - 1) / lm_block_rows : 1;
     DevKV kvd = kv->dev;
     kvd.seq0 = seq0;
     kvd.step_batch = step_batch;
@@ -633,7 +636,7 @@ int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const 
     FF_FUSED_FAMILIES(FF_TRY_FAMILY)
 #undef FF_TRY_FAMILY
     if (e != hipSuccess) return fail(e == hipErrorLaunchOutOfResources ? FF_ERR_UNSUPPORTED : FF_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
-    if (!lm_in_kernel) {   // LM head of a different weight type than the layers, or a wide pass: separate launches
+    if (!lm_in_kernel) {   // LM head of a different weight type than the layers: separate launches
         const ff_config& c = m->cfg;
         op_final_x<<<16, kThreads, 0, st>>>(D.x, D.cx, D.cdelta, batch * c.d_model);
         op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, D.gf, D.xn, c.d_model, c.rms_eps);
