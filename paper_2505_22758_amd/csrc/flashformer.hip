@@ -327,8 +327,12 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
         // pairs and a staged K chunk of the down projection is a whole number of "one pair per wave" rounds
         const int nw = m->n_cta * kFusedWaves;
         const int chunk_elems = cfg->wdtype == W_BF16 ? kChunkUnitsOf<W_BF16> * 8 : cfg->wdtype == W_INT8 ? kChunkUnitsOf<W_INT8> * 16 : kChunkUnitsOf<W_INT4> * 32;
-        const char* off = getenv("FF_NO_GLU_PIPE");
-        const bool ok = cfg->d_ffn % nw == 0 && chunk_elems % nw == 0 && !(off && off[0] == '1');
+        // FF_GLU_PIPE: "0" keeps the two projections apart (A/B measurements), "all" also fuses them for int8
+        // weights, where it measured slower (2.70 against 2.43 ms per step at the 8B shape: a wave's gate/up share
+        // is only 14 stages long there, too few to stage the four chunks of h behind it) and is off by default
+        const char* pipe = getenv("FF_GLU_PIPE");
+        const bool pipe_off = pipe && pipe[0] == '0', pipe_all = pipe && pipe[0] == 'a';
+        const bool ok = cfg->d_ffn % nw == 0 && chunk_elems % nw == 0 && !pipe_off;
         D.gu = ok ? GuPerm{cfg->d_ffn / nw, nw} : GuPerm{0, 0};
         // glu_run (single-sequence passes) needs the staged h beside the staged projection input, the
         // per-lane partial sums of a wave's down-projection rows at the end of the aux region, at most
@@ -340,7 +344,7 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
         const int cpr_g = (cfg->d_model + chunk_elems - 1) / chunk_elems;      // stages per gate/up pair
         const bool fits = (size_t)in_off + (size_t)f_pad * 4 + (size_t)kFusedWaves * pd * 512 <= (size_t)kLdsActBytes + kLdsAuxBytes &&
                           f_pad / chunk_elems <= kGluMaxChunks && (cfg->d_ffn / nw) * cpr_g >= 4;
-        m->glu_off = ok && fits ? in_off : -1;
+        m->glu_off = ok && fits && (cfg->wdtype != W_INT8 || pipe_all) ? in_off : -1;
     }
     D.layers = (const PLayer*)(m->packed + P.layers_tab);
     D.embed = (const bf16_t*)(m->packed + P.embed);

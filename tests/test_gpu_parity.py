@@ -740,12 +740,13 @@ def test_overlap_switch_changes_timing_not_results():
     dec.close()
 
 
-def test_glu_as_one_stream_small_model_all_formats():
+def test_glu_as_one_stream_small_model_all_formats(monkeypatch):
     """Single-sequence steps of a small model whose FFN is a whole number of gate/up pairs per wave
     (d_ffn 8192 over 1024 waves), so gate/up + down run as one stream with the down projection's input
     staged chunk by chunk (four chunks with bf16 weights, two with int8 / int4); the same models at
     batch 2 and 3 use the interleaved gate/up row order with the ordinary phase sequence."""
     S = synth.TINY.replace(name="glu", n_layers=3, d_model=2048, n_q_heads=16, n_kv_heads=4, head_dim=128, d_ffn=8192, vocab=3000)
+    monkeypatch.setenv("FF_GLU_PIPE", "all")   # int8 weights take the one-stream form only on request (read when a model is created)
     for wd in (synth.WDTYPE_BF16, synth.WDTYPE_INT8, synth.WDTYPE_INT4):
         _run_teacher_forced(S, 0x250522780 + wd, wd, batch=1, T0=37, steps=3)
     _run_teacher_forced(S, 0x250522784, synth.WDTYPE_BF16, batch=2, T0=20, steps=2)
