@@ -29,7 +29,7 @@ namespace ff {
 
 constexpr int kDenseMaxTiles = 14;   // tiles of 16 rows one workgroup can own (224 rows: the 70B gate/up projection on 256 workgroups)
 constexpr int kDenseSegUnits = kLdsActBytes / (kMaxBatchWide * 8 * 4);   // 16-byte units (8 columns) of one staged K segment
-static_assert(kDenseSegUnits == 256 && kDenseSegUnits == kChunkUnitsOf<W_BF16>, "a wide pass's K segment is one chunk of 2048 columns: 64 units per wave, two stages of 32");
+static_assert(kDenseSegUnits == 256 && kDenseSegUnits % kChunkUnitsOf<W_BF16> == 0, "a wide pass's K segment is 2048 columns (64 units per wave, two stages of 32), a whole number of staging chunks");
 typedef __bf16 mfma_bf8 __attribute__((ext_vector_type(8)));
 
 struct DenseStream {

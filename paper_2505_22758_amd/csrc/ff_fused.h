@@ -250,6 +250,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         DenseStream DS;
         if constexpr (kWide) {
             DS = DenseStream::make(D.W, seg, n_ctas);
+            DS.nup = S.nup;   // plane stride of the staged segment (the segment's units rounded up to whole staging chunks)
             if (seg == 0) dense_prefetch(DS, wring, wave, lane);   // (later segments: requested at the end of the previous one)
         } else if (!kHasSwitch || !no_overlap) prefetch_stream<kQuad>(S, ring, lane);
         if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_PF_ISSUED, lane);

@@ -15,7 +15,10 @@ template <> struct WTraits<W_INT4> { static constexpr int EPU = 32; };
 // 16-byte units per row and pipeline stage (per lane).  A unit of int4 weights spans 32 columns, so
 // four units per lane would cover 8192 columns per stage: rows of 4096 columns would leave half
 // the lanes multiplying padding.  int4 stages are therefore half as wide and its ring twice as deep.
-template <int WD> constexpr int kUnrOf = WD == W_INT4 ? 2 : 4;
+#ifndef FF_UNR
+#define FF_UNR 4   // 16-byte units per row, lane and stage for bf16 / int8 weights (can be overridden at build time for sweeps)
+#endif
+template <int WD> constexpr int kUnrOf = WD == W_INT4 ? 2 : FF_UNR;
 // Pipeline stages (register ring slots) per wave.  Two stages (16 loads of 16 bytes per lane) keep
 // the memory pipe full; deeper rings measured slower in the fused kernel, because every byte
 // prefetched across a projection boundary queues in front of the loads of the next input vector
