@@ -43,6 +43,7 @@ WORKLOADS = {
     # the full 80-layer model: 139 GB of packed weights, generated and packed layer by layer on the GPU
     "llama3-70b-bf16-b1-ctx2048": ("llama3-70b", 0, 1, 2048),
     "llama3-70b-bf16-b16-ctx2048": ("llama3-70b", 0, 16, 2048),
+    "llama3-70b-int4-b1-ctx2048": ("llama3-70b", 2, 1, 2048),   # the paper's largest configuration (int4 group-128, 35 GB)
 }
 
 

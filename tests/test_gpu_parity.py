@@ -349,6 +349,15 @@ def test_llama70b_shaped_one_layer_batch16():
     _run_teacher_forced(synth.LLAMA_70B.replace(n_layers=1), 0x250522765, synth.WDTYPE_BF16, batch=16, T0=64, steps=1, gpu_generated=True)
 
 
+def test_llama70b_shaped_one_layer_int4_and_int8():
+    """The quantised formats at the 70B width (one layer; eight query heads per KV head, 8192-column
+    rows = 64 int4 groups per row, gate/up rows in the interleaved order), batch 1 and a batch of 3."""
+    S = synth.LLAMA_70B.replace(n_layers=1)
+    _run_teacher_forced(S, 0x250522767, synth.WDTYPE_INT4, batch=1, T0=300, steps=2, gpu_generated=True)
+    _run_teacher_forced(S, 0x250522768, synth.WDTYPE_INT4, batch=3, T0=[64, 0, 130], steps=1, gpu_generated=True)
+    _run_teacher_forced(S, 0x250522769, synth.WDTYPE_INT8, batch=1, T0=100, steps=1, gpu_generated=True)
+
+
 def test_llama8b_shaped_one_layer_batch8_single_pass():
     """Eight sequences in ONE pass at the 8B width (one layer): the matrix-core projections with two
     sets of four sequences, input rows staged in two groups, the down projection cut into four
