@@ -140,6 +140,108 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
     return D;
 }
 
+// The whole step of a wide pass (see ff_wide.h): the same phases, with activations exchanged as
+// images of the consumers' LDS layout, epochs instead of per-word counters, and the residual stream
+// kept by the workgroups that own its rows.  The step's embedding rows (residual rows, first image,
+// partial sums of squares) are prepared by k_wide_embed, launched in front of the fused kernel.
+// n_lm: LM-head phases (row blocks of at most kDenseMaxTiles tiles per workgroup), 0 = not here.
+// Returns false after a time-out (status is set).
+template <int HD, int G>
+__device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, const int* pos_lds, const float2* rope_lds, float* logits, int batch,
+                                          int n_lm, int ncta, uint8_t* lds, WgVote& vote, u32 steps_done, u32 sl, u32 tag_base) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const UDiv n_ctas = UDiv::of((u32)ncta);
+    float4* xs = (float4*)lds;
+    float* rs = (float*)(lds + kLdsActBytes);   // aux region: 1/rms per sequence, scratch of the reduction, verdict word
+    float* part = rs + 16;
+    const WideSync sync{M.wflag, ncta, (lds_u32*)(part + 256)};
+    float* ssl = (float*)(lds + 64 * 1024);     // behind the partial tiles of the reduction (at most 56 KB)
+    const u32 ebase = steps_done * (u32)(4 * M.L);   // epochs of this step: ebase + 4 l + {1: attention, 2: O, 3: gate/up, 4: down}
+    const int n_phases = 4 * M.L + n_lm;
+    mfma_f4 acc[kDenseMaxTiles];
+    Stage<W_BF16> ring[2];
+    for (int ph = 0; ph < n_phases; ph++) {
+        const int lm_block = max(ph - 4 * M.L, 0);
+        PhaseDesc D = phase_desc(M, nullptr, tag_base, sl, ph - lm_block, 1, phase_state(M, ph - lm_block), true);
+        EpiFused epf{D.kind, D.out_tag, D.out_cnt, M, KV, pos_lds, D.layer, rope_lds, logits};
+        if (D.kind == PH_LM) {
+            const int block_rows = kDenseMaxTiles * 16 * ncta, row0 = lm_block * block_rows;
+            D.W.w += (size_t)row0 * D.W.row_bytes();
+            D.W.n = min(block_rows, D.W.n - row0);
+            epf.pair0 = row0 >> 1;
+        }
+        const int l = D.layer;
+        const FF_CONST PLayer* Lp = as_const(M.layers) + min(l, M.L - 1);
+        DenseStream DS = DenseStream::make(D.W, 0, n_ctas);
+        dense_prefetch(DS, ring, wave, lane);
+#ifdef FF_WIDE_STATS
+        u64 T0 = wall_clock64();
+#define FF_WT(k) if (blockIdx.x == 7 && threadIdx.x == 0) { const u64 tn = wall_clock64(); atomicAdd(M.status + 8 * (1 + D.kind) + k, (int)(tn - T0)); T0 = tn; }
+#else
+#define FF_WT(k)
+#endif
+        u32 wait_epoch = 0;
+        const uint8_t* img = M.wimg_x;
+        bool normed = true;
+        if (D.kind == PH_QKV) wait_epoch = l > 0 ? ebase + 4u * (u32)l : 0u;
+        else if (D.kind == PH_O) {
+            __syncthreads();   // the previous projection's epilogue has read its sums out of LDS
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, l, lds, tag_of(tag_base, l, TAG_QKV), tag_of(tag_base, l, TAG_ATT),
+                                                                sl + l, n_ctas, vote, nullptr, M.wimg_a);
+            if (!ok) return false;
+            sync.arrive(ebase + 4u * (u32)l + 1u);
+            FF_WT(0)
+            wait_epoch = ebase + 4u * (u32)l + 1u; img = M.wimg_a; normed = false;
+        } else if (D.kind == PH_GU) wait_epoch = ebase + 4u * (u32)l + 2u;
+        else if (D.kind == PH_DOWN) { wait_epoch = ebase + 4u * (u32)l + 3u; img = M.wimg_h; normed = false; }
+        else wait_epoch = ebase + 4u * (u32)M.L;
+        if (wait_epoch) {
+            if (!sync.wait(wait_epoch, wave, lane)) {
+                if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);
+                return false;
+            }
+        } else __syncthreads();
+        FF_WT(1)
+        if (normed) wide_rms(M.wsspart, ncta, D.W.k, M.eps, part, rs, threadIdx.x);
+        FF_WT(2)
+#pragma unroll
+        for (int t = 0; t < kDenseMaxTiles; t++) acc[t] = mfma_f4{0.f, 0.f, 0.f, 0.f};
+        const int nseg = (D.W.k / 8 + kDenseSegUnits - 1) / kDenseSegUnits;
+        for (int seg = 0; seg < nseg; seg++) {
+            DS = DenseStream::make(D.W, seg, n_ctas);
+            if (seg > 0) __syncthreads();   // every wave is done with the previous segment
+            FF_WT(3)
+            if (DS.T > 0) wide_copy_segment(img + (size_t)seg * kWideSegBytes, lds, threadIdx.x);
+            __syncthreads();
+            FF_WT(4)
+            const float* rsp = normed ? rs : nullptr;
+            if (D.kind == PH_GU) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiSwiGLU{M.wimg_h, M.gu}, rsp);
+            else if (D.kind == PH_O) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiResidual{M.wxres, M.d, Lp->g2, M.wimg_x, ssl, DS.r0}, rsp);
+            else if (D.kind == PH_DOWN)
+                dense_run_wide(DS, ring, xs, acc, batch, wave, lane,
+                               WideEpiResidual{M.wxres, M.d, l + 1 < M.L ? (as_const(M.layers) + l + 1)->g1 : M.gf, M.wimg_x, ssl, DS.r0}, rsp);
+            else dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiPairs<EpiFused>{epf}, rsp);
+        }
+        FF_WT(5)
+        if (D.kind == PH_O || D.kind == PH_DOWN) {
+            // this workgroup's share of every sequence's sum of squares of the new residual rows
+            __syncthreads();
+            if (threadIdx.x < kMaxBatchWide) {
+                float t = 0.f;
+                const int ngrp = (DS.r1 - DS.r0) >> 2;
+                if ((int)threadIdx.x < batch) for (int q = 0; q < ngrp; q++) t += ssl[q * kMaxBatchWide + threadIdx.x];
+                xst(M.wsspart + (size_t)blockIdx.x * kMaxBatchWide + threadIdx.x, t);
+            }
+        }
+        if (D.kind == PH_O) sync.arrive(ebase + 4u * (u32)l + 2u);
+        else if (D.kind == PH_GU) sync.arrive(ebase + 4u * (u32)l + 3u);
+        else if (D.kind == PH_DOWN) sync.arrive(ebase + 4u * (u32)l + 4u);
+        FF_WT(6)
+    }
+    return true;
+}
+
 template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
@@ -214,6 +316,14 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // segments of a projection (see dense_run)
     Stage<W_BF16> wring[2];
     mfma_f4 dah[kDenseMaxTiles], dal[kDenseMaxTiles];
+    if constexpr (kWide) {
+        if (!wide_loop<HD, G>(M, KV, pos_lds, rope_lds, logits, batch, lm_in_kernel, ncta, lds, vote, steps_done, sl, tag_base)) return;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            xst_u32(M.stepctr + 1, 0u);   // the compact exchange rows were not written: the next narrow pass re-initialises its rows
+            xst_u32(M.stepctr, steps_done + 1u);
+        }
+        return;
+    }
     int ph = 0, seg = 0;
     for (;;) {
         if constexpr (kScalarState) {

@@ -3,6 +3,7 @@
 #include "ff_phases.h"
 #include "ff_glu.h"
 #include "ff_dense.h"
+#include "ff_wide.h"
 
 namespace ff {
 
@@ -59,7 +60,8 @@ __device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const 
 // the wave wait for every load it has in flight, weight tiles included.
 template <int NW, int HD, int G>
 __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
-                                                       uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, const UDiv& nc, WgVote& vote, u64* ev = nullptr) {
+                                                       uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, const UDiv& nc, WgVote& vote, u64* ev = nullptr,
+                                                       uint8_t* merged_img = nullptr) {
     constexpr int NT = NW * 64;
     const int ncta = (int)nc.n;
     const int share = max(1, (int)((u32)ncta / (u32)(batch * M.Hkv)));
@@ -78,7 +80,7 @@ __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const 
             const int t0 = (int)((u32)T * (u32)s / (u32)ns), t1 = (int)((u32)T * (u32)(s + 1) / (u32)ns);   // T * 64 < 2^32
             bool cur = s == ns - 1;
             ok = attn_item<HD, G, NW>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds, ev) && ok;
-            if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, out_cnt, (float*)lds, vote, ev) && ok;
+            if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, out_cnt, (float*)lds, vote, ev, merged_img) && ok;
         }
         base = (int)nc.mod((u32)base + (u32)nitems);
     }

@@ -58,6 +58,44 @@ __global__ void __launch_bounds__(kThreads) k_scrub_rows(DevModel M, int batch) 
     }
 }
 
+// Wide pass (ff_wide.h), launched in front of the fused kernel: the step's embedding rows become the
+// residual rows, the first layer's input image (gain x value as bf16 head + remainder) and the
+// workgroups' partial sums of squares, each block doing what the workgroup of the same index owns
+// (rows of the d-wide projections in groups of four, dealt like DenseStream does).  A token outside
+// the vocabulary reads row 0: the fused kernel rejects the whole step.
+__global__ void __launch_bounds__(kThreads) k_wide_embed(DevModel M, const int* tokens, int batch) {
+    __shared__ float red[kThreads];
+    const u32 ngroups = (u32)(M.d + 3) / 4;
+    const int r0 = 4 * (int)((u64)ngroups * blockIdx.x / gridDim.x), r1 = min(4 * (int)((u64)ngroups * (blockIdx.x + 1) / gridDim.x), M.d);
+    const int nrows = r1 - r0;
+    const bf16_t* g1 = as_const(M.layers)->g1;
+    for (int n = 0; n < kMaxBatchWide; n++) {
+        float ss = 0.f;
+        if (n < batch) {
+            int t = tokens[n];
+            if (t < 0 || t >= M.V) t = 0;
+            for (int i = threadIdx.x; i < nrows; i += kThreads) {
+                const int row = r0 + i;
+                const float x = bf_to_f(as_global(M.embed)[(size_t)t * M.d + row]);
+                as_global(M.wxres)[(size_t)n * M.d + row] = x;
+                ss += x * x;
+                u32 hi, lo;
+                split_bf16x2(x * bf_to_f(as_global(g1)[row]), 0.f, hi, lo);
+                *as_global((uint16_t*)(M.wimg_x + wide_img_off(n, 0, row))) = (uint16_t)hi;
+                *as_global((uint16_t*)(M.wimg_x + wide_img_off(n, 1, row))) = (uint16_t)lo;
+            }
+        }
+        red[threadIdx.x] = ss;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            for (int i = 0; i < min(nrows, kThreads); i++) t += red[i];
+            as_global(M.wsspart)[(size_t)blockIdx.x * kMaxBatchWide + n] = t;
+        }
+        __syncthreads();
+    }
+}
+
 __global__ void __launch_bounds__(kThreads) op_final_x(float* x, const u32* tx, const u32* tdelta, int n) {
     for (int i = blockIdx.x * kThreads + threadIdx.x; i < n; i += gridDim.x * kThreads)
         x[i] = __uint_as_float(tx[i] & ~kCntMask) + __uint_as_float(tdelta[i] & ~kCntMask);

@@ -168,6 +168,22 @@ __device__ __forceinline__ u32 pack_bf16(float a, float b) {
     return __builtin_bit_cast(u32, __builtin_convertvector(pk_f2{a, b}, pk_bf2));
 }
 
+// fp32 pair -> packed bf16 heads and packed bf16 remainders, both round to nearest even:
+// |error| <= 2^-18 |v|.
+__device__ __forceinline__ void split_bf16x2(float a, float b, u32& hi, u32& lo) {
+    hi = pack_bf16(a, b);
+    lo = pack_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
+}
+// Wide pass (see ff_wide.h): byte offset of column `col` of sequence n in a global image of the
+// consumers' LDS layout (plane 0: heads, 1: remainders): K segment of 2048 columns, then plane-major
+// with 16-byte unit j at index j ^ n.
+constexpr int kWideSegUnits = 256;
+constexpr int kWideSegBytes = kLdsActBytes;
+__device__ __forceinline__ size_t wide_img_off(int n, int plane, int col) {
+    const int j = col >> 3;
+    return (size_t)(j >> 8) * kWideSegBytes + ((size_t)((2 * n + plane) * kWideSegUnits + ((j & 255) ^ n))) * 16 + (size_t)(col & 7) * 2;
+}
+
 // Writes quad qi (elements 4*qi .. 4*qi+3) of sequence b into the staged vector.  Plain form: the
 // quad-planar fp32 layout of stage_act.  SPLIT form (input of gemv_run_quad): every value v is
 // stored as bf16 head h = v rounded to nearest and bf16 remainder = v - h rounded to nearest (the
@@ -842,7 +858,10 @@ __device__ void attn_merge(const DevModel& M, int b, int j, int nsplit, float* l
 // (b, j) gathers all splits, re-reading until every partial carries this layer's attention tag,
 // and publishes attn_o with the same tag.  Returns false on a time-out.
 template <int HD, int G, int NT>
-__device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, u32 out_cnt, float* lds, WgVote& vote, u64* ev = nullptr) {
+// img (wide pass): the merged output goes into the output projection's input image as bf16 head +
+// remainder instead of the compact vector.
+__device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int j, int nsplit, u32 tag, u32 out_cnt, float* lds, WgVote& vote, u64* ev = nullptr,
+                                                  uint8_t* img = nullptr) {
     float* ms = lds;
     float* ls = lds + G * kMaxSplits;
     constexpr int kSB = 16;   // splits gathered per batch of loads
@@ -922,7 +941,15 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
                 a1 = fmaf(__uint_as_float(r[u].z), w, a1);
             }
         }
-        cst2(M.cattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, out_cnt);
+        if (img) {
+            u32 hi, lo;
+            split_bf16x2(a0, a1, hi, lo);
+            const int col = (j * G + g) * HD + d2;
+            xst_u32((u32*)(img + wide_img_off(b, 0, col)), hi);
+            xst_u32((u32*)(img + wide_img_off(b, 1, col)), lo);
+        } else {
+            cst2(M.cattn_o + ((size_t)b * M.Hq + (j * G + g)) * HD + d2, a0, a1, out_cnt);
+        }
     }
     if (ev && threadIdx.x == 0) as_global(ev)[5] = wall_clock64();
     return vote.all<NT>(all_ok);

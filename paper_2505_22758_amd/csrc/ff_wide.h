@@ -1,0 +1,218 @@
+// The wide pass (9..16 sequences, bf16 weights): exchange between workgroups and the phase loop.
+//
+// Up to eight sequences every workgroup stages every sequence's whole input itself (load the tagged
+// words, add the sublayer output, normalise, convert to the matrix cores' head/remainder form).  At
+// 16 sequences that conversion alone costs more than half of what streaming the weights costs
+// (16 x 70 K values per layer and workgroup at the 70B shape), all of it replicated 256 times.  The
+// wide pass therefore exchanges activations in the form their consumers multiply, produced once by
+// the workgroup that OWNS the value:
+//   * every workgroup owns a fixed range of rows of the residual stream (the rows of the output
+//     and down projections it computes, N / workgroups) and keeps them in a plain buffer of its
+//     own; the epilogue of those two projections adds the projection output to its rows, and writes
+//     (gain of the next normalised projection) x (new value) as bf16 head + bf16 remainder straight
+//     into a global IMAGE of the consumers' LDS layout, plus the workgroup's share of every
+//     sequence's sum of squares (the 1/rms factor is applied by the consumer to its finished sums:
+//     a scalar per sequence that commutes with the projection);
+//   * the SwiGLU epilogue and the attention merge write their outputs into such images too;
+//   * a consumer's staging is a copy: image segment (2048 columns x 16 sequences, 128 KB) -> LDS,
+//     16 bytes per lane and instruction, no arithmetic;
+//   * the image words have no room for the per-word write counters of the other paths, so the
+//     dependency is carried by one flag per workgroup and phase (paper Section 4.1: the global
+//     barrier between dependent phases, here as an epoch per workgroup that consumers poll): a
+//     producer makes its exchange stores (all write-through, agent scope), waits until they have
+//     completed, and publishes the phase's epoch; a consumer polls until all workgroups show the
+//     epoch, drops cached copies of earlier contents (agent-scope acquire) and reads with plain
+//     cacheable loads, which the workgroups of an XCD serve each other out of their L2.
+//     Queries, keys, values and attention partials keep their tagged 8-byte format.
+// Write-after-read on the images is ordered by the same epochs (an image is rewritten only by
+// workgroups that have waited for an epoch which every reader of the old contents published after
+// its last read).
+#pragma once
+#include "ff_dense.h"
+
+namespace ff {
+
+__host__ __device__ inline size_t wide_img_bytes(int K) { return (size_t)((K + 2047) / 2048) * kWideSegBytes; }
+
+// ---------------------------------------------------------------- epochs
+struct WideSync {
+    u32* flags;       // [workgroups] last epoch each workgroup has published
+    int ncta;
+    lds_u32* ok_slot; // LDS word for the verdict
+    // All of this workgroup's exchange stores of the phase are made: publish the epoch.
+    __device__ __forceinline__ void arrive(u32 epoch) const {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's write-through stores have completed
+        __syncthreads();
+        if (threadIdx.x == 0) xst_u32(flags + blockIdx.x, epoch);
+    }
+    // Every workgroup has published `epoch` (or a later one).  Returns false (uniformly) on a time-out.
+    __device__ __forceinline__ bool wait(u32 epoch, int wave, int lane) const {
+        if (wave == 0) {
+            bool ok = false;
+            for (int spins = 0; spins < kSpinLimit && !ok; spins++) {
+                bool mine = true;
+                for (int i = lane; i < ncta; i += 64) mine = mine && (int)(xld_u32(flags + i) - epoch) >= 0;
+                ok = __all(mine);
+                if (!ok) __builtin_amdgcn_s_sleep(4);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // cached copies of the images' earlier contents are dropped
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0) *ok_slot = ok ? 1u : 0u;
+        }
+        __syncthreads();
+        const bool ok = *ok_slot != 0u;
+        __syncthreads();   // (the slot is rewritten by the next wait)
+        return ok;
+    }
+};
+
+// ---------------------------------------------------------------- consumer side
+// Copies one image segment into LDS (same layout); all threads of the workgroup.
+__device__ __forceinline__ void wide_copy_segment(const uint8_t* img_seg, uint8_t* lds, int tid) {
+    const FF_GLOBAL u32x4* src = as_global((const u32x4*)img_seg);
+    u32x4* dst = (u32x4*)lds;
+    constexpr int kPer = kWideSegBytes / 16 / kThreads;   // 32 units per thread
+#pragma unroll
+    for (int b0 = 0; b0 < kPer; b0 += 8) {
+        u32x4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[i] = src[tid + (b0 + i) * kThreads];
+#pragma unroll
+        for (int i = 0; i < 8; i++) dst[tid + (b0 + i) * kThreads] = v[i];
+    }
+}
+// 1/rms of every sequence from the workgroups' partial sums of squares ([workgroups][16] floats,
+// added in a fixed order) into rs[16] (LDS).  part: LDS scratch of 256 floats.
+__device__ __forceinline__ void wide_rms(const float* sspart, int ncta, int K, float eps, float* part, float* rs, int tid) {
+    const int n = tid & 15, grp = tid >> 4;   // 16 groups of workgroups
+    float s = 0.f;
+    for (int w = grp; w < ncta; w += 16) s += as_global(sspart)[w * kMaxBatchWide + n];
+    part[grp * 16 + n] = s;
+    __syncthreads();
+    if (tid < 16) {
+        float t = 0.f;
+#pragma unroll
+        for (int gI = 0; gI < 16; gI++) t += part[gI * 16 + tid];
+        rs[tid] = rsqrtf(t / (float)K + eps);
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------- producer side (epilogues)
+// Called by dense_run_wide for lane (n = sequence, rows row .. row+3 of the projection, nv of them
+// inside the workgroup's range: 2 or 4) with the finished sums c[0..3].
+template <class E>
+struct WideEpiPairs {   // projections whose epilogue works on row pairs (QKV: RoPE + cache append; LM head)
+    E& e;
+    __device__ __forceinline__ void operator()(int row, int n, const float (&c)[4], int nv) const {
+        e(row >> 1, n, c[0], c[1]);
+        if (nv > 2) e((row >> 1) + 1, n, c[2], c[3]);
+    }
+};
+struct WideEpiSwiGLU {   // gate/up pairs -> h = silu(gate) * up into the image of the down projection's input
+    uint8_t* img; GuPerm perm;
+    __device__ __forceinline__ void operator()(int row, int n, const float (&c)[4], int nv) const {
+#pragma unroll
+        for (int p = 0; p < 2; p++) {
+            if (2 * p < nv) {
+                const float g = c[2 * p], u = c[2 * p + 1];
+                const float h = g / (1.0f + expf(-g)) * u;
+                u32 hi, lo;
+                split_bf16x2(h, 0.f, hi, lo);
+                const int f = perm.unit_of_pair((row >> 1) + p);
+                __hip_atomic_store(as_global((uint16_t*)(img + wide_img_off(n, 0, f))), (uint16_t)hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(as_global((uint16_t*)(img + wide_img_off(n, 1, f))), (uint16_t)lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+};
+struct WideEpiResidual {   // output / down projection: residual rows of this workgroup += output; image of gain * new value
+    float* xres; int d;          // residual stream [16][d] (rows owned by this workgroup only are touched)
+    const bf16_t* gain;          // gain of the next normalised projection
+    uint8_t* img;                // its input image
+    float* ssl;                  // LDS: this workgroup's partial sums of squares, [slot][16]
+    int r0;
+    __device__ __forceinline__ void operator()(int row, int n, const float (&c)[4], int nv) const {
+        // (rows come in whole groups of four here: d is a multiple of 4)
+        FF_GLOBAL f32x4* xp = as_global((f32x4*)(xres + (size_t)n * d + row));
+        const u32x2 gw = *as_global((const u32x2*)(gain + row));
+        f32x4 x = *xp;
+        x.x += c[0]; x.y += c[1]; x.z += c[2]; x.w += c[3];
+        *xp = x;
+        ssl[((row - r0) >> 2) * kMaxBatchWide + n] = (x.x * x.x + x.y * x.y) + (x.z * x.z + x.w * x.w);
+        u32 h0, l0, h1, l1;
+        split_bf16x2(x.x * bf_lo(gw.x), x.y * bf_hi(gw.x), h0, l0);
+        split_bf16x2(x.z * bf_lo(gw.y), x.w * bf_hi(gw.y), h1, l1);
+        xst2((float*)(img + wide_img_off(n, 0, row)), __uint_as_float(h0), __uint_as_float(h1));
+        xst2((float*)(img + wide_img_off(n, 1, row)), __uint_as_float(l0), __uint_as_float(l1));
+    }
+};
+
+// One K segment of the workgroup's tiles like dense_run, with the per-sequence 1/rms factors in
+// LDS (rs, or null) and an epilogue on groups of four rows (see the epilogue structs above).
+template <class Epi>
+__device__ __forceinline__ void dense_run_wide(const DenseStream& D, Stage<W_BF16> (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
+                                               int batch, int wave, int lane, const Epi& epi, const float* rs_lds) {
+    const int n = lane & 15, g = lane >> 4;
+    const u32x4* xh = (const u32x4*)xs + (size_t)(2 * n) * kDenseSegUnits;
+    const u32x4* xl = xh + kDenseSegUnits;
+    auto compute = [&](const Stage<W_BF16>& st, int h, mfma_f4& cc) {
+#pragma unroll
+        for (int u0 = 0; u0 < 8; u0 += 4) {
+            u32x4 bh[4], bl[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int j = (64 * wave + 32 * h + 4 * (u0 + u) + g) ^ n;
+                bh[u] = xh[j];
+                bl[u] = xl[j];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const mfma_bf8 a = __builtin_bit_cast(mfma_bf8, st.w[(u0 + u) >> 2][(u0 + u) & 3]);
+                cc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(mfma_bf8, bh[u]), cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(mfma_bf8, bl[u]), cc, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    const int j0n = D.j0 + kDenseSegUnits, nunitsn = min(kDenseSegUnits, D.total_units - j0n);   // the next segment (if D.more)
+#pragma unroll
+    for (int t = 0; t < kDenseMaxTiles; t++) {
+        if (t < D.T) {
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                compute(ring[h], h, acc[t]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 1 < D.T) dense_load(D, D.j0, D.nunits, t + 1, h, ring[h], wave, lane);
+                else if (D.more) dense_load(D, j0n, nunitsn, 0, h, ring[h], wave, lane);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    if (!D.last) return;
+    // ---- the four waves' partial tiles meet in LDS (the staged segment is no longer needed) ----
+    __syncthreads();
+    float* rb = (float*)xs;   // [T][wave][4][64]
+#pragma unroll
+    for (int t = 0; t < kDenseMaxTiles; t++) {
+        if (t < D.T) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) rb[((t * kWaves + wave) * 4 + i) * 64 + lane] = acc[t][i];
+        }
+    }
+    __syncthreads();
+    const float rs = rs_lds ? rs_lds[n] : 1.f;
+    for (int t = wave; t < D.T; t += kWaves) {
+        float c[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const float* p = rb + ((t * kWaves) * 4 + i) * 64 + lane;
+            c[i] = ((p[0] + p[4 * 64]) + (p[8 * 64] + p[12 * 64])) * rs;
+        }
+        const int row = D.r0 + 16 * t + 4 * g;
+        if (n < batch && row < D.r1) epi(row, n, c, min(4, D.r1 - row));
+    }
+}
+
+}  // namespace ff

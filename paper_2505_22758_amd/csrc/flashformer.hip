@@ -55,6 +55,7 @@ struct Plan {
     // scratch
     size_t x, xn, q, kvcur, attn_o, h, y, part_m, part_l, part_o, status, scratch_bytes;
     size_t cx, cx2, cdelta, tq, tkvcur, cattn_o, ch, stepctr, tpart_m, tpart_l, tpart_o;
+    size_t wxres, wimg_x, wimg_a, wimg_h, wsspart, wflag;   // wide pass only (zero bytes otherwise)
 };
 
 size_t mat_w_bytes(int n, int k, int wd) { return wd == W_BF16 ? (size_t)n * k * 2 : wd == W_INT8 ? (size_t)n * k : (size_t)n * k / 2; }
@@ -169,6 +170,13 @@ Plan make_plan(const ff_config& c) {
     P.tpart_m = take(mb * c.n_q_heads * kMaxSplits * 8);
     P.tpart_l = take(mb * c.n_q_heads * kMaxSplits * 8);
     P.tpart_o = take(mb * c.n_q_heads * kMaxSplits * c.head_dim * 8);
+    const bool wide = mb > (size_t)kMaxBatchFused;
+    P.wxres = take(wide ? mb * c.d_model * 4 : 0);
+    P.wimg_x = take(wide ? wide_img_bytes(c.d_model) : 0);
+    P.wimg_a = take(wide ? wide_img_bytes(qd) : 0);
+    P.wimg_h = take(wide ? wide_img_bytes(c.d_ffn) : 0);
+    P.wsspart = take(wide ? (size_t)kGridCtas * kMaxBatchWide * 4 : 0);
+    P.wflag = take(wide ? (size_t)kGridCtas * 4 : 0);
     P.status = take(256);
     P.scratch_bytes = s;
     return P;
@@ -315,7 +323,7 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     m->n_cta = prop.multiProcessorCount;
     m->lds_bytes = kLdsFusedBytes;
     if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
-    if (fused_pass_rows(*cfg) > kMaxBatchFused && !wide_fits(*cfg, m->n_cta)) {
+    if (fused_pass_rows(*cfg) > kMaxBatchFused && (!wide_fits(*cfg, m->n_cta) || m->n_cta > kGridCtas)) {
         delete m;
         return fail(FF_ERR_UNSUPPORTED, "max_batch %d needs the wide pass, whose row tiles do not fit a grid of %d workgroups", cfg->max_batch, prop.multiProcessorCount);
     }
@@ -357,6 +365,8 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     D.status = (int*)(s + P.status);
     D.cx = (u32*)(s + P.cx); D.cx2 = (u32*)(s + P.cx2); D.cdelta = (u32*)(s + P.cdelta); D.tq = (u32x2*)(s + P.tq);
     D.tkvcur = (u32x2*)(s + P.tkvcur); D.cattn_o = (u32*)(s + P.cattn_o); D.ch = (u32*)(s + P.ch);
+    D.wxres = (float*)(s + P.wxres); D.wimg_x = s + P.wimg_x; D.wimg_a = s + P.wimg_a; D.wimg_h = s + P.wimg_h;
+    D.wsspart = (float*)(s + P.wsspart); D.wflag = (u32*)(s + P.wflag);
     D.stepctr = (u32*)(s + P.stepctr);
     D.tpart_m = (u32x2*)(s + P.tpart_m); D.tpart_l = (u32x2*)(s + P.tpart_l); D.tpart_o = (u32x2*)(s + P.tpart_o);
     D.dbg = nullptr;
@@ -625,7 +635,10 @@ int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const 
     DevKV kvd = kv->dev;
     kvd.seq0 = seq0;
     kvd.step_batch = step_batch;
-    if (m->cfg.max_batch > 1) {   // rows a smaller batch left behind: see k_scrub_rows (decides on the device)
+    if (wide) {   // the step's embedding rows in the wide pass's exchange form
+        k_wide_embed<<<m->n_cta, kThreads, 0, st>>>(D, tokens_dev, batch);
+        HIPCHK(hipGetLastError());
+    } else if (m->cfg.max_batch > 1) {   // rows a smaller batch left behind: see k_scrub_rows (decides on the device)
         k_scrub_rows<<<64, kThreads, 0, st>>>(D, batch);
         HIPCHK(hipGetLastError());
     }
@@ -763,6 +776,8 @@ int ff_decode_step_static(ff_model* m, const int32_t* tokens_dev, const int32_t*
     D.part_m = (float*)(s + P.part_m); D.part_l = (float*)(s + P.part_l); D.part_o = (float*)(s + P.part_o);
     D.cx = (u32*)(s + P.cx); D.cx2 = (u32*)(s + P.cx2); D.cdelta = (u32*)(s + P.cdelta); D.tq = (u32x2*)(s + P.tq);
     D.tkvcur = (u32x2*)(s + P.tkvcur); D.cattn_o = (u32*)(s + P.cattn_o); D.ch = (u32*)(s + P.ch);
+    D.wxres = (float*)(s + P.wxres); D.wimg_x = s + P.wimg_x; D.wimg_a = s + P.wimg_a; D.wimg_h = s + P.wimg_h;
+    D.wsspart = (float*)(s + P.wsspart); D.wflag = (u32*)(s + P.wflag);
     D.stepctr = (u32*)(s + P.stepctr);
     D.tpart_m = (u32x2*)(s + P.tpart_m); D.tpart_l = (u32x2*)(s + P.tpart_l); D.tpart_o = (u32x2*)(s + P.tpart_o);
     // The array keeps whatever the last call (of any model) left: everything this step's kernels
