@@ -175,12 +175,6 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         const FF_CONST PLayer* Lp = as_const(M.layers) + min(l, M.L - 1);
         DenseStream DS = DenseStream::make(D.W, 0, n_ctas);
         dense_prefetch(DS, ring, wave, lane);
-#ifdef FF_WIDE_STATS
-        u64 T0 = wall_clock64();
-#define FF_WT(k) if (blockIdx.x == 7 && threadIdx.x == 0) { const u64 tn = wall_clock64(); atomicAdd(M.status + 8 * (1 + D.kind) + k, (int)(tn - T0)); T0 = tn; }
-#else
-#define FF_WT(k)
-#endif
         u32 wait_epoch = 0;
         const uint8_t* img = M.wimg_x;
         bool normed = true;
@@ -191,7 +185,6 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
                                                                 sl + l, n_ctas, vote, nullptr, M.wimg_a);
             if (!ok) return false;
             sync.arrive(ebase + 4u * (u32)l + 1u);
-            FF_WT(0)
             wait_epoch = ebase + 4u * (u32)l + 1u; img = M.wimg_a; normed = false;
         } else if (D.kind == PH_GU) wait_epoch = ebase + 4u * (u32)l + 2u;
         else if (D.kind == PH_DOWN) { wait_epoch = ebase + 4u * (u32)l + 3u; img = M.wimg_h; normed = false; }
@@ -202,19 +195,15 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
                 return false;
             }
         } else __syncthreads();
-        FF_WT(1)
         if (normed) wide_rms(M.wsspart, ncta, D.W.k, M.eps, part, rs, threadIdx.x);
-        FF_WT(2)
 #pragma unroll
         for (int t = 0; t < kDenseMaxTiles; t++) acc[t] = mfma_f4{0.f, 0.f, 0.f, 0.f};
         const int nseg = (D.W.k / 8 + kDenseSegUnits - 1) / kDenseSegUnits;
         for (int seg = 0; seg < nseg; seg++) {
             DS = DenseStream::make(D.W, seg, n_ctas);
             if (seg > 0) __syncthreads();   // every wave is done with the previous segment
-            FF_WT(3)
             if (DS.T > 0) wide_copy_segment(img + (size_t)seg * kWideSegBytes, lds, threadIdx.x);
             __syncthreads();
-            FF_WT(4)
             const float* rsp = normed ? rs : nullptr;
             if (D.kind == PH_GU) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiSwiGLU{M.wimg_h, M.gu}, rsp);
             else if (D.kind == PH_O) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiResidual{M.wxres, M.d, Lp->g2, M.wimg_x, ssl, DS.r0}, rsp);
@@ -223,7 +212,6 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
                                WideEpiResidual{M.wxres, M.d, l + 1 < M.L ? (as_const(M.layers) + l + 1)->g1 : M.gf, M.wimg_x, ssl, DS.r0}, rsp);
             else dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiPairs<EpiFused>{epf}, rsp);
         }
-        FF_WT(5)
         if (D.kind == PH_O || D.kind == PH_DOWN) {
             // this workgroup's share of every sequence's sum of squares of the new residual rows
             __syncthreads();
@@ -237,7 +225,6 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         if (D.kind == PH_O) sync.arrive(ebase + 4u * (u32)l + 2u);
         else if (D.kind == PH_GU) sync.arrive(ebase + 4u * (u32)l + 3u);
         else if (D.kind == PH_DOWN) sync.arrive(ebase + 4u * (u32)l + 4u);
-        FF_WT(6)
     }
     return true;
 }
@@ -276,7 +263,6 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     static_assert(kLdsRopeBytes == kMaxBatchFused * 64 * sizeof(float2) && kLdsMiscBytes >= (16 + 2 * (1 + WgVote::kMaxSums) * kFusedWaves) * 4, "LDS layout");
     int* pos_lds = kWide ? (int*)(lds + kLdsActBytes + kLdsAuxBytes + kLdsRopeBytes + kLdsMiscBytes)
                          : (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64 + 8);
-    float* rowss = (float*)(lds + kLdsActBytes + kLdsAuxBytes + kLdsRopeBytes + kLdsMiscBytes) + kMaxBatchWide;   // wide pass only: [wave][sequence]
     if ((int)threadIdx.x < batch) pos_lds[threadIdx.x] = pos[threadIdx.x];
     if (!kWide && threadIdx.x < 2) ((lds_u32*)(pairbox_of(xs) + 4 * kPairBoxFloats))[threadIdx.x] = 0u;
     if (B == 1 && threadIdx.x < kGluMaxChunks) ((lds_u32*)pairbox_of(xs))[threadIdx.x] = 0u;   // arrival counters of the staged h chunks (glu_run)
@@ -284,7 +270,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // projections only; attention runs right after each PH_QKV.  The LM head runs here unless its
     // weight type differs from the layers' (then the host launches it separately).
     // (lm_in_kernel: number of LM-head phases; 1, or with a wide pass the number of row blocks)
-    const int n_phases = 4 * M.L + lm_in_kernel;
+    const int n_phases = 4 * M.L + (kWide ? lm_in_kernel : lm_in_kernel ? 1 : 0);
     const int dbg_phases = 4 * M.L + (lm_in_kernel ? 1 : 0);   // phases the optional timeline buffer has slots for (further LM blocks share the last)
     // steps executed so far on the compact buffers (kept on the device: a skipped step does not count)
     const u32 steps_done = (u32)__builtin_amdgcn_readfirstlane(xld_u32(M.stepctr));
@@ -312,10 +298,6 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // the previous projection), so batch 1 keeps the unpinned form.
     constexpr bool kScalarState = B > 1;
     constexpr bool kQuad = kQuadOf<WD, B>;   // matrix-core GEMV on groups of four rows, split-bf16 staged input
-    // wide pass: register ring and tile accumulators of the dense projections, alive over the K
-    // segments of a projection (see dense_run)
-    Stage<W_BF16> wring[2];
-    mfma_f4 dah[kDenseMaxTiles], dal[kDenseMaxTiles];
     if constexpr (kWide) {
         if (!wide_loop<HD, G>(M, KV, pos_lds, rope_lds, logits, batch, lm_in_kernel, ncta, lds, vote, steps_done, sl, tag_base)) return;
         if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -323,26 +305,15 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             xst_u32(M.stepctr, steps_done + 1u);
         }
         return;
-    }
+    } else {
     int ph = 0, seg = 0;
     for (;;) {
         if constexpr (kScalarState) {
             ph = __builtin_amdgcn_readfirstlane(ph);
             seg = __builtin_amdgcn_readfirstlane(seg);
         }
-        // (wide pass: the LM head runs in row blocks of at most kDenseMaxTiles tiles per workgroup,
-        // one phase per block, all described like the first)
-        const int lm_block = kWide ? max(ph - 4 * M.L, 0) : 0;
-        PhaseDesc D = phase_desc(M, tokens, tag_base, sl, ph - lm_block, lm_in_kernel, phase_state(M, ph - lm_block), kScalarState);
+        const PhaseDesc D = phase_desc(M, tokens, tag_base, sl, ph, lm_in_kernel, phase_state(M, ph), kScalarState);
         EpiFused epi{D.kind, D.out_tag, D.out_cnt, M, KV, pos_lds, D.layer, rope_lds, logits};
-        if constexpr (kWide) {
-            if (D.kind == PH_LM) {
-                const int block_rows = kDenseMaxTiles * 16 * ncta, row0 = lm_block * block_rows;
-                D.W.w += (size_t)row0 * D.W.row_bytes();
-                D.W.n = min(block_rows, D.W.n - row0);
-                epi.pair0 = row0 >> 1;
-            }
-        }
         const Stream<WD, B> S = Stream<WD, B>::make(D.W, seg, gwave, n_gwaves, kQuad);
         // The wave's first tiles of this projection are requested before anything it has to wait
         // for (its input vector; for the output projection the whole attention), so the memory
@@ -351,18 +322,13 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         // the loads were issued to (a copy would have to wait for the data).
         TSrc src = D.src;
         src.ncta = n_ctas;
-        if (!kWide && seg > 0) src.wb = nullptr;   // (a wide pass publishes the residual stream segment by segment)
+        if (seg > 0) src.wb = nullptr;
         const bool att_first = D.kind == PH_O && seg == 0;
         Stage<WD> ring[kDepthOf<WD>];
         // (ablation switch, single-sequence bf16 instances only: with no_overlap the tiles are requested
         // after the input has arrived, as in a fused kernel without cross-layer memory overlap)
         constexpr bool kHasSwitch = B == 1 && WD == W_BF16;
-        DenseStream DS;
-        if constexpr (kWide) {
-            DS = DenseStream::make(D.W, seg, n_ctas);
-            DS.nup = S.nup;   // plane stride of the staged segment (the segment's units rounded up to whole staging chunks)
-            if (seg == 0) dense_prefetch(DS, wring, wave, lane);   // (later segments: requested at the end of the previous one)
-        } else if (!kHasSwitch || !no_overlap) prefetch_stream<kQuad>(S, ring, lane);
+        if (!kHasSwitch || !no_overlap) prefetch_stream<kQuad>(S, ring, lane);
         if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_PF_ISSUED, lane);
         // Touch the descriptor the NEXT phase will fetch, so that it sits in the scalar cache by
         // then instead of costing a trip to memory at the head of that phase.
@@ -386,8 +352,8 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_H_START, lane);
         bool ok;
         u64* ev = dbg_stage_slots(M, dbg_phases, ncta, D.layer, D.kind);
-        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev, rowss);
-        else ok = stage_tagged<EPU, false, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev, rowss);
+        if (src.add) ok = stage_tagged<EPU, true, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
+        else ok = stage_tagged<EPU, false, kFusedThreads, kQuad, B>(src, batch, S.K, S.j0 * EPU, S.nunits, S.nup, xs, red, threadIdx.x, vote, ev);
         if (ev && threadIdx.x == 0) as_global(ev)[4] = wall_clock64();
         if (!ok) {
             if (threadIdx.x == 0) atomicCAS(M.status, 0, -55 - 10 * ph);
@@ -420,13 +386,6 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             }
         }
         if (glu_done) { /* both projections are finished */ }
-        else if constexpr (kWide) {
-            if (seg == 0) {
-#pragma unroll
-                for (int t = 0; t < kDenseMaxTiles; t++) { dah[t] = mfma_f4{0.f, 0.f, 0.f, 0.f}; dal[t] = mfma_f4{0.f, 0.f, 0.f, 0.f}; }
-            }
-            dense_run(DS, wring, xs, dah, dal, batch, wave, lane, epi, PostScale{src.gain ? rowss : nullptr, 1.f / (float)S.K, M.eps});
-        }
         else if constexpr (kQuad) gemv_run_quad<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         else gemv_run<WD, B>(S, ring, xs, myacc, batch, lane, epi);
         asm volatile("" ::"s"(warm));   // keeps the touch alive
@@ -446,6 +405,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         xst_u32(M.stepctr + 1, (u32)batch);
         xst_u32(M.stepctr, steps_done + 1u);
     }
+    }   // (!kWide)
 }
 
 // Host-side launcher of one weight-type family; defined once per weight type in its own
@@ -478,11 +438,17 @@ inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what)
 }
 template <int WD, int HD, int G>
 inline hipError_t launch_fused_family(const FusedLaunch& a, const char** what) {
+    if constexpr (WD == W_BF16) {   // the wide instance (bf16 only; the host decides, and sizes lm_in_kernel and the buffers for it)
+        if (a.wide) return launch_fused_instance<WD, kMaxBatchWide, HD, G>(a, what);
+    } else if (a.wide) {
+        *what = "no wide instance for this weight type";
+        return hipErrorInvalidValue;
+    }
     if (a.batch == 1) return launch_fused_instance<WD, 1, HD, G>(a, what);
     if (a.batch == 2) return launch_fused_instance<WD, 2, HD, G>(a, what);
-    if constexpr (WD == W_BF16) {   // more than four sequences per pass: bf16 only (fused_pass_rows on the host decides)
-        if (a.wide) return launch_fused_instance<WD, kMaxBatchWide, HD, G>(a, what);
-        if (a.batch > kMaxBatch) return launch_fused_instance<WD, kMaxBatchFused, HD, G>(a, what);
+    if (a.batch > kMaxBatch) {
+        *what = "more than four sequences per pass without the wide instance";
+        return hipErrorInvalidValue;
     }
     return launch_fused_instance<WD, 4, HD, G>(a, what);
 }

@@ -275,7 +275,7 @@ struct Stream {
         // range [gwave * h, (gwave + 1) * h) of (group, chunk) iterations, h = chunks per wave, so
         // an odd wave starts in the middle of the group its even neighbour (same workgroup)
         // began; the two exchange their partial sums through LDS (gemv_run_quad).
-        if (quad && B <= kMaxBatchFused && S.nseg == 1 && (S.cpr & 1) == 0 && n_gwaves.mod(2 * npairs) == 0 && (n_gwaves.div(2 * npairs) & 1)) {
+        if (quad && S.nseg == 1 && (S.cpr & 1) == 0 && n_gwaves.mod(2 * npairs) == 0 && (n_gwaves.div(2 * npairs) & 1)) {
             const int h = (int)n_gwaves.div(2 * npairs) * (S.cpr / 2);
             S.p0 = gwave * h / S.cpr;
             S.c0 = gwave * h % S.cpr;
@@ -485,20 +485,12 @@ template <int I>
 __device__ __forceinline__ float quad_bcast(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), I * 0x55, 0xF, 0xF, true));
 }
-// RMSNorm scale applied to the finished sums instead of the staged input (wide passes, whose
-// normalised inputs are staged one K segment at a time: the sum of squares of a row is only complete
-// when its last segment has been staged, and 1/rms is a scalar per sequence that commutes with the
-// projection).  ss[w * kMaxBatchWide + b] = wave w's share of the sum of squares of sequence b (LDS).
-struct PostScale {
-    const float* ss;   // null: the staged input is already scaled
-    float inv_k, eps;
-};
 typedef short mfma_s4 __attribute__((ext_vector_type(4)));
 typedef float mfma_f4 __attribute__((ext_vector_type(4)));
 
 template <int WD, int B, class Epi>
 __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], const float4* xs,
-                                              float* myacc, int batch, int lane, Epi& epi, const PostScale post = PostScale{nullptr, 0.f, 0.f}) {
+                                              float* myacc, int batch, int lane, Epi& epi) {
     static_assert(WD == W_BF16 || B <= 4, "more than one set of four sequences: bf16 only");
     constexpr int kDepth = kDepthOf<WD>;
     constexpr int NL = kQuadLoadsOf<WD>, kUnr = kUnrOf<WD>;
@@ -676,12 +668,6 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
                         }
                     }
                     if (S.seg == S.nseg - 1) {
-                        if (post.ss) {
-                            const float* q = post.ss + b;
-                            const float rs = rsqrtf(((q[0] + q[kMaxBatchWide]) + (q[2 * kMaxBatchWide] + q[3 * kMaxBatchWide])) * post.inv_k + post.eps);
-#pragma unroll
-                            for (int i = 0; i < 4; i++) t[c][i] *= rs;
-                        }
                         epi(2 * pc, b, t[c][0], t[c][1]);
                         if (4 * pc + 2 < S.N) epi(2 * pc + 1, b, t[c][2], t[c][3]);
                     }

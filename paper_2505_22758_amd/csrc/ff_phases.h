@@ -144,30 +144,12 @@ __device__ __forceinline__ bool light_wait(const TSrc& S, int batch, int k0, int
     return false;
 }
 
-// The same over all batch rows: lane i samples row (i / 4) % batch at one of four positions (shifted
-// per workgroup), one coherent 4-byte load per lane and round.
-template <bool HAS_ADD>
-__device__ __forceinline__ bool light_wait_rows(const TSrc& S, int batch, int k0, int nel, int lane) {
-    const int sample = min(k0 + (int)(((long)(lane & 3) * nel) / 4) + (int)(blockIdx.x % 64) * 2 + (lane >> 6), k0 + nel - 1);
-    const int row = (lane >> 2) % batch;
-    const cword_t* sb = S.base + (size_t)row * S.stride;
-    const cword_t* sa = HAS_ADD ? S.add + (size_t)row * S.add_stride : nullptr;
-    for (int spins = 0; spins < kSpinLimit; spins++) {
-        bool ok = cfresh(cld1(sb, sample), S.tag);
-        if constexpr (HAS_ADD) ok = ok && cfresh(cld1(sa, sample), S.add_tag);
-        if (__all(ok)) return true;
-        __builtin_amdgcn_s_sleep(4);
-    }
-    return false;
-}
-
 // (a, b) rounded to bf16 (nearest even) and packed, a in the low half: v_cvt_pk_bf16_f32.
 typedef float pk_f2 __attribute__((ext_vector_type(2)));
 typedef __bf16 pk_bf2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ u32 pack_bf16(float a, float b) {
     return __builtin_bit_cast(u32, __builtin_convertvector(pk_f2{a, b}, pk_bf2));
 }
-
 // fp32 pair -> packed bf16 heads and packed bf16 remainders, both round to nearest even:
 // |error| <= 2^-18 |v|.
 __device__ __forceinline__ void split_bf16x2(float a, float b, u32& hi, u32& lo) {
@@ -195,8 +177,7 @@ __device__ __forceinline__ size_t wide_img_off(int n, int plane, int col) {
 //   index 4 j + (q ^ (b & 3)), and the sum of the unit's 32 values in xsum_of(xs)[b * nup + j].
 // Either way the four lanes of a matrix-core block (same j, sequences 0..3) hit different banks.
 // All lanes of a unit must call together (int4: eight consecutive quads = eight consecutive lanes).
-// XSW (bf16 weights, wide pass): unit j of sequence b at index j ^ b instead (the layout dense_run reads).
-template <int EPU, bool SPLIT, bool XSW = false>
+template <int EPU, bool SPLIT>
 __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, const float4& t) {
     constexpr int NQ = EPU / 4;
     if constexpr (!SPLIT) {
@@ -205,13 +186,14 @@ __device__ __forceinline__ void stage_store(float4* xs, int nup, int b, int qi, 
         static_assert(EPU == 8 || EPU == 16 || EPU == 32, "bf16, int8 or int4 weights");
         // heads and remainders with the packed conversion (two values per instruction, round to
         // nearest even): |error| <= 2^-18 |v|
-        const u32 h01 = pack_bf16(t.x, t.y), h23 = pack_bf16(t.z, t.w);
-        u32 h[4] = {h01 << 16, h01 & 0xFFFF0000u, h23 << 16, h23 & 0xFFFF0000u};
-        const u32 l01 = pack_bf16(t.x - __uint_as_float(h[0]), t.y - __uint_as_float(h[1])), l23 = pack_bf16(t.z - __uint_as_float(h[2]), t.w - __uint_as_float(h[3]));
-        u32 l[4] = {l01 << 16, l01 & 0xFFFF0000u, l23 << 16, l23 & 0xFFFF0000u};   // (only the int4 unit sums below look at these)
+        u32 h01, l01, h23, l23;
+        split_bf16x2(t.x, t.y, h01, l01);
+        split_bf16x2(t.z, t.w, h23, l23);
+        const u32 h[4] = {h01 << 16, h01 & 0xFFFF0000u, h23 << 16, h23 & 0xFFFF0000u};   // (only the int4 unit sums below look at these)
+        const u32 l[4] = {l01 << 16, l01 & 0xFFFF0000u, l23 << 16, l23 & 0xFFFF0000u};
         u32x2 *ph, *pl;
         if constexpr (EPU == 8) {
-            const int j = XSW ? (qi >> 1) ^ (b & 15) : (qi >> 1) ^ ((b & 3) << 2);
+            const int j = (qi >> 1) ^ ((b & 3) << 2);
             ph = (u32x2*)(xs + (size_t)(2 * b) * nup + j) + (qi & 1);
             pl = (u32x2*)(xs + (size_t)(2 * b + 1) * nup + j) + (qi & 1);
         } else if constexpr (EPU == 16) {
@@ -356,23 +338,8 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
 // a single workgroup barrier and the staged vectors are written once, already scaled.  The loads
 // of all RB rows are in flight together: behind a wave's weight prefetch a round trip takes
 // microseconds, and one per row would make the hand-over grow with the batch.
-// DEFER (wide passes, where [k0, k0 + nunits*EPU) is one K segment of a longer row): the staged
-// values keep the gain but not the 1/rms factor; every wave adds its share of the segment's sums of
-// squares to rowss[wave * kMaxBatchWide + b] (set, not added, by the first segment), and the
-// projection scales its finished sums instead (PostScale).
-//
-// CACHED (passes of eight or more sequences): a workgroup then reads hundreds of kilobytes per
-// projection, every workgroup of the chip the same ones, and the 8-byte coherent loads (which each
-// fetch from the memory side) are what the hand-over costs.  Here wave 0 first waits on a sample of
-// coherent loads for the producers to finish, drops the cached copies of earlier contents (an
-// agent-scope acquire fence = one invalidate of the vector caches; at the first segment of an
-// input and after any stale read), and the rows are then read with plain 16-byte loads that the
-// workgroups of an XCD serve each other out of their L2.  The counter in every word still decides:
-// a word that comes back stale (read before its producer wrote it, and thereby cached again) sends
-// the workgroup round the loop -- sample wait, invalidate, re-read of the stale quads.
-template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT, int RB, bool DEFER = false, bool CACHED = false>
-__device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, int tid, WgVote& vote, u64* ev,
-                                                     float* rowss = nullptr) {
+template <int EPU, bool HAS_ADD, bool HAS_GAIN, int NT, int QB, bool SPLIT, int RB>
+__device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, int tid, WgVote& vote, u64* ev) {
     constexpr int NQ = EPU / 4;
     if (ev && tid == 0) { as_global(ev)[0] = wall_clock64(); as_global(ev)[2] = 0; as_global(ev)[5] = 0; }
     const int lane = tid & 63;
@@ -414,44 +381,22 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                             u32x2 w = *as_global((const u32x2*)(erow[r] + k));
                             const u32 t = S.tag & kCntMask;
                             v[r][u] = u32x4{(w.x << 16) | t, (w.x & 0xFFFF0000u) | t, (w.y << 16) | t, (w.y & 0xFFFF0000u) | t};
-                        } else if constexpr (CACHED) {
-                            v[r][u] = *as_global((const u32x4*)(src[r] + k));
                         } else {
                             const u32x2 lo = cld2(src[r], k), hi = cld2(src[r], k + 2);
                             v[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
                         }
                         if constexpr (HAS_ADD) {
-                            if constexpr (CACHED) a[r][u] = *as_global((const u32x4*)(add[r] + k));
-                            else {
-                                const u32x2 lo = cld2(add[r], k), hi = cld2(add[r], k + 2);
-                                a[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
-                            }
+                            const u32x2 lo = cld2(add[r], k), hi = cld2(add[r], k + 2);
+                            a[r][u] = u32x4{lo.x, lo.y, hi.x, hi.y};
                         }
                     }
                     if constexpr (HAS_GAIN && kAll) { if (r == 0) g[u] = *as_global((const u32x2*)(S.gain + k)); }
                 }
             }
         };
-        // CACHED: sample wait by wave 0, optionally followed by the invalidate; false on a time-out
-        auto sync_in = [&](bool invalidate) {
-            bool lw = true;
-            if (tid < 64 && !S.tokens) {
-                lw = light_wait_rows<HAS_ADD>(S, batch, k0, nunits * EPU, lane);
-                if (invalidate) {
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                }
-            }
-            return vote.all<NT>(lw);
-        };
-        if constexpr (CACHED) {
-            // first segment of an input: wait + invalidate; later segments are read on the strength
-            // of the first one's wait (a stale word still sends the workgroup round the loop below)
-            if (b0 == 0 && k0 == 0 && !sync_in(true)) return false;
-        }
         load_quads(std::true_type{});
-        float ss[RB];   // only meaningful if the vote passes
         for (int spins = 0; spins < kSpinLimit && !all_ok; spins++) {
+            float ss[RB];   // only meaningful if the vote passes
             bool mine = true;
             // With a single row in flight the lane first ORs the counter mismatches of all its
             // words together (one operation per word) and looks at single quads only if something
@@ -487,16 +432,10 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                 mine = mine && stale[r] == 0;
                 if constexpr (HAS_GAIN) ss[r] = wave_sum_uniform(ss[r]);
             }
-            if constexpr (HAS_GAIN && !DEFER) all_ok = vote.all_sum<NT, RB>(mine, ss, tot);
+            if constexpr (HAS_GAIN) all_ok = vote.all_sum<NT, RB>(mine, ss, tot);
             else all_ok = vote.all<NT>(mine);
             if (ev && tid == 0 && spins == 0 && b0 == 0) as_global(ev)[1] = wall_clock64();
-            if constexpr (CACHED) {
-                if (!all_ok) {
-                    __builtin_amdgcn_s_sleep(8);
-                    if (!sync_in(true)) return false;
-                    if (ev && tid == 0) { as_global(ev)[2] = wall_clock64(); as_global(ev)[5] += 1; }
-                }
-            } else if (!all_ok && !S.eager) {
+            if (!all_ok && !S.eager) {
                 // A producer that is still streaming weights should not have to compete with 256
                 // workgroups re-reading its output: wait on a few samples.  An eager source is
                 // written by a handful of workgroups while the rest of the chip idles (the merged
@@ -511,26 +450,10 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
         }
         if (!all_ok) return false;
         if (ev && tid == 0) as_global(ev)[3] = wall_clock64();
-        if constexpr (HAS_GAIN && DEFER) {
-            if (lane == 0) {
-#pragma unroll
-                for (int r = 0; r < RB; r++) {
-                    if (b0 + r < batch) {
-                        float* p = rowss + (tid >> 6) * kMaxBatchWide + b0 + r;
-                        *p = (k0 == 0 ? 0.f : *p) + ss[r];
-                    }
-                }
-            }
-        }
         // Usually every (lane, u) holds a real quad (the vector is a whole number of NT*QB quads,
         // no padding): that case runs without the per-lane range tests, each of which is a
         // divergent branch -- expensive for a wave that has its SIMD to itself.
         const bool exact = nquads == padquads && padquads == QB * NT;
-        float gf[HAS_GAIN && DEFER ? QB : 1][4];   // the gains as floats, converted once for all rows
-        if constexpr (HAS_GAIN && DEFER) {
-#pragma unroll
-            for (int u = 0; u < QB; u++) { gf[u][0] = bf_lo(g[u].x); gf[u][1] = bf_hi(g[u].x); gf[u][2] = bf_lo(g[u].y); gf[u][3] = bf_hi(g[u].y); }
-        }
         auto write_quad = [&](auto EX, int r, int u, int b, float rs) {
             constexpr bool kExact = decltype(EX)::value;
             const int qi = tid + u * NT;
@@ -545,18 +468,17 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
                         cst2(w + 2, t.z, t.w, S.wb_tag);
                     }
                     if constexpr (HAS_GAIN) {
-                        if constexpr (DEFER) { t.x *= gf[u][0]; t.y *= gf[u][1]; t.z *= gf[u][2]; t.w *= gf[u][3]; }
-                        else { t.x *= bf_lo(g[u].x) * rs; t.y *= bf_hi(g[u].x) * rs; t.z *= bf_lo(g[u].y) * rs; t.w *= bf_hi(g[u].y) * rs; }
+                        t.x *= bf_lo(g[u].x) * rs; t.y *= bf_hi(g[u].x) * rs; t.z *= bf_lo(g[u].y) * rs; t.w *= bf_hi(g[u].y) * rs;
                     }
                 }
-                stage_store<EPU, SPLIT, DEFER>(xs, nup, b, qi, t);   // (DEFER = wide pass = the dense layout)
+                stage_store<EPU, SPLIT>(xs, nup, b, qi, t);
             }
         };
 #pragma unroll
         for (int r = 0; r < RB; r++) {
             const int b = b0 + r;
             if (b < batch) {
-                const float rs = HAS_GAIN && !DEFER ? rsqrtf(tot[r] / (float)K + S.eps) : 1.f;
+                const float rs = HAS_GAIN ? rsqrtf(tot[r] / (float)K + S.eps) : 1.f;
                 if (exact) {
 #pragma unroll
                     for (int u = 0; u < QB; u++) write_quad(std::true_type{}, r, u, b, rs);
@@ -578,30 +500,22 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
 // no SPLIT form (the host rejects such configurations).
 template <int EPU, bool HAS_ADD, int NT, bool SPLIT, int RBMAX>
 __device__ __forceinline__ bool stage_tagged(const TSrc& S, int batch, int K, int k0, int nunits, int nup, float4* xs, float* red, int tid,
-                                             WgVote& vote, u64* ev = nullptr, float* rowss = nullptr) {
+                                             WgVote& vote, u64* ev = nullptr) {
     constexpr int RB4 = RBMAX < 4 ? RBMAX : 4, RB2 = RBMAX < 2 ? RBMAX : 2;
-    constexpr bool C = RBMAX >= kMaxBatchFused;   // cached reads behind an invalidate (see stage_tagged_onepass)
     const int per_thread = (nup * (EPU / 4) + NT - 1) / NT;
-    if constexpr (RBMAX > kMaxBatchFused) {
-        // wide pass: K segments of two quads per thread, eight rows in flight together, deferred
-        // normalisation (a segment never holds a whole normalised row's worth of squares)
-        static_assert(SPLIT && (kLdsActBytes / (RBMAX * 4)) / 4 <= 2 * NT, "a wide pass's segment is two quads per thread");
-        if constexpr (HAS_ADD) return stage_tagged_onepass<EPU, true, true, NT, 2, true, 8, true, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev, rowss);
-        else if (S.gain) return stage_tagged_onepass<EPU, false, true, NT, 2, true, 8, true, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev, rowss);
-        else return stage_tagged_onepass<EPU, false, false, NT, 2, true, 8, true, true>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-    } else if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
-        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4, SPLIT, RB4, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8, SPLIT, RB2, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+    if constexpr (HAS_ADD) {   // residual stream + sublayer output, always normalised
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, true, true, NT, 4, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, true, true, NT, 8, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         if constexpr (SPLIT) return false;
         else return stage_tagged_multipass<EPU, true, true, NT, 8, false>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else if (S.gain) {       // embedding rows
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8, SPLIT, RB2, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, true, NT, 8, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         if constexpr (SPLIT) return false;
         else return stage_tagged_multipass<EPU, false, true, NT, 8, false>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     } else {
-        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4, SPLIT, RB4, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8, SPLIT, RB4, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
-        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14, SPLIT, RB2, false, C>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 4) return stage_tagged_onepass<EPU, false, false, NT, 4, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 8) return stage_tagged_onepass<EPU, false, false, NT, 8, SPLIT, RB4>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
+        if (per_thread <= 14) return stage_tagged_onepass<EPU, false, false, NT, 14, SPLIT, RB2>(S, batch, K, k0, nunits, nup, xs, tid, vote, ev);
         return stage_tagged_multipass<EPU, false, false, NT, 14, SPLIT>(S, batch, K, k0, nunits, nup, xs, red, tid, vote, ev);
     }
 }
@@ -694,7 +608,7 @@ struct TaggedAttnIO {
 };
 
 #ifndef FF_ATTN_BATCH
-#define FF_ATTN_BATCH 4   // wave loads of K and of V in flight per wave (can be overridden at build time for sweeps)
+#define FF_ATTN_BATCH 4   // wave loads of K and of V in flight per wave (can be overridden at build time for sweeps; 8 measured no faster)
 #endif
 template <int HD, int G, int NW, class XIO>
 __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, int layer, int b, int j, int t0, int t1, bool with_cur,

@@ -96,34 +96,33 @@ int check_config(const ff_config* c) {
     return FF_OK;
 }
 
-// Does a pass of `batch` sequences run on the wide instance of the fused kernel (bf16 weights, up to
-// kMaxBatchWide sequences, inputs staged one K segment at a time)?  Five to eight sequences whose whole
-// input rows fit the on-chip buffer together take the eight-sequence instance instead.
-bool pass_is_wide(const ff_config& c, int batch) {
-    if (c.wdtype != W_BF16 || batch <= kMaxBatch) return false;
-    return batch > kMaxBatchFused || (size_t)c.d_model * 4 * kMaxBatchFused > (size_t)kLdsActBytes;
-}
 // The wide instance gives every workgroup a contiguous range of rows of each projection, in tiles
 // of 16 whose accumulators stay in registers: at most kDenseMaxTiles tiles per workgroup (on a grid
-// of n_cta workgroups), and whole row pairs.
+// of n_cta workgroups), and whole groups of four rows of the d-wide projections.
 bool wide_fits(const ff_config& c, int n_cta) {
     const int qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     const int rows = std::max(std::max(qkv_rows, c.d_model), 2 * c.d_ffn);
     const int groups = ((rows + 3) / 4 + n_cta - 1) / n_cta;
-    return (4 * groups + 15) / 16 <= kDenseMaxTiles && c.d_model % 2 == 0;
+    return (4 * groups + 15) / 16 <= kDenseMaxTiles && c.d_model % 8 == 0 && qkv_rows % 4 == 0;
 }
 constexpr int kGridCtas = 256;   // workgroups of the fused kernel's grid on the chip the kernels are built for
 
-// Sequences one pass of the fused kernel serves: with bf16 weights and a model created for more than
-// four, 8 (input rows fit the on-chip buffer together) or 16 (wide instance); else up to 4.
+// Sequences one pass of the fused kernel serves: up to 4 on the row-partitioned paths (paper Section
+// 5.2), or, with bf16 weights and a model created for more than that, up to 16 in one wide pass.
+// FF_WIDE_MIN (experiments): smallest batch that takes the wide pass (default 5; it measured equal
+// to the former eight-sequence instance at 5 sequences and faster from 6 on, slower than the
+// four-sequence path below that).
+int wide_min_batch() {
+    const char* e = getenv("FF_WIDE_MIN");
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : kMaxBatch + 1;
+}
 int fused_pass_rows(const ff_config& c) {
-    if (c.wdtype == W_BF16 && c.max_batch > kMaxBatch) {
-        if (c.max_batch <= kMaxBatchFused && !pass_is_wide(c, c.max_batch)) return kMaxBatchFused;
-        if (wide_fits(c, kGridCtas)) return kMaxBatchWide;
-        if (!pass_is_wide(c, kMaxBatchFused)) return kMaxBatchFused;
-    }
+    if (c.wdtype == W_BF16 && c.max_batch >= wide_min_batch() && wide_fits(c, kGridCtas)) return kMaxBatchWide;
     return std::min(c.max_batch, kMaxBatch);
 }
+// Does a pass of `batch` sequences (batch <= fused_pass_rows) run on the wide instance?
+bool pass_is_wide(const ff_config& c, int batch) { return fused_pass_rows(c) == kMaxBatchWide && batch >= wide_min_batch(); }
 
 Plan make_plan(const ff_config& c) {
     Plan P;
@@ -170,7 +169,7 @@ Plan make_plan(const ff_config& c) {
     P.tpart_m = take(mb * c.n_q_heads * kMaxSplits * 8);
     P.tpart_l = take(mb * c.n_q_heads * kMaxSplits * 8);
     P.tpart_o = take(mb * c.n_q_heads * kMaxSplits * c.head_dim * 8);
-    const bool wide = mb > (size_t)kMaxBatchFused;
+    const bool wide = mb == (size_t)kMaxBatchWide;
     P.wxres = take(wide ? mb * c.d_model * 4 : 0);
     P.wimg_x = take(wide ? wide_img_bytes(c.d_model) : 0);
     P.wimg_a = take(wide ? wide_img_bytes(qd) : 0);
@@ -323,7 +322,7 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     m->n_cta = prop.multiProcessorCount;
     m->lds_bytes = kLdsFusedBytes;
     if ((size_t)prop.sharedMemPerBlock < m->lds_bytes + 256) { delete m; return fail(FF_ERR_UNSUPPORTED, "device LDS per workgroup too small"); }
-    if (fused_pass_rows(*cfg) > kMaxBatchFused && (!wide_fits(*cfg, m->n_cta) || m->n_cta > kGridCtas)) {
+    if (fused_pass_rows(*cfg) == kMaxBatchWide && (!wide_fits(*cfg, m->n_cta) || m->n_cta > kGridCtas)) {
         delete m;
         return fail(FF_ERR_UNSUPPORTED, "max_batch %d needs the wide pass, whose row tiles do not fit a grid of %d workgroups", cfg->max_batch, prop.multiProcessorCount);
     }
