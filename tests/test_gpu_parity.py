@@ -441,29 +441,24 @@ def test_two_models_interleaved_on_a_side_stream():
         m[0].close()
 
 
-def test_batch_size_changing_from_step_to_step():
-    """Steps of different batch sizes on one model and one cache: a sequence that sits out some steps
-    (the exchange vectors' 2-bit write counters come round every step of this 4-layer model, so any
-    number of skipped steps leaves the counter bits a reader would accept) must not be served values
-    its exchange rows kept from its last step."""
+def _run_changing_batches(nseq, sizes):
     from paper_2505_22758_amd import binding
     from oracle import oracle
     shape, seed, T0 = synth.TINY, 0x77, 20
-    sizes = [4, 1, 1, 1, 1, 4, 2, 2, 2, 2, 3, 1, 4, 4, 1, 1, 1, 1, 1, 1, 1, 1, 2]
     max_ctx = T0 + len(sizes) + 2
     layers = [synth.make_layer(shape, seed, l, synth.WDTYPE_BF16, "cpu") for l in range(shape.n_layers)]
     M = oracle.OracleModel(shape, layers, synth.make_head(shape, seed, synth.WDTYPE_BF16, "cpu"))
     okv = []
-    for b in range(4):
+    for b in range(nseq):
         kv = M.new_kv(1, max_ctx)
         for l in range(shape.n_layers):
             k, v = synth.make_kv_prefill(shape, seed, l, b, T0, "cpu")
             kv[l, 0, 0, :T0], kv[l, 0, 1, :T0] = oracle._np(k), oracle._np(v)
         okv.append(kv)
-    dec, caches = helpers.hip_side(shape, seed, synth.WDTYPE_BF16, 4, T0, max_ctx, n_caches=1)
-    toks = synth.make_tokens(shape, seed, len(sizes), 4)
-    pos = [T0] * 4
-    logits = torch.zeros(4, shape.vocab, dtype=torch.float32, device="cuda:0")
+    dec, caches = helpers.hip_side(shape, seed, synth.WDTYPE_BF16, nseq, T0, max_ctx, n_caches=1)
+    toks = synth.make_tokens(shape, seed, len(sizes), nseq)
+    pos = [T0] * nseq
+    logits = torch.zeros(nseq, shape.vocab, dtype=torch.float32, device="cuda:0")
     for s, b in enumerate(sizes):
         tok_d = toks[s, :b].contiguous().to("cuda:0")
         pos_d = torch.tensor(pos[:b], dtype=torch.int32, device="cuda:0")
@@ -476,6 +471,21 @@ def test_batch_size_changing_from_step_to_step():
             assert ma <= helpers.MAX_ABS_TOL and rl <= helpers.REL_L2_TOL and same.all(), (s, b, r, ma, rl)
             pos[r] += 1
     dec.close()
+
+
+def test_batch_size_changing_from_step_to_step():
+    """Steps of different batch sizes on one model and one cache: a sequence that sits out some steps
+    (the exchange vectors' 2-bit write counters come round every step of this 4-layer model, so any
+    number of skipped steps leaves the counter bits a reader would accept) must not be served values
+    its exchange rows kept from its last step."""
+    _run_changing_batches(4, [4, 1, 1, 1, 1, 4, 2, 2, 2, 2, 3, 1, 4, 4, 1, 1, 1, 1, 1, 1, 1, 1, 2])
+
+
+def test_wide_and_row_partitioned_steps_alternate_on_one_model():
+    """A model created for 16 sequences stepped with batches on both sides of the wide pass's
+    threshold: wide steps leave the compact exchange rows of the other paths untouched (those are
+    re-initialised before the next small batch), small steps leave the wide pass's epochs alone."""
+    _run_changing_batches(16, [6, 1, 16, 4, 9, 2, 5, 5, 1, 1, 12, 3, 16])
 
 
 def test_llama70b_full_depth_batch1_and_batch16_ctx2048(capsys):
@@ -582,10 +592,11 @@ def test_fused_step_replayed_from_a_hip_graph():
     """ff_decode_step carries no host-side per-step state, so a captured step can be replayed: tokens
     and positions live in fixed device tensors that are updated between replays (with the program's
     own eager work and synchronisations in between), and every replay must equal the eager result
-    of the same step on a second cache; batch 1 and batch 3 (with the row re-initialisation launch)."""
+    of the same step on a second cache; batch 1, batch 3 (with the row re-initialisation launch) and
+    batch 6 (wide pass: embedding launch + fused kernel, epochs derived from the device-side counter)."""
     from paper_2505_22758_amd import binding
     S, seed, T0, steps = synth.TINY, 97, 30, 6
-    for B in (1, 3):
+    for B in (1, 3, 6):
         dec, caches = helpers.hip_side(S, seed, synth.WDTYPE_BF16, B, T0, max_ctx=T0 + steps + 2, n_caches=2)
         toks = synth.make_tokens(S, seed, steps, B).to("cuda:0")
         tok_s = toks[0].clone()
@@ -621,7 +632,7 @@ def test_a_silent_workgroup_ends_in_a_timeout_not_a_hang():
     import time
     from paper_2505_22758_amd import binding
     S, seed, T0 = synth.TINY, 99, 20
-    for B in (1, 2):
+    for B in (1, 2, 6):   # 6: wide pass (waits on epochs instead of per-word counters)
         dec, caches = helpers.hip_side(S, seed, synth.WDTYPE_BF16, B, T0, max_ctx=T0 + 4)
         tok = torch.arange(3, 3 + B, dtype=torch.int32, device="cuda:0")
         pos = torch.full((B,), T0, dtype=torch.int32, device="cuda:0")
