@@ -35,7 +35,7 @@ WORKLOADS = {
     # name: (shape, wdtype, batch, context)
     "tiny-bf16-b1-ctx128": ("tiny", 0, 1, 128),
     "llama3-8b-bf16-b1-ctx1024": ("llama3-8b", 0, 1, 1024),
-    "llama3-8b-bf16-b8-ctx1024": ("llama3-8b", 0, 8, 1024),     # one pass of eight sequences
+    "llama3-8b-bf16-b8-ctx1024": ("llama3-8b", 0, 8, 1024),     # one wide pass
     "llama3-8b-bf16-b16-ctx1024": ("llama3-8b", 0, 16, 1024),   # one wide pass
     "llama3-8b-int8-b1-ctx4096": ("llama3-8b", 1, 1, 4096),
     "llama3-8b-int4-b1-ctx2048": ("llama3-8b", 2, 1, 2048),
@@ -273,8 +273,10 @@ def main():
         "metric": "per-token decode latency", "value": ms_per_step * 1e3, "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": {0: "bf16", 1: "int8", 2: "int4"}[wdtype] + " weights, f32 accumulate; activations exchanged between phases as f32 rounded to 22 mantissa bits"
-                 + ("" if batch == 1 else ", staged projection inputs as bf16 head + bf16 remainder (17 bits)"),
+        "dtype": {0: "bf16", 1: "int8", 2: "int4"}[wdtype] + " weights, f32 accumulate; "
+                 + ("activations exchanged between phases and multiplied as bf16 head + bf16 remainder (17 bits), residual stream f32" if wdtype == 0 and batch > 4
+                    else "activations exchanged between phases as f32 rounded to 22 mantissa bits"
+                         + ("" if batch == 1 else ", staged projection inputs as bf16 head + bf16 remainder (17 bits)")),
         "data": "synthetic",
         "config": {"workload": args.workload if not (args.batch or args.ctx) else f"{args.workload} with batch {batch}, ctx {ctx}",
                    "batch": batch, "kv_context": ctx,

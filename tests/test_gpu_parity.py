@@ -176,8 +176,8 @@ def test_sequences_of_different_lengths_in_one_batch():
 
 
 def test_tiny_batches_above_one_pass():
-    """Batches 5..16: with bf16 weights one pass serves up to eight sequences (5, 7, 8 in one pass,
-    16 in two), with int8 weights four (6 = a full and a ragged pass)."""
+    """Batches 5..16: with bf16 weights one wide pass each (a single K segment at this width, workgroups
+    that own one row group or none), with int8 weights passes of four (6 = a full and a ragged pass)."""
     for b in (5, 7, 8, 16):
         _run_teacher_forced(synth.TINY, 40 + b, synth.WDTYPE_BF16, batch=b, T0=24, steps=2)
     _run_teacher_forced(synth.TINY.replace(d_ffn=1408), 61, synth.WDTYPE_INT8, batch=6, T0=24, steps=2)
@@ -359,9 +359,9 @@ def test_llama70b_shaped_one_layer_int4_and_int8():
 
 
 def test_llama8b_shaped_one_layer_batch8_single_pass():
-    """Eight sequences in ONE pass at the 8B width (one layer): the matrix-core projections with two
-    sets of four sequences, input rows staged in two groups, the down projection cut into four
-    segments along K, sequences of different lengths."""
+    """Eight sequences in ONE (wide) pass at the 8B width (one layer): one or two tiles of 16 rows per
+    workgroup (seven for gate/up), inputs copied in two K segments (seven for the down projection),
+    sequences of different lengths."""
     _run_teacher_forced(synth.LLAMA_8B.replace(n_layers=1), 0x250522766, synth.WDTYPE_BF16, batch=8, T0=[96, 1, 300, 64, 63, 65, 0, 200], steps=2,
                         gpu_generated=True)
 
@@ -386,8 +386,8 @@ def test_wide_model_staged_in_several_passes():
 
 def test_eight_query_heads_per_kv_head_small_model_all_formats():
     """The (head_dim 128, 8 query heads per kv head) kernel family on a small model, in the batch
-    classes the 70B-shaped tests do not reach: eight sequences in one pass (bf16), and the int8 and
-    int4 matrix-core projections at batch 4 and 3."""
+    classes the 70B-shaped tests do not reach: eight sequences in one wide pass (bf16), and the int8
+    and int4 matrix-core projections at batch 4 and 3."""
     S = synth.TINY.replace(name="g8", n_layers=2, d_model=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, d_ffn=1536, vocab=1500)
     _run_teacher_forced(S, 0x25052276b, synth.WDTYPE_BF16, batch=8, T0=70, steps=2)
     _run_teacher_forced(S, 0x25052276c, synth.WDTYPE_INT8, batch=4, T0=33, steps=2)
@@ -774,11 +774,11 @@ def test_glu_as_one_stream_small_model_all_formats(monkeypatch):
 
 
 def test_wide_pass_of_up_to_16_sequences_small_model():
-    """More than eight sequences (bf16 weights) run as ONE pass whose inputs are staged one K segment
-    of 2048 elements at a time (d_model 4096 = 2 segments, d_ffn 6144 = 3), with the RMSNorm scale
-    applied to the projection outputs and the LM head in launches of its own: a full pass of 16 and a
-    ragged one of 11, sequences of different lengths, two layers so that the second one stages
-    residual stream + sublayer output segment by segment."""
+    """More than four sequences (bf16 weights) run as ONE wide pass: projections on 16x16x32 matrix-core
+    tiles, inputs copied one K segment of 2048 columns at a time (d_model 4096 = 2 segments, d_ffn 6144
+    = 3) from images written by the workgroups that own the values, the RMSNorm factor applied to the
+    projection outputs, the LM head in row blocks: a full pass of 16 and a ragged one of 11, sequences
+    of different lengths, two layers so that the residual rows are carried from layer to layer."""
     S = synth.TINY.replace(name="wide", n_layers=2, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ffn=6144, vocab=3000)
     _run_teacher_forced(S, 0x250522790, synth.WDTYPE_BF16, batch=16, T0=[40, 0, 1, 130, 64, 63, 65, 9, 300, 17, 128, 5, 77, 256, 2, 33], steps=2)
     _run_teacher_forced(S, 0x250522791, synth.WDTYPE_BF16, batch=11, T0=[7, 70, 0, 129, 31, 64, 200, 1, 90, 12, 55], steps=2)
