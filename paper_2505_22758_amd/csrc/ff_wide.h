@@ -15,7 +15,8 @@
 //     a scalar per sequence that commutes with the projection);
 //   * the SwiGLU epilogue and the attention merge write their outputs into such images too;
 //   * a consumer's staging is a copy: image segment (2048 columns x 16 sequences, 128 KB) -> LDS,
-//     16 bytes per lane and instruction, no arithmetic;
+//     16 bytes per lane and instruction, no arithmetic, each wave copying the K quarter it multiplies
+//     (no workgroup barrier between segments);
 //   * the image words have no room for the per-word write counters of the other paths, so the
 //     dependency is carried by one flag per workgroup and phase (paper Section 4.1: the global
 //     barrier between dependent phases, here as an epoch per workgroup that consumers poll): a
@@ -67,18 +68,22 @@ struct WideSync {
 };
 
 // ---------------------------------------------------------------- consumer side
-// Copies one image segment into LDS (same layout); all threads of the workgroup.
-__device__ __forceinline__ void wide_copy_segment(const uint8_t* img_seg, uint8_t* lds, int tid) {
-    const FF_GLOBAL u32x4* src = as_global((const u32x4*)img_seg);
-    u32x4* dst = (u32x4*)lds;
-    constexpr int kPer = kWideSegBytes / 16 / kThreads;   // 32 units per thread
+// Copies this wave's quarter of one image segment into LDS (same layout): units [64 w, 64 w + 64) of
+// each of the 32 planes, one 16-byte unit per lane and plane.  A wave multiplies only its own K
+// quarter of a segment (and the unit swizzle j ^ n stays inside a quarter), so the copy is private
+// to the wave: no workgroup barrier between K segments, the waves of a workgroup drift apart and one
+// wave's copy overlaps the others' weight streams.
+__device__ __forceinline__ void wide_copy_quarter(const uint8_t* img_seg, uint8_t* lds, int wave, int lane) {
+    const FF_GLOBAL u32x4* src = as_global((const u32x4*)img_seg) + 64 * wave + lane;
+    u32x4* dst = (u32x4*)lds + 64 * wave + lane;
+    constexpr int kPlanes = 2 * kMaxBatchWide;
 #pragma unroll
-    for (int b0 = 0; b0 < kPer; b0 += 8) {
+    for (int p0 = 0; p0 < kPlanes; p0 += 8) {
         u32x4 v[8];
 #pragma unroll
-        for (int i = 0; i < 8; i++) v[i] = src[tid + (b0 + i) * kThreads];
+        for (int i = 0; i < 8; i++) v[i] = src[(p0 + i) * kDenseSegUnits];
 #pragma unroll
-        for (int i = 0; i < 8; i++) dst[tid + (b0 + i) * kThreads] = v[i];
+        for (int i = 0; i < 8; i++) dst[(p0 + i) * kDenseSegUnits] = v[i];
     }
 }
 // 1/rms of every sequence from the workgroups' partial sums of squares ([workgroups][16] floats,
