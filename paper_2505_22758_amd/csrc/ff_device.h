@@ -17,10 +17,10 @@ typedef uint16_t f16_t;    // raw bits
 
 constexpr int kThreads = 256;            // threads per workgroup (4 waves, one per SIMD)
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxBatch = 4;        // sequences one kernel pass works on
-constexpr int kMaxBatchFused = 8;   // ... of the fused kernel with bf16 weights, if the input rows of 8 sequences fit in LDS
-constexpr int kMaxBatchWide = 16;   // ... of its wide instance (bf16 weights): inputs staged one K segment at a time, RMSNorm scale applied to the outputs
-constexpr int kMaxBatchApi = 16;    // sequences one decode step accepts (run as passes of kMaxBatch)
+constexpr int kMaxBatch = 4;        // sequences one pass of the row-partitioned paths works on
+constexpr int kMaxBatchFused = 8;   // sequences the regular RoPE / position / mailbox regions of the fused kernel's LDS are laid out for
+constexpr int kMaxBatchWide = 16;   // sequences of a wide pass (bf16 weights, see ff_wide.h)
+constexpr int kMaxBatchApi = 16;    // sequences one decode step accepts (one wide pass, or passes of kMaxBatch)
 constexpr int kMaxSplits = 64;           // max KV splits per (sequence, kv head)
 #ifndef FF_MIN_SPLIT
 #define FF_MIN_SPLIT 64   // can be overridden at build time for sweeps (32 and 128 both measured 2 % slower at ctx 1024)

@@ -243,13 +243,12 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float4* xs = (float4*)lds;
-    // A wide pass (more than kMaxBatchFused sequences, bf16 weights) keeps its RoPE rows in the tail of
-    // the aux region that only int4 weights use plus the regular RoPE region behind it, and its
-    // positions and per-wave sums of squares (deferred RMSNorm, see PostScale) in the mailbox region
-    // (wave pairs never share a row group there).
+    // The wide instance (up to 16 sequences, bf16 weights) keeps its RoPE rows in the tail of the aux
+    // region that only int4 weights use plus the regular RoPE region behind it, and its positions
+    // in the mailbox region (no wave pairs share a row group there).
     constexpr bool kWide = B > kMaxBatchFused;
-    static_assert(!kWide || (WD == W_BF16 && kLdsXsumBytes + kLdsRopeBytes >= B * 64 * (int)sizeof(float2) && kLdsPairBytes >= (B + kFusedWaves * kMaxBatchWide) * 4 &&
-                             B <= kMaxBatchWide), "LDS layout of the wide pass");
+    static_assert(!kWide || (WD == W_BF16 && kLdsXsumBytes + kLdsRopeBytes >= B * 64 * (int)sizeof(float2) && kLdsPairBytes >= B * 4 && B <= kMaxBatchWide),
+                  "LDS layout of the wide pass");
     float2* rope_lds = (float2*)(lds + kLdsActBytes + kLdsAuxBytes - (kWide ? kLdsXsumBytes : 0));   // [batch][hd/2]
     for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kFusedThreads) {
         int b = i / (M.hd / 2), f = i % (M.hd / 2);
