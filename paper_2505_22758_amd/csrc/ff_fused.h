@@ -201,7 +201,7 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         const int nseg = (D.W.k / 8 + kDenseSegUnits - 1) / kDenseSegUnits;
         for (int seg = 0; seg < nseg; seg++) {
             DS = DenseStream::make(D.W, seg, n_ctas);
-            if (DS.T > 0) wide_copy_quarter(img + (size_t)seg * kWideSegBytes, lds, wave, lane);   // (private to the wave: no barrier)
+            if (DS.T > 0) wide_copy_quarter(img + (size_t)seg * kWideSegBytes, lds, wave, lane, batch);   // (private to the wave: no barrier)
             const float* rsp = normed ? rs : nullptr;
             if (D.kind == PH_GU) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiSwiGLU{M.wimg_h, M.gu}, rsp);
             else if (D.kind == PH_O) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiResidual{M.wxres, M.d, Lp->g2, M.wimg_x, ssl, DS.r0}, rsp);

@@ -69,22 +69,33 @@ struct WideSync {
 
 // ---------------------------------------------------------------- consumer side
 // Copies this wave's quarter of one image segment into LDS (same layout): units [64 w, 64 w + 64) of
-// each of the 32 planes, one 16-byte unit per lane and plane.  A wave multiplies only its own K
-// quarter of a segment (and the unit swizzle j ^ n stays inside a quarter), so the copy is private
-// to the wave: no workgroup barrier between K segments, the waves of a workgroup drift apart and one
-// wave's copy overlaps the others' weight streams.
-__device__ __forceinline__ void wide_copy_quarter(const uint8_t* img_seg, uint8_t* lds, int wave, int lane) {
-    const FF_GLOBAL u32x4* src = as_global((const u32x4*)img_seg) + 64 * wave + lane;
-    u32x4* dst = (u32x4*)lds + 64 * wave + lane;
-    constexpr int kPlanes = 2 * kMaxBatchWide;
+// the two planes of each of the pass's sequences, one 16-byte unit per lane and plane.  A wave
+// multiplies only its own K quarter of a segment (and the unit swizzle j ^ n stays inside a quarter),
+// so the copy is private to the wave: no workgroup barrier between K segments, the waves of a
+// workgroup drift apart and one wave's copy overlaps the others' weight streams.  The copy uses the
+// loads that write LDS directly (global_load_lds_dwordx4: lane i's 16 bytes land at M0 base + 16 i),
+// so all planes are requested at once without passing through registers, and one wait covers them.
+// The planes of sequences beyond the pass's batch are not copied: their matrix-core columns are never
+// stored.  The compiler does not order LDS reads against these loads by itself: the caller's last
+// reads of the old contents are complete (their results have been multiplied), and nothing is moved
+// across the wait at the end.
+__device__ __forceinline__ void wide_copy_quarter(const uint8_t* img_seg, uint8_t* lds, int wave, int lane, int batch) {
+    typedef __attribute__((address_space(1))) const void gvoid;
+    typedef __attribute__((address_space(3))) void lvoid;
+    constexpr int kPlaneBytes = kDenseSegUnits * 16;
+    const uint8_t* src = img_seg + (size_t)(64 * wave + lane) * 16;
+    uint8_t* dst = lds + (size_t)(64 * wave) * 16;   // wave-uniform
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
 #pragma unroll
-    for (int p0 = 0; p0 < kPlanes; p0 += 8) {
-        u32x4 v[8];
-#pragma unroll
-        for (int i = 0; i < 8; i++) v[i] = src[(p0 + i) * kDenseSegUnits];
-#pragma unroll
-        for (int i = 0; i < 8; i++) dst[(p0 + i) * kDenseSegUnits] = v[i];
+    for (int n = 0; n < kMaxBatchWide; n++) {
+        if (n < batch) {
+            __builtin_amdgcn_global_load_lds((gvoid*)(src + (2 * n) * kPlaneBytes), (lvoid*)(dst + (2 * n) * kPlaneBytes), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gvoid*)(src + (2 * n + 1) * kPlaneBytes), (lvoid*)(dst + (2 * n + 1) * kPlaneBytes), 16, 0, 0);
+        }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 }
 // 1/rms of every sequence from the workgroups' partial sums of squares ([workgroups][16] floats,
 // added in a fixed order) into rs[16] (LDS).  part: LDS scratch of 256 floats.
