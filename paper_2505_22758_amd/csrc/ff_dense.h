@@ -50,14 +50,18 @@ struct DenseStream {
 // Loads of stage h (0, 1) of tile t in the K segment that starts at unit j0 and holds nunits units.
 // Every load is issued from a clamped address: rows past the workgroup's range repeat its last row
 // (same addresses within one wave load, i.e. no extra traffic; their results are never stored),
-// units past the segment meet zeros in the staged input.
-__device__ __forceinline__ void dense_load(const DenseStream& D, int j0, int nunits, int t, int h, Stage<W_BF16>& st, int wave, int lane) {
+// units past the segment meet zeros in the staged input.  With `real` false (no further stage in the
+// projection) the eight loads are still issued, all lanes reading the matrix's first 16 bytes: the
+// number of loads in flight then never depends on a branch, which is what lets the compiler wait for
+// a ring slot with the other slot's loads still outstanding (where code paths that issued different
+// numbers of loads meet, it has to assume the fewest, i.e. wait for everything).
+__device__ __forceinline__ void dense_load(const DenseStream& D, int j0, int nunits, int t, int h, Stage<W_BF16>& st, int wave, int lane, bool real = true) {
     const int row = min(D.r0 + 16 * t + (lane & 15), D.r1 - 1);
     const uint8_t* rp = D.w + (size_t)row * D.rowb + (size_t)j0 * 16;
 #pragma unroll
     for (int u = 0; u < 8; u++) {
         const int j = min(64 * wave + 32 * h + 4 * u + (lane >> 4), nunits - 1);
-        st.w[u >> 2][u & 3] = ldg_stream(rp + (size_t)j * 16);
+        st.w[u >> 2][u & 3] = ldg_stream(real ? rp + (size_t)j * 16 : D.w);
     }
 }
 

@@ -101,8 +101,14 @@ __device__ __forceinline__ void wide_copy_quarter(const uint8_t* img_seg, uint8_
 // added in a fixed order) into rs[16] (LDS).  part: LDS scratch of 256 floats.
 __device__ __forceinline__ void wide_rms(const float* sspart, int ncta, int K, float eps, float* part, float* rs, int tid) {
     const int n = tid & 15, grp = tid >> 4;   // 16 groups of workgroups
+    // (all loads of a thread are issued before the first is added: one trip to the L2 instead of sixteen;
+    // a wide pass runs on at most 256 workgroups, which the host checks when the model is created)
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) v[i] = as_global(sspart)[min(grp + 16 * i, ncta - 1) * kMaxBatchWide + n];
     float s = 0.f;
-    for (int w = grp; w < ncta; w += 16) s += as_global(sspart)[w * kMaxBatchWide + n];
+#pragma unroll
+    for (int i = 0; i < 16; i++) s += grp + 16 * i < ncta ? v[i] : 0.f;
     part[grp * 16 + n] = s;
     __syncthreads();
     if (tid < 16) {
@@ -200,8 +206,9 @@ __device__ __forceinline__ void dense_run_wide(const DenseStream& D, Stage<W_BF1
             for (int h = 0; h < 2; h++) {
                 compute(ring[h], h, acc[t]);
                 __builtin_amdgcn_sched_barrier(0);
-                if (t + 1 < D.T) dense_load(D, D.j0, D.nunits, t + 1, h, ring[h], wave, lane);
-                else if (D.more) dense_load(D, j0n, nunitsn, 0, h, ring[h], wave, lane);
+                // (the next tile's stage, the next segment's first, or a dummy: always eight loads, see dense_load)
+                const bool in_seg = t + 1 < D.T;
+                dense_load(D, in_seg ? D.j0 : j0n, in_seg ? D.nunits : nunitsn, in_seg ? t + 1 : 0, h, ring[h], wave, lane, in_seg || D.more);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
