@@ -181,10 +181,19 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         if (D.kind == PH_QKV) wait_epoch = l > 0 ? ebase + 4u * (u32)l : 0u;
         else if (D.kind == PH_O) {
             __syncthreads();   // the previous projection's epilogue has read its sums out of LDS
-            const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, l, lds, tag_of(tag_base, l, TAG_QKV), tag_of(tag_base, l, TAG_ATT),
-                                                                sl + l, n_ctas, vote, nullptr, M.wimg_a);
+#ifdef FF_WSTATS
+            u64* aev = blockIdx.x == FF_WSTATS ? (u64*)(M.status + 48) : nullptr;
+            if (aev && threadIdx.x == 0) as_global(aev)[0] = wall_clock64();
+#else
+            u64* aev = nullptr;
+#endif
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, true>(M, KV, pos_lds, batch, l, lds, tag_of(tag_base, l, TAG_QKV), tag_of(tag_base, l, TAG_ATT),
+                                                                      sl + l, n_ctas, vote, aev, M.wimg_a);
             if (!ok) return false;
             sync.arrive(ebase + 4u * (u32)l + 1u);
+#ifdef FF_WSTATS
+            if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
+#endif
             wait_epoch = ebase + 4u * (u32)l + 1u; img = M.wimg_a; normed = false;
         } else if (D.kind == PH_GU) wait_epoch = ebase + 4u * (u32)l + 2u;
         else if (D.kind == PH_DOWN) { wait_epoch = ebase + 4u * (u32)l + 3u; img = M.wimg_h; normed = false; }

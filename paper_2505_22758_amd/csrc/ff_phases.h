@@ -610,9 +610,25 @@ struct TaggedAttnIO {
 #ifndef FF_ATTN_BATCH
 #define FF_ATTN_BATCH 4   // wave loads of K and of V in flight per wave (can be overridden at build time for sweeps; 8 measured no faster)
 #endif
-template <int HD, int G, int NW, class XIO>
+// MM (wide pass, head dimension 128: hundreds of cached rows per wave and item, where the vector ALUs
+// and not the memory set the pace): the scores of a batch of 16 rows come from the matrix cores, and
+// the running maximum is updated once per batch instead of once per row.
+//   * v_mfma_f32_16x16x32_bf16 with A = 16 cached key rows (lane (r, g4) loads dims [32 kk + 8 g4, + 8)
+//     of row r for the k-steps kk = 0..3) and B = the queries as bf16 head (columns 0..G-1) and bf16
+//     remainder (columns 8..8+G-1), so the products are as accurate as the fp32 ones of the row-wise
+//     path; column n + 8 is added to column n, the scores are scaled and handed through a small LDS
+//     area of the wave to the lane groups that hold the value rows (row r = 4 i + grp of the batch is
+//     value load i of group grp, as in the row-wise path);
+//   * per head: one maximum over the batch's four rows of the group, one rescaling of the running
+//     output, then four multiply-adds per output element (rows past the item's end get weight 0).
+// Two batches of loads are kept in flight, the refills issued unconditionally (behind the item's
+// last row they repeat that row), like the refills of the weight ring: where code paths that issued
+// different numbers of loads meet, the compiler waits for all.
+typedef __bf16 attn_bf8 __attribute__((ext_vector_type(8)));
+template <int HD, int G, int NW, class XIO, bool WIDE = false>
 __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, int layer, int b, int j, int t0, int t1, bool with_cur,
                           int split, uint8_t* lds, u64* ev = nullptr) {
+    constexpr bool MM = WIDE && HD == 128 && G <= 8;
     constexpr int LPR = HD / 8;        // lanes per cache row
     constexpr int RPW = 64 / LPR;      // rows per wave load
     constexpr int NS = NW * RPW;       // partial states per workgroup
@@ -652,7 +668,20 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     // queries are waited for, so the wait for the QKV projection overlaps them.
     constexpr int kAttnBatch = FF_ATTN_BATCH;
     constexpr int kStride = NW * RPW * kAttnBatch;
-    u32x4 kw[kAttnBatch], vw[kAttnBatch];
+    static_assert(!MM || (kAttnBatch == 4 && 64 / (HD / 8) == 4), "a batch is 16 rows: four value loads of four rows");
+    u32x4 kw[MM ? 2 * kAttnBatch : kAttnBatch], vw[MM ? 2 * kAttnBatch : kAttnBatch];   // MM: two batches ([buffer][load]); keys in matrix-core layout
+    // MM: loads of the batch that starts at row tb (for this wave) into buffer bf
+    auto issue_mm = [&](int bf, int tb) {
+        const int r = lane & 15, g4 = lane >> 4;
+        const int tk = min(tb + (r >> 2) * NW * RPW + (r & 3), t1 - 1);   // clamped: every load is issued
+#pragma unroll
+        for (int kk = 0; kk < 4; kk++) kw[bf * 4 + kk] = ldg_stream(Kp + (size_t)tk * HD + 32 * kk + 8 * g4);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int t = min(tb + i * NW * RPW + grp, t1 - 1);
+            vw[bf * 4 + i] = ldg_stream(Vp + (size_t)t * HD + sub * 8);
+        }
+    };
     auto issue = [&](int tb0) {
 #pragma unroll
         for (int i = 0; i < kAttnBatch; i++) {
@@ -662,29 +691,105 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
         }
     };
     int tb0 = t0 + wave * RPW;
-    if (tb0 < t1) issue(tb0);
+    if constexpr (MM) {
+        if (t0 < t1) {   // (uniform; an empty range has no row to clamp to)
+            issue_mm(0, tb0);
+            issue_mm(1, tb0 + kStride);
+        }
+    } else {
+        if (tb0 < t1) issue(tb0);
+    }
     // queries of the G heads and this step's own k, v: staged once per workgroup behind the state
     // merge area, then read by every lane from LDS
     float* xin = (float*)lds + 2 * NS * G + (size_t)NS * G * HD;
     const bool ok = xio.template stage_inputs<HD, G, NT>(M, b, j, with_cur, xin);
     if (ev && threadIdx.x == 0) as_global(ev)[1] = wall_clock64();
     if (!ok) return false;   // uniform
+    auto load_qr = [&]() {
 #pragma unroll
-    for (int g = 0; g < G; g++) {
-        const float4 q0 = *(const float4*)(xin + g * HD + sub * 8), q1 = *(const float4*)(xin + g * HD + sub * 8 + 4);
-        qr[g][0] = q0.x; qr[g][1] = q0.y; qr[g][2] = q0.z; qr[g][3] = q0.w;
-        qr[g][4] = q1.x; qr[g][5] = q1.y; qr[g][6] = q1.z; qr[g][7] = q1.w;
-    }
-    for (bool first = true; tb0 < t1; tb0 += kStride, first = false) {
-        if (!first) issue(tb0);
+        for (int g = 0; g < G; g++) {
+            const float4 q0 = *(const float4*)(xin + g * HD + sub * 8), q1 = *(const float4*)(xin + g * HD + sub * 8 + 4);
+            qr[g][0] = q0.x; qr[g][1] = q0.y; qr[g][2] = q0.z; qr[g][3] = q0.w;
+            qr[g][4] = q1.x; qr[g][5] = q1.y; qr[g][6] = q1.z; qr[g][7] = q1.w;
+        }
+    };
+    if constexpr (MM) {
+        // queries as matrix-core B operand: column n = head n % 8, bf16 head (n < 8) or remainder (n >= 8)
+        const int n = lane & 15, g4 = lane >> 4;
+        u32x4 qb[4];
 #pragma unroll
-        for (int i = 0; i < kAttnBatch; i++) {
-            const bool valid = tb0 + i * NW * RPW + grp < t1;
-            float kf[8] = {bf_lo(kw[i].x), bf_hi(kw[i].x), bf_lo(kw[i].y), bf_hi(kw[i].y), bf_lo(kw[i].z), bf_hi(kw[i].z), bf_lo(kw[i].w), bf_hi(kw[i].w)};
-            float vf[8] = {bf_lo(vw[i].x), bf_hi(vw[i].x), bf_lo(vw[i].y), bf_hi(vw[i].y), bf_lo(vw[i].z), bf_hi(vw[i].z), bf_lo(vw[i].w), bf_hi(vw[i].w)};
-            update(kf, vf, valid);
+        for (int kk = 0; kk < 4; kk++) {
+            const float* qp = xin + min(n & 7, G - 1) * HD + 32 * kk + 8 * g4;
+            const float4 a = *(const float4*)qp, c = *(const float4*)(qp + 4);
+            u32 h0, l0, h1, l1, h2, l2, h3, l3;
+            split_bf16x2(a.x, a.y, h0, l0); split_bf16x2(a.z, a.w, h1, l1);
+            split_bf16x2(c.x, c.y, h2, l2); split_bf16x2(c.z, c.w, h3, l3);
+            qb[kk] = n < 8 ? u32x4{h0, h1, h2, h3} : u32x4{l0, l1, l2, l3};
+        }
+        float* sx = xin + (G + 2) * HD + wave * 128;   // this wave's score exchange: [16 rows][8 heads]
+        auto consume = [&](int bf, int tb) {
+            mfma_f4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; kk++)
+                c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(attn_bf8, kw[bf * 4 + kk]), __builtin_bit_cast(attn_bf8, qb[kk]), c, 0, 0, 0);
+            // lane (n, g4), element i: row 4 g4 + i of the batch, column n; heads + remainders
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const float v = c[i] + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(c[i]), 0x128, 0xF, 0xF, true));   // row_ror:8
+                if (n < 8) sx[(4 * g4 + i) * 8 + n] = v * sc;
+            }
+            float vf[4][8];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const u32x4 w = vw[bf * 4 + i];
+                vf[i][0] = bf_lo(w.x); vf[i][1] = bf_hi(w.x); vf[i][2] = bf_lo(w.y); vf[i][3] = bf_hi(w.y);
+                vf[i][4] = bf_lo(w.z); vf[i][5] = bf_hi(w.z); vf[i][6] = bf_lo(w.w); vf[i][7] = bf_hi(w.w);
+            }
+            float sr[4][8];   // scores of this group's four rows (row 4 i + grp), all heads
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const float4 s0 = *(const float4*)(sx + (4 * i + grp) * 8), s1 = *(const float4*)(sx + (4 * i + grp) * 8 + 4);
+                const bool valid = tb + i * NW * RPW + grp < t1;
+                sr[i][0] = valid ? s0.x : -INFINITY; sr[i][1] = valid ? s0.y : -INFINITY; sr[i][2] = valid ? s0.z : -INFINITY; sr[i][3] = valid ? s0.w : -INFINITY;
+                sr[i][4] = valid ? s1.x : -INFINITY; sr[i][5] = valid ? s1.y : -INFINITY; sr[i][6] = valid ? s1.z : -INFINITY; sr[i][7] = valid ? s1.w : -INFINITY;
+            }
+#pragma unroll
+            for (int g = 0; g < G; g++) {
+                const float mn = fmaxf(fmaxf(m[g], fmaxf(sr[0][g], sr[1][g])), fmaxf(sr[2][g], sr[3][g]));
+                const float mref = mn == -INFINITY ? 0.f : mn;   // nothing valid so far: all weights 0
+                const float corr = exp2_hw(m[g] - mref);
+                const float p0 = exp2_hw(sr[0][g] - mref), p1 = exp2_hw(sr[1][g] - mref), p2 = exp2_hw(sr[2][g] - mref), p3 = exp2_hw(sr[3][g] - mref);
+                l[g] = fmaf(l[g], corr, (p0 + p1) + (p2 + p3));
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    o[g][e] = fmaf(p3, vf[3][e], fmaf(p2, vf[2][e], fmaf(p1, vf[1][e], fmaf(p0, vf[0][e], o[g][e] * corr))));
+                m[g] = mn;
+            }
+        };
+        for (; tb0 < t1; tb0 += 2 * kStride) {
+            consume(0, tb0);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_mm(0, tb0 + 2 * kStride);
+            __builtin_amdgcn_sched_barrier(0);
+            if (tb0 + kStride < t1) consume(1, tb0 + kStride);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_mm(1, tb0 + 3 * kStride);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+        load_qr();
+        for (bool first = true; tb0 < t1; tb0 += kStride, first = false) {
+            if (!first) issue(tb0);
+#pragma unroll
+            for (int i = 0; i < kAttnBatch; i++) {
+                const bool valid = tb0 + i * NW * RPW + grp < t1;
+                float kf[8] = {bf_lo(kw[i].x), bf_hi(kw[i].x), bf_lo(kw[i].y), bf_hi(kw[i].y), bf_lo(kw[i].z), bf_hi(kw[i].z), bf_lo(kw[i].w), bf_hi(kw[i].w)};
+                float vf[8] = {bf_lo(vw[i].x), bf_hi(vw[i].x), bf_lo(vw[i].y), bf_hi(vw[i].y), bf_lo(vw[i].z), bf_hi(vw[i].z), bf_lo(vw[i].w), bf_hi(vw[i].w)};
+                update(kf, vf, valid);
+            }
         }
     }
+    if constexpr (MM) { if (with_cur && wave == 0) load_qr(); }   // (the row-wise update below needs the queries per lane)
     if (with_cur && wave == 0) {   // this step's own key/value (uniform branch per wave)
         float kf[8], vf[8];
         const float* kc = xin + G * HD + sub * 8;

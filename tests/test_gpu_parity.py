@@ -390,6 +390,8 @@ def test_eight_query_heads_per_kv_head_small_model_all_formats():
     and int4 matrix-core projections at batch 4 and 3."""
     S = synth.TINY.replace(name="g8", n_layers=2, d_model=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, d_ffn=1536, vocab=1500)
     _run_teacher_forced(S, 0x25052276b, synth.WDTYPE_BF16, batch=8, T0=70, steps=2)
+    # (wide pass, ragged: its attention takes the scores of 16 rows at a time from the matrix cores)
+    _run_teacher_forced(S, 0x25052276f, synth.WDTYPE_BF16, batch=6, T0=[0, 1, 15, 17, 333, 640], steps=2)
     _run_teacher_forced(S, 0x25052276c, synth.WDTYPE_INT8, batch=4, T0=33, steps=2)
     _run_teacher_forced(S, 0x25052276d, synth.WDTYPE_INT4, batch=3, T0=90, steps=2)
     _run_teacher_forced(S, 0x25052276e, synth.WDTYPE_INT4, batch=1, T0=130, steps=2)
