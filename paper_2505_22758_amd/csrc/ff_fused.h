@@ -187,7 +187,7 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
 #else
             u64* aev = nullptr;
 #endif
-            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, true>(M, KV, pos_lds, batch, l, lds, tag_of(tag_base, l, TAG_QKV), tag_of(tag_base, l, TAG_ATT),
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, 2>(M, KV, pos_lds, batch, l, lds, tag_of(tag_base, l, TAG_QKV), tag_of(tag_base, l, TAG_ATT),
                                                                       sl + l, n_ctas, vote, aev, M.wimg_a);
             if (!ok) return false;
             sync.arrive(ebase + 4u * (u32)l + 1u);
@@ -236,6 +236,9 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
     return true;
 }
 
+#ifndef FF_ATTN_MODE
+#define FF_ATTN_MODE 0   // attention form of the passes of up to four sequences (see attn_item)
+#endif
 template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
@@ -349,7 +352,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_ATT_START, lane);
             u64* aev = dbg_stage_slots(M, dbg_phases, ncta, D.layer, 4);
             if (aev && threadIdx.x == 0) { as_global(aev)[0] = wall_clock64(); as_global(aev)[4] = 0; as_global(aev)[5] = 0; }
-            const bool ok = attention_phase_tagged<kFusedWaves, HD, G>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, FF_ATTN_MODE>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
                                                                 tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, n_ctas, vote, aev);
             if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
             if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_ATT_END, lane);

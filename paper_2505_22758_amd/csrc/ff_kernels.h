@@ -58,7 +58,7 @@ __device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const 
 // kernel down to what the model at hand needs.  `pos` points to the positions staged in LDS and
 // ncta is the grid size: both are read often, and fetching them from global memory here would make
 // the wave wait for every load it has in flight, weight tiles included.
-template <int NW, int HD, int G, bool WIDE = false>
+template <int NW, int HD, int G, int MODE = 0>
 __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
                                                        uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, const UDiv& nc, WgVote& vote, u64* ev = nullptr,
                                                        uint8_t* merged_img = nullptr) {
@@ -79,7 +79,7 @@ __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const 
             const int j = (int)((u32)it / (u32)ns), s = it - j * ns;
             const int t0 = (int)((u32)T * (u32)s / (u32)ns), t1 = (int)((u32)T * (u32)(s + 1) / (u32)ns);   // T * 64 < 2^32
             bool cur = s == ns - 1;
-            ok = attn_item<HD, G, NW, TaggedAttnIO, WIDE>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds, ev) && ok;
+            ok = attn_item<HD, G, NW, TaggedAttnIO, MODE>(M, KV, xio, layer, b, j, t0, t1, cur, s, lds, ev) && ok;
             if (cur) ok = attn_merge_tagged<HD, G, NT>(M, b, j, ns, out_tag, out_cnt, (float*)lds, vote, ev, merged_img) && ok;
         }
         base = (int)nc.mod((u32)base + (u32)nitems);

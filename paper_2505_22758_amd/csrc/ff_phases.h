@@ -625,10 +625,11 @@ struct TaggedAttnIO {
 // last row they repeat that row), like the refills of the weight ring: where code paths that issued
 // different numbers of loads meet, the compiler waits for all.
 typedef __bf16 attn_bf8 __attribute__((ext_vector_type(8)));
-template <int HD, int G, int NW, class XIO, bool WIDE = false>
+template <int HD, int G, int NW, class XIO, int MODE = 0>   // 0: row-wise; 1: MM, one batch of loads in flight; 2: MM, two
 __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, const XIO& xio, int layer, int b, int j, int t0, int t1, bool with_cur,
                           int split, uint8_t* lds, u64* ev = nullptr) {
-    constexpr bool MM = WIDE && HD == 128 && G <= 8;
+    constexpr bool MM = MODE > 0 && HD == 128 && G <= 8;
+    constexpr bool PIPE = MODE == 2;
     constexpr int LPR = HD / 8;        // lanes per cache row
     constexpr int RPW = 64 / LPR;      // rows per wave load
     constexpr int NS = NW * RPW;       // partial states per workgroup
@@ -692,9 +693,9 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
     };
     int tb0 = t0 + wave * RPW;
     if constexpr (MM) {
-        if (t0 < t1) {   // (uniform; an empty range has no row to clamp to)
+        if (PIPE ? t0 < t1 : tb0 < t1) {   // (an empty range has no row to clamp to)
             issue_mm(0, tb0);
-            issue_mm(1, tb0 + kStride);
+            if (PIPE) issue_mm(1, tb0 + kStride);
         }
     } else {
         if (tb0 < t1) issue(tb0);
@@ -766,6 +767,12 @@ __device__ __forceinline__ bool attn_item(const DevModel& M, const DevKV& KV, co
                 m[g] = mn;
             }
         };
+        if constexpr (!PIPE) {
+            for (bool first = true; tb0 < t1; tb0 += kStride, first = false) {
+                if (!first) issue_mm(0, tb0);
+                consume(0, tb0);
+            }
+        } else
         for (; tb0 < t1; tb0 += 2 * kStride) {
             consume(0, tb0);
             __builtin_amdgcn_sched_barrier(0);
