@@ -24,24 +24,54 @@ constexpr int kDenseSegUnits = kWideSegUnits;   // 16-byte units (8 columns) of 
 static_assert(kDenseSegUnits == 256 && kDenseSegUnits * kMaxBatchWide * 2 * 16 == kLdsActBytes, "a wide pass's K segment is 2048 columns: 64 units per wave, two stages of 32");
 typedef __bf16 mfma_bf8 __attribute__((ext_vector_type(8)));
 
+// K-split projections (output and down projection: few rows per workgroup, so the copies of the
+// input images weigh as much as the weights): workgroups 2 p and 2 p + 1 form a pair that multiplies the
+// rows of BOTH, each over its half of the K segments, and hands the partner the partial sums of the
+// partner's rows (dense_run_wide); every workgroup then reads half the image bytes for the same weight bytes.
+constexpr int kWideXchFloats = (kDenseMaxTiles / 2) * 16 * kMaxBatchWide;   // partial sums one workgroup can receive: its own rows (at most half the tiles) x 16 sequences
 struct DenseStream {
     const uint8_t* w; size_t rowb;
-    int r0, r1, T;            // rows [r0, r1) of this workgroup; tiles
+    int r0, r1, T;            // rows [r0, r1) this workgroup multiplies (with a K split: the pair's); tiles
+    int own0, own1;           // rows it finishes (= [r0, r1) without a K split)
+    int seg0, seg1;           // K segments [seg0, seg1) it multiplies
     int total_units;          // K / 8
     int j0, nunits, nup;      // this K segment: first unit, units, padded units (= kDenseSegUnits)
-    bool last, more;          // last segment of the projection / another one follows
-    __device__ __forceinline__ static DenseStream make(const PMat& M, int seg, const UDiv& n_ctas) {
+    bool last, more;          // last segment of this workgroup's share / another one follows
+    bool split;
+    // Is this projection split between the workgroups of a pair?  Even grid, the pair's tiles fit, and an even
+    // number of at least four K segments: with fewer (or unequal halves) the hand-over between the partners costs
+    // more than the copies it saves (8B shape: output projection 2 segments, down projection 7 -- slower split;
+    // 70B shape: 4 and 14 -- 2.5 % faster per step).
+    __device__ __forceinline__ static bool can_split(const PMat& M, const UDiv& n_ctas) {
+        const u32 ngroups = (u32)(M.n + 3) / 4;
+        const int rows_max = 4 * (int)n_ctas.div(ngroups + n_ctas.n - 1u);
+        const int nseg = (M.k / 8 + kDenseSegUnits - 1) / kDenseSegUnits;
+        return (n_ctas.n & 1u) == 0 && nseg >= 4 && (nseg & 1) == 0 && 2 * rows_max <= kDenseMaxTiles * 16;
+    }
+    __device__ __forceinline__ static DenseStream make(const PMat& M, int seg, const UDiv& n_ctas, bool split = false) {
         DenseStream D;
         D.w = M.w; D.rowb = (size_t)M.k * 2;
         const u32 ngroups = (u32)(M.n + 3) / 4;
-        D.r0 = 4 * (int)n_ctas.div(ngroups * blockIdx.x);
-        D.r1 = min(4 * (int)n_ctas.div(ngroups * (blockIdx.x + 1)), M.n);
-        D.T = (D.r1 - D.r0 + 15) >> 4;
+        D.own0 = 4 * (int)n_ctas.div(ngroups * blockIdx.x);
+        D.own1 = min(4 * (int)n_ctas.div(ngroups * (blockIdx.x + 1)), M.n);
         D.total_units = M.k / 8;
+        const int nseg = (D.total_units + kDenseSegUnits - 1) / kDenseSegUnits;
+        D.split = split;
+        if (split) {
+            const u32 p = blockIdx.x & ~1u;
+            D.r0 = 4 * (int)n_ctas.div(ngroups * p);
+            D.r1 = min(4 * (int)n_ctas.div(ngroups * (p + 2)), M.n);
+            const int half = (nseg + 1) / 2;
+            D.seg0 = (blockIdx.x & 1) ? half : 0;
+            D.seg1 = (blockIdx.x & 1) ? nseg : half;
+        } else {
+            D.r0 = D.own0; D.r1 = D.own1; D.seg0 = 0; D.seg1 = nseg;
+        }
+        D.T = (D.r1 - D.r0 + 15) >> 4;
         D.j0 = seg * kDenseSegUnits;
         D.nunits = min(kDenseSegUnits, D.total_units - D.j0);
         D.nup = kDenseSegUnits;
-        D.more = D.j0 + kDenseSegUnits < D.total_units;
+        D.more = seg + 1 < D.seg1;
         D.last = !D.more;
         return D;
     }

@@ -99,7 +99,7 @@ struct DevModel {
     // wide pass (ff_wide.h): residual rows [16][d] (each row touched by its owning workgroup only), images of
     // the consumers' LDS layout for the d-wide inputs, the merged attention output and the SwiGLU output, the
     // workgroups' partial sums of squares [workgroups][16], one epoch word per workgroup
-    float* wxres;  uint8_t* wimg_x;  uint8_t* wimg_a;  uint8_t* wimg_h;  float* wsspart;  u32* wflag;
+    float* wxres;  uint8_t* wimg_x;  uint8_t* wimg_a;  uint8_t* wimg_h;  float* wsspart;  u32* wflag;  float* wxch;  u32* wpflag;
     u32* stepctr;    // [0] fused launches executed so far on these buffers (skipped steps do not count); [1] sequences the last one served
     u32x2* tpart_m;  u32x2* tpart_l;  u32x2* tpart_o;
     int* status;

@@ -146,6 +146,9 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
 // partial sums of squares) are prepared by k_wide_embed, launched in front of the fused kernel.
 // n_lm: LM-head phases (row blocks of at most kDenseMaxTiles tiles per workgroup), 0 = not here.
 // Returns false after a time-out (status is set).
+#ifndef FF_WIDE_SPLIT
+#define FF_WIDE_SPLIT 1   // K split of the wide pass's output and down projections (0: every workgroup multiplies its own rows over all of K)
+#endif
 template <int HD, int G>
 __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, const int* pos_lds, const float2* rope_lds, float* logits, int batch,
                                           int n_lm, int ncta, uint8_t* lds, WgVote& vote, u32 steps_done, u32 sl, u32 tag_base) {
@@ -155,7 +158,7 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
     float4* xs = (float4*)lds;
     float* rs = (float*)(lds + kLdsActBytes);   // aux region: 1/rms per sequence, scratch of the reduction, verdict word
     float* part = rs + 16;
-    const WideSync sync{M.wflag, ncta, (lds_u32*)(part + 256)};
+    const WideSync sync{M.wflag, ncta, (lds_u32*)(part + 256), M.wpflag};
     float* ssl = (float*)(lds + 64 * 1024);     // behind the partial tiles of the reduction (at most 56 KB)
     const u32 ebase = steps_done * (u32)(4 * M.L);   // epochs of this step: ebase + 4 l + {1: attention, 2: O, 3: gate/up, 4: down}
     const int n_phases = 4 * M.L + n_lm;
@@ -173,7 +176,11 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         }
         const int l = D.layer;
         const FF_CONST PLayer* Lp = as_const(M.layers) + min(l, M.L - 1);
-        DenseStream DS = DenseStream::make(D.W, 0, n_ctas);
+        // output and down projection: K split between the workgroups of a pair where the shapes allow (see DenseStream)
+        const bool split = FF_WIDE_SPLIT && (D.kind == PH_O || D.kind == PH_DOWN) && DenseStream::can_split(D.W, n_ctas);
+        DenseStream DS = DenseStream::make(D.W, 0, n_ctas, split);
+        const int seg0 = DS.seg0, seg1 = DS.seg1;
+        DS = DenseStream::make(D.W, seg0, n_ctas, split);
         dense_prefetch(DS, ring, wave, lane);
         u32 wait_epoch = 0;
         const uint8_t* img = M.wimg_x;
@@ -181,19 +188,10 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         if (D.kind == PH_QKV) wait_epoch = l > 0 ? ebase + 4u * (u32)l : 0u;
         else if (D.kind == PH_O) {
             __syncthreads();   // the previous projection's epilogue has read its sums out of LDS
-#ifdef FF_WSTATS
-            u64* aev = blockIdx.x == FF_WSTATS ? (u64*)(M.status + 48) : nullptr;
-            if (aev && threadIdx.x == 0) as_global(aev)[0] = wall_clock64();
-#else
-            u64* aev = nullptr;
-#endif
             const bool ok = attention_phase_tagged<kFusedWaves, HD, G, 2>(M, KV, pos_lds, batch, l, lds, tag_of(tag_base, l, TAG_QKV), tag_of(tag_base, l, TAG_ATT),
-                                                                      sl + l, n_ctas, vote, aev, M.wimg_a);
+                                                                      sl + l, n_ctas, vote, nullptr, M.wimg_a);
             if (!ok) return false;
             sync.arrive(ebase + 4u * (u32)l + 1u);
-#ifdef FF_WSTATS
-            if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
-#endif
             wait_epoch = ebase + 4u * (u32)l + 1u; img = M.wimg_a; normed = false;
         } else if (D.kind == PH_GU) wait_epoch = ebase + 4u * (u32)l + 2u;
         else if (D.kind == PH_DOWN) { wait_epoch = ebase + 4u * (u32)l + 3u; img = M.wimg_h; normed = false; }
@@ -207,24 +205,31 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         if (normed) wide_rms(M.wsspart, ncta, D.W.k, M.eps, part, rs, threadIdx.x);
 #pragma unroll
         for (int t = 0; t < kDenseMaxTiles; t++) acc[t] = mfma_f4{0.f, 0.f, 0.f, 0.f};
-        const int nseg = (D.W.k / 8 + kDenseSegUnits - 1) / kDenseSegUnits;
-        for (int seg = 0; seg < nseg; seg++) {
-            DS = DenseStream::make(D.W, seg, n_ctas);
+        bool run_ok = true;
+        for (int seg = seg0; seg < seg1; seg++) {
+            DS = DenseStream::make(D.W, seg, n_ctas, split);
             if (DS.T > 0) wide_copy_quarter(img + (size_t)seg * kWideSegBytes, lds, wave, lane, batch);   // (private to the wave: no barrier)
             const float* rsp = normed ? rs : nullptr;
             if (D.kind == PH_GU) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiSwiGLU{M.wimg_h, M.gu}, rsp);
-            else if (D.kind == PH_O) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiResidual{M.wxres, M.d, Lp->g2, M.wimg_x, ssl, DS.r0}, rsp);
+            else if (D.kind == PH_O)
+                run_ok = dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiResidual{M.wxres, M.d, Lp->g2, M.wimg_x, ssl, DS.own0}, rsp,
+                                        M.wxch, &sync, ebase + 4u * (u32)l + 2u);
             else if (D.kind == PH_DOWN)
-                dense_run_wide(DS, ring, xs, acc, batch, wave, lane,
-                               WideEpiResidual{M.wxres, M.d, l + 1 < M.L ? (as_const(M.layers) + l + 1)->g1 : M.gf, M.wimg_x, ssl, DS.r0}, rsp);
+                run_ok = dense_run_wide(DS, ring, xs, acc, batch, wave, lane,
+                                        WideEpiResidual{M.wxres, M.d, l + 1 < M.L ? (as_const(M.layers) + l + 1)->g1 : M.gf, M.wimg_x, ssl, DS.own0}, rsp,
+                                        M.wxch, &sync, ebase + 4u * (u32)l + 4u);
             else dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiPairs<EpiFused>{epf}, rsp);
+        }
+        if (!run_ok) {   // (uniform) the partner of a K-split projection did not deliver
+            if (threadIdx.x == 0) atomicCAS(M.status, 0, -58 - 10 * ph);
+            return false;
         }
         if (D.kind == PH_O || D.kind == PH_DOWN) {
             // this workgroup's share of every sequence's sum of squares of the new residual rows
             __syncthreads();
             if (threadIdx.x < kMaxBatchWide) {
                 float t = 0.f;
-                const int ngrp = (DS.r1 - DS.r0) >> 2;
+                const int ngrp = (DS.own1 - DS.own0) >> 2;
                 if ((int)threadIdx.x < batch) for (int q = 0; q < ngrp; q++) t += ssl[q * kMaxBatchWide + threadIdx.x];
                 xst(M.wsspart + (size_t)blockIdx.x * kMaxBatchWide + threadIdx.x, t);
             }

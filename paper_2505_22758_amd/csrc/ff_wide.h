@@ -40,6 +40,28 @@ struct WideSync {
     u32* flags;       // [workgroups] last epoch each workgroup has published
     int ncta;
     lds_u32* ok_slot; // LDS word for the verdict
+    u32* pflags;      // [workgroups] last epoch whose partial sums each workgroup has handed to its partner (K-split projections)
+    // This workgroup's partial sums for its partner are stored: publish.
+    __device__ __forceinline__ void arrive_pair(u32 epoch) const {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0) xst_u32(pflags + blockIdx.x, epoch);
+    }
+    // The partner has published `epoch`.  Its sums are read with coherent loads, so no fence here.  False (uniformly) on a time-out.
+    __device__ __forceinline__ bool wait_pair(u32 epoch, int wave, int lane) const {
+        if (wave == 0) {
+            bool ok = false;
+            for (int spins = 0; spins < kSpinLimit && !ok; spins++) {
+                ok = (int)(xld_u32(pflags + (blockIdx.x ^ 1u)) - epoch) >= 0;
+                if (!ok) __builtin_amdgcn_s_sleep(2);
+            }
+            if (lane == 0) *ok_slot = ok ? 1u : 0u;
+        }
+        __syncthreads();
+        const bool ok = *ok_slot != 0u;
+        __syncthreads();
+        return ok;
+    }
     // All of this workgroup's exchange stores of the phase are made: publish the epoch.
     __device__ __forceinline__ void arrive(u32 epoch) const {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's write-through stores have completed
@@ -172,9 +194,14 @@ struct WideEpiResidual {   // output / down projection: residual rows of this wo
 
 // One K segment of the workgroup's tiles like dense_run, with the per-sequence 1/rms factors in
 // LDS (rs, or null) and an epilogue on groups of four rows (see the epilogue structs above).
+// With a K split (D.split) the finished tiles cover the rows of both workgroups of the pair over this
+// workgroup's K segments: the sums of the partner's rows go to the partner (xch: [workgroup][group of
+// four rows][sequence][4], write-through stores, then the pair flag), the sums of the own rows wait
+// for the partner's share and then take the epilogue.  Returns false after a time-out.
 template <class Epi>
-__device__ __forceinline__ void dense_run_wide(const DenseStream& D, Stage<W_BF16> (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
-                                               int batch, int wave, int lane, const Epi& epi, const float* rs_lds) {
+__device__ __forceinline__ bool dense_run_wide(const DenseStream& D, Stage<W_BF16> (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
+                                               int batch, int wave, int lane, const Epi& epi, const float* rs_lds,
+                                               float* xch = nullptr, const WideSync* sync = nullptr, u32 pepoch = 0) {
     const int n = lane & 15, g = lane >> 4;
     const u32x4* xh = (const u32x4*)xs + (size_t)(2 * n) * kDenseSegUnits;
     const u32x4* xl = xh + kDenseSegUnits;
@@ -213,7 +240,7 @@ __device__ __forceinline__ void dense_run_wide(const DenseStream& D, Stage<W_BF1
             }
         }
     }
-    if (!D.last) return;
+    if (!D.last) return true;
     // ---- the four waves' partial tiles meet in LDS (the staged segment is no longer needed) ----
     __syncthreads();
     float* rb = (float*)xs;   // [T][wave][4][64]
@@ -226,16 +253,53 @@ __device__ __forceinline__ void dense_run_wide(const DenseStream& D, Stage<W_BF1
     }
     __syncthreads();
     const float rs = rs_lds ? rs_lds[n] : 1.f;
-    for (int t = wave; t < D.T; t += kWaves) {
-        float c[4];
+    auto tile_sums = [&](int t, float (&c)[4]) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             const float* p = rb + ((t * kWaves) * 4 + i) * 64 + lane;
             c[i] = ((p[0] + p[4 * 64]) + (p[8 * 64] + p[12 * 64])) * rs;
         }
-        const int row = D.r0 + 16 * t + 4 * g;
-        if (n < batch && row < D.r1) epi(row, n, c, min(4, D.r1 - row));
+    };
+    if (!D.split) {
+        for (int t = wave; t < D.T; t += kWaves) {
+            float c[4];
+            tile_sums(t, c);
+            const int row = D.r0 + 16 * t + 4 * g;
+            if (n < batch && row < D.r1) epi(row, n, c, min(4, D.r1 - row));
+        }
+        return true;
     }
+    // ---- K split: the partner's rows first, so that it can go on ----
+    const bool second = (blockIdx.x & 1u) != 0;
+    const int p0 = second ? D.r0 : D.own1, p1 = second ? D.own0 : D.r1;   // the partner's rows
+    float* xout = xch + (size_t)(blockIdx.x ^ 1u) * kWideXchFloats;
+    for (int t = wave; t < D.T; t += kWaves) {
+        const int row = D.r0 + 16 * t + 4 * g;
+        if (n < batch && row >= p0 && row < p1) {
+            float c[4];
+            tile_sums(t, c);
+            float* q = xout + ((size_t)((row - p0) >> 2) * kMaxBatchWide + n) * 4;
+            xst2(q, c[0], c[1]);
+            xst2(q + 2, c[2], c[3]);
+        }
+    }
+    sync->arrive_pair(pepoch);
+    if (!sync->wait_pair(pepoch, wave, lane)) return false;
+    const float* xin = xch + (size_t)blockIdx.x * kWideXchFloats;
+    for (int t = wave; t < D.T; t += kWaves) {
+        const int row = D.r0 + 16 * t + 4 * g;
+        if (n < batch && row >= D.own0 && row < D.own1) {
+            float c[4];
+            tile_sums(t, c);
+            const float* q = xin + ((size_t)((row - D.own0) >> 2) * kMaxBatchWide + n) * 4;
+            const u64 a = __hip_atomic_load(as_global((const u64*)q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const u64 b = __hip_atomic_load(as_global((const u64*)(q + 2)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c[0] += __uint_as_float((u32)a); c[1] += __uint_as_float((u32)(a >> 32));
+            c[2] += __uint_as_float((u32)b); c[3] += __uint_as_float((u32)(b >> 32));
+            epi(row, n, c, min(4, D.own1 - row));
+        }
+    }
+    return true;
 }
 
 }  // namespace ff

@@ -55,7 +55,7 @@ struct Plan {
     // scratch
     size_t x, xn, q, kvcur, attn_o, h, y, part_m, part_l, part_o, status, scratch_bytes;
     size_t cx, cx2, cdelta, tq, tkvcur, cattn_o, ch, stepctr, tpart_m, tpart_l, tpart_o;
-    size_t wxres, wimg_x, wimg_a, wimg_h, wsspart, wflag;   // wide pass only (zero bytes otherwise)
+    size_t wxres, wimg_x, wimg_a, wimg_h, wsspart, wflag, wxch, wpflag;   // wide pass only (zero bytes otherwise)
 };
 
 size_t mat_w_bytes(int n, int k, int wd) { return wd == W_BF16 ? (size_t)n * k * 2 : wd == W_INT8 ? (size_t)n * k : (size_t)n * k / 2; }
@@ -176,6 +176,8 @@ Plan make_plan(const ff_config& c) {
     P.wimg_h = take(wide ? wide_img_bytes(c.d_ffn) : 0);
     P.wsspart = take(wide ? (size_t)kGridCtas * kMaxBatchWide * 4 : 0);
     P.wflag = take(wide ? (size_t)kGridCtas * 4 : 0);
+    P.wxch = take(wide ? (size_t)kGridCtas * kWideXchFloats * 4 : 0);   // partial sums handed to the partner workgroup (K-split projections)
+    P.wpflag = take(wide ? (size_t)kGridCtas * 4 : 0);
     P.status = take(256);
     P.scratch_bytes = s;
     return P;
@@ -365,7 +367,7 @@ int ff_model_create(const ff_config* cfg, void* packed_dev, size_t packed_bytes,
     D.cx = (u32*)(s + P.cx); D.cx2 = (u32*)(s + P.cx2); D.cdelta = (u32*)(s + P.cdelta); D.tq = (u32x2*)(s + P.tq);
     D.tkvcur = (u32x2*)(s + P.tkvcur); D.cattn_o = (u32*)(s + P.cattn_o); D.ch = (u32*)(s + P.ch);
     D.wxres = (float*)(s + P.wxres); D.wimg_x = s + P.wimg_x; D.wimg_a = s + P.wimg_a; D.wimg_h = s + P.wimg_h;
-    D.wsspart = (float*)(s + P.wsspart); D.wflag = (u32*)(s + P.wflag);
+    D.wsspart = (float*)(s + P.wsspart); D.wflag = (u32*)(s + P.wflag); D.wxch = (float*)(s + P.wxch); D.wpflag = (u32*)(s + P.wpflag);
     D.stepctr = (u32*)(s + P.stepctr);
     D.tpart_m = (u32x2*)(s + P.tpart_m); D.tpart_l = (u32x2*)(s + P.tpart_l); D.tpart_o = (u32x2*)(s + P.tpart_o);
     D.dbg = nullptr;
@@ -776,7 +778,7 @@ int ff_decode_step_static(ff_model* m, const int32_t* tokens_dev, const int32_t*
     D.cx = (u32*)(s + P.cx); D.cx2 = (u32*)(s + P.cx2); D.cdelta = (u32*)(s + P.cdelta); D.tq = (u32x2*)(s + P.tq);
     D.tkvcur = (u32x2*)(s + P.tkvcur); D.cattn_o = (u32*)(s + P.cattn_o); D.ch = (u32*)(s + P.ch);
     D.wxres = (float*)(s + P.wxres); D.wimg_x = s + P.wimg_x; D.wimg_a = s + P.wimg_a; D.wimg_h = s + P.wimg_h;
-    D.wsspart = (float*)(s + P.wsspart); D.wflag = (u32*)(s + P.wflag);
+    D.wsspart = (float*)(s + P.wsspart); D.wflag = (u32*)(s + P.wflag); D.wxch = (float*)(s + P.wxch); D.wpflag = (u32*)(s + P.wpflag);
     D.stepctr = (u32*)(s + P.stepctr);
     D.tpart_m = (u32x2*)(s + P.tpart_m); D.tpart_l = (u32x2*)(s + P.tpart_l); D.tpart_o = (u32x2*)(s + P.tpart_o);
     // The array keeps whatever the last call (of any model) left: everything this step's kernels

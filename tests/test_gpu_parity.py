@@ -627,14 +627,27 @@ def test_fused_step_replayed_from_a_hip_graph():
         dec.close()
 
 
+KSPLIT = synth.TINY.replace(name="ksplit", n_layers=2, d_model=1024, n_q_heads=64, n_kv_heads=8, head_dim=128, d_ffn=8192, vocab=2000)
+
+
+def test_wide_pass_output_and_down_projection_split_along_k():
+    """Wide pass on a model whose output and down projections have four K segments each (8192 input
+    columns): the workgroups of a pair multiply the rows of both over half of the segments and hand each
+    other the partial sums of the partner's rows.  Eight query heads per KV head, ragged lengths (the
+    matrix-core attention form), a full pass of 16 and a pass of 7, two layers."""
+    _run_teacher_forced(KSPLIT, 0x2505227a0, synth.WDTYPE_BF16, batch=16, T0=[40, 0, 1, 130, 64, 63, 65, 9, 300, 17, 128, 5, 77, 256, 2, 33], steps=2)
+    _run_teacher_forced(KSPLIT, 0x2505227a1, synth.WDTYPE_BF16, batch=7, T0=[7, 70, 0, 129, 31, 64, 200], steps=2)
+
+
 def test_a_silent_workgroup_ends_in_a_timeout_not_a_hang():
     """ff_debug_mute_workgroup makes one workgroup leave without publishing: every workgroup that
     needs its output gives up after its own bounded wait, the launch ends normally and ff_status
     reports FF_ERR_TIMEOUT.  A model created again on the same buffers then works."""
     import time
     from paper_2505_22758_amd import binding
-    S, seed, T0 = synth.TINY, 99, 20
-    for B in (1, 2, 6):   # 6: wide pass (waits on epochs instead of per-word counters)
+    seed, T0 = 99, 20
+    # 6: wide pass (waits on epochs instead of per-word counters); KSPLIT: the muted workgroup's partner waits for its partial sums
+    for S, B in ((synth.TINY, 1), (synth.TINY, 2), (synth.TINY, 6), (KSPLIT, 6)):
         dec, caches = helpers.hip_side(S, seed, synth.WDTYPE_BF16, B, T0, max_ctx=T0 + 4)
         tok = torch.arange(3, 3 + B, dtype=torch.int32, device="cuda:0")
         pos = torch.full((B,), T0, dtype=torch.int32, device="cuda:0")
