@@ -29,13 +29,18 @@ typedef __bf16 mfma_bf8 __attribute__((ext_vector_type(8)));
 // rows of BOTH, each over its half of the K segments, and hands the partner the partial sums of the
 // partner's rows (dense_run_wide); every workgroup then reads half the image bytes for the same weight bytes.
 constexpr int kWideXchFloats = (kDenseMaxTiles / 2) * 16 * kMaxBatchWide;   // partial sums one workgroup can receive: its own rows (at most half the tiles) x 16 sequences
+// Weight formats of the wide pass: bf16 (a 16-byte unit = 8 columns, 256 units per K segment) and
+// int8 per-channel (16 columns per unit, 128 units per segment; the codes are converted to bf16 --
+// exact -- in registers, the row scales applied to the finished sums).
+template <int WD> constexpr int kDenseSegW = WD == W_BF16 ? kDenseSegUnits : kDenseSegUnits / 2;   // weight units per K segment
 struct DenseStream {
     const uint8_t* w; size_t rowb;
+    const f16_t* s;           // int8: row scales
     int r0, r1, T;            // rows [r0, r1) this workgroup multiplies (with a K split: the pair's); tiles
     int own0, own1;           // rows it finishes (= [r0, r1) without a K split)
     int seg0, seg1;           // K segments [seg0, seg1) it multiplies
-    int total_units;          // K / 8
-    int j0, nunits, nup;      // this K segment: first unit, units, padded units (= kDenseSegUnits)
+    int total_units;          // weight units per row (K / 8 or K / 16)
+    int j0, nunits, nup;      // this K segment: first weight unit, units, padded units
     bool last, more;          // last segment of this workgroup's share / another one follows
     bool split;
     // Is this projection split between the workgroups of a pair?  Even grid, the pair's tiles fit, and an even
@@ -48,14 +53,16 @@ struct DenseStream {
         const int nseg = (M.k / 8 + kDenseSegUnits - 1) / kDenseSegUnits;
         return (n_ctas.n & 1u) == 0 && nseg >= 4 && (nseg & 1) == 0 && 2 * rows_max <= kDenseMaxTiles * 16;
     }
+    template <int WD = W_BF16>
     __device__ __forceinline__ static DenseStream make(const PMat& M, int seg, const UDiv& n_ctas, bool split = false) {
+        constexpr int SEGW = kDenseSegW<WD>;
         DenseStream D;
-        D.w = M.w; D.rowb = (size_t)M.k * 2;
+        D.w = M.w; D.s = M.s; D.rowb = WD == W_BF16 ? (size_t)M.k * 2 : (size_t)M.k;
         const u32 ngroups = (u32)(M.n + 3) / 4;
         D.own0 = 4 * (int)n_ctas.div(ngroups * blockIdx.x);
         D.own1 = min(4 * (int)n_ctas.div(ngroups * (blockIdx.x + 1)), M.n);
-        D.total_units = M.k / 8;
-        const int nseg = (D.total_units + kDenseSegUnits - 1) / kDenseSegUnits;
+        D.total_units = M.k / (WD == W_BF16 ? 8 : 16);
+        const int nseg = (D.total_units + SEGW - 1) / SEGW;
         D.split = split;
         if (split) {
             const u32 p = blockIdx.x & ~1u;
@@ -68,9 +75,9 @@ struct DenseStream {
             D.r0 = D.own0; D.r1 = D.own1; D.seg0 = 0; D.seg1 = nseg;
         }
         D.T = (D.r1 - D.r0 + 15) >> 4;
-        D.j0 = seg * kDenseSegUnits;
-        D.nunits = min(kDenseSegUnits, D.total_units - D.j0);
-        D.nup = kDenseSegUnits;
+        D.j0 = seg * SEGW;
+        D.nunits = min(SEGW, D.total_units - D.j0);
+        D.nup = SEGW;
         D.more = seg + 1 < D.seg1;
         D.last = !D.more;
         return D;
@@ -92,6 +99,39 @@ __device__ __forceinline__ void dense_load(const DenseStream& D, int j0, int nun
     for (int u = 0; u < 8; u++) {
         const int j = min(64 * wave + 32 * h + 4 * u + (lane >> 4), nunits - 1);
         st.w[u >> 2][u & 3] = ldg_stream(real ? rp + (size_t)j * 16 : D.w);
+    }
+}
+
+// int8: a wave's K quarter of a segment is 32 units of 16 columns = ONE stage of eight loads per tile (lane (r, g):
+// unit 32 w + 4 u + g of row r).  The stream of stages then runs segment by segment, tile by tile, and the cursor of
+// the next stage to load is carried from stage to stage.
+struct DenseCursor {
+    int seg, t;
+    __device__ __forceinline__ void advance(int T) {   // (selects, not branches)
+        const int wt = t + 1 >= T ? 1 : 0;
+        t = wt ? 0 : t + 1;
+        seg += wt;
+    }
+};
+__device__ __forceinline__ void dense_load_i8(const DenseStream& D, const DenseCursor& c, Stage<W_INT8>& st, int wave, int lane) {
+    constexpr int SEGW = kDenseSegW<W_INT8>;
+    const bool real = c.seg < D.seg1;   // behind the last stage: eight loads of one address (see dense_load)
+    const int row = min(D.r0 + 16 * c.t + (lane & 15), D.r1 - 1);
+    const uint8_t* rp = D.w + (size_t)row * D.rowb + (size_t)c.seg * (SEGW * 16);
+    const int jmax = D.total_units - c.seg * SEGW - 1;
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+        const int j = min(32 * wave + 4 * u + (lane >> 4), jmax);
+        st.w[u >> 2][u & 3] = ldg_stream(real ? rp + (size_t)j * 16 : D.w);
+    }
+}
+__device__ __forceinline__ void dense_prefetch_i8(const DenseStream& D, DenseCursor& c, Stage<W_INT8> (&ring)[2], int wave, int lane) {
+    c = DenseCursor{D.seg0, 0};
+    if (D.T > 0) {
+        dense_load_i8(D, c, ring[0], wave, lane);
+        c.advance(D.T);
+        dense_load_i8(D, c, ring[1], wave, lane);
+        c.advance(D.T);
     }
 }
 

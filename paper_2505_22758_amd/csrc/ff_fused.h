@@ -149,7 +149,7 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
 #ifndef FF_WIDE_SPLIT
 #define FF_WIDE_SPLIT 1   // K split of the wide pass's output and down projections (0: every workgroup multiplies its own rows over all of K)
 #endif
-template <int HD, int G>
+template <int WD, int HD, int G>
 __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, const int* pos_lds, const float2* rope_lds, float* logits, int batch,
                                           int n_lm, int ncta, uint8_t* lds, WgVote& vote, u32 steps_done, u32 sl, u32 tag_base) {
     const int lane = threadIdx.x & 63;
@@ -163,7 +163,8 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
     const u32 ebase = steps_done * (u32)(4 * M.L);   // epochs of this step: ebase + 4 l + {1: attention, 2: O, 3: gate/up, 4: down}
     const int n_phases = 4 * M.L + n_lm;
     mfma_f4 acc[kDenseMaxTiles];
-    Stage<W_BF16> ring[2];
+    Stage<WD> ring[2];
+    DenseCursor cur{0, 0};   // int8: next stage to load
     for (int ph = 0; ph < n_phases; ph++) {
         const int lm_block = max(ph - 4 * M.L, 0);
         PhaseDesc D = phase_desc(M, nullptr, tag_base, sl, ph - lm_block, 1, phase_state(M, ph - lm_block), true);
@@ -171,6 +172,7 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         if (D.kind == PH_LM) {
             const int block_rows = kDenseMaxTiles * 16 * ncta, row0 = lm_block * block_rows;
             D.W.w += (size_t)row0 * D.W.row_bytes();
+            if constexpr (WD == W_INT8) D.W.s += row0;   // row scales of the block
             D.W.n = min(block_rows, D.W.n - row0);
             epf.pair0 = row0 >> 1;
         }
@@ -178,10 +180,11 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         const FF_CONST PLayer* Lp = as_const(M.layers) + min(l, M.L - 1);
         // output and down projection: K split between the workgroups of a pair where the shapes allow (see DenseStream)
         const bool split = FF_WIDE_SPLIT && (D.kind == PH_O || D.kind == PH_DOWN) && DenseStream::can_split(D.W, n_ctas);
-        DenseStream DS = DenseStream::make(D.W, 0, n_ctas, split);
+        DenseStream DS = DenseStream::make<WD>(D.W, 0, n_ctas, split);
         const int seg0 = DS.seg0, seg1 = DS.seg1;
-        DS = DenseStream::make(D.W, seg0, n_ctas, split);
-        dense_prefetch(DS, ring, wave, lane);
+        DS = DenseStream::make<WD>(D.W, seg0, n_ctas, split);
+        if constexpr (WD == W_INT8) dense_prefetch_i8(DS, cur, ring, wave, lane);
+        else dense_prefetch(DS, ring, wave, lane);
         u32 wait_epoch = 0;
         const uint8_t* img = M.wimg_x;
         bool normed = true;
@@ -207,18 +210,19 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         for (int t = 0; t < kDenseMaxTiles; t++) acc[t] = mfma_f4{0.f, 0.f, 0.f, 0.f};
         bool run_ok = true;
         for (int seg = seg0; seg < seg1; seg++) {
-            DS = DenseStream::make(D.W, seg, n_ctas, split);
+            DS = DenseStream::make<WD>(D.W, seg, n_ctas, split);
             if (DS.T > 0) wide_copy_quarter(img + (size_t)seg * kWideSegBytes, lds, wave, lane, batch);   // (private to the wave: no barrier)
             const float* rsp = normed ? rs : nullptr;
-            if (D.kind == PH_GU) dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiSwiGLU{M.wimg_h, M.gu}, rsp);
+            const int par = ((seg - seg0) * DS.T) & 1;   // int8: ring slot of the segment's first stage
+            if (D.kind == PH_GU) dense_run_wide<WD>(DS, ring, xs, acc, batch, wave, lane, WideEpiSwiGLU{M.wimg_h, M.gu}, rsp, nullptr, nullptr, 0u, &cur, par);
             else if (D.kind == PH_O)
-                run_ok = dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiResidual{M.wxres, M.d, Lp->g2, M.wimg_x, ssl, DS.own0}, rsp,
-                                        M.wxch, &sync, ebase + 4u * (u32)l + 2u);
+                run_ok = dense_run_wide<WD>(DS, ring, xs, acc, batch, wave, lane, WideEpiResidual{M.wxres, M.d, Lp->g2, M.wimg_x, ssl, DS.own0}, rsp,
+                                            M.wxch, &sync, ebase + 4u * (u32)l + 2u, &cur, par);
             else if (D.kind == PH_DOWN)
-                run_ok = dense_run_wide(DS, ring, xs, acc, batch, wave, lane,
-                                        WideEpiResidual{M.wxres, M.d, l + 1 < M.L ? (as_const(M.layers) + l + 1)->g1 : M.gf, M.wimg_x, ssl, DS.own0}, rsp,
-                                        M.wxch, &sync, ebase + 4u * (u32)l + 4u);
-            else dense_run_wide(DS, ring, xs, acc, batch, wave, lane, WideEpiPairs<EpiFused>{epf}, rsp);
+                run_ok = dense_run_wide<WD>(DS, ring, xs, acc, batch, wave, lane,
+                                            WideEpiResidual{M.wxres, M.d, l + 1 < M.L ? (as_const(M.layers) + l + 1)->g1 : M.gf, M.wimg_x, ssl, DS.own0}, rsp,
+                                            M.wxch, &sync, ebase + 4u * (u32)l + 4u, &cur, par);
+            else dense_run_wide<WD>(DS, ring, xs, acc, batch, wave, lane, WideEpiPairs<EpiFused>{epf}, rsp, nullptr, nullptr, 0u, &cur, par);
         }
         if (!run_ok) {   // (uniform) the partner of a K-split projection did not deliver
             if (threadIdx.x == 0) atomicCAS(M.status, 0, -58 - 10 * ph);
@@ -264,7 +268,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // region that only int4 weights use plus the regular RoPE region behind it, and its positions
     // in the mailbox region (no wave pairs share a row group there).
     constexpr bool kWide = B > kMaxBatchFused;
-    static_assert(!kWide || (WD == W_BF16 && kLdsXsumBytes + kLdsRopeBytes >= B * 64 * (int)sizeof(float2) && kLdsPairBytes >= B * 4 && B <= kMaxBatchWide),
+    static_assert(!kWide || ((WD == W_BF16 || WD == W_INT8) && kLdsXsumBytes + kLdsRopeBytes >= B * 64 * (int)sizeof(float2) && kLdsPairBytes >= B * 4 && B <= kMaxBatchWide),
                   "LDS layout of the wide pass");
     float2* rope_lds = (float2*)(lds + kLdsActBytes + kLdsAuxBytes - (kWide ? kLdsXsumBytes : 0));   // [batch][hd/2]
     for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kFusedThreads) {
@@ -313,7 +317,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     constexpr bool kScalarState = B > 1;
     constexpr bool kQuad = kQuadOf<WD, B>;   // matrix-core GEMV on groups of four rows, split-bf16 staged input
     if constexpr (kWide) {
-        if (!wide_loop<HD, G>(M, KV, pos_lds, rope_lds, logits, batch, lm_in_kernel, ncta, lds, vote, steps_done, sl, tag_base)) return;
+        if (!wide_loop<WD, HD, G>(M, KV, pos_lds, rope_lds, logits, batch, lm_in_kernel, ncta, lds, vote, steps_done, sl, tag_base)) return;
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             xst_u32(M.stepctr + 1, 0u);   // the compact exchange rows were not written: the next narrow pass re-initialises its rows
             xst_u32(M.stepctr, steps_done + 1u);
@@ -452,7 +456,7 @@ inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what)
 }
 template <int WD, int HD, int G>
 inline hipError_t launch_fused_family(const FusedLaunch& a, const char** what) {
-    if constexpr (WD == W_BF16) {   // the wide instance (bf16 only; the host decides, and sizes lm_in_kernel and the buffers for it)
+    if constexpr (WD == W_BF16 || WD == W_INT8) {   // the wide instance (bf16 and int8; the host decides, and sizes lm_in_kernel and the buffers for it)
         if (a.wide) return launch_fused_instance<WD, kMaxBatchWide, HD, G>(a, what);
     } else if (a.wide) {
         *what = "no wide instance for this weight type";

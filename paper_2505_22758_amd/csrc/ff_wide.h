@@ -198,11 +198,66 @@ struct WideEpiResidual {   // output / down projection: residual rows of this wo
 // workgroup's K segments: the sums of the partner's rows go to the partner (xch: [workgroup][group of
 // four rows][sequence][4], write-through stores, then the pair flag), the sums of the own rows wait
 // for the partner's share and then take the epilogue.  Returns false after a time-out.
-template <class Epi>
-__device__ __forceinline__ bool dense_run_wide(const DenseStream& D, Stage<W_BF16> (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
-                                               int batch, int wave, int lane, const Epi& epi, const float* rs_lds,
-                                               float* xch = nullptr, const WideSync* sync = nullptr, u32 pepoch = 0) {
+// int8: the tiles of one K segment, one ring stage each.  The slot of tile t is (t + PAR) mod 2 with PAR = (stages
+// before this segment) mod 2; the tile loop is unrolled, so PAR is static, and the early exit is tested only where
+// a T of parity TP can end: all exits of one form leave the ring in the same state (the compiler keeps track of the
+// loads in flight per code path and assumes the worst where paths meet).  A lane's 16 codes are two k-steps: codes
+// 0..7 against input unit 2 J, codes 8..15 against unit 2 J + 1 (J = 32 w + 4 u + g: the unit's index in the segment).
+template <int PAR, int TP>
+__device__ __forceinline__ void dense_tiles_i8(const DenseStream& D, Stage<W_INT8> (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
+                                               DenseCursor& cur, int wave, int lane) {
     const int n = lane & 15, g = lane >> 4;
+    const u32x4* xh = (const u32x4*)xs + (size_t)(2 * n) * kDenseSegUnits;
+    const u32x4* xl = xh + kDenseSegUnits;
+    auto pack = [](float lo, float hi) { return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u); };   // upper halves of two floats: a signed byte is exact in bf16
+    auto codes = [&](u32 wa, u32 wb) {
+        const u32x4 v{pack((float)(int)(int8_t)wa, (float)(int)(int8_t)(wa >> 8)), pack((float)(int)(int8_t)(wa >> 16), (float)((int)wa >> 24)),
+                      pack((float)(int)(int8_t)wb, (float)(int)(int8_t)(wb >> 8)), pack((float)(int)(int8_t)(wb >> 16), (float)((int)wb >> 24))};
+        return __builtin_bit_cast(mfma_bf8, v);
+    };
+#pragma unroll
+    for (int t = 0; t < kDenseMaxTiles; t++) {
+        if ((t & 1) == TP && t >= D.T) break;
+        Stage<W_INT8>& st = ring[(t + PAR) & 1];
+        mfma_f4& cc = acc[t];
+#pragma unroll
+        for (int u0 = 0; u0 < 8; u0 += 2) {
+            u32x4 bh[4], bl[4];
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int j = 2 * (32 * wave + 4 * (u0 + u) + g);
+                bh[2 * u] = xh[j ^ n]; bl[2 * u] = xl[j ^ n];
+                bh[2 * u + 1] = xh[(j + 1) ^ n]; bl[2 * u + 1] = xl[(j + 1) ^ n];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const u32x4 w = st.w[(u0 + u) >> 2][(u0 + u) & 3];
+                const mfma_bf8 a0 = codes(w.x, w.y), a1 = codes(w.z, w.w);
+                cc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(mfma_bf8, bh[2 * u]), cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(mfma_bf8, bl[2 * u]), cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(mfma_bf8, bh[2 * u + 1]), cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(mfma_bf8, bl[2 * u + 1]), cc, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        dense_load_i8(D, cur, st, wave, lane);   // the stage two further on (always eight loads)
+        cur.advance(D.T);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int WD, class Epi>
+__device__ __forceinline__ bool dense_run_wide(const DenseStream& D, Stage<WD> (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
+                                               int batch, int wave, int lane, const Epi& epi, const float* rs_lds,
+                                               float* xch = nullptr, const WideSync* sync = nullptr, u32 pepoch = 0, DenseCursor* cur = nullptr, int par = 0) {
+    const int n = lane & 15, g = lane >> 4;
+  if constexpr (WD == W_INT8) {
+    if (D.T & 1) {
+        if (par) dense_tiles_i8<1, 1>(D, ring, xs, acc, *cur, wave, lane);
+        else dense_tiles_i8<0, 1>(D, ring, xs, acc, *cur, wave, lane);
+    } else dense_tiles_i8<0, 0>(D, ring, xs, acc, *cur, wave, lane);
+  } else {
     const u32x4* xh = (const u32x4*)xs + (size_t)(2 * n) * kDenseSegUnits;
     const u32x4* xl = xh + kDenseSegUnits;
     auto compute = [&](const Stage<W_BF16>& st, int h, mfma_f4& cc) {
@@ -240,6 +295,7 @@ __device__ __forceinline__ bool dense_run_wide(const DenseStream& D, Stage<W_BF1
             }
         }
     }
+  }
     if (!D.last) return true;
     // ---- the four waves' partial tiles meet in LDS (the staged segment is no longer needed) ----
     __syncthreads();
@@ -258,6 +314,7 @@ __device__ __forceinline__ bool dense_run_wide(const DenseStream& D, Stage<W_BF1
         for (int i = 0; i < 4; i++) {
             const float* p = rb + ((t * kWaves) * 4 + i) * 64 + lane;
             c[i] = ((p[0] + p[4 * 64]) + (p[8 * 64] + p[12 * 64])) * rs;
+            if constexpr (WD == W_INT8) c[i] *= f16_to_f(as_global(D.s)[min(D.r0 + 16 * t + 4 * g + i, D.r1 - 1)]);   // row scale
         }
     };
     if (!D.split) {

@@ -108,7 +108,8 @@ bool wide_fits(const ff_config& c, int n_cta) {
 constexpr int kGridCtas = 256;   // workgroups of the fused kernel's grid on the chip the kernels are built for
 
 // Sequences one pass of the fused kernel serves: up to 4 on the row-partitioned paths (paper Section
-// 5.2), or, with bf16 weights and a model created for more than that, up to 16 in one wide pass.
+// 5.2), or, with bf16 or int8 weights and a model created for more than that, up to 16 in one wide
+// pass.
 // FF_WIDE_MIN (experiments): smallest batch that takes the wide pass (default 5; it measured equal
 // to the former eight-sequence instance at 5 sequences and faster from 6 on, slower than the
 // four-sequence path below that).
@@ -118,7 +119,9 @@ int wide_min_batch() {
     return v > 0 ? v : kMaxBatch + 1;
 }
 int fused_pass_rows(const ff_config& c) {
-    if (c.wdtype == W_BF16 && c.max_batch >= wide_min_batch() && wide_fits(c, kGridCtas)) return kMaxBatchWide;
+    // (int8 layers with a bf16 LM head keep the passes of four: the wide pass runs the LM head inside the kernel, in the layers' format)
+    const bool fmt_ok = c.wdtype == W_BF16 || (c.wdtype == W_INT8 && c.quant_lm_head);
+    if (fmt_ok && c.max_batch >= wide_min_batch() && wide_fits(c, kGridCtas)) return kMaxBatchWide;
     return std::min(c.max_batch, kMaxBatch);
 }
 // Does a pass of `batch` sequences (batch <= fused_pass_rows) run on the wide instance?

@@ -627,6 +627,20 @@ def test_fused_step_replayed_from_a_hip_graph():
         dec.close()
 
 
+def test_wide_pass_with_int8_weights():
+    """The wide pass with int8 per-channel weights (five or more sequences, int8 LM head): the codes are
+    converted to bf16 in registers (exact) and multiplied on the same 16x16x32 tiles, one ring stage of 512
+    columns per tile and K segment, row scales on the finished sums.  A small model with an odd and an even
+    number of tiles per workgroup (16 and 11 sequences, ragged lengths), the model whose output and down
+    projections are split along K, and one layer at the 8B width."""
+    S = synth.TINY.replace(name="wide8", n_layers=2, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ffn=6144, vocab=3000)
+    _run_teacher_forced(S, 0x2505227b0, synth.WDTYPE_INT8, batch=16, T0=[40, 0, 1, 130, 64, 63, 65, 9, 300, 17, 128, 5, 77, 256, 2, 33], steps=2)
+    _run_teacher_forced(S, 0x2505227b1, synth.WDTYPE_INT8, batch=11, T0=[7, 70, 0, 129, 31, 64, 200, 1, 90, 12, 55], steps=2)
+    _run_teacher_forced(KSPLIT, 0x2505227b2, synth.WDTYPE_INT8, batch=9, T0=[3, 70, 0, 129, 31, 64, 200, 1, 90], steps=2)
+    _run_teacher_forced(synth.LLAMA_8B.replace(n_layers=1), 0x2505227b3, synth.WDTYPE_INT8, batch=8, T0=[96, 1, 300, 64, 63, 65, 0, 200], steps=2,
+                        gpu_generated=True)
+
+
 KSPLIT = synth.TINY.replace(name="ksplit", n_layers=2, d_model=1024, n_q_heads=64, n_kv_heads=8, head_dim=128, d_ffn=8192, vocab=2000)
 
 
