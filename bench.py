@@ -38,6 +38,7 @@ WORKLOADS = {
     "llama3-8b-bf16-b8-ctx1024": ("llama3-8b", 0, 8, 1024),     # one wide pass
     "llama3-8b-bf16-b16-ctx1024": ("llama3-8b", 0, 16, 1024),   # one wide pass
     "llama3-8b-int8-b1-ctx4096": ("llama3-8b", 1, 1, 4096),
+    "llama3-8b-int8-b16-ctx4096": ("llama3-8b", 1, 16, 4096),   # one wide pass (int8 codes converted to bf16 in registers)
     "llama3-8b-int4-b1-ctx2048": ("llama3-8b", 2, 1, 2048),
     "llama3-8b-int4-b4-ctx2048": ("llama3-8b", 2, 4, 2048),
     # the full 80-layer model: 139 GB of packed weights, generated and packed layer by layer on the GPU
@@ -274,7 +275,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "bf16", 1: "int8", 2: "int4"}[wdtype] + " weights, f32 accumulate; "
-                 + ("activations exchanged between phases and multiplied as bf16 head + bf16 remainder (17 bits), residual stream f32" if wdtype == 0 and batch > 4
+                 + ("activations exchanged between phases and multiplied as bf16 head + bf16 remainder (17 bits), residual stream f32" if wdtype in (0, 1) and batch > 4
                     else "activations exchanged between phases as f32 rounded to 22 mantissa bits"
                          + ("" if batch == 1 else ", staged projection inputs as bf16 head + bf16 remainder (17 bits)")),
         "data": "synthetic",

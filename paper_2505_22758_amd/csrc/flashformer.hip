@@ -124,8 +124,14 @@ int fused_pass_rows(const ff_config& c) {
     if (fmt_ok && c.max_batch >= wide_min_batch() && wide_fits(c, kGridCtas)) return kMaxBatchWide;
     return std::min(c.max_batch, kMaxBatch);
 }
-// Does a pass of `batch` sequences (batch <= fused_pass_rows) run on the wide instance?
-bool pass_is_wide(const ff_config& c, int batch) { return fused_pass_rows(c) == kMaxBatchWide && batch >= wide_min_batch(); }
+// Does a pass of `batch` sequences (batch <= fused_pass_rows) run on the wide instance?  A model created
+// for more than four sequences has the wide pass's buffers; with int8 weights its passes of four take the
+// wide instance too (8B shape, context 4096: 3.53 ms against 3.87 ms on the row-partitioned path; at
+// three sequences the two are equal, below that and with bf16 weights the row-partitioned path is faster).
+bool pass_is_wide(const ff_config& c, int batch) {
+    const bool env = getenv("FF_WIDE_MIN") != nullptr;
+    return fused_pass_rows(c) == kMaxBatchWide && batch >= (!env && c.wdtype == W_INT8 ? kMaxBatch : wide_min_batch());
+}
 
 Plan make_plan(const ff_config& c) {
     Plan P;

@@ -443,13 +443,13 @@ def test_two_models_interleaved_on_a_side_stream():
         m[0].close()
 
 
-def _run_changing_batches(nseq, sizes):
+def _run_changing_batches(nseq, sizes, wdtype=synth.WDTYPE_BF16):
     from paper_2505_22758_amd import binding
     from oracle import oracle
     shape, seed, T0 = synth.TINY, 0x77, 20
     max_ctx = T0 + len(sizes) + 2
-    layers = [synth.make_layer(shape, seed, l, synth.WDTYPE_BF16, "cpu") for l in range(shape.n_layers)]
-    M = oracle.OracleModel(shape, layers, synth.make_head(shape, seed, synth.WDTYPE_BF16, "cpu"))
+    layers = [synth.make_layer(shape, seed, l, wdtype, "cpu") for l in range(shape.n_layers)]
+    M = oracle.OracleModel(shape, layers, synth.make_head(shape, seed, wdtype, "cpu"))
     okv = []
     for b in range(nseq):
         kv = M.new_kv(1, max_ctx)
@@ -457,7 +457,7 @@ def _run_changing_batches(nseq, sizes):
             k, v = synth.make_kv_prefill(shape, seed, l, b, T0, "cpu")
             kv[l, 0, 0, :T0], kv[l, 0, 1, :T0] = oracle._np(k), oracle._np(v)
         okv.append(kv)
-    dec, caches = helpers.hip_side(shape, seed, synth.WDTYPE_BF16, nseq, T0, max_ctx, n_caches=1)
+    dec, caches = helpers.hip_side(shape, seed, wdtype, nseq, T0, max_ctx, n_caches=1)
     toks = synth.make_tokens(shape, seed, len(sizes), nseq)
     pos = [T0] * nseq
     logits = torch.zeros(nseq, shape.vocab, dtype=torch.float32, device="cuda:0")
@@ -488,6 +488,8 @@ def test_wide_and_row_partitioned_steps_alternate_on_one_model():
     threshold: wide steps leave the compact exchange rows of the other paths untouched (those are
     re-initialised before the next small batch), small steps leave the wide pass's epochs alone."""
     _run_changing_batches(16, [6, 1, 16, 4, 9, 2, 5, 5, 1, 1, 12, 3, 16])
+    # int8: the wide pass from four sequences on
+    _run_changing_batches(16, [5, 1, 4, 3, 16, 2, 4, 1, 9, 3], wdtype=synth.WDTYPE_INT8)
 
 
 def test_llama70b_full_depth_batch1_and_batch16_ctx2048(capsys):
