@@ -31,11 +31,14 @@ typedef __bf16 mfma_bf8 __attribute__((ext_vector_type(8)));
 constexpr int kWideXchFloats = (kDenseMaxTiles / 2) * 16 * kMaxBatchWide;   // partial sums one workgroup can receive: its own rows (at most half the tiles) x 16 sequences
 // Weight formats of the wide pass: bf16 (a 16-byte unit = 8 columns, 256 units per K segment) and
 // int8 per-channel (16 columns per unit, 128 units per segment; the codes are converted to bf16 --
-// exact -- in registers, the row scales applied to the finished sums).
-template <int WD> constexpr int kDenseSegW = WD == W_BF16 ? kDenseSegUnits : kDenseSegUnits / 2;   // weight units per K segment
+// exact -- in registers, the row scales applied to the finished sums), int4 group-128 (32 columns per
+// unit, 64 units per segment; see dense_tiles_i4).
+template <int WD> constexpr int kDenseSegW = WD == W_BF16 ? kDenseSegUnits : WD == W_INT8 ? kDenseSegUnits / 2 : kDenseSegUnits / 4;   // weight units per K segment
 struct DenseStream {
     const uint8_t* w; size_t rowb;
-    const f16_t* s;           // int8: row scales
+    const f16_t* s;           // int8: row scales; int4: group scales [n][K / 128]
+    const f16_t* z;           // int4: group zeros
+    int ng;                   // int4: groups per row
     int r0, r1, T;            // rows [r0, r1) this workgroup multiplies (with a K split: the pair's); tiles
     int own0, own1;           // rows it finishes (= [r0, r1) without a K split)
     int seg0, seg1;           // K segments [seg0, seg1) it multiplies
@@ -57,11 +60,12 @@ struct DenseStream {
     __device__ __forceinline__ static DenseStream make(const PMat& M, int seg, const UDiv& n_ctas, bool split = false) {
         constexpr int SEGW = kDenseSegW<WD>;
         DenseStream D;
-        D.w = M.w; D.s = M.s; D.rowb = WD == W_BF16 ? (size_t)M.k * 2 : (size_t)M.k;
+        D.w = M.w; D.s = M.s; D.z = M.z; D.ng = M.k / 128;
+        D.rowb = WD == W_BF16 ? (size_t)M.k * 2 : WD == W_INT8 ? (size_t)M.k : (size_t)M.k / 2;
         const u32 ngroups = (u32)(M.n + 3) / 4;
         D.own0 = 4 * (int)n_ctas.div(ngroups * blockIdx.x);
         D.own1 = min(4 * (int)n_ctas.div(ngroups * (blockIdx.x + 1)), M.n);
-        D.total_units = M.k / (WD == W_BF16 ? 8 : 16);
+        D.total_units = M.k / (WD == W_BF16 ? 8 : WD == W_INT8 ? 16 : 32);
         const int nseg = (D.total_units + SEGW - 1) / SEGW;
         D.split = split;
         if (split) {
@@ -134,6 +138,44 @@ __device__ __forceinline__ void dense_prefetch_i8(const DenseStream& D, DenseCur
         c.advance(D.T);
     }
 }
+
+// int4: a unit is 32 columns of ONE group of 128; a wave's K quarter of a segment is 16 units = four groups, lane
+// (r, g) loading unit 16 w + 4 u + g of row r (u = 0..3: the four lanes g of a row hold the four units of group u).
+// That is four loads per tile, so a ring stage covers a PAIR of tiles (2 tp, 2 tp + 1: eight loads; the second
+// tile of the last pair may not exist -- its loads are then dummies), plus per tile the row's scales and zeros of the
+// quarter's four groups (8 bytes each).  Needs K to be a multiple of 512 (whole quarters of groups), which the host checks.
+struct WideStageI4 {
+    u32x4 w[2][4];     // [tile of the pair][u]
+    u32x2 s[2], z[2];  // raw fp16 scales / zeros of row r, groups 4 w .. 4 w + 3 of the segment
+};
+__device__ __forceinline__ void dense_load_i4(const DenseStream& D, const DenseCursor& c, WideStageI4& st, int wave, int lane) {
+    constexpr int SEGW = kDenseSegW<W_INT4>;
+    const bool real = c.seg < D.seg1;   // behind the last stage: loads of one address (see dense_load)
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+        const int t = 2 * c.t + k;   // (c.t counts tile pairs)
+        const bool rt = real && t < D.T;
+        const int row = min(D.r0 + 16 * t + (lane & 15), D.r1 - 1);
+        const uint8_t* rp = D.w + (size_t)row * D.rowb + (size_t)c.seg * (SEGW * 16);
+#pragma unroll
+        for (int u = 0; u < 4; u++) st.w[k][u] = ldg_stream(rt ? rp + (size_t)(16 * wave + 4 * u + (lane >> 4)) * 16 : D.w);
+        const size_t gi = (size_t)row * D.ng + (size_t)c.seg * (SEGW / 4) + 4 * wave;
+        st.s[k] = *as_global((const u32x2*)(rt ? D.s + gi : D.s));
+        st.z[k] = *as_global((const u32x2*)(rt ? D.z + gi : D.z));
+    }
+}
+__device__ __forceinline__ void dense_prefetch_i4(const DenseStream& D, DenseCursor& c, WideStageI4 (&ring)[2], int wave, int lane) {
+    c = DenseCursor{D.seg0, 0};
+    if (D.T > 0) {
+        const int TP = (D.T + 1) >> 1;
+        dense_load_i4(D, c, ring[0], wave, lane);
+        c.advance(TP);
+        dense_load_i4(D, c, ring[1], wave, lane);
+        c.advance(TP);
+    }
+}
+template <int WD> struct WideStageOf { typedef Stage<WD> type; };
+template <> struct WideStageOf<W_INT4> { typedef WideStageI4 type; };
 
 // First two stages of a projection (tile 0 of segment 0), issued before its input is waited for.
 __device__ __forceinline__ void dense_prefetch(const DenseStream& D, Stage<W_BF16> (&ring)[2], int wave, int lane) {
