@@ -157,9 +157,10 @@ __device__ __forceinline__ void dense_load_i4(const DenseStream& D, const DenseC
         const bool rt = real && t < D.T;
         const int row = min(D.r0 + 16 * t + (lane & 15), D.r1 - 1);
         const uint8_t* rp = D.w + (size_t)row * D.rowb + (size_t)c.seg * (SEGW * 16);
+        const int jmax = D.total_units - c.seg * SEGW - 1;   // units past the end of K are clamped (they meet zeros in the staged input)
 #pragma unroll
-        for (int u = 0; u < 4; u++) st.w[k][u] = ldg_stream(rt ? rp + (size_t)(16 * wave + 4 * u + (lane >> 4)) * 16 : D.w);
-        const size_t gi = (size_t)row * D.ng + (size_t)c.seg * (SEGW / 4) + 4 * wave;
+        for (int u = 0; u < 4; u++) st.w[k][u] = ldg_stream(rt ? rp + (size_t)min(16 * wave + 4 * u + (lane >> 4), jmax) * 16 : D.w);
+        const size_t gi = (size_t)row * D.ng + (size_t)min(c.seg * (SEGW / 4) + 4 * wave, D.ng - 4);   // (likewise the groups: ng is a multiple of four)
         st.s[k] = *as_global((const u32x2*)(rt ? D.s + gi : D.s));
         st.z[k] = *as_global((const u32x2*)(rt ? D.z + gi : D.z));
     }

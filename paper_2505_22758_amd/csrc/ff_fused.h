@@ -163,8 +163,8 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
     const u32 ebase = steps_done * (u32)(4 * M.L);   // epochs of this step: ebase + 4 l + {1: attention, 2: O, 3: gate/up, 4: down}
     const int n_phases = 4 * M.L + n_lm;
     mfma_f4 acc[kDenseMaxTiles];
-    Stage<WD> ring[2];
-    DenseCursor cur{0, 0};   // int8: next stage to load
+    typename WideStageOf<WD>::type ring[2];
+    DenseCursor cur{0, 0};   // int8, int4: next stage to load
     for (int ph = 0; ph < n_phases; ph++) {
         const int lm_block = max(ph - 4 * M.L, 0);
         PhaseDesc D = phase_desc(M, nullptr, tag_base, sl, ph - lm_block, 1, phase_state(M, ph - lm_block), true);
@@ -173,6 +173,7 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
             const int block_rows = kDenseMaxTiles * 16 * ncta, row0 = lm_block * block_rows;
             D.W.w += (size_t)row0 * D.W.row_bytes();
             if constexpr (WD == W_INT8) D.W.s += row0;   // row scales of the block
+            if constexpr (WD == W_INT4) { D.W.s += (size_t)row0 * (D.W.k / 128); D.W.z += (size_t)row0 * (D.W.k / 128); }   // group scales and zeros
             D.W.n = min(block_rows, D.W.n - row0);
             epf.pair0 = row0 >> 1;
         }
@@ -183,7 +184,8 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         DenseStream DS = DenseStream::make<WD>(D.W, 0, n_ctas, split);
         const int seg0 = DS.seg0, seg1 = DS.seg1;
         DS = DenseStream::make<WD>(D.W, seg0, n_ctas, split);
-        if constexpr (WD == W_INT8) dense_prefetch_i8(DS, cur, ring, wave, lane);
+        if constexpr (WD == W_INT4) dense_prefetch_i4(DS, cur, ring, wave, lane);
+        else if constexpr (WD == W_INT8) dense_prefetch_i8(DS, cur, ring, wave, lane);
         else dense_prefetch(DS, ring, wave, lane);
         u32 wait_epoch = 0;
         const uint8_t* img = M.wimg_x;
@@ -213,7 +215,7 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
             DS = DenseStream::make<WD>(D.W, seg, n_ctas, split);
             if (DS.T > 0) wide_copy_quarter(img + (size_t)seg * kWideSegBytes, lds, wave, lane, batch);   // (private to the wave: no barrier)
             const float* rsp = normed ? rs : nullptr;
-            const int par = ((seg - seg0) * DS.T) & 1;   // int8: ring slot of the segment's first stage
+            const int par = ((seg - seg0) * (WD == W_INT4 ? (DS.T + 1) >> 1 : DS.T)) & 1;   // int8, int4: ring slot of the segment's first stage
             if (D.kind == PH_GU) dense_run_wide<WD>(DS, ring, xs, acc, batch, wave, lane, WideEpiSwiGLU{M.wimg_h, M.gu}, rsp, nullptr, nullptr, 0u, &cur, par);
             else if (D.kind == PH_O)
                 run_ok = dense_run_wide<WD>(DS, ring, xs, acc, batch, wave, lane, WideEpiResidual{M.wxres, M.d, Lp->g2, M.wimg_x, ssl, DS.own0}, rsp,
@@ -268,7 +270,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     // region that only int4 weights use plus the regular RoPE region behind it, and its positions
     // in the mailbox region (no wave pairs share a row group there).
     constexpr bool kWide = B > kMaxBatchFused;
-    static_assert(!kWide || ((WD == W_BF16 || WD == W_INT8) && kLdsXsumBytes + kLdsRopeBytes >= B * 64 * (int)sizeof(float2) && kLdsPairBytes >= B * 4 && B <= kMaxBatchWide),
+    static_assert(!kWide || (kLdsXsumBytes + kLdsRopeBytes >= B * 64 * (int)sizeof(float2) && kLdsPairBytes >= B * 4 && B <= kMaxBatchWide),
                   "LDS layout of the wide pass");
     float2* rope_lds = (float2*)(lds + kLdsActBytes + kLdsAuxBytes - (kWide ? kLdsXsumBytes : 0));   // [batch][hd/2]
     for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kFusedThreads) {
@@ -456,12 +458,7 @@ inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what)
 }
 template <int WD, int HD, int G>
 inline hipError_t launch_fused_family(const FusedLaunch& a, const char** what) {
-    if constexpr (WD == W_BF16 || WD == W_INT8) {   // the wide instance (bf16 and int8; the host decides, and sizes lm_in_kernel and the buffers for it)
-        if (a.wide) return launch_fused_instance<WD, kMaxBatchWide, HD, G>(a, what);
-    } else if (a.wide) {
-        *what = "no wide instance for this weight type";
-        return hipErrorInvalidValue;
-    }
+    if (a.wide) return launch_fused_instance<WD, kMaxBatchWide, HD, G>(a, what);   // (the host decides, and sizes lm_in_kernel and the buffers for it)
     if (a.batch == 1) return launch_fused_instance<WD, 1, HD, G>(a, what);
     if (a.batch == 2) return launch_fused_instance<WD, 2, HD, G>(a, what);
     if (a.batch > kMaxBatch) {

@@ -247,12 +247,111 @@ __device__ __forceinline__ void dense_tiles_i8(const DenseStream& D, Stage<W_INT
     }
 }
 
+// int4 group-128: the tiles of one K segment, one ring stage per PAIR of tiles (see dense_load_i4); slots and exits
+// as in dense_tiles_i8, counted in tile pairs (PAR = (stages before this segment) mod 2, TP = (tile pairs) mod 2).
+// A wave's quarter of the segment is four groups u = 0..3 of 128 columns; the four lanes g of a row hold the four
+// units of a group, so the four k-steps q = 0..3 of one group (codes 8 q .. 8 q + 7 of every lane's unit against
+// input unit 4 J + q) sum exactly that group:  with the codes n turned into the bf16 numbers 128 + n by bit
+// operations (0x4300 | n), a group yields d = sum (128 + n) x per (row, sequence), and with X = sum of the
+// group's x per sequence
+//     sum s (n - z) x  =  s (d - (128 + z) X).
+// X comes from the same matrix-core instructions with an A operand of ones (once per segment and group: every
+// row of that product is X).  Scale s and zero z belong to the ROW: they are loaded by the lanes that load the row's
+// codes (lane (r, g): row r, the quarter's four groups) and fetched into the accumulator layout (lane (n, g):
+// rows 4 g + i) with one cross-lane read per row and group.
+template <int PAR, int TP>
+__device__ __forceinline__ void dense_tiles_i4(const DenseStream& D, WideStageI4 (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
+                                               DenseCursor& cur, int wave, int lane) {
+    const int n = lane & 15, g = lane >> 4;
+    const u32x4* xh = (const u32x4*)xs + (size_t)(2 * n) * kDenseSegUnits;
+    const u32x4* xl = xh + kDenseSegUnits;
+    const int TPn = (D.T + 1) >> 1;
+    // input units of group u, k-step q for this lane: 4 (16 w + 4 u + g) + q
+    auto xunit = [&](int u, int q) { return (4 * (16 * wave + 4 * u + g) + q) ^ n; };
+    // X[u] = sum of the group's inputs of sequence n (same in every lane (n, .))
+    float X[4];
+    {
+        const u32x4 ones{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            mfma_f4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const u32x4 bh = xh[xunit(u, q)], bl = xl[xunit(u, q)];
+                c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(mfma_bf8, ones), __builtin_bit_cast(mfma_bf8, bh), c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(mfma_bf8, ones), __builtin_bit_cast(mfma_bf8, bl), c, 0, 0, 0);
+            }
+            X[u] = c[0];
+        }
+    }
+    auto codes = [](u32 w) {   // eight codes of one word as bf16 128 + n, in column order
+        const u32 e = w & 0x0F0F0F0Fu, o = (w >> 4) & 0x0F0F0F0Fu;   // codes 0,2,4,6 / 1,3,5,7 as bytes
+        const u32x4 v{__builtin_amdgcn_perm(o, e, 0x0c040c00u) | 0x43004300u, __builtin_amdgcn_perm(o, e, 0x0c050c01u) | 0x43004300u,
+                      __builtin_amdgcn_perm(o, e, 0x0c060c02u) | 0x43004300u, __builtin_amdgcn_perm(o, e, 0x0c070c03u) | 0x43004300u};
+        return __builtin_bit_cast(mfma_bf8, v);
+    };
+    // two k-steps of one group of one tile
+    auto steps2 = [&](const u32x4& w, int q0, const u32x4 (&bh)[2], const u32x4 (&bl)[2], mfma_f4& d) {
+        const u32 ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+            const mfma_bf8 a = codes(ww[q0 + q]);
+            d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(mfma_bf8, bh[q]), d, 0, 0, 0);
+            d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(mfma_bf8, bl[q]), d, 0, 0, 0);
+        }
+    };
+    // the group's contribution with the rows' scales and zeros: those of rows 4 g + i are held by lane 4 g + i
+    auto combine = [&](u32 sbits, u32 zbits, float Xu, const mfma_f4& d, mfma_f4& cc) {
+        const u32 szp = sbits | (zbits << 16);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const u32 v = (u32)__builtin_amdgcn_ds_bpermute((4 * g + i) * 4, (int)szp);
+            const float sc = f16_to_f((f16_t)(v & 0xFFFFu)), zp = 128.f + f16_to_f((f16_t)(v >> 16));
+            cc[i] = fmaf(sc, fmaf(-zp, Xu, d[i]), cc[i]);
+        }
+    };
+    auto half16 = [](const u32x2& v, int u) { const u32 w = u < 2 ? v.x : v.y; return (u & 1) ? w >> 16 : w & 0xFFFFu; };
+#pragma unroll
+    for (int tp = 0; tp < (kDenseMaxTiles + 1) / 2; tp++) {
+        if ((tp & 1) == TP && tp >= TPn) break;
+        WideStageI4& st = ring[(tp + PAR) & 1];
+        const bool two = 2 * tp + 1 < D.T;
+        mfma_f4& c0 = acc[2 * tp];
+        mfma_f4& c1 = acc[2 * tp + 1 < kDenseMaxTiles ? 2 * tp + 1 : 0];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            mfma_f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q0 = 0; q0 < 4; q0 += 2) {
+                u32x4 bh[2], bl[2];   // the inputs of two k-steps: shared by the two tiles of the pair
+#pragma unroll
+                for (int q = 0; q < 2; q++) { bh[q] = xh[xunit(u, q0 + q)]; bl[q] = xl[xunit(u, q0 + q)]; }
+                __builtin_amdgcn_sched_barrier(0);
+                steps2(st.w[0][u], q0, bh, bl, d0);
+                if (two) steps2(st.w[1][u], q0, bh, bl, d1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            combine(half16(st.s[0], u), half16(st.z[0], u), X[u], d0, c0);
+            if (two) combine(half16(st.s[1], u), half16(st.z[1], u), X[u], d1, c1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        dense_load_i4(D, cur, st, wave, lane);   // the stage two further on (always the same number of loads)
+        cur.advance(TPn);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <int WD, class Epi>
-__device__ __forceinline__ bool dense_run_wide(const DenseStream& D, Stage<WD> (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
+__device__ __forceinline__ bool dense_run_wide(const DenseStream& D, typename WideStageOf<WD>::type (&ring)[2], const float4* xs, mfma_f4 (&acc)[kDenseMaxTiles],
                                                int batch, int wave, int lane, const Epi& epi, const float* rs_lds,
                                                float* xch = nullptr, const WideSync* sync = nullptr, u32 pepoch = 0, DenseCursor* cur = nullptr, int par = 0) {
     const int n = lane & 15, g = lane >> 4;
-  if constexpr (WD == W_INT8) {
+  if constexpr (WD == W_INT4) {
+    if (((D.T + 1) >> 1) & 1) {
+        if (par) dense_tiles_i4<1, 1>(D, ring, xs, acc, *cur, wave, lane);
+        else dense_tiles_i4<0, 1>(D, ring, xs, acc, *cur, wave, lane);
+    } else dense_tiles_i4<0, 0>(D, ring, xs, acc, *cur, wave, lane);
+  } else if constexpr (WD == W_INT8) {
     if (D.T & 1) {
         if (par) dense_tiles_i8<1, 1>(D, ring, xs, acc, *cur, wave, lane);
         else dense_tiles_i8<0, 1>(D, ring, xs, acc, *cur, wave, lane);

@@ -119,8 +119,10 @@ int wide_min_batch() {
     return v > 0 ? v : kMaxBatch + 1;
 }
 int fused_pass_rows(const ff_config& c) {
-    // (int8 layers with a bf16 LM head keep the passes of four: the wide pass runs the LM head inside the kernel, in the layers' format)
-    const bool fmt_ok = c.wdtype == W_BF16 || (c.wdtype == W_INT8 && c.quant_lm_head);
+    // (quantised layers with a bf16 LM head keep the passes of four: the wide pass runs the LM head inside the kernel, in the layers' format)
+    // (int4: the wide pass takes a row's scales and zeros four groups at a time: every input width a multiple of 512)
+    const bool k512 = c.d_model % 512 == 0 && (c.n_q_heads * c.head_dim) % 512 == 0 && c.d_ffn % 512 == 0;
+    const bool fmt_ok = c.wdtype == W_BF16 || ((c.wdtype == W_INT8 || (c.wdtype == W_INT4 && k512)) && c.quant_lm_head);
     if (fmt_ok && c.max_batch >= wide_min_batch() && wide_fits(c, kGridCtas)) return kMaxBatchWide;
     return std::min(c.max_batch, kMaxBatch);
 }

@@ -643,6 +643,20 @@ def test_wide_pass_with_int8_weights():
                         gpu_generated=True)
 
 
+def test_wide_pass_with_int4_weights():
+    """The wide pass with int4 group-128 weights (input widths multiples of 512, int4 LM head): codes as bf16
+    128 + n on the 16x16x32 tiles, one ring stage per pair of tiles, group sums of the inputs from a ones operand,
+    scales and zeros fetched across lanes into the accumulator layout.  A small model with odd and even numbers
+    of tile pairs (16 and 11 sequences, ragged lengths), the model whose output and down projections are split
+    along K, and one layer at the 8B width."""
+    S = synth.TINY.replace(name="wide4", n_layers=2, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ffn=6144, vocab=3000)
+    _run_teacher_forced(S, 0x2505227c0, synth.WDTYPE_INT4, batch=16, T0=[40, 0, 1, 130, 64, 63, 65, 9, 300, 17, 128, 5, 77, 256, 2, 33], steps=2)
+    _run_teacher_forced(S, 0x2505227c1, synth.WDTYPE_INT4, batch=11, T0=[7, 70, 0, 129, 31, 64, 200, 1, 90, 12, 55], steps=2)
+    _run_teacher_forced(KSPLIT, 0x2505227c2, synth.WDTYPE_INT4, batch=9, T0=[3, 70, 0, 129, 31, 64, 200, 1, 90], steps=2)
+    _run_teacher_forced(synth.LLAMA_8B.replace(n_layers=1), 0x2505227c3, synth.WDTYPE_INT4, batch=8, T0=[96, 1, 300, 64, 63, 65, 0, 200], steps=2,
+                        gpu_generated=True)
+
+
 KSPLIT = synth.TINY.replace(name="ksplit", n_layers=2, d_model=1024, n_q_heads=64, n_kv_heads=8, head_dim=128, d_ffn=8192, vocab=2000)
 
 
