@@ -41,6 +41,7 @@ WORKLOADS = {
     "llama3-8b-int8-b16-ctx4096": ("llama3-8b", 1, 16, 4096),   # one wide pass (int8 codes converted to bf16 in registers)
     "llama3-8b-int4-b1-ctx2048": ("llama3-8b", 2, 1, 2048),
     "llama3-8b-int4-b4-ctx2048": ("llama3-8b", 2, 4, 2048),
+    "llama3-8b-int4-b16-ctx2048": ("llama3-8b", 2, 16, 2048),   # one wide pass (int4 codes as bf16 128 + n on the matrix cores)
     # the full 80-layer model: 139 GB of packed weights, generated and packed layer by layer on the GPU
     "llama3-70b-bf16-b1-ctx2048": ("llama3-70b", 0, 1, 2048),
     "llama3-70b-bf16-b16-ctx2048": ("llama3-70b", 0, 16, 2048),
@@ -275,7 +276,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "bf16", 1: "int8", 2: "int4"}[wdtype] + " weights, f32 accumulate; "
-                 + ("activations exchanged between phases and multiplied as bf16 head + bf16 remainder (17 bits), residual stream f32" if wdtype in (0, 1) and batch > 4
+                 + ("activations exchanged between phases and multiplied as bf16 head + bf16 remainder (17 bits), residual stream f32" if batch > 4
                     else "activations exchanged between phases as f32 rounded to 22 mantissa bits"
                          + ("" if batch == 1 else ", staged projection inputs as bf16 head + bf16 remainder (17 bits)")),
         "data": "synthetic",

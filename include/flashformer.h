@@ -144,12 +144,13 @@ int ff_kv_free(ff_kv *kv);
  * A step's launches carry no host-side per-step state (exchange tags and write counters derive
  * from a counter in the model's scratch), so a step may be recorded into a HIP graph and replayed.
  * One kernel pass serves up to 4 sequences (paper Section 5.2: batches 2-4 replicate the inputs and
- * read every weight once); with bf16 weights, or int8 weights and an int8 LM head (quant_lm_head),
- * and max_batch > 4, batches of 5 to 16 run as ONE "wide" pass (the paper stops at 4): projections on
- * 16x16x32 matrix-core tiles (int8 codes converted to bf16 in registers), activations exchanged in
- * the consumers' on-chip layout by the workgroups that own them, preceded by a small launch that
- * prepares the step's embedding rows.  With int4 weights, or int8 layers under a bf16 LM head, a
- * batch above 4 runs as consecutive passes of 4 on the stream, each streaming the weights again. */
+ * read every weight once); with max_batch > 4, batches of 5 to 16 run as ONE "wide" pass (the paper
+ * stops at 4): projections on 16x16x32 matrix-core tiles (int8 and int4 codes converted to bf16 in
+ * registers), activations exchanged in the consumers' on-chip layout by the workgroups that own them,
+ * preceded by a small launch that prepares the step's embedding rows.  The wide pass needs the LM head
+ * in the layers' format (quant_lm_head for int8 / int4) and, for int4, d_model, n_q_heads * head_dim
+ * and d_ffn multiples of 512; otherwise a batch above 4 runs as consecutive passes of 4 on the
+ * stream, each streaming the weights again. */
 int ff_decode_step(ff_model *m, const int32_t *tokens_dev, const int32_t *positions_dev, ff_kv *kv,
                    float *logits_dev, int32_t batch, void *stream);
 
