@@ -42,13 +42,17 @@ enum {
     FF_OK = 0,
     FF_ERR_ARG = -1,         /* null pointer, batch outside [1, max_batch], bad index */
     FF_ERR_UNSUPPORTED = -2, /* configuration has no compiled kernel instance */
-    FF_ERR_RANGE = -3,       /* a position is >= max_ctx, or a token id >= vocab (seen on device) */
+    FF_ERR_RANGE = -3,       /* a position outside [0, max_ctx), or a token id that is neither in [0, vocab) nor FF_TOKEN_SKIP (seen on device) */
     FF_ERR_NOMEM = -4,       /* a caller-provided buffer is too small or misaligned */
     FF_ERR_TIMEOUT = -5,     /* a workgroup gave up waiting for another one's output (not co-resident?) */
     FF_ERR_HIP = -6          /* a HIP runtime call failed; text in ff_last_error() */
 };
 
 enum { FF_W_BF16 = 0, FF_W_INT8_PC = 1, FF_W_INT4_G128 = 2 };
+
+/* Token id of a sequence that takes no part in a decode step (it has stopped early while the rest
+ * of the batch decodes on; the paper's batches advance in lock step, Section 5.2). */
+#define FF_TOKEN_SKIP (-1)
 
 /* Which matrix ff_debug_dequant exports. */
 enum { FF_MAT_WQ = 0, FF_MAT_WK, FF_MAT_WV, FF_MAT_WO, FF_MAT_WGATE, FF_MAT_WUP, FF_MAT_WDOWN, FF_MAT_LMHEAD };
@@ -132,7 +136,12 @@ int ff_kv_fill_synthetic(ff_kv *kv, uint64_t seed, int32_t n_ctx, void *stream);
 int ff_kv_free(ff_kv *kv);
 
 /* One decode step (paper Section 4.2, attention and GLU schedules; final norm and LM head added).
- *   tokens_dev    int32 [batch]   token ids, each in [0, vocab)
+ *   tokens_dev    int32 [batch]   token ids, each in [0, vocab), or FF_TOKEN_SKIP: that sequence sits
+ *                                 this step out -- its position is ignored, nothing is appended to
+ *                                 its cache and its row of logits_dev is not written.  (Its slot
+ *                                 still travels through the kernel as a placeholder, so the step
+ *                                 costs what the full batch costs; the other sequences' results are
+ *                                 bit-identical to a step in which it takes part.)
  *   positions_dev int32 [batch]   number of rows already cached for each sequence (= the position
  *                                 of this token); this step appends K,V at that row and attends to
  *                                 rows 0..position inclusive.  The caller advances positions.

@@ -21,6 +21,7 @@ _lib = C.CDLL(LIB_PATH)
 
 FF_OK, FF_ERR_ARG, FF_ERR_UNSUPPORTED, FF_ERR_RANGE, FF_ERR_NOMEM, FF_ERR_TIMEOUT, FF_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 FF_W_BF16, FF_W_INT8_PC, FF_W_INT4_G128 = 0, 1, 2
+FF_TOKEN_SKIP = -1   # token id of a sequence that sits a decode step out (see include/flashformer.h)
 FF_MAT = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 6, "lm_head": 7}
 
 EXPORTS = ["ff_last_error", "ff_model_bytes", "ff_model_create", "ff_model_load_layer", "ff_model_load_head",

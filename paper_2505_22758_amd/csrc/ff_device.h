@@ -182,4 +182,12 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 __device__ __forceinline__ u32x4 ldg_stream(const void* p) { return __builtin_nontemporal_load(as_global((const u32x4*)p)); }
 
+// A sequence whose token is kTokenSkip takes no part in the step (it has stopped while the rest of
+// the batch decodes on): its position is ignored, its cache and its logits row are left as they are.
+// Inside the kernels such a sequence has position -1; it is carried through the layers as a
+// placeholder (token 0 at an empty cache) whose k, v and logits are never stored, so the launch
+// shape and the exchange protocol do not depend on which sequences are active.
+constexpr int kTokenSkip = -1;
+__device__ __forceinline__ int step_pos(const int* tokens, const int* pos, int b) { return tokens[b] == kTokenSkip ? -1 : pos[b]; }
+
 }  // namespace ff

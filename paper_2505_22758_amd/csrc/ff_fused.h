@@ -68,7 +68,7 @@ struct EpiFused {
         switch (kind) {
             case PH_QKV: EpiQKVTagged{M, KV, pos, layer, rope, tag}(pair, b, v0, v1); break;
             case PH_GU: EpiSwiGLUTagged{M.ch, M.F, cnt, M.gu}(pair, b, v0, v1); break;
-            case PH_LM: EpiStore{logits, M.V}(pair + pair0, b, v0, v1); break;
+            case PH_LM: if (pos[b] >= 0) EpiStore{logits, M.V}(pair + pair0, b, v0, v1); break;   // (no logits for a sequence that sits the step out)
             default: EpiDeltaTagged{M.cdelta, M.d, cnt}(pair, b, v0, v1); break;
         }
     }
@@ -275,7 +275,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     float2* rope_lds = (float2*)(lds + kLdsActBytes + kLdsAuxBytes - (kWide ? kLdsXsumBytes : 0));   // [batch][hd/2]
     for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kFusedThreads) {
         int b = i / (M.hd / 2), f = i % (M.hd / 2);
-        rope_lds[i] = KV.rope[(size_t)pos[b] * (M.hd / 2) + f];
+        rope_lds[i] = KV.rope[(size_t)max(step_pos(tokens, pos, b), 0) * (M.hd / 2) + f];
     }
     // Launch dimensions and positions are read again and again below; a vector load of them would
     // make the wave wait for everything it has in flight (its prefetched weight tiles included), so
@@ -283,7 +283,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     static_assert(kLdsRopeBytes == kMaxBatchFused * 64 * sizeof(float2) && kLdsMiscBytes >= (16 + 2 * (1 + WgVote::kMaxSums) * kFusedWaves) * 4, "LDS layout");
     int* pos_lds = kWide ? (int*)(lds + kLdsActBytes + kLdsAuxBytes + kLdsRopeBytes + kLdsMiscBytes)
                          : (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64 + 8);
-    if ((int)threadIdx.x < batch) pos_lds[threadIdx.x] = pos[threadIdx.x];
+    if ((int)threadIdx.x < batch) pos_lds[threadIdx.x] = step_pos(tokens, pos, threadIdx.x);   // -1: the sequence sits this step out
     if (!kWide && threadIdx.x < 2) ((lds_u32*)(pairbox_of(xs) + 4 * kPairBoxFloats))[threadIdx.x] = 0u;
     if (B == 1 && threadIdx.x < kGluMaxChunks) ((lds_u32*)pairbox_of(xs))[threadIdx.x] = 0u;   // arrival counters of the staged h chunks (glu_run)
     __syncthreads();

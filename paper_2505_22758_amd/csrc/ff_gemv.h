@@ -114,7 +114,7 @@ __device__ void stage_act(const ActSrc& S, int batch, int K, int k0, int nunits,
         float4* xb = xs + (size_t)b * NQ * nup;
         const float* src = S.base + (size_t)b * S.stride;
         const float* add = S.add ? S.add + (size_t)b * S.add_stride : nullptr;
-        const bf16_t* erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
+        const bf16_t* erow = S.tokens ? S.embed + (size_t)max(as_global(S.tokens)[b], 0) * K : nullptr;
         float ss = 0.f;
         for (int q0 = tid; q0 < padquads; q0 += NT * kStageBatch) {
             float4 v[kStageBatch], a[kStageBatch];

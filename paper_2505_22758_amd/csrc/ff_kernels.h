@@ -19,7 +19,7 @@ __device__ __forceinline__ bool inputs_ok(const DevModel& M, const DevKV& KV, co
     bool ok = true;
     for (int b = -KV.seq0; b < KV.step_batch - KV.seq0; b++) {
         int p = pos[b], t = tokens[b];
-        ok = ok && p >= 0 && p < KV.max_ctx && t >= 0 && t < M.V;
+        ok = ok && (t == kTokenSkip || (p >= 0 && p < KV.max_ctx && t >= 0 && t < M.V));
     }
     return ok;
 }
@@ -28,13 +28,13 @@ __device__ __forceinline__ bool inputs_ok(const DevModel& M, const DevKV& KV, co
 // one list that is dealt round-robin to the workgroups (a per-layer work queue with a static
 // owner per entry; the split count follows each sequence's current length).
 template <int NW>
-__device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer, uint8_t* lds) {
+__device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const int* tokens, const int* pos, int batch, int layer, uint8_t* lds) {
     const int G = M.Hq / M.Hkv;
     const int share = max(1, (int)gridDim.x / (batch * M.Hkv));
     int base = 0;
     PlainAttnIO xio;
     for (int b = 0; b < batch; b++) {
-        const int T = pos[b];
+        const int T = max(step_pos(tokens, pos, b), 0);
         const int ns = attn_nsplit(T, share);
         const int nitems = M.Hkv * ns;
         int first = ((int)blockIdx.x - base) % (int)gridDim.x;
@@ -69,7 +69,7 @@ __device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const 
     bool ok = true;
     TaggedAttnIO xio{in_tag, out_tag, &vote};
     for (int b = 0; b < batch; b++) {
-        const int T = pos[b];
+        const int T = max(pos[b], 0);   // (-1: the sequence sits this step out and is carried as a placeholder with an empty cache)
         const int ns = attn_nsplit(T, share);
         const int nitems = M.Hkv * ns;
         // (32-bit unsigned arithmetic throughout: this runs between the end of the QKV projection

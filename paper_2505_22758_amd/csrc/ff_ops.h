@@ -13,7 +13,7 @@ __global__ void __launch_bounds__(kThreads) op_embed(DevModel M, DevKV KV, const
     const int tot = batch * M.d;
     for (int i = blockIdx.x * kThreads + threadIdx.x; i < tot; i += gridDim.x * kThreads) {
         int b = i / M.d, c = i % M.d;
-        M.x[(size_t)b * M.d + c] = bf_to_f(M.embed[(size_t)tokens[b] * M.d + c]);
+        M.x[(size_t)b * M.d + c] = bf_to_f(M.embed[(size_t)max(tokens[b], 0) * M.d + c]);   // (a sequence that sits the step out is carried as token 0)
     }
 }
 // grid = batch
@@ -123,15 +123,19 @@ __device__ __forceinline__ void op_gemv_body(const PMat& W, const ActSrc& src, i
     }
 }
 template <int WD, int B>
-__global__ void __launch_bounds__(kThreads) op_gemv(PMat W, const float* in, int in_stride, float* out, int batch, int epi_kind) {
+// skip_tokens (may be null; EPI_STORE only): the step's tokens; output rows of sequences that sit the step out are not written
+__global__ void __launch_bounds__(kThreads) op_gemv(PMat W, const float* in, int in_stride, float* out, int batch, int epi_kind, const int* skip_tokens) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    u32 skip = 0;
+    if (skip_tokens)
+        for (int b = 0; b < batch; b++) skip |= (u32)(skip_tokens[b] == kTokenSkip) << b;
     ActSrc src;
     src.base = in; src.stride = (size_t)in_stride;
     if (epi_kind == EPI_RESIDUAL) {
         EpiResidual epi{out, W.n};
         op_gemv_body<WD, B>(W, src, batch, lds, epi);
     } else {
-        EpiStore epi{out, W.n};
+        EpiStore epi{out, W.n, skip};
         op_gemv_body<WD, B>(W, src, batch, lds, epi);
     }
 }
@@ -180,11 +184,11 @@ __global__ void __launch_bounds__(kThreads) op_rope_append(DevModel M, DevKV KV,
     __shared__ float2 rope_s[kMaxBatch * 64];
     for (int i = threadIdx.x; i < batch * (M.hd / 2); i += kThreads) {
         int b = i / (M.hd / 2), f = i % (M.hd / 2);
-        rope_s[i] = KV.rope[(size_t)pos[b] * (M.hd / 2) + f];
+        rope_s[i] = KV.rope[(size_t)max(step_pos(tokens, pos, b), 0) * (M.hd / 2) + f];
     }
     __syncthreads();
     const int rows = (M.Hq + 2 * M.Hkv) * M.hd, npairs = rows / 2;
-    EpiQKV<PlainIO> epi{M, KV, pos, layer, rope_s};
+    EpiQKV<PlainIO> epi{M, KV, tokens, pos, layer, rope_s};
     for (int i = blockIdx.x * kThreads + threadIdx.x; i < npairs * batch; i += gridDim.x * kThreads) {
         int b = i / npairs, p = i % npairs;
         const float* y = M.y + (size_t)b * rows + 2 * p;
@@ -194,13 +198,13 @@ __global__ void __launch_bounds__(kThreads) op_rope_append(DevModel M, DevKV KV,
 __global__ void __launch_bounds__(kThreads) op_attn_partial(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch, int layer) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     if (!inputs_ok(M, KV, tokens, pos)) return;
-    attention_phase_plain<kWaves>(M, KV, pos, batch, layer, lds);
+    attention_phase_plain<kWaves>(M, KV, tokens, pos, batch, layer, lds);
 }
 // grid = batch * Hkv; must be launched with the same share (= partial grid / (batch*Hkv)) in `share`
 __global__ void __launch_bounds__(kThreads) op_attn_merge(DevModel M, DevKV KV, const int* tokens, const int* pos, int batch, int share) {
     if (!inputs_ok(M, KV, tokens, pos)) return;
     int b = blockIdx.x / M.Hkv, j = blockIdx.x % M.Hkv;
-    int ns = attn_nsplit(pos[b], share);
+    int ns = attn_nsplit(max(step_pos(tokens, pos, b), 0), share);
     const int G = M.Hq / M.Hkv;
     __shared__ float mlds[3 * 8 * kMaxSplits];
     if (M.hd == 64 && G == 4) attn_merge<64, 4, kThreads>(M, b, j, ns, mlds);

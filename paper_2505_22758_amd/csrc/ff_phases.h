@@ -240,7 +240,7 @@ __device__ __forceinline__ bool stage_tagged_multipass(const TSrc& S, int batch,
         const cword_t* src = S.base + (size_t)b * S.stride;
         const cword_t* add = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
         const bf16_t* erow = nullptr;   // embedding rows only come through the (no add, gain) instance
-        if constexpr (!HAS_ADD && HAS_GAIN) erow = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
+        if constexpr (!HAS_ADD && HAS_GAIN) erow = S.tokens ? S.embed + (size_t)max(as_global(S.tokens)[b], 0) * K : nullptr;
         float ss = 0.f;
         for (int q0 = tid; q0 < padquads; q0 += NT * QB) {
             u32x4 v[QB], a[HAS_ADD ? QB : 1];   // four compact words per quad and source
@@ -357,7 +357,7 @@ __device__ __forceinline__ bool stage_tagged_onepass(const TSrc& S, int batch, i
             src[r] = S.base + (size_t)b * S.stride;
             add[r] = HAS_ADD ? S.add + (size_t)b * S.add_stride : nullptr;
             erow[r] = nullptr;
-            if constexpr (!HAS_ADD && HAS_GAIN) erow[r] = S.tokens ? S.embed + (size_t)as_global(S.tokens)[b] * K : nullptr;
+            if constexpr (!HAS_ADD && HAS_GAIN) erow[r] = S.tokens ? S.embed + (size_t)max(as_global(S.tokens)[b], 0) * K : nullptr;
         }
         u32x4 v[RB][QB], a[HAS_ADD ? RB : 1][HAS_ADD ? QB : 1];   // four compact words per quad and source
         u32x2 g[HAS_GAIN ? QB : 1];
@@ -1001,12 +1001,12 @@ __device__ __forceinline__ int attn_nsplit(int ncache, int share) {
 // QKV rows in packed order: q heads then k heads with RoPE partners (i, i+hd/2) adjacent, then v.
 template <class IO>
 struct EpiQKV {
-    const DevModel& M; const DevKV& KV; const int* pos; int layer;
+    const DevModel& M; const DevKV& KV; const int* tokens; const int* pos; int layer;
     const float2* rope;   // [batch][hd/2] (cos, sin) of each sequence's position; LDS in the fused kernel
     __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         const int half = M.hd / 2;
         const int nq = M.Hq * half, nk = M.Hkv * half;
-        const int p = as_global(pos)[b];
+        const int p = as_global(tokens)[b] == kTokenSkip ? -1 : as_global(pos)[b];   // -1: the cache of this sequence is not touched
         if (pair < nq + nk) {
             bool isq = pair < nq;
             int pp = isq ? pair : pair - nq;
@@ -1020,7 +1020,7 @@ struct EpiQKV {
             } else {
                 bf16_t ab = f_to_bf(a), cb = f_to_bf(c);
                 bf16_t* row = KV.plane(M, layer, b, head, 0) + (size_t)p * M.hd;
-                as_global(row)[i] = ab; as_global(row)[i + half] = cb;
+                if (p >= 0) { as_global(row)[i] = ab; as_global(row)[i + half] = cb; }
                 float* kc = M.kvcur + ((size_t)b * 2 + 0) * M.Hkv * M.hd + (size_t)head * M.hd;
                 IO::st(kc + i, bf_to_f(ab)); IO::st(kc + i + half, bf_to_f(cb));
             }
@@ -1029,7 +1029,7 @@ struct EpiQKV {
             int head = pp / half, i = (pp % half) * 2;
             bf16_t ab = f_to_bf(v0), cb = f_to_bf(v1);
             bf16_t* row = KV.plane(M, layer, b, head, 1) + (size_t)p * M.hd;
-            *as_global((u32*)(row + i)) = (u32)ab | ((u32)cb << 16);
+            if (p >= 0) *as_global((u32*)(row + i)) = (u32)ab | ((u32)cb << 16);
             float* vc = M.kvcur + ((size_t)b * 2 + 1) * M.Hkv * M.hd + (size_t)head * M.hd;
             IO::st2(vc + i, bf_to_f(ab), bf_to_f(cb));
         }
@@ -1054,7 +1054,7 @@ struct EpiSwiGLU {
     }
 };
 // ---- fused-kernel epilogues: outputs go to the tagged exchange buffers ----
-struct EpiQKVTagged {   // pos: positions of this step, staged in LDS
+struct EpiQKVTagged {   // pos: positions of this step, staged in LDS (-1: the sequence sits the step out, its cache is not touched)
     const DevModel& M; const DevKV& KV; const int* pos; int layer; const float2* rope; u32 tag;
     __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
         const int half = M.hd / 2;
@@ -1073,7 +1073,7 @@ struct EpiQKVTagged {   // pos: positions of this step, staged in LDS
             } else {
                 bf16_t ab = f_to_bf(a), cb = f_to_bf(c);
                 bf16_t* row = KV.plane(M, layer, b, head, 0) + (size_t)p * M.hd;
-                as_global(row)[i] = ab; as_global(row)[i + half] = cb;
+                if (p >= 0) { as_global(row)[i] = ab; as_global(row)[i + half] = cb; }
                 tagged_t* kc = M.tkvcur + ((size_t)b * 2 + 0) * M.Hkv * M.hd + (size_t)head * M.hd;
                 tst(kc + i, bf_to_f(ab), tag); tst(kc + i + half, bf_to_f(cb), tag);
             }
@@ -1082,7 +1082,7 @@ struct EpiQKVTagged {   // pos: positions of this step, staged in LDS
             int head = pp / half, i = (pp % half) * 2;
             bf16_t ab = f_to_bf(v0), cb = f_to_bf(v1);
             bf16_t* row = KV.plane(M, layer, b, head, 1) + (size_t)p * M.hd;
-            *as_global((u32*)(row + i)) = (u32)ab | ((u32)cb << 16);
+            if (p >= 0) *as_global((u32*)(row + i)) = (u32)ab | ((u32)cb << 16);
             tagged_t* vc = M.tkvcur + ((size_t)b * 2 + 1) * M.Hkv * M.hd + (size_t)head * M.hd;
             tst2(vc + i, bf_to_f(ab), bf_to_f(cb), tag);
         }
@@ -1101,7 +1101,9 @@ struct EpiSwiGLUTagged {   // packed rows (2i, 2i+1) = (gate_i, up_i):  h_i = si
 };
 struct EpiStore {   // plain output rows (logits; per-op raw projections)
     float* y; int n;
+    u32 skip = 0;   // bit b set: row b is not written (logits of a sequence that sits the step out)
     __device__ __forceinline__ void operator()(int pair, int b, float v0, float v1) const {
+        if ((skip >> b) & 1u) return;
         FF_GLOBAL float* p = as_global(y + (size_t)b * n + 2 * pair);
         p[0] = v0;
         if (2 * pair + 1 < n) p[1] = v1;

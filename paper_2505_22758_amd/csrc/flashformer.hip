@@ -269,27 +269,28 @@ int check_step_args(ff_model* m, const int32_t* tokens, const int32_t* pos, ff_k
 }
 
 template <int WD, int B>
-int launch_gemv(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st) {
+int launch_gemv(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st, const int* skip_tokens = nullptr) {
     auto kern = op_gemv<WD, B>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)m->lds_bytes); });
     if (attr_err != hipSuccess) return fail(FF_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(attr_err));
-    kern<<<m->n_cta, kThreads, m->lds_bytes, st>>>(W, in, in_stride, out, batch, epi);
+    kern<<<m->n_cta, kThreads, m->lds_bytes, st>>>(W, in, in_stride, out, batch, epi, skip_tokens);
     return FF_OK;
 }
 template <int B>
-int gemv_any(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st) {
+int gemv_any(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st, const int* skip_tokens) {
     switch (W.wd) {
-        case W_BF16: return launch_gemv<W_BF16, B>(m, W, in, in_stride, out, batch, epi, st);
-        case W_INT8: return launch_gemv<W_INT8, B>(m, W, in, in_stride, out, batch, epi, st);
-        default: return launch_gemv<W_INT4, B>(m, W, in, in_stride, out, batch, epi, st);
+        case W_BF16: return launch_gemv<W_BF16, B>(m, W, in, in_stride, out, batch, epi, st, skip_tokens);
+        case W_INT8: return launch_gemv<W_INT8, B>(m, W, in, in_stride, out, batch, epi, st, skip_tokens);
+        default: return launch_gemv<W_INT4, B>(m, W, in, in_stride, out, batch, epi, st, skip_tokens);
     }
 }
-int gemv_op(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st) {
-    if (batch == 1) return gemv_any<1>(m, W, in, in_stride, out, batch, epi, st);
-    if (batch == 2) return gemv_any<2>(m, W, in, in_stride, out, batch, epi, st);
-    return gemv_any<4>(m, W, in, in_stride, out, batch, epi, st);
+// skip_tokens (EPI_STORE only, may be null): the tokens of the `batch` sequences; rows of sequences that sit the step out are not written
+int gemv_op(ff_model* m, const PMat& W, const float* in, int in_stride, float* out, int batch, int epi, hipStream_t st, const int* skip_tokens = nullptr) {
+    if (batch == 1) return gemv_any<1>(m, W, in, in_stride, out, batch, epi, st, skip_tokens);
+    if (batch == 2) return gemv_any<2>(m, W, in, in_stride, out, batch, epi, st, skip_tokens);
+    return gemv_any<4>(m, W, in, in_stride, out, batch, epi, st, skip_tokens);
 }
 
 }  // namespace
@@ -670,7 +671,8 @@ int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const 
         op_final_x<<<16, kThreads, 0, st>>>(D.x, D.cx, D.cdelta, batch * c.d_model);
         op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, D.gf, D.xn, c.d_model, c.rms_eps);
         for (int b0 = 0; b0 < batch; b0 += kMaxBatch) {
-            int rc = gemv_op(m, D.lm, D.xn + (size_t)b0 * c.d_model, c.d_model, logits_dev + (size_t)b0 * c.vocab, std::min(kMaxBatch, batch - b0), EPI_STORE, st);
+            int rc = gemv_op(m, D.lm, D.xn + (size_t)b0 * c.d_model, c.d_model, logits_dev + (size_t)b0 * c.vocab, std::min(kMaxBatch, batch - b0), EPI_STORE, st,
+                             tokens_dev + b0);
             if (rc) return rc;
         }
         HIPCHK(hipGetLastError());
@@ -725,7 +727,7 @@ int perop_pass(ff_model* m, const int32_t* tokens_dev, const int32_t* positions_
         if ((rc = gemv_op(m, L.down, D.h, c.d_ffn, D.x, batch, EPI_RESIDUAL, st))) return rc;
     }
     op_rmsnorm<<<batch, kThreads, 0, st>>>(D.x, D.gf, D.xn, c.d_model, c.rms_eps);
-    if ((rc = gemv_op(m, D.lm, D.xn, c.d_model, logits_dev, batch, EPI_STORE, st))) return rc;
+    if ((rc = gemv_op(m, D.lm, D.xn, c.d_model, logits_dev, batch, EPI_STORE, st, tokens_dev))) return rc;
     (void)qkv_rows;
     HIPCHK(hipGetLastError());
     return FF_OK;
@@ -816,7 +818,7 @@ int ff_status(ff_model* m, void* stream) {
     HIPCHK(hipMemcpy(&s, m->dev.status, sizeof(int), hipMemcpyDeviceToHost));
     if (s != 0) {
         HIPCHK(hipMemset(m->dev.status, 0, sizeof(int)));
-        if (s == kStatusRange) return fail(FF_ERR_RANGE, "a decode step saw a position >= max_ctx or a token id >= vocab and was skipped");
+        if (s == kStatusRange) return fail(FF_ERR_RANGE, "a decode step saw a position outside [0, max_ctx) or a token id that is neither in [0, vocab) nor FF_TOKEN_SKIP, and was skipped");
         if (s <= -50 || s == kStatusTimeout)
             return fail(FF_ERR_TIMEOUT, "a workgroup gave up waiting for another workgroup's output (site code %d): workgroups not co-resident?", s);
         return fail(FF_ERR_HIP, "unknown device status %d", s);

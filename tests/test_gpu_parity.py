@@ -492,6 +492,83 @@ def test_wide_and_row_partitioned_steps_alternate_on_one_model():
     _run_changing_batches(16, [5, 1, 4, 3, 16, 2, 4, 1, 9, 3], wdtype=synth.WDTYPE_INT8)
 
 
+def _run_sequences_stopping_early(nseq, stops, steps, wdtype=synth.WDTYPE_BF16, quant_lm_head=True, perop=False):
+    """Teacher-forced steps of one batch in which sequence b takes part only in steps < stops[b]
+    (token FF_TOKEN_SKIP afterwards, with a position the kernels must ignore).  Active sequences are
+    compared with the oracle stepped one sequence at a time; a stopped sequence's cache planes and
+    logits row must stay bit for bit what they were."""
+    from paper_2505_22758_amd import binding
+    from oracle import oracle
+    shape, seed, T0 = (synth.TINY if wdtype == synth.WDTYPE_BF16 else synth.TINY.replace(d_ffn=1408)), 0x51, 9
+    max_ctx = T0 + steps + 1
+    layers = [synth.make_layer(shape, seed, l, wdtype, "cpu") for l in range(shape.n_layers)]
+    M = oracle.OracleModel(shape, layers, synth.make_head(shape, seed, wdtype, "cpu", quant_lm_head))
+    okv = []
+    for b in range(nseq):
+        kv = M.new_kv(1, max_ctx)
+        for l in range(shape.n_layers):
+            k, v = synth.make_kv_prefill(shape, seed, l, b, T0, "cpu")
+            kv[l, 0, 0, :T0], kv[l, 0, 1, :T0] = oracle._np(k), oracle._np(v)
+        okv.append(kv)
+    dec, caches = helpers.hip_side(shape, seed, wdtype, nseq, T0, max_ctx, n_caches=2, quant_lm_head=quant_lm_head)
+    step_fn = binding.ff_decode_step_perop if perop else binding.ff_decode_step
+    n_cache_words = shape.n_layers * nseq * shape.n_kv_heads * 2 * max_ctx * shape.head_dim
+    planes = [c[1][:2 * n_cache_words].view(torch.int16).view(shape.n_layers, nseq, -1) for c in caches]   # [layer][sequence][rows of all heads]
+    toks = synth.make_tokens(shape, seed, steps, nseq)
+    pos = [T0] * nseq
+    sentinel = 7.25
+    logits = torch.full((nseq, shape.vocab), sentinel, dtype=torch.float32, device="cuda:0")
+    # One sequence sitting out does not change the others' results by a bit: the same first step on
+    # the second cache with everybody taking part.
+    if stops[0] > 0 and min(stops) == 0:
+        full = torch.zeros_like(logits)
+        step_fn(dec.model, toks[0].contiguous().to("cuda:0"), torch.tensor(pos, dtype=torch.int32, device="cuda:0"), caches[1][0], full, nseq)
+        binding.ff_status(dec.model)
+    else:
+        full = None
+    for s in range(steps):
+        active = [s < stops[b] for b in range(nseq)]
+        tok = toks[s].clone()
+        p = torch.tensor(pos, dtype=torch.int32)
+        for b in range(nseq):
+            if not active[b]:
+                tok[b] = binding.FF_TOKEN_SKIP
+                p[b] = (-7, 10 ** 6, max_ctx)[(s + b) % 3]   # ignored for a sequence that sits the step out
+        frozen = [planes[0][:, b].clone() for b in range(nseq)]
+        step_fn(dec.model, tok.contiguous().to("cuda:0"), p.to("cuda:0"), caches[0][0], logits, nseq)
+        binding.ff_status(dec.model)
+        got = logits.cpu().numpy()
+        for b in range(nseq):
+            if active[b]:
+                ref = M.decode_step(toks[s, b:b + 1].numpy(), np.array([pos[b]], dtype=np.int32), okv[b])
+                ma, rl, same = helpers.compare_logits(got[b:b + 1], ref)
+                assert ma <= helpers.MAX_ABS_TOL and rl <= helpers.REL_L2_TOL and same.all(), (s, b, ma, rl)
+                if s == 0 and full is not None:
+                    assert torch.equal(logits[b], full[b]), ("another sequence sitting out changed this one's logits", b)
+                pos[b] += 1
+                logits[b] = sentinel
+            else:
+                assert (got[b] == sentinel).all(), ("logits written for a sequence that sat the step out", s, b)
+                assert torch.equal(frozen[b], planes[0][:, b]), ("cache touched for a sequence that sat the step out", s, b)
+    dec.close()
+
+
+def test_sequences_that_stop_early_in_a_batch():
+    """Early stop inside a batch (beyond the lock-step batches of the paper's Section 5.2): on the
+    row-partitioned pass of up to four sequences, the wide pass, consecutive passes with the LM head
+    as separate launches, the quantised formats and the per-operation path; also a step in which
+    nobody takes part."""
+    _run_sequences_stopping_early(4, [6, 0, 3, 6], 6)
+    _run_sequences_stopping_early(2, [2, 3], 4)                                   # last step: nobody
+    _run_sequences_stopping_early(1, [1], 2)
+    _run_sequences_stopping_early(7, [5, 0, 5, 2, 5, 1, 3], 5)                     # one wide pass
+    _run_sequences_stopping_early(16, [3] * 5 + [0] + [1] * 9 + [3], 3)
+    _run_sequences_stopping_early(6, [4, 0, 2, 4, 1, 4], 4, wdtype=synth.WDTYPE_INT8, quant_lm_head=False)   # passes of four and two, bf16 LM head
+    _run_sequences_stopping_early(6, [4, 0, 2, 4, 1, 4], 4, wdtype=synth.WDTYPE_INT8)                        # int8 wide pass
+    _run_sequences_stopping_early(3, [3, 0, 1], 3, wdtype=synth.WDTYPE_INT4)
+    _run_sequences_stopping_early(5, [3, 0, 1, 3, 2], 3, perop=True)
+
+
 def test_llama70b_full_depth_batch1_and_batch16_ctx2048(capsys):
     """The 80-layer 70B configuration at full size (139 GB of packed weights): batch 1 for four
     teacher-forced steps and batch 16 for one, context 2048, every logit against the oracle run
