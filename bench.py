@@ -175,6 +175,9 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-bf16-b1-ctx1024", choices=sorted(WORKLOADS))
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (sweeps)")
     ap.add_argument("--ctx", type=int, default=0, help="override the workload's KV context (sweeps)")
+    ap.add_argument("--ctx-list", default="", help="one KV context per sequence, comma separated (ragged batch; overrides --batch and --ctx)")
+    ap.add_argument("--uniform-attention-shares", action="store_true",
+                    help="attention work list with the same number of workgroups for every sequence (default: by length)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-perop", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the streaming-read ceiling measurement")
@@ -198,6 +201,8 @@ def main():
 
     shape_name, wdtype, batch, ctx = WORKLOADS[args.workload]
     batch, ctx = args.batch or batch, args.ctx or ctx
+    ctxs = [int(v) for v in args.ctx_list.split(",")] if args.ctx_list else [ctx] * batch   # rows cached per sequence before the first step
+    batch, ctx = len(ctxs), max(ctxs)
     shape = synth.SHAPES[shape_name]
     seed = 0x250522758
     dev = "cuda:0"
@@ -207,6 +212,8 @@ def main():
 
     # weights and cache prefill: the library's device-side generator (same bits as synth.py, tested)
     dec = binding.Decoder.synthetic(shape, seed, wdtype, max_batch=batch, device=dev)
+    if args.uniform_attention_shares:
+        binding.ff_debug_set_attention_balance(dec.model, False)
     torch.cuda.synchronize()
 
     def new_cache():
@@ -217,7 +224,7 @@ def main():
         return kv, buf
 
     toks = synth.make_tokens(shape, seed, total_steps, batch).to(dev)
-    pos = (torch.arange(total_steps, dtype=torch.int32, device=dev)[:, None] + ctx).repeat(1, batch).contiguous()
+    pos = (torch.arange(total_steps, dtype=torch.int32, device=dev)[:, None] + torch.tensor(ctxs, dtype=torch.int32, device=dev)[None, :]).contiguous()
     logits = torch.zeros(batch, shape.vocab, dtype=torch.float32, device=dev)
 
     def run(fn, kv, n0, n):
@@ -267,7 +274,7 @@ def main():
     kern_ms = float(np.mean(per_step_ms))   # one kernel per step: event spacing = launch duration + gap
 
     wbytes = synth.weight_bytes_per_step(shape, wdtype)
-    kvb = [synth.kv_bytes_per_step(shape, batch, ctx + args.warmup + i) for i in range(args.steps)]
+    kvb = [sum(synth.kv_bytes_per_step(shape, 1, c + args.warmup + i) for c in ctxs) for i in range(args.steps)]
     alg_bytes = wbytes + float(np.mean(kvb))
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
 
@@ -280,13 +287,14 @@ def main():
                     else "activations exchanged between phases as f32 rounded to 22 mantissa bits"
                          + ("" if batch == 1 else ", staged projection inputs as bf16 head + bf16 remainder (17 bits)")),
         "data": "synthetic",
-        "config": {"workload": args.workload if not (args.batch or args.ctx) else f"{args.workload} with batch {batch}, ctx {ctx}",
-                   "batch": batch, "kv_context": ctx,
+        "config": {"workload": args.workload if not (args.batch or args.ctx or args.ctx_list) else f"{args.workload} with batch {batch}, ctx {ctx}",
+                   "batch": batch, "kv_context": ctx if not args.ctx_list else ctxs,
+                   "attention_shares": "equal" if args.uniform_attention_shares else "by length",
                    "weight_bytes_per_step": wbytes, "kv_bytes_per_step_mean": float(np.mean(kvb))},
         "tokens_per_s": batch / (ms_per_step * 1e-3),
         "latency_us_p10_p50_p90": [float(np.percentile(per_step_ms, q)) * 1e3 for q in (10, 50, 90)],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.batch or args.ctx) else measured_traffic(args.workload),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.batch or args.ctx or args.ctx_list) else measured_traffic(args.workload),
                      "kernel": "fused_decode_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": alg_bytes,
                      "ceiling_gbs": ceiling_gbs, "frac_of_ceiling": None if ceiling_gbs is None else achieved / ceiling_gbs},
     }

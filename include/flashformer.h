@@ -240,6 +240,16 @@ int ff_debug_stack_linear(const void *w_dev, int32_t d, int32_t n_layers, const 
  * max_batch 1 only (FF_ERR_UNSUPPORTED otherwise).  Results are identical either way. */
 int ff_debug_set_overlap(ff_model *m, int32_t overlap);
 
+/* Measurement switch for the attention work list.  By default the fused kernel rebuilds the list
+ * every step from the sequences' lengths: each (sequence, kv head) gets one workgroup, the rest of
+ * the grid is dealt out in proportion to the rows each sequence has to read, so a ragged batch is
+ * cut into slices of about equal length (the paper's Section 6 names load balance at variable
+ * context as the case for scheduling at run time; here the list is recomputed per step on the
+ * device, its entries keep fixed owners).  by_length = 0 gives every sequence the same number of
+ * workgroups, as the paper's static partition does; nonzero restores the default.  Results agree
+ * to rounding either way (the slices differ); batches of equal lengths are sliced identically. */
+int ff_debug_set_attention_balance(ff_model *m, int32_t by_length);
+
 /* Test hook for the FF_ERR_TIMEOUT path: while `workgroup` is >= 0, that workgroup of every
  * following fused step leaves at once without publishing anything, so each workgroup that needs its
  * output gives up after its own bounded wait (a fraction of a second), all kernels end normally and

@@ -26,7 +26,7 @@ FF_MAT = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 
 
 EXPORTS = ["ff_last_error", "ff_model_bytes", "ff_model_create", "ff_model_load_layer", "ff_model_load_head",
            "ff_model_load", "ff_model_load_synthetic", "ff_model_free", "ff_kv_bytes", "ff_kv_alloc", "ff_kv_fill", "ff_kv_read", "ff_kv_fill_synthetic", "ff_kv_free",
-           "ff_decode_step", "ff_decode_step_static", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_stream_read", "ff_debug_stack_linear", "ff_debug_set_overlap", "ff_debug_mute_workgroup",
+           "ff_decode_step", "ff_decode_step_static", "ff_decode_step_perop", "ff_status", "ff_debug_dequant", "ff_debug_gemv", "ff_debug_timeline", "ff_debug_stream_read", "ff_debug_stack_linear", "ff_debug_set_overlap", "ff_debug_set_attention_balance", "ff_debug_mute_workgroup",
            "ff_fused_schedule"]
 
 
@@ -76,6 +76,7 @@ _lib.ff_debug_gemv.argtypes = [_vp, _i32, _i32, _vp, _vp, _i32, _i32, _vp]
 _lib.ff_debug_timeline.argtypes = [_vp, _vp]
 _lib.ff_debug_mute_workgroup.argtypes = [_vp, _i32]
 _lib.ff_debug_set_overlap.argtypes = [_vp, _i32]
+_lib.ff_debug_set_attention_balance.argtypes = [_vp, _i32]
 _lib.ff_fused_schedule.argtypes = [_vp, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32)]
 
 
@@ -245,6 +246,10 @@ def ff_debug_timeline(model: int, buf) -> None:
 
 def ff_debug_set_overlap(model: int, overlap: bool) -> None:
     _check(_lib.ff_debug_set_overlap(model, int(overlap)), "ff_debug_set_overlap")
+
+
+def ff_debug_set_attention_balance(model: int, by_length: bool) -> None:
+    _check(_lib.ff_debug_set_attention_balance(model, int(by_length)), "ff_debug_set_attention_balance")
 
 
 def ff_debug_mute_workgroup(model: int, workgroup: int) -> None:

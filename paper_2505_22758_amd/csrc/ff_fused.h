@@ -36,6 +36,9 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 // The projections of all phases run through ONE instance of the streaming loop; what differs per
 // phase (input, epilogue) is selected at run time once per row pair.
 enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3, PH_LM = 4 };
+// Measurement switches of a launch (debug entry points): tiles requested only after the input has
+// arrived; attention shares equal for every sequence instead of by length (attn_share_of).
+enum { kSwNoOverlap = 1, kSwUniformShares = 2 };
 enum { TAG_QKV = 0, TAG_ATT = 1, TAG_O = 2, TAG_GU = 3, TAG_DOWN = 4 };
 
 // Optional profile (100 MHz wall clock), written only while a buffer is set through the debug entry
@@ -150,7 +153,7 @@ __device__ __forceinline__ PhaseDesc phase_desc(const DevModel& M, const int* to
 #define FF_WIDE_SPLIT 1   // K split of the wide pass's output and down projections (0: every workgroup multiplies its own rows over all of K)
 #endif
 template <int WD, int HD, int G>
-__device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, const int* pos_lds, const float2* rope_lds, float* logits, int batch,
+__device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, const int* pos_lds, const int* share_lds, const float2* rope_lds, float* logits, int batch,
                                           int n_lm, int ncta, uint8_t* lds, WgVote& vote, u32 steps_done, u32 sl, u32 tag_base) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -193,7 +196,7 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
         if (D.kind == PH_QKV) wait_epoch = l > 0 ? ebase + 4u * (u32)l : 0u;
         else if (D.kind == PH_O) {
             __syncthreads();   // the previous projection's epilogue has read its sums out of LDS
-            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, 2>(M, KV, pos_lds, batch, l, lds, tag_of(tag_base, l, TAG_QKV), tag_of(tag_base, l, TAG_ATT),
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, 2>(M, KV, pos_lds, share_lds, batch, l, lds, tag_of(tag_base, l, TAG_QKV), tag_of(tag_base, l, TAG_ATT),
                                                                       sl + l, n_ctas, vote, nullptr, M.wimg_a);
             if (!ok) return false;
             sync.arrive(ebase + 4u * (u32)l + 1u);
@@ -253,7 +256,7 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
 template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
-                                                                     int batch, int lm_in_kernel, int ncta, int mute_wg, int no_overlap, int glu_off) {
+                                                                     int batch, int lm_in_kernel, int ncta, int mute_wg, int switches, int glu_off) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     if (!inputs_ok(M, KV, tokens, pos)) {
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(M.status, kStatusRange);
@@ -283,7 +286,12 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     static_assert(kLdsRopeBytes == kMaxBatchFused * 64 * sizeof(float2) && kLdsMiscBytes >= (16 + 2 * (1 + WgVote::kMaxSums) * kFusedWaves) * 4, "LDS layout");
     int* pos_lds = kWide ? (int*)(lds + kLdsActBytes + kLdsAuxBytes + kLdsRopeBytes + kLdsMiscBytes)
                          : (int*)((float*)(lds + kLdsActBytes + kLdsAuxBytes) + 2 * kMaxBatchFused * 64 + 8);
-    if ((int)threadIdx.x < batch) pos_lds[threadIdx.x] = step_pos(tokens, pos, threadIdx.x);   // -1: the sequence sits this step out
+    int* share_lds = pos_lds + (kWide ? kMaxBatchWide : kMaxBatch);   // workgroups per kv head of each sequence's attention (attn_share_of)
+    static_assert(kLdsPairBytes >= 2 * kMaxBatchWide * 4 && 2 * kMaxBatch <= 8, "positions and attention shares in LDS");
+    if ((int)threadIdx.x < batch) {
+        pos_lds[threadIdx.x] = step_pos(tokens, pos, threadIdx.x);   // -1: the sequence sits this step out
+        share_lds[threadIdx.x] = attn_share_of(tokens, pos, batch, threadIdx.x, ncta, M.Hkv, (switches & kSwUniformShares) != 0);
+    }
     if (!kWide && threadIdx.x < 2) ((lds_u32*)(pairbox_of(xs) + 4 * kPairBoxFloats))[threadIdx.x] = 0u;
     if (B == 1 && threadIdx.x < kGluMaxChunks) ((lds_u32*)pairbox_of(xs))[threadIdx.x] = 0u;   // arrival counters of the staged h chunks (glu_run)
     __syncthreads();
@@ -319,7 +327,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
     constexpr bool kScalarState = B > 1;
     constexpr bool kQuad = kQuadOf<WD, B>;   // matrix-core GEMV on groups of four rows, split-bf16 staged input
     if constexpr (kWide) {
-        if (!wide_loop<WD, HD, G>(M, KV, pos_lds, rope_lds, logits, batch, lm_in_kernel, ncta, lds, vote, steps_done, sl, tag_base)) return;
+        if (!wide_loop<WD, HD, G>(M, KV, pos_lds, share_lds, rope_lds, logits, batch, lm_in_kernel, ncta, lds, vote, steps_done, sl, tag_base)) return;
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             xst_u32(M.stepctr + 1, 0u);   // the compact exchange rows were not written: the next narrow pass re-initialises its rows
             xst_u32(M.stepctr, steps_done + 1u);
@@ -345,10 +353,10 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         if (seg > 0) src.wb = nullptr;
         const bool att_first = D.kind == PH_O && seg == 0;
         Stage<WD> ring[kDepthOf<WD>];
-        // (ablation switch, single-sequence bf16 instances only: with no_overlap the tiles are requested
+        // (ablation switch, single-sequence bf16 instances only: with kSwNoOverlap the tiles are requested
         // after the input has arrived, as in a fused kernel without cross-layer memory overlap)
         constexpr bool kHasSwitch = B == 1 && WD == W_BF16;
-        if (!kHasSwitch || !no_overlap) prefetch_stream<kQuad>(S, ring, lane);
+        if (!kHasSwitch || !(switches & kSwNoOverlap)) prefetch_stream<kQuad>(S, ring, lane);
         if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_PF_ISSUED, lane);
         // Touch the descriptor the NEXT phase will fetch, so that it sits in the scalar cache by
         // then instead of costing a trip to memory at the head of that phase.
@@ -363,7 +371,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_ATT_START, lane);
             u64* aev = dbg_stage_slots(M, dbg_phases, ncta, D.layer, 4);
             if (aev && threadIdx.x == 0) { as_global(aev)[0] = wall_clock64(); as_global(aev)[4] = 0; as_global(aev)[5] = 0; }
-            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, FF_ATTN_MODE>(M, KV, pos_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, FF_ATTN_MODE>(M, KV, pos_lds, share_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
                                                                 tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, n_ctas, vote, aev);
             if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
             if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_ATT_END, lane);
@@ -380,7 +388,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             return;
         }
         if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_SYNCED, lane);
-        if (kHasSwitch && no_overlap) prefetch_stream<kQuad>(S, ring, lane);
+        if (kHasSwitch && (switches & kSwNoOverlap)) prefetch_stream<kQuad>(S, ring, lane);
         u64* wv = D.kind < 4 ? dbg_wave_slots(M, dbg_phases, D.layer, wave) : nullptr;
         if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
         bool glu_done = false;
@@ -432,7 +440,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
 // translation unit so that the instances compile in parallel.
 struct FusedLaunch {
     DevModel M; DevKV KV; const int* tokens; const int* pos; float* logits;
-    int batch; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream; int mute_wg; int no_overlap;
+    int batch; int lm_in_kernel; int n_cta; size_t lds_bytes; hipStream_t stream; int mute_wg; int switches;   // switches: kSw* bits
     int glu_off;   // >= 0: single-sequence passes run gate/up + down as one stream (glu_run), staged h at this LDS offset
     int wide;      // the pass runs on the wide instance (K-segmented inputs, LM head outside the kernel)
 };
@@ -452,7 +460,7 @@ inline hipError_t launch_fused_instance(const FusedLaunch& a, const char** what)
         if (occ < 1) { setup_what = "fused kernel does not fit on a compute unit"; setup_err = hipErrorLaunchOutOfResources; }
     });
     if (setup_err != hipSuccess) { *what = setup_what; return setup_err; }
-    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.lm_in_kernel, a.n_cta, a.mute_wg, a.no_overlap, a.glu_off);
+    kern<<<a.n_cta, kFusedThreads, a.lds_bytes, a.stream>>>(a.M, a.KV, a.tokens, a.pos, a.logits, a.batch, a.lm_in_kernel, a.n_cta, a.mute_wg, a.switches, a.glu_off);
     *what = "fused kernel launch";
     return hipGetLastError();
 }

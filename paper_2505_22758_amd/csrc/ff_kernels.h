@@ -58,19 +58,38 @@ __device__ void attention_phase_plain(const DevModel& M, const DevKV& KV, const 
 // kernel down to what the model at hand needs.  `pos` points to the positions staged in LDS and
 // ncta is the grid size: both are read often, and fetching them from global memory here would make
 // the wave wait for every load it has in flight, weight tiles included.
+// Workgroups per (sequence, kv head) for a step's attention, by the sequences' lengths: every
+// sequence gets one per kv head, and what is left of the grid is dealt out in proportion to the
+// rows each has to read (cached rows + its own).  A sequence much longer than its neighbours is cut
+// into correspondingly more slices, so the slices of a ragged batch come out about equally long
+// instead of the long sequence's being as many times longer as it is (the paper names load balance
+// at variable context as the reason for scheduling at run time, Section 6); with equal lengths this
+// is the equal division n_workgroups / (batch * Hkv).  The shares sum to at most n_workgroups / Hkv.
+// Every workgroup computes the same list from the step's positions: the work list is rebuilt each
+// step, its entries have fixed owners, nothing is claimed with atomics.
+__device__ __forceinline__ int attn_share_of(const int* tokens, const int* pos, int batch, int b, int ncta, int Hkv, bool uniform) {
+    const u32 floor_items = (u32)(batch * Hkv);
+    const u32 budget = (u32)ncta > floor_items ? (u32)ncta - floor_items : 0u;
+    if (uniform) return 1 + (int)(budget / floor_items);
+    u32 tot = 0;
+    for (int i = 0; i < batch; i++) tot += (u32)max(step_pos(tokens, pos, i), 0) + 1u;
+    const u32 mine = (u32)max(step_pos(tokens, pos, b), 0) + 1u;
+    return 1 + (int)((u32)((u64)budget * mine / tot) / (u32)Hkv);
+}
+
+// share: workgroups per kv head of each sequence (attn_share_of), staged in LDS like the positions.
 template <int NW, int HD, int G, int MODE = 0>
-__device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, int batch, int layer,
+__device__ __forceinline__ bool attention_phase_tagged(const DevModel& M, const DevKV& KV, const int* pos, const int* share, int batch, int layer,
                                                        uint8_t* lds, u32 in_tag, u32 out_tag, u32 out_cnt, const UDiv& nc, WgVote& vote, u64* ev = nullptr,
                                                        uint8_t* merged_img = nullptr) {
     constexpr int NT = NW * 64;
     const int ncta = (int)nc.n;
-    const int share = max(1, (int)((u32)ncta / (u32)(batch * M.Hkv)));
     int base = 0;
     bool ok = true;
     TaggedAttnIO xio{in_tag, out_tag, &vote};
     for (int b = 0; b < batch; b++) {
         const int T = max(pos[b], 0);   // (-1: the sequence sits this step out and is carried as a placeholder with an empty cache)
-        const int ns = attn_nsplit(T, share);
+        const int ns = attn_nsplit(T, share[b]);
         const int nitems = M.Hkv * ns;
         // (32-bit unsigned arithmetic throughout: this runs between the end of the QKV projection
         // and the first cache loads, and 64-bit or signed divisions are long instruction sequences)

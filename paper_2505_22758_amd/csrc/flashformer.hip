@@ -208,7 +208,7 @@ struct ff_model {
     int n_cta;
     size_t lds_bytes;
     int mute_wg = -1;   // test hook (ff_debug_mute_workgroup)
-    int no_overlap = 0; // ablation switch (ff_debug_set_overlap)
+    int switches = 0;   // kSw* bits of the fused launches (ff_debug_set_overlap, ff_debug_set_attention_balance)
     int glu_off = -1;   // >= 0: LDS offset of the staged SwiGLU output when gate/up + down run as one stream (glu_run)
 };
 struct ff_kv {
@@ -655,7 +655,7 @@ int fused_pass(ff_model* m, const DevModel& D, const int32_t* tokens_dev, const 
         k_scrub_rows<<<64, kThreads, 0, st>>>(D, batch);
         HIPCHK(hipGetLastError());
     }
-    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg, m->no_overlap, m->glu_off,
+    FusedLaunch a{D, kvd, tokens_dev, positions_dev, logits_dev, batch, lm_in_kernel, m->n_cta, m->lds_bytes, st, m->mute_wg, m->switches, m->glu_off,
                   wide ? 1 : 0};
     const char* what = "";
     const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
@@ -985,7 +985,13 @@ int ff_debug_set_overlap(ff_model* m, int32_t overlap) {
     if (!m) return fail(FF_ERR_ARG, "null argument");
     if (!overlap && (m->cfg.wdtype != W_BF16 || m->cfg.max_batch != 1))
         return fail(FF_ERR_UNSUPPORTED, "the no-overlap variant exists for bf16 models with max_batch 1 only");
-    m->no_overlap = overlap ? 0 : 1;
+    m->switches = overlap ? (m->switches & ~kSwNoOverlap) : (m->switches | kSwNoOverlap);
+    return FF_OK;
+}
+
+int ff_debug_set_attention_balance(ff_model* m, int32_t by_length) {
+    if (!m) return fail(FF_ERR_ARG, "null argument");
+    m->switches = by_length ? (m->switches & ~kSwUniformShares) : (m->switches | kSwUniformShares);
     return FF_OK;
 }
 

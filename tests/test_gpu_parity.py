@@ -91,7 +91,7 @@ def oracle_bits_to_f64(a):
 
 
 def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, gpu_generated=False, quant_lm_head=True, perop_steps=None,
-                        capsys=None):
+                        capsys=None, attention_by_length=True):
     """Teacher-forced decoding on both sides; every logit of every step is compared.  perop_steps
     limits how many steps the per-operation path runs as well (it shares no kernels' schedule with
     the fused one; long runs check it on their first steps only)."""
@@ -104,6 +104,8 @@ def _run_teacher_forced(shape, seed, wdtype, batch, T0, steps, check_kv=True, gp
     else:
         M, okv = helpers.oracle_side(shape, seed, wdtype, batch, T0, max_ctx, quant_lm_head=quant_lm_head)
         dec, caches = helpers.hip_side(shape, seed, wdtype, batch, T0, max_ctx, n_caches=2, quant_lm_head=quant_lm_head)
+    if not attention_by_length:
+        binding.ff_debug_set_attention_balance(dec.model, False)
     toks = synth.make_tokens(shape, seed, steps, batch)
     logits_f = torch.zeros(batch, shape.vocab, dtype=torch.float32, device="cuda:0")
     logits_p = torch.zeros_like(logits_f)
@@ -173,6 +175,17 @@ def test_sequences_of_different_lengths_in_one_batch():
     _run_teacher_forced(synth.TINY, 71, synth.WDTYPE_BF16, batch=4, T0=[0, 5, 77, 300], steps=3)
     _run_teacher_forced(synth.TINY, 72, synth.WDTYPE_BF16, batch=7, T0=[1, 0, 130, 64, 63, 65, 9], steps=2)
     _run_teacher_forced(synth.LLAMA_8B, 0x250522766, synth.WDTYPE_BF16, batch=4, T0=[1024, 1000, 7, 2048], steps=1, gpu_generated=True)
+
+
+def test_attention_work_list_follows_the_lengths():
+    """One long sequence among short ones: the step's attention work list gives it most of the grid
+    (16 slices where equal shares allow 8, resp. 2 in the wide pass); both forms of the list against
+    the oracle, on a model with 8 kv heads (32 / 96 head groups on 256 workgroups)."""
+    S = synth.TINY.replace(name="kv8", n_layers=2, n_q_heads=32, n_kv_heads=8)
+    for by_length in (True, False):
+        _run_teacher_forced(S, 0x2505227a0, synth.WDTYPE_BF16, batch=4, T0=[2100, 3, 40, 0], steps=2, perop_steps=1, attention_by_length=by_length)
+        _run_teacher_forced(S, 0x2505227a1, synth.WDTYPE_BF16, batch=12, T0=[5, 1800] + [6 * i for i in range(10)], steps=2, perop_steps=1,
+                            attention_by_length=by_length)
 
 
 def test_tiny_batches_above_one_pass():
