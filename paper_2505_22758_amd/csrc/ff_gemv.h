@@ -28,6 +28,24 @@ template <int WD> constexpr int kUnrOf = WD == W_INT4 ? 2 : FF_UNR;
 #endif
 template <int WD> constexpr int kDepthOf = WD == W_INT4 ? 2 * FF_DEPTH : FF_DEPTH;
 template <int WD> constexpr int kChunkUnitsOf = 64 * kUnrOf<WD>;   // units of one row covered by one stage of one wave
+// Refill granularity of the single-sequence streams: a ring slot is refilled in kRefillParts parts,
+// each right behind the multiply-accumulates that freed its registers, so that 16 - 8 / parts of
+// the wave's 16 loads stay in flight while a stage is being multiplied (8 with whole-stage refills).
+#ifndef FF_REFILL_PARTS
+#define FF_REFILL_PARTS 2
+#endif
+#ifndef FF_REFILL_PARTS_I4
+#define FF_REFILL_PARTS_I4 1
+#endif
+template <int WD, int B> constexpr int kRefillPartsOf = B != 1 ? 1 : WD == W_INT4 ? FF_REFILL_PARTS_I4 : (kUnrOf<WD> % FF_REFILL_PARTS == 0 ? FF_REFILL_PARTS : 1);
+template <int U0, int U1> struct StageUnits { static constexpr int u0 = U0, u1 = U1; };   // units [U0, U1) of a stage
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(StageUnits<I, N>{});   // (I of N: the callee derives its unit range)
+        static_for<I + 1, N>(f);
+    }
+}
 // With two or more sequences per pass the projections run on the matrix cores in groups of four
 // rows (gemv_run_quad below) instead of row pairs on the vector ALUs.
 template <int WD, int B> constexpr bool kQuadOf = B > 1;
@@ -288,11 +306,11 @@ struct Stream {
 // Issue the loads of iteration (pair, chunk).  Every load is issued unconditionally from a clamped
 // address: out-of-range units meet zeros in the staged input, out-of-range rows are dropped by the
 // epilogue.  Nothing is converted here, so no load result is waited for at issue time.
-template <int WD, int B>
+template <int WD, int B, int U0 = 0, int U1 = kUnrOf<WD>>
 __device__ __forceinline__ void load_stage(const Stream<WD, B>& S, int pair, int chunk, Stage<WD>& st, int lane) {
     constexpr int kUnr = kUnrOf<WD>;
 #pragma unroll
-    for (int u = 0; u < kUnr; u++) {
+    for (int u = U0; u < U1; u++) {
         const int j = min((chunk * kUnr + u) * 64 + lane, S.nunits - 1);
 #pragma unroll
         for (int r = 0; r < 2; r++) {
@@ -305,7 +323,7 @@ __device__ __forceinline__ void load_stage(const Stream<WD, B>& S, int pair, int
             }
         }
     }
-    if constexpr (WD == W_INT8) {
+    if constexpr (WD == W_INT8 && U1 == kUnr) {
         if (chunk == S.cpr - 1) {
             st.rs[0] = as_global(S.s)[min(2 * pair, S.N - 1)];
             st.rs[1] = as_global(S.s)[min(2 * pair + 1, S.N - 1)];
@@ -353,12 +371,12 @@ __device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD>
 }
 
 // The multiply-accumulates of one stage: chunk cc of a row pair against the staged input.
-template <int WD, int B>
+template <int WD, int B, int U0 = 0, int U1 = kUnrOf<WD>>
 __device__ __forceinline__ void stage_fma(const Stage<WD>& st, const float4* xs, int nup, int cc, int lane, float (&acc)[2][B]) {
     constexpr int kUnr = kUnrOf<WD>;
     constexpr int NQ = WTraits<WD>::EPU / 4;
 #pragma unroll
-    for (int u = 0; u < kUnr; u++) {
+    for (int u = U0; u < U1; u++) {
         const int j = (cc * kUnr + u) * 64 + lane;
 #pragma unroll
         for (int b = 0; b < B; b++) {
@@ -415,8 +433,11 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
     int pl = S.p0, cl = 0;          // (pair, chunk) of the next load = iteration kDepth
     for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
 
-    auto compute = [&](const Stage<WD>& st) {
-        stage_fma<WD, B>(st, xs, nup, cc, lane, acc);
+    constexpr int kUnr = kUnrOf<WD>, kParts = kRefillPartsOf<WD, B>;
+    auto compute = [&](const Stage<WD>& st, auto units) {   // units: the StageUnits range multiplied by this call; the last one finishes the iteration
+        constexpr int U0 = decltype(units)::u0, U1 = decltype(units)::u1;
+        stage_fma<WD, B, U0, U1>(st, xs, nup, cc, lane, acc);
+        if constexpr (U1 < kUnr) return;
         if (cc == S.cpr - 1) {   // row pair finished (for this K segment)
             const int lp = pc - S.p0;
 #pragma unroll
@@ -436,8 +457,10 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
         }
         if (++cc == S.cpr) { cc = 0; ++pc; }
     };
-    auto load = [&](Stage<WD>& st) {
-        load_stage(S, pl, cl, st, lane);
+    auto load = [&](Stage<WD>& st, auto units) {
+        constexpr int U0 = decltype(units)::u0, U1 = decltype(units)::u1;
+        load_stage<WD, B, U0, U1>(S, pl, cl, st, lane);
+        if constexpr (U1 < kUnr) return;
         if (++cl == S.cpr) { cl = 0; ++pl; }
     };
     int it = 0;
@@ -447,10 +470,14 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
         for (int s = 0; s < kDepth; s++) {
             // keep the instruction scheduler from hoisting a slot's refill above the FMAs that
             // still read the slot: that doubles the live tile registers and ends in spills
-            compute(ring[s]);
-            __builtin_amdgcn_sched_barrier(0);
-            load(ring[s]);
-            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, kParts>([&](auto part) {
+                constexpr int P = decltype(part)::u0;
+                typedef StageUnits<P * kUnr / kParts, (P + 1) * kUnr / kParts> Units;
+                compute(ring[s], Units{});
+                __builtin_amdgcn_sched_barrier(0);
+                load(ring[s], Units{});
+                __builtin_amdgcn_sched_barrier(0);
+            });
         }
     }
     // tail
@@ -458,9 +485,9 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
 #pragma unroll
         for (int s = 0; s < kDepth; s++) {
             if (it + s < S.n_it) {
-                compute(ring[s]);
+                compute(ring[s], StageUnits<0, kUnr>{});
                 __builtin_amdgcn_sched_barrier(0);
-                if (it + s + kDepth < S.n_it) load(ring[s]);
+                if (it + s + kDepth < S.n_it) load(ring[s], StageUnits<0, kUnr>{});
                 __builtin_amdgcn_sched_barrier(0);
             }
         }

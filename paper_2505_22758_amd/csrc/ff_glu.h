@@ -122,9 +122,12 @@ __device__ __forceinline__ bool glu_run(const Stream<WD, 1>& Sg, const Stream<WD
     int pairs_done = 0;   // gate/up pairs this wave has finished
     bool ok = true;
 
-    auto compute = [&](const Stage<WD>& st) {
+    constexpr int kUnr = kUnrOf<WD>, kParts = kRefillPartsOf<WD, 1>;
+    auto compute = [&](const Stage<WD>& st, auto units) {   // units: the StageUnits range multiplied by this call (first: the chunk's checks, last: the iteration's end)
+        constexpr int U0 = decltype(units)::u0, U1 = decltype(units)::u1;
         if (!cc.down) {
-            stage_fma<WD, 1>(st, xs, Sg.nup, cc.chunk, lane, acc);
+            stage_fma<WD, 1, U0, U1>(st, xs, Sg.nup, cc.chunk, lane, acc);
+            if constexpr (U1 < kUnr) return;
             if (cc.chunk == Sg.cpr - 1) {
                 float v0 = wave_sum_uniform(acc[0][0]), v1 = wave_sum_uniform(acc[1][0]);
                 acc[0][0] = acc[1][0] = 0.f;
@@ -134,7 +137,7 @@ __device__ __forceinline__ bool glu_run(const Stream<WD, 1>& Sg, const Stream<WD
             }
         } else {
             const int pl = cc.pair - Sd.p0;
-            if (pl == 0) {
+            if (U0 == 0 && pl == 0) {
                 // first row pair of a chunk: the chunk must be staged (normally it has been for a while)
                 if (__builtin_expect(stg.staged <= cc.chunk, 0)) ok = stg.finish(cc.chunk, tid, lane) && ok;
                 bool there = false;
@@ -146,8 +149,9 @@ __device__ __forceinline__ bool glu_run(const Stream<WD, 1>& Sg, const Stream<WD
                 ok = ok && there;
             }
             float* la = lacc + (size_t)pl * 128 + lane;
-            if (cc.chunk > 0) { acc[0][0] = la[0]; acc[1][0] = la[64]; }
-            stage_fma<WD, 1>(st, stg.hs, Sd.nup, cc.chunk, lane, acc);
+            if (U0 == 0 && cc.chunk > 0) { acc[0][0] = la[0]; acc[1][0] = la[64]; }
+            stage_fma<WD, 1, U0, U1>(st, stg.hs, Sd.nup, cc.chunk, lane, acc);
+            if constexpr (U1 < kUnr) return;
             if (cc.chunk == Sd.cpr - 1) {
                 float v0 = wave_sum_uniform(acc[0][0]), v1 = wave_sum_uniform(acc[1][0]);
                 if constexpr (WD == W_INT8) { v0 *= f16_to_f((f16_t)st.rs[0]); v1 *= f16_to_f((f16_t)st.rs[1]); }
@@ -159,10 +163,11 @@ __device__ __forceinline__ bool glu_run(const Stream<WD, 1>& Sg, const Stream<WD
         }
         advance(cc);
     };
-    auto load = [&](Stage<WD>& st) {
-        if (!lc.down) load_stage(Sg, lc.pair, lc.chunk, st, lane);
-        else load_stage(Sd, lc.pair, lc.chunk, st, lane);
-        advance(lc);
+    auto load = [&](Stage<WD>& st, auto units) {
+        constexpr int U0 = decltype(units)::u0, U1 = decltype(units)::u1;
+        if (!lc.down) load_stage<WD, 1, U0, U1>(Sg, lc.pair, lc.chunk, st, lane);
+        else load_stage<WD, 1, U0, U1>(Sd, lc.pair, lc.chunk, st, lane);
+        if constexpr (U1 == kUnr) advance(lc);
     };
     // chunks of h whose producing pairs this wave itself has finished, with one pair of slack (the
     // other waves are usually within a pair of this one)
@@ -171,10 +176,14 @@ __device__ __forceinline__ bool glu_run(const Stream<WD, 1>& Sg, const Stream<WD
     for (; it + 2 * kDepth <= n_total && ok; it += kDepth) {
 #pragma unroll
         for (int s = 0; s < kDepth; s++) {
-            compute(ring[s]);
-            __builtin_amdgcn_sched_barrier(0);
-            load(ring[s]);
-            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, kParts>([&](auto part) {
+                constexpr int P = decltype(part)::u0;
+                typedef StageUnits<P * kUnr / kParts, (P + 1) * kUnr / kParts> Units;
+                compute(ring[s], Units{});
+                __builtin_amdgcn_sched_barrier(0);
+                load(ring[s], Units{});
+                __builtin_amdgcn_sched_barrier(0);
+            });
             if (s == 0) stg.step(ready_chunks(), tid, lane);
         }
     }
@@ -182,9 +191,9 @@ __device__ __forceinline__ bool glu_run(const Stream<WD, 1>& Sg, const Stream<WD
 #pragma unroll
         for (int s = 0; s < kDepth; s++) {
             if (it + s < n_total) {
-                compute(ring[s]);
+                compute(ring[s], StageUnits<0, kUnr>{});
                 __builtin_amdgcn_sched_barrier(0);
-                if (it + s + kDepth < n_total) load(ring[s]);
+                if (it + s + kDepth < n_total) load(ring[s], StageUnits<0, kUnr>{});
                 __builtin_amdgcn_sched_barrier(0);
                 if (s == 0) stg.step(ready_chunks(), tid, lane);
             }
