@@ -250,9 +250,18 @@ __device__ __forceinline__ bool wide_loop(const DevModel& M, const DevKV& KV, co
     return true;
 }
 
+// Attention form of the passes of up to four sequences (see attn_item): 0 = row by row on the vector
+// ALU, 1 = scores of 16 cached rows at a time on the matrix cores (head dimension 128 only).  With
+// eight query heads per KV head the row-wise form is bound by the vector ALU (the 70B shape at batch
+// 1: 23.8 -> 23.3 ms per step with form 1); with four, form 1 is ahead by 0.2 % (8B bf16, batch 1,
+// context 1024) to 1.1 % (context 6144).  FF_ATTN_MODE / FF_ATTN_MODE_I4 override at build time.
 #ifndef FF_ATTN_MODE
-#define FF_ATTN_MODE 0   // attention form of the passes of up to four sequences (see attn_item)
+#define FF_ATTN_MODE 1
 #endif
+#ifndef FF_ATTN_MODE_I4
+#define FF_ATTN_MODE_I4 0   // int4 instances: form 1 spills a few registers at batch 2-4 and measured 1 % slower there
+#endif
+template <int WD> constexpr int kAttnModeOf = WD == W_INT4 ? FF_ATTN_MODE_I4 : FF_ATTN_MODE;
 template <int WD, int B, int HD, int G>
 __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M, DevKV KV, const int* __restrict__ tokens,
                                                                      const int* __restrict__ pos, float* __restrict__ logits,
@@ -356,7 +365,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
         // (ablation switch, single-sequence bf16 instances only: with kSwNoOverlap the tiles are requested
         // after the input has arrived, as in a fused kernel without cross-layer memory overlap)
         constexpr bool kHasSwitch = B == 1 && WD == W_BF16;
-        if (!kHasSwitch || !(switches & kSwNoOverlap)) prefetch_stream<kQuad>(S, ring, lane);
+        if (!kHasSwitch || !(switches & kSwNoOverlap)) prefetch_stream<kQuad>(S, ring, lane, 0, kPrefetchOf<WD>);
         if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_PF_ISSUED, lane);
         // Touch the descriptor the NEXT phase will fetch, so that it sits in the scalar cache by
         // then instead of costing a trip to memory at the head of that phase.
@@ -371,7 +380,7 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_ATT_START, lane);
             u64* aev = dbg_stage_slots(M, dbg_phases, ncta, D.layer, 4);
             if (aev && threadIdx.x == 0) { as_global(aev)[0] = wall_clock64(); as_global(aev)[4] = 0; as_global(aev)[5] = 0; }
-            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, FF_ATTN_MODE>(M, KV, pos_lds, share_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
+            const bool ok = attention_phase_tagged<kFusedWaves, HD, G, kAttnModeOf<WD>>(M, KV, pos_lds, share_lds, batch, D.layer, lds, tag_of(tag_base, D.layer, TAG_QKV),
                                                                 tag_of(tag_base, D.layer, TAG_ATT), sl + D.layer, n_ctas, vote, aev);
             if (aev && threadIdx.x == 0) as_global(aev)[6] = wall_clock64();
             if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_ATT_END, lane);
@@ -388,7 +397,8 @@ __global__ void __launch_bounds__(kFusedThreads) fused_decode_kernel(DevModel M,
             return;
         }
         if (wave == 0) dbg_event(M, min(ph, dbg_phases - 1), EV_SYNCED, lane);
-        if (kHasSwitch && (switches & kSwNoOverlap)) prefetch_stream<kQuad>(S, ring, lane);
+        if (kHasSwitch && (switches & kSwNoOverlap)) prefetch_stream<kQuad>(S, ring, lane, 0, kPrefetchOf<WD>);
+        if constexpr (kPrefetchOf<WD> < kDepthOf<WD>) prefetch_stream<kQuad>(S, ring, lane, kPrefetchOf<WD>, kDepthOf<WD>);   // the rest of the ring, behind the input
         u64* wv = D.kind < 4 ? dbg_wave_slots(M, dbg_phases, D.layer, wave) : nullptr;
         if (wv && lane == 0) as_global(wv)[4 + D.kind] = wall_clock64();
         bool glu_done = false;

@@ -38,6 +38,10 @@ template <int WD> constexpr int kChunkUnitsOf = 64 * kUnrOf<WD>;   // units of o
 #define FF_REFILL_PARTS_I4 1
 #endif
 template <int WD, int B> constexpr int kRefillPartsOf = B != 1 ? 1 : WD == W_INT4 ? FF_REFILL_PARTS_I4 : (kUnrOf<WD> % FF_REFILL_PARTS == 0 ? FF_REFILL_PARTS : 1);
+#ifndef FF_REFILL_PARTS_QUAD
+#define FF_REFILL_PARTS_QUAD 2
+#endif
+template <int WD> constexpr int kQuadRefillPartsOf = WD == W_INT4 ? 1 : FF_REFILL_PARTS_QUAD;   // the same for the matrix-core streams of 2-4 sequences
 template <int U0, int U1> struct StageUnits { static constexpr int u0 = U0, u1 = U1; };   // units [U0, U1) of a stage
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -333,13 +337,13 @@ __device__ __forceinline__ void load_stage(const Stream<WD, B>& S, int pair, int
 
 // The same for a group of four rows: lane (blk = lane / 4, r = lane % 4) loads unit blk of row r of
 // each of the stage's 16-unit slices, i.e. a wave load covers 256 contiguous bytes of four rows.
-template <int WD, int B>
+template <int WD, int B, int U0 = 0, int U1 = kQuadLoadsOf<WD>>
 __device__ __forceinline__ void load_stage_quad(const Stream<WD, B>& S, int grp, int chunk, Stage<WD>& st, int lane) {
     constexpr int NL = kQuadLoadsOf<WD>, kUnr = kUnrOf<WD>;
     const int row = min(4 * grp + (lane & 3), S.N - 1);
     const uint8_t* rp = S.w + (size_t)row * S.rowb + (size_t)S.j0 * 16;
 #pragma unroll
-    for (int u = 0; u < NL; u++) {
+    for (int u = U0; u < U1; u++) {
         const int j = min((chunk * NL + u) * 16 + (lane >> 2), S.nunits - 1);
         st.w[u / kUnr][u % kUnr] = ldg_stream(rp + (size_t)j * 16);
         if constexpr (WD == W_INT4) {
@@ -348,26 +352,32 @@ __device__ __forceinline__ void load_stage_quad(const Stream<WD, B>& S, int grp,
             st.z[u / kUnr][u % kUnr] = as_global(S.z)[gi];
         }
     }
-    if constexpr (WD == W_INT8) {
+    if constexpr (WD == W_INT8 && U1 == NL) {
         st.rs[0] = as_global(S.s)[row];   // this lane's row (every stage: a wave may end in the middle of a group)
     }
 }
 
-// Issue the first min(kDepth, n_it) iterations of a stream into the ring; returns how many.
+// Issue iterations [s0, min(s1, n_it)) of a stream into ring slots of the same index (by default the
+// whole ring: the first min(kDepth, n_it) iterations).
+// FF_PREFETCH_STAGES: how many of them the fused kernel requests BEFORE it waits for a projection's
+// input (what is requested across a hand-over queues in front of the input's loads); the rest of the
+// ring is requested once the input is there.
+#ifndef FF_PREFETCH_STAGES
+#define FF_PREFETCH_STAGES FF_DEPTH
+#endif
+template <int WD> constexpr int kPrefetchOf = (WD == W_INT4 ? 2 : 1) * (FF_PREFETCH_STAGES < FF_DEPTH ? FF_PREFETCH_STAGES : FF_DEPTH);
 template <bool QUAD, int WD, int B>
-__device__ __forceinline__ int prefetch_stream(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], int lane) {
+__device__ __forceinline__ void prefetch_stream(const Stream<WD, B>& S, Stage<WD> (&ring)[kDepthOf<WD>], int lane, int s0 = 0, int s1 = kDepthOf<WD>) {
     constexpr int kDepth = kDepthOf<WD>;
-    int pair = S.p0, chunk = S.c0, n = 0;
+    int pair = S.p0, chunk = S.c0;
 #pragma unroll
     for (int s = 0; s < kDepth; s++) {
-        if (s < S.n_it) {
+        if (s >= s0 && s < s1 && s < S.n_it) {
             if constexpr (QUAD) load_stage_quad(S, pair, chunk, ring[s], lane);
             else load_stage(S, pair, chunk, ring[s], lane);
-            if (++chunk == S.cpr) { chunk = 0; ++pair; }
-            n = s + 1;
         }
+        if (++chunk == S.cpr) { chunk = 0; ++pair; }
     }
-    return n;
 }
 
 // The multiply-accumulates of one stage: chunk cc of a row pair against the staged input.
@@ -542,7 +552,9 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
     for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
 
     auto half = [](u32 a, u32 b) { u32x2 v{a, b}; return __builtin_bit_cast(mfma_s4, v); };
-    auto compute = [&](const Stage<WD>& st, bool last) {
+    constexpr int kParts = kQuadRefillPartsOf<WD>;
+    auto compute = [&](const Stage<WD>& st, bool last, auto units) {   // units: the StageUnits range of the stage's loads multiplied by this call; the last one finishes the iteration
+        constexpr int U0 = decltype(units)::u0, U1 = decltype(units)::u1;
         // int4: the staged inputs of unit u+1 are requested from LDS before unit u is multiplied
         // (with one wave per SIMD nothing else hides the LDS latency, and a unit needs nine reads)
         u32x4 hx[2][4], lx[2][4];
@@ -558,7 +570,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
         };
         if constexpr (WD == W_INT4) fetch(0, 0);
 #pragma unroll
-        for (int u = 0; u < NL; u++) {
+        for (int u = U0; u < U1; u++) {
             const int off = (cc * NL + u) * 16;
             const u32x4 w = st.w[u / kUnr][u % kUnr];
             if constexpr (WD == W_INT4) {
@@ -627,6 +639,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
                 acc0[0][3] = fmaf(quad_bcast<3>(sc), fmaf(-quad_bcast<3>(zp), X, dh[3] + dl[3]), acc0[0][3]);
             }
         }
+        if constexpr (U1 < NL) return;
         if (cc == S.cpr - 1 || last) {   // group finished (for this K segment, or this wave's part of it): add up the sixteen blocks
             float t[NC][4];
 #pragma unroll
@@ -703,27 +716,33 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
         }
         if (++cc == S.cpr) { cc = 0; ++pc; }
     };
-    auto load = [&](Stage<WD>& st) {
-        load_stage_quad(S, pl, cl, st, lane);
+    auto load = [&](Stage<WD>& st, auto units) {
+        constexpr int U0 = decltype(units)::u0, U1 = decltype(units)::u1;
+        load_stage_quad<WD, B, U0, U1>(S, pl, cl, st, lane);
+        if constexpr (U1 < NL) return;
         if (++cl == S.cpr) { cl = 0; ++pl; }
     };
     int it = 0;
     for (; it + 2 * kDepth <= S.n_it; it += kDepth) {
 #pragma unroll
         for (int s = 0; s < kDepth; s++) {
-            compute(ring[s], false);
-            __builtin_amdgcn_sched_barrier(0);
-            load(ring[s]);
-            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, kParts>([&](auto part) {
+                constexpr int P = decltype(part)::u0;
+                typedef StageUnits<P * NL / kParts, (P + 1) * NL / kParts> Units;
+                compute(ring[s], false, Units{});
+                __builtin_amdgcn_sched_barrier(0);
+                load(ring[s], Units{});
+                __builtin_amdgcn_sched_barrier(0);
+            });
         }
     }
     for (; it < S.n_it; it += kDepth) {
 #pragma unroll
         for (int s = 0; s < kDepth; s++) {
             if (it + s < S.n_it) {
-                compute(ring[s], it + s == S.n_it - 1);
+                compute(ring[s], it + s == S.n_it - 1, StageUnits<0, NL>{});
                 __builtin_amdgcn_sched_barrier(0);
-                if (it + s + kDepth < S.n_it) load(ring[s]);
+                if (it + s + kDepth < S.n_it) load(ring[s], StageUnits<0, NL>{});
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
