@@ -38,6 +38,9 @@ template <int WD> constexpr int kChunkUnitsOf = 64 * kUnrOf<WD>;   // units of o
 #define FF_REFILL_PARTS_I4 1
 #endif
 template <int WD, int B> constexpr int kRefillPartsOf = B != 1 ? 1 : WD == W_INT4 ? FF_REFILL_PARTS_I4 : (kUnrOf<WD> % FF_REFILL_PARTS == 0 ? FF_REFILL_PARTS : 1);
+#ifndef FF_XQ_PRELOAD
+#define FF_XQ_PRELOAD 0
+#endif
 #ifndef FF_REFILL_PARTS_QUAD
 #define FF_REFILL_PARTS_QUAD 2
 #endif
@@ -423,6 +426,49 @@ __device__ __forceinline__ void stage_fma(const Stage<WD>& st, const float4* xs,
     }
 }
 
+// The staged inputs of a whole stage read from LDS ahead of its multiply-accumulates (single
+// sequence, bf16 and int8 weights): with one wave per SIMD nothing else hides the latency of an LDS read,
+// and a read issued right in front of its use costs that latency once per unit.  With
+// FF_X_PRELOAD the reads of all units of a stage (int8: of a part) are issued when its first part
+// (the part) starts (8B bf16, batch 1: 2968 -> 2946 us per step; issuing them a whole stage ahead
+// gained nothing further).
+#ifndef FF_X_PRELOAD
+#define FF_X_PRELOAD 1
+#endif
+template <int WD, int B> constexpr bool kXPreloadOf = FF_X_PRELOAD && (WD == W_BF16 || WD == W_INT8) && B == 1;
+template <int WD> constexpr int kXQuadsOf = WTraits<WD>::EPU / 4;   // float4 reads per unit (bf16: 2, int8: 4)
+// Units [U0, U1) of a stage: bf16 reads the whole stage's inputs with its first part (16 registers per
+// part), int8 each part's inputs when the part starts (its units are twice as wide).
+template <int WD, int U0, int U1>
+__device__ __forceinline__ void stage_x_load(const float4* xs, int nup, int cc, int lane, float4 (&xr)[kUnrOf<WD>][kXQuadsOf<WD>]) {
+    constexpr int kUnr = kUnrOf<WD>, NX = kXQuadsOf<WD>;
+    constexpr int L0 = WD == W_BF16 ? 0 : U0, L1 = WD == W_BF16 ? (U0 == 0 ? kUnr : 0) : U1;
+#pragma unroll
+    for (int u = L0; u < L1; u++) {
+        const float4* xq = xs + (cc * kUnr + u) * 64 + lane;
+#pragma unroll
+        for (int q = 0; q < NX; q++) xr[u][q] = xq[q * nup];
+    }
+}
+template <int WD, int U0, int U1>
+__device__ __forceinline__ void stage_fma_x(const Stage<WD>& st, const float4 (&xr)[kUnrOf<WD>][kXQuadsOf<WD>], float (&acc)[2][1]) {
+#pragma unroll
+    for (int u = U0; u < U1; u++) {
+        if constexpr (WD == W_BF16) {
+            acc[0][0] = dot_bf16(st.w[0][u], xr[u][0], xr[u][1], acc[0][0]);
+            acc[1][0] = dot_bf16(st.w[1][u], xr[u][0], xr[u][1], acc[1][0]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 2; r++) {
+                float a = acc[r][0];
+                a = dot_i8x4(st.w[r][u].x, xr[u][0], a); a = dot_i8x4(st.w[r][u].y, xr[u][1], a);
+                a = dot_i8x4(st.w[r][u].z, xr[u][2], a); a = dot_i8x4(st.w[r][u].w, xr[u][3], a);
+                acc[r][0] = a;
+            }
+        }
+    }
+}
+
 // Weight-streaming GEMV over one stream for up to B batch rows (paper Section 4.2: batch-one
 // projections are matrix-vector products with the input cached on chip and each workgroup owning
 // some rows of W; Section 5.2: at batch 2-4 the weights are still read exactly once and the inputs
@@ -444,9 +490,13 @@ __device__ __forceinline__ void gemv_run(const Stream<WD, B>& S, Stage<WD> (&rin
     for (int s = 0; s < kDepth; s++) if (++cl == S.cpr) { cl = 0; ++pl; }
 
     constexpr int kUnr = kUnrOf<WD>, kParts = kRefillPartsOf<WD, B>;
+    float4 xr[kUnr][kXQuadsOf<WD>];   // (kXPreloadOf) the stage's inputs, read ahead of their multiply-accumulates
     auto compute = [&](const Stage<WD>& st, auto units) {   // units: the StageUnits range multiplied by this call; the last one finishes the iteration
         constexpr int U0 = decltype(units)::u0, U1 = decltype(units)::u1;
-        stage_fma<WD, B, U0, U1>(st, xs, nup, cc, lane, acc);
+        if constexpr (kXPreloadOf<WD, B>) {
+            stage_x_load<WD, U0, U1>(xs, nup, cc, lane, xr);
+            stage_fma_x<WD, U0, U1>(st, xr, acc);
+        } else stage_fma<WD, B, U0, U1>(st, xs, nup, cc, lane, acc);
         if constexpr (U1 < kUnr) return;
         if (cc == S.cpr - 1) {   // row pair finished (for this K segment)
             const int lp = pc - S.p0;
@@ -569,6 +619,20 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
             Xs[slot] = xsum[off];
         };
         if constexpr (WD == W_INT4) fetch(0, 0);
+        // bf16: the staged inputs of all loads of this call are read from LDS in one batch (a lone
+        // wave pays the LDS latency once per batch of reads instead of once per load)
+        constexpr bool kXqPre = FF_XQ_PRELOAD && WD == W_BF16;
+        u32x4 hq[kXqPre ? U1 - U0 : 1][NC], lq[kXqPre ? U1 - U0 : 1][NC];
+        if constexpr (kXqPre) {
+#pragma unroll
+            for (int u = U0; u < U1; u++)
+#pragma unroll
+                for (int c = 0; c < NC; c++) {
+                    const int off = (cc * NL + u) * 16;
+                    hq[u - U0][c] = xh[c][off];
+                    lq[u - U0][c] = xh[c][off + nup];
+                }
+        }
 #pragma unroll
         for (int u = U0; u < U1; u++) {
             const int off = (cc * NL + u) * 16;
@@ -580,7 +644,9 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
             if constexpr (WD == W_BF16) {
 #pragma unroll
                 for (int c = 0; c < NC; c++) {
-                    const u32x4 h = xh[c][off], l = xh[c][off + nup];
+                    u32x4 h, l;
+                    if constexpr (kXqPre) { h = hq[u - U0][c]; l = lq[u - U0][c]; }
+                    else { h = xh[c][off]; l = xh[c][off + nup]; }
                     acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(h.x, h.y), acc0[c], 0, 0, 0);
                     acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(l.x, l.y), acc1[c], 0, 0, 0);
                     acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(h.z, h.w), acc0[c], 0, 0, 0);

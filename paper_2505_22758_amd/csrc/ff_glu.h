@@ -123,9 +123,14 @@ __device__ __forceinline__ bool glu_run(const Stream<WD, 1>& Sg, const Stream<WD
     bool ok = true;
 
     constexpr int kUnr = kUnrOf<WD>, kParts = kRefillPartsOf<WD, 1>;
+    float4 xr[kUnr][kXQuadsOf<WD>];   // (kXPreloadOf) the stage's inputs, read ahead of their multiply-accumulates
     auto compute = [&](const Stage<WD>& st, auto units) {   // units: the StageUnits range multiplied by this call (first: the chunk's checks, last: the iteration's end)
         constexpr int U0 = decltype(units)::u0, U1 = decltype(units)::u1;
         if (!cc.down) {
+            if constexpr (kXPreloadOf<WD, 1>) {
+                stage_x_load<WD, U0, U1>(xs, Sg.nup, cc.chunk, lane, xr);
+                stage_fma_x<WD, U0, U1>(st, xr, acc);
+            } else
             stage_fma<WD, 1, U0, U1>(st, xs, Sg.nup, cc.chunk, lane, acc);
             if constexpr (U1 < kUnr) return;
             if (cc.chunk == Sg.cpr - 1) {
@@ -150,6 +155,10 @@ __device__ __forceinline__ bool glu_run(const Stream<WD, 1>& Sg, const Stream<WD
             }
             float* la = lacc + (size_t)pl * 128 + lane;
             if (U0 == 0 && cc.chunk > 0) { acc[0][0] = la[0]; acc[1][0] = la[64]; }
+            if constexpr (kXPreloadOf<WD, 1>) {
+                stage_x_load<WD, U0, U1>(stg.hs, Sd.nup, cc.chunk, lane, xr);
+                stage_fma_x<WD, U0, U1>(st, xr, acc);
+            } else
             stage_fma<WD, 1, U0, U1>(st, stg.hs, Sd.nup, cc.chunk, lane, acc);
             if constexpr (U1 < kUnr) return;
             if (cc.chunk == Sd.cpr - 1) {
