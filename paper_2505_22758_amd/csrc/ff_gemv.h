@@ -38,9 +38,6 @@ template <int WD> constexpr int kChunkUnitsOf = 64 * kUnrOf<WD>;   // units of o
 #define FF_REFILL_PARTS_I4 1
 #endif
 template <int WD, int B> constexpr int kRefillPartsOf = B != 1 ? 1 : WD == W_INT4 ? FF_REFILL_PARTS_I4 : (kUnrOf<WD> % FF_REFILL_PARTS == 0 ? FF_REFILL_PARTS : 1);
-#ifndef FF_XQ_PRELOAD
-#define FF_XQ_PRELOAD 0
-#endif
 #ifndef FF_REFILL_PARTS_QUAD
 #define FF_REFILL_PARTS_QUAD 2
 #endif
@@ -619,20 +616,6 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
             Xs[slot] = xsum[off];
         };
         if constexpr (WD == W_INT4) fetch(0, 0);
-        // bf16: the staged inputs of all loads of this call are read from LDS in one batch (a lone
-        // wave pays the LDS latency once per batch of reads instead of once per load)
-        constexpr bool kXqPre = FF_XQ_PRELOAD && WD == W_BF16;
-        u32x4 hq[kXqPre ? U1 - U0 : 1][NC], lq[kXqPre ? U1 - U0 : 1][NC];
-        if constexpr (kXqPre) {
-#pragma unroll
-            for (int u = U0; u < U1; u++)
-#pragma unroll
-                for (int c = 0; c < NC; c++) {
-                    const int off = (cc * NL + u) * 16;
-                    hq[u - U0][c] = xh[c][off];
-                    lq[u - U0][c] = xh[c][off + nup];
-                }
-        }
 #pragma unroll
         for (int u = U0; u < U1; u++) {
             const int off = (cc * NL + u) * 16;
@@ -644,9 +627,7 @@ __device__ __forceinline__ void gemv_run_quad(const Stream<WD, B>& S, Stage<WD> 
             if constexpr (WD == W_BF16) {
 #pragma unroll
                 for (int c = 0; c < NC; c++) {
-                    u32x4 h, l;
-                    if constexpr (kXqPre) { h = hq[u - U0][c]; l = lq[u - U0][c]; }
-                    else { h = xh[c][off]; l = xh[c][off + nup]; }
+                    const u32x4 h = xh[c][off], l = xh[c][off + nup];
                     acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(h.x, h.y), acc0[c], 0, 0, 0);
                     acc1[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.x, w.y), half(l.x, l.y), acc1[c], 0, 0, 0);
                     acc0[c] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(half(w.z, w.w), half(h.z, h.w), acc0[c], 0, 0, 0);
