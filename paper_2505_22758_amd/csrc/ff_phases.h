@@ -610,9 +610,10 @@ struct TaggedAttnIO {
 #ifndef FF_ATTN_BATCH
 #define FF_ATTN_BATCH 4   // wave loads of K and of V in flight per wave (can be overridden at build time for sweeps; 8 measured no faster)
 #endif
-// MM (wide pass, head dimension 128: hundreds of cached rows per wave and item, where the vector ALUs
-// and not the memory set the pace): the scores of a batch of 16 rows come from the matrix cores, and
-// the running maximum is updated once per batch instead of once per row.
+// MM (head dimension 128; built for the wide pass with its hundreds of cached rows per wave and item,
+// where the vector ALUs and not the memory set the pace, and also used by the bf16 and int8 passes of
+// up to four sequences, with one batch of loads in flight): the scores of a batch of 16 rows come
+// from the matrix cores, and the running maximum is updated once per batch instead of once per row.
 //   * v_mfma_f32_16x16x32_bf16 with A = 16 cached key rows (lane (r, g4) loads dims [32 kk + 8 g4, + 8)
 //     of row r for the k-steps kk = 0..3) and B = the queries as bf16 head (columns 0..G-1) and bf16
 //     remainder (columns 8..8+G-1), so the products are as accurate as the fp32 ones of the row-wise
@@ -621,7 +622,7 @@ struct TaggedAttnIO {
 //     value load i of group grp, as in the row-wise path);
 //   * per head: one maximum over the batch's four rows of the group, one rescaling of the running
 //     output, then four multiply-adds per output element (rows past the item's end get weight 0).
-// Two batches of loads are kept in flight, the refills issued unconditionally (behind the item's
+// In the wide pass two batches of loads are kept in flight, the refills issued unconditionally (behind the item's
 // last row they repeat that row), like the refills of the weight ring: where code paths that issued
 // different numbers of loads meet, the compiler waits for all.
 typedef __bf16 attn_bf8 __attribute__((ext_vector_type(8)));
