@@ -986,9 +986,12 @@ __device__ __forceinline__ bool attn_merge_tagged(const DevModel& M, int b, int 
 // available per (sequence, kv head).
 __device__ __forceinline__ int attn_nsplit(int ncache, int share) {
     int ns = ncache / kMinSplitLen;
-    // more than 16 slices cost the merge a second, serial round of partial loads (it gathers 16
-    // at a time): go beyond 16 only once the slices are 128 rows long
-    if (ns > 16) ns = max(16, ncache / (2 * kMinSplitLen));
+    // The merge gathers the partials 16 at a time, and every further round is a serial round of loads:
+    // 16 slices until they are 256 rows long, then whole rounds of 16 (measured at the 8B shape, batch 1,
+    // us per step: context 3072 as 24 x 128 rows 3112, as 16 x 192 3062; 6144 as 32 x 192 3182, as
+    // 24 x 256 3212, as 16 x 384 3199; 8192 as 32 x 256 3231, as 16 x 512 3285).
+    constexpr int kRound = 16, kRoundRows = kRound * 256;
+    if (ns > kRound) ns = kRound * ((ncache + kRoundRows - 1) / kRoundRows);
     ns = min(ns, min(share, kMaxSplits));
     return max(ns, 1);
 }
