@@ -424,7 +424,7 @@ __device__ __forceinline__ void stage_fma(const Stage<WD>& st, const float4* xs,
 }
 
 // The staged inputs of a whole stage read from LDS ahead of its multiply-accumulates (single
-// sequence, bf16 and int8 weights): with one wave per SIMD nothing else hides the latency of an LDS read,
+// sequence): with one wave per SIMD nothing else hides the latency of an LDS read,
 // and a read issued right in front of its use costs that latency once per unit.  With
 // FF_X_PRELOAD the reads of all units of a stage (int8: of a part) are issued when its first part
 // (the part) starts (8B bf16, batch 1: 2968 -> 2946 us per step; issuing them a whole stage ahead
@@ -432,14 +432,17 @@ __device__ __forceinline__ void stage_fma(const Stage<WD>& st, const float4* xs,
 #ifndef FF_X_PRELOAD
 #define FF_X_PRELOAD 1
 #endif
-template <int WD, int B> constexpr bool kXPreloadOf = FF_X_PRELOAD && (WD == W_BF16 || WD == W_INT8) && B == 1;
+#ifndef FF_X_PRELOAD_I4
+#define FF_X_PRELOAD_I4 1   // int4: both units of a stage (8B int4, batch 1: 2395 -> 2384 us per step)
+#endif
+template <int WD, int B> constexpr bool kXPreloadOf = FF_X_PRELOAD && (WD == W_BF16 || WD == W_INT8 || (WD == W_INT4 && FF_X_PRELOAD_I4)) && B == 1;
 template <int WD> constexpr int kXQuadsOf = WTraits<WD>::EPU / 4;   // float4 reads per unit (bf16: 2, int8: 4)
 // Units [U0, U1) of a stage: bf16 reads the whole stage's inputs with its first part (16 registers per
 // part), int8 each part's inputs when the part starts (its units are twice as wide).
 template <int WD, int U0, int U1>
 __device__ __forceinline__ void stage_x_load(const float4* xs, int nup, int cc, int lane, float4 (&xr)[kUnrOf<WD>][kXQuadsOf<WD>]) {
     constexpr int kUnr = kUnrOf<WD>, NX = kXQuadsOf<WD>;
-    constexpr int L0 = WD == W_BF16 ? 0 : U0, L1 = WD == W_BF16 ? (U0 == 0 ? kUnr : 0) : U1;
+    constexpr int L0 = WD == W_INT8 ? U0 : 0, L1 = WD == W_INT8 ? U1 : (U0 == 0 ? kUnr : 0);   // int4 (whole-stage parts only): like bf16
 #pragma unroll
     for (int u = L0; u < L1; u++) {
         const float4* xq = xs + (cc * kUnr + u) * 64 + lane;
@@ -454,13 +457,25 @@ __device__ __forceinline__ void stage_fma_x(const Stage<WD>& st, const float4 (&
         if constexpr (WD == W_BF16) {
             acc[0][0] = dot_bf16(st.w[0][u], xr[u][0], xr[u][1], acc[0][0]);
             acc[1][0] = dot_bf16(st.w[1][u], xr[u][0], xr[u][1], acc[1][0]);
-        } else {
+        } else if constexpr (WD == W_INT8) {
 #pragma unroll
             for (int r = 0; r < 2; r++) {
                 float a = acc[r][0];
                 a = dot_i8x4(st.w[r][u].x, xr[u][0], a); a = dot_i8x4(st.w[r][u].y, xr[u][1], a);
                 a = dot_i8x4(st.w[r][u].z, xr[u][2], a); a = dot_i8x4(st.w[r][u].w, xr[u][3], a);
                 acc[r][0] = a;
+            }
+        } else {
+            const float4 (&x)[8] = xr[u];
+            const float xsum = ((sum4(x[0]) + sum4(x[1])) + (sum4(x[2]) + sum4(x[3]))) + ((sum4(x[4]) + sum4(x[5])) + (sum4(x[6]) + sum4(x[7])));
+#pragma unroll
+            for (int r = 0; r < 2; r++) {
+                const float sc = f16_to_f((f16_t)st.s[r][u]), zp = f16_to_f((f16_t)st.z[r][u]);
+                float t = dot_i4x8_codes(st.w[r][u].x, x[0], x[1], 0.f);
+                t = dot_i4x8_codes(st.w[r][u].y, x[2], x[3], t);
+                t = dot_i4x8_codes(st.w[r][u].z, x[4], x[5], t);
+                t = dot_i4x8_codes(st.w[r][u].w, x[6], x[7], t);
+                acc[r][0] = fmaf(sc, fmaf(-zp, xsum, t), acc[r][0]);
             }
         }
     }
